@@ -1,0 +1,184 @@
+"""Pins for the arithmetic half of the CPU oracle (no GPU).
+
+Each test checks the oracle against something that is not the oracle: a value the paper
+prints, an identity the paper states, a brute-force loop, an exact sum, or a closed form.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import sfmp_oracle as O
+import sfmp_workloads as W
+
+
+def _small_problem(seed=7, N=256, K=384, M=3, fractions=None, **kw):
+    return W.make_problem("small", K, N, M, seed, fractions=fractions, keep_weights=True, **kw)
+
+
+# ---- Appendix B worked example and Eq. 10 (bit-plane decomposition) -----------------------
+def test_bit_plane_worked_example(golden):
+    g = golden("bitplane_example.txt")
+    ints = np.array(g["integers"], dtype=np.uint8)
+    assert O.bit_plane(ints, 0).tolist() == g["lowest_bit"]
+    assert O.bit_plane(ints, 3).tolist() == g["highest_bit"]
+    assert O.codes_from_bit_planes([O.bit_plane(ints, i) for i in range(4)]).tolist() == g["integers"]
+
+
+def test_bit_plane_linearity_eq10():
+    rng = np.random.default_rng(1)
+    for q in (2, 3, 4):
+        Wint = rng.integers(0, 1 << q, size=(24, 40)).astype(np.uint8)
+        X = rng.integers(-8, 9, size=(5, 40)).astype(np.int64)  # integers: both sides exact
+        lhs = X @ Wint.astype(np.int64).T
+        rhs = sum((1 << i) * (X @ O.bit_plane(Wint, i).astype(np.int64).T) for i in range(q))
+        assert np.array_equal(lhs, rhs)
+
+
+# ---- dequant (Appendix B Eq. 11; groups along K inside a tile) -----------------------------
+def test_dequant_matches_bruteforce_loops():
+    p = _small_problem(seed=11, N=128, K=256, M=1)
+    w_hat = O.dequant(p.codes, p.scales, p.zeros)
+    for n in range(0, p.N, 7):
+        for k in range(0, p.K, 5):
+            g = k // 128
+            expect = float(p.scales[g, n]) * int(p.codes[n, k]) + float(p.zeros[g, n])
+            assert w_hat[n, k] == expect
+
+
+def test_dequant_catches_transposed_scale_layout():
+    # scales are [K/128, N]; a [N, K/128] reading must not give the same result
+    p = _small_problem(seed=12, N=256, K=256, M=1)
+    w_hat = O.dequant(p.codes, p.scales, p.zeros)
+    wrong = (p.scales.astype(np.float64).reshape(p.N, -1).repeat(128, axis=1) * p.codes
+             + p.zeros.astype(np.float64).reshape(p.N, -1).repeat(128, axis=1))
+    assert not np.allclose(w_hat, wrong)
+
+
+@pytest.mark.parametrize("b", [2, 4])
+def test_uniform_bitmap_reduces_to_plain_group_quantisation(b):
+    N, K = 256, 512
+    bitmap = np.full((N // 128, K // 128), b, dtype=np.int8)
+    p = W.make_problem("u", K, N, 2, 21 + b, bitmap=bitmap)
+    ng = K // 128
+    # independent expression of uniform per-row group quantisation, group 128
+    indep = (p.scales.T.astype(np.float64).reshape(N, ng, 1) * p.codes.reshape(N, ng, 128).astype(np.float64)
+             + p.zeros.T.astype(np.float64).reshape(N, ng, 1)).reshape(N, K)
+    assert np.array_equal(O.dequant(p.codes, p.scales, p.zeros), indep)
+    assert int(p.codes.max()) == (1 << b) - 1  # min-max quantiser reaches the top level
+
+
+def test_mirror_identity_eq12():
+    # s^ = s/2, W^_i = 2 W_i - 1, z^ = z + 1/2 sum_i 2^i s  ==>  sum_i 2^i s^ W^_i + z^ == s q + z
+    p = _small_problem(seed=31, N=128, K=256, M=1)
+    w_hat = O.dequant(p.codes, p.scales, p.zeros)
+    bm = np.repeat(np.repeat(p.bitmap, 128, axis=0), 128, axis=1).astype(np.int64)
+    s = np.repeat(p.scales.astype(np.float64).T, 128, axis=1)
+    z = np.repeat(p.zeros.astype(np.float64).T, 128, axis=1)
+    acc = np.zeros_like(w_hat)
+    zhat = z.copy()
+    for i in range(4):
+        active = (i < bm)
+        mirrored = 2.0 * O.bit_plane(p.codes, i) - 1.0
+        acc += np.where(active, (2.0 ** i) * (s / 2.0) * mirrored, 0.0)
+        zhat += np.where(active, 0.5 * (2.0 ** i) * s, 0.0)
+    assert np.allclose(acc + zhat, w_hat, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("b", [2, 3, 4])
+def test_quantiser_error_variance_is_step_squared_over_12(b):
+    # Eq. 5: a uniform quantiser with step delta has E[(w - w')^2] = delta^2 / 12.
+    N, K = 512, 512
+    bitmap = np.full((N // 128, K // 128), b, dtype=np.int8)
+    p = W.make_problem("v", K, N, 1, 40 + b, bitmap=bitmap, keep_weights=True)
+    err = O.dequant(p.codes, p.scales, p.zeros) - p.Wt.astype(np.float64)
+    s = np.repeat(p.scales.astype(np.float64).T, 128, axis=1)
+    ratio = float(np.mean(err ** 2) / np.mean(s ** 2 / 12.0))
+    assert 0.85 < ratio < 1.15, ratio
+    assert float(np.max(np.abs(err) / s)) <= 0.5 + 2e-2  # never more than half a step (+ fp16 rounding of z)
+
+
+# ---- matmul ----------------------------------------------------------------------------
+def test_gemm_matches_triple_loop_and_exact_sum():
+    p = _small_problem(seed=51, N=128, K=128, M=3, use_col_perm=True, use_row_perm=True)
+    Y = O.gemm(p.X, p.col_perm, p.codes, p.scales, p.zeros, p.row_perm)
+    assert Y.shape == (3, 128) and Y.dtype == np.float64
+    for m in range(3):
+        for i in range(0, 128, 9):
+            terms = []
+            for j in range(p.K):
+                w = float(p.scales[j // 128, i]) * int(p.codes[i, j]) + float(p.zeros[j // 128, i])
+                terms.append(float(p.X[m, p.col_perm[j]]) * w)
+            exact = math.fsum(terms)
+            assert abs(Y[m, p.row_perm[i]] - exact) <= 1e-12 * max(1.0, abs(exact))
+
+
+def test_gemm_rows_agrees_with_full_product():
+    p = _small_problem(seed=52, N=256, K=256, M=2)
+    rows = np.array([0, 5, 130, 255])
+    Yt = O.gemm(p.X, p.col_perm, p.codes, p.scales, p.zeros, None)
+    part = O.gemm_rows(p.X, p.col_perm, p.codes, p.scales, p.zeros, rows)
+    assert np.allclose(part, Yt[:, rows], rtol=1e-13, atol=1e-13)
+
+
+# ---- permutations (Section 3.4, Eq. 8-9) ---------------------------------------------------
+def test_permutation_equivalence_in_original_coordinates():
+    p = W.make_problem("perm", 384, 256, 4, 61, from_original=True, keep_weights=True)
+    w_hat = O.dequant(p.codes, p.scales, p.zeros)  # reordered coordinates
+    # scatter the dequantised weight back to original coordinates without using the oracle's gather
+    W_orig = np.zeros_like(w_hat)
+    for i in range(p.N):
+        W_orig[p.row_perm[i], p.col_perm] = w_hat[i]
+    Y_direct = p.X.astype(np.float64) @ W_orig.T
+    Y = O.gemm(p.X, p.col_perm, p.codes, p.scales, p.zeros, p.row_perm)
+    assert np.allclose(Y, Y_direct, rtol=1e-12, atol=1e-12)
+    # gathering X beforehand and passing the identity gives the same product
+    Xg = p.X[:, p.col_perm]
+    Y2 = O.gemm(Xg, None, p.codes, p.scales, p.zeros, p.row_perm)
+    assert np.array_equal(Y, Y2)
+    # leaving rows reordered, then un-permuting by hand
+    Yt = O.gemm(p.X, p.col_perm, p.codes, p.scales, p.zeros, None)
+    assert np.array_equal(Yt, Y[:, p.row_perm])
+    # the reordered weight really is W[row_perm][:, col_perm]
+    assert np.array_equal(p.Wt, p.W[p.row_perm][:, p.col_perm])
+
+
+def test_identity_permutations_are_noops():
+    p = _small_problem(seed=62, N=128, K=256, M=2)
+    ident_c = np.arange(p.K, dtype=np.int32)
+    ident_r = np.arange(p.N, dtype=np.int32)
+    a = O.gemm(p.X, None, p.codes, p.scales, p.zeros, None)
+    b = O.gemm(p.X, ident_c, p.codes, p.scales, p.zeros, ident_r)
+    assert np.array_equal(a, b)
+
+
+def test_wrong_permutation_direction_is_detected():
+    # the inverse permutation on the activation must NOT reproduce the product (guards the gather direction)
+    p = W.make_problem("perm", 256, 128, 2, 63, from_original=True, keep_weights=True)
+    inv = np.argsort(p.col_perm).astype(np.int32)
+    good = O.gemm(p.X, p.col_perm, p.codes, p.scales, p.zeros, p.row_perm)
+    bad = O.gemm(p.X, inv, p.codes, p.scales, p.zeros, p.row_perm)
+    ref = p.X.astype(np.float64) @ p.W.astype(np.float64).T
+    assert O.rel_frobenius(good, ref) < 0.5 * O.rel_frobenius(bad, ref)
+
+
+# ---- end-to-end sanity: the quantised product sits where the quantisation noise predicts -----
+def test_quantised_product_noise_band():
+    N, K, M = 512, 1024, 8
+    p = W.make_problem("band", K, N, M, 71, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, from_original=True,
+                       keep_weights=True)
+    Y = O.gemm(p.X, p.col_perm, p.codes, p.scales, p.zeros, p.row_perm)
+    Y_fp = p.X.astype(np.float64) @ p.W.astype(np.float64).T
+    # independent noise with variance s^2/12 per weight -> E||dY||^2 = sum_m sum_n sum_k x^2 s^2/12
+    s = np.repeat(p.scales.astype(np.float64).T, 128, axis=1)  # [N, K] reordered
+    x2 = (p.X.astype(np.float64)[:, p.col_perm]) ** 2  # [M, K] reordered
+    predicted = math.sqrt(float((x2 @ (s ** 2 / 12.0).T).sum()))
+    observed = float(np.linalg.norm(Y - Y_fp))
+    assert 0.8 < observed / predicted < 1.25, (observed, predicted)
+
+
+def test_rel_frobenius_definition():
+    a = np.array([[3.0, 4.0]])
+    b = np.array([[3.0, 0.0]])
+    assert O.rel_frobenius(a, b) == pytest.approx(4.0 / 3.0)
+    assert O.rel_frobenius(b, b) == 0.0
