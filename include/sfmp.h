@@ -1,0 +1,145 @@
+/*
+ * sfmp.h - C ABI of the MI355X (gfx950) block-wise mixed-precision GEMM / GEMV library.
+ *
+ * The operation (paper: Fig. 3(c); Section 3.3 block-wise bit allocation; Section 3.4
+ * Eq. 8-9 row/column reordering; Section 3.5 unified mixed-precision kernel; Appendix B
+ * Eq. 11 dequantisation form):
+ *
+ *     Y[m, row_perm[i]] = sum_j  X[m, col_perm[j]] * ( s[j/128, i] * q[i, j] + z[j/128, i] )
+ *
+ * where q is the integer code matrix of the reordered weight Wt [N, K] (N output features,
+ * K input features), every 128 x 128 tile of Wt carries its own bit-width b in {2,3,4}
+ * (the "bitmap"), and (s, z) is one fp16 scale / additive zero-point pair per row per
+ * group of 128 reordered columns.
+ *
+ * Conventions
+ *   - Every function returns SFMP_OK (0) or a negative SFMP_ERR_* code and never throws.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory on
+ *     the current device.  All buffers are owned by the caller; the library allocates and
+ *     frees no device memory and never synchronises the stream.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *   - N and K must be positive multiples of 128; M >= 1 is arbitrary.
+ *
+ * Packed format (what sfmp_pack writes and the kernels read)
+ *   Three byte streams S2, S3, S4.  Stream S_b holds all tiles of width b in ascending
+ *   (tile row, tile column) order; a tile of width b occupies exactly 2048*b bytes.
+ *   A tile is seen as 64 lanes that each own 8*b little-endian 32-bit words; word d of lane
+ *   l is at byte offset (d/4)*1024 + l*16 + (d%4)*4 of the tile, so one 16-byte load per
+ *   lane of a 64-wide wavefront reads 1024 contiguous bytes.
+ *   Element (r, c) of the tile (r = row, c = column inside the tile) belongs to
+ *       lane  l     = 16*((c%32)/8) + r/8
+ *       slab  sigma = r%8      (lane words [sigma*b, sigma*b+b) hold the slab's 32 codes)
+ *       step  kappa = c/32,  slot v = c%8,  pair = v/2,  half = v%2
+ *   and its bits sit inside the slab's b words at
+ *       b=4: word kappa,     bits [16*half + 4*pair, +4)
+ *       b=2: word kappa/2,   bits [16*half + 2*(4*(kappa%2) + pair), +2)
+ *       b=3: pi = 4*kappa + pair.  pi < 15: word pi/5, bits [16*half + 3*(pi%5), +3);
+ *            pi = 15: bit t of the code is bit 16*half + 15 of word t (t = 0,1,2).
+ *   With this placement the two codes of a (pair) share one 32-bit mask, land inside the
+ *   fp16 mantissa window of the two halves, and the 8 slots of a lane are exactly the 8
+ *   k-values that lane feeds to a 16x16x32 fp16 matrix instruction.
+ *
+ *   Block-index table (int32 words), replacing any run-time offset computation
+ *   (Appendix H attributes a <=3 % cost to computing block offsets at run time):
+ *       [0,3)                 number of tiles of width 2, 3, 4
+ *       [3, 3+nt)             tile_desc[tr*(K/128)+tc] = (slot << 2) | (b-2); slot = index of
+ *                             the tile inside stream S_b
+ *       3 x (N/128 + 1)       row_ptr_b for b = 2,3,4 (CSR over tile rows)
+ *       count2+count3+count4  col_idx_b for b = 2,3,4 (tile column of each tile, stream order)
+ */
+#ifndef SFMP_H
+#define SFMP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SFMP_TILE 128
+#define SFMP_GROUP 128
+
+#define SFMP_OK 0
+#define SFMP_ERR_NULL (-1)        /* a required pointer is NULL */
+#define SFMP_ERR_SHAPE (-2)       /* N or K not a positive multiple of 128, or M < 1 */
+#define SFMP_ERR_BITWIDTH (-3)    /* a bitmap entry is not 2, 3 or 4 */
+#define SFMP_ERR_CODE_RANGE (-4)  /* a code is >= 2^b for its tile */
+#define SFMP_ERR_WORKSPACE (-5)   /* workspace missing, misaligned (256 B) or too small */
+#define SFMP_ERR_HIP (-6)         /* a HIP call or kernel launch failed */
+#define SFMP_ERR_PERM (-7)        /* sfmp_check_perm: not a permutation of 0..n-1 */
+#define SFMP_ERR_LAYOUT (-8)      /* layout struct inconsistent with itself */
+
+/* Sizes of a packed matrix.  Filled by sfmp_pack_query / sfmp_pack; passed by the caller,
+ * unchanged, to the device entry points. */
+typedef struct sfmp_layout {
+  int32_t N, K;                    /* rows (output features) and columns (input features) of Wt */
+  int32_t tile, group;             /* 128, 128 */
+  int32_t count2, count3, count4;  /* tiles of each width */
+  int32_t index_words;             /* length of the block-index table in int32 words */
+  int64_t bytes_s2, bytes_s3, bytes_s4, bytes_index;
+} sfmp_layout_t;
+
+/* Text for an error code (static storage, never NULL).  For SFMP_ERR_HIP the text of the last
+ * HIP error seen by the calling thread is appended. */
+const char* sfmp_strerror(int code);
+
+/* Host only.  Sizes of the three streams and of the index table for a bitmap
+ * (int8 [N/128, K/128], row-major, host).  Section 4.3 "Extra Metadata": one int8 per block. */
+int sfmp_pack_query(const int8_t* bitmap_host, int32_t N, int32_t K, sfmp_layout_t* out);
+
+/* Host only.  Packs codes (uint8 [N, K] row-major, reordered coordinates, host) into the three
+ * streams and writes the block-index table; all four outputs are host buffers of the sizes
+ * sfmp_pack_query reports (a stream of size 0 may be NULL).  Every code is checked against
+ * its tile's width.  The caller uploads the buffers (each to a 16-byte aligned device
+ * address).  This is the offline packing step of Section 3.5 / Appendix F ("block-major
+ * layout, contiguous within each block"), in the byte format described above. */
+int sfmp_pack(const uint8_t* codes_host, const int8_t* bitmap_host, int32_t N, int32_t K,
+              uint8_t* s2_host, uint8_t* s3_host, uint8_t* s4_host, int32_t* index_host,
+              sfmp_layout_t* out);
+
+/* Device.  Expands the packed streams back to codes_dev (uint8 [N, K] row-major, device) with
+ * the same device unpack routines the GEMM kernels use.  Asynchronous on hip_stream.
+ * Debug / parity entry point: unpacked codes must equal the packer's input bit for bit. */
+int sfmp_unpack(const sfmp_layout_t* layout, const void* s2_dev, const void* s3_dev, const void* s4_dev,
+                const int32_t* index_dev, uint8_t* codes_dev, void* hip_stream);
+
+/* Host only.  Bytes of device workspace sfmp_gemm needs for this layout and M
+ * (256-byte granularity; never 0). */
+int sfmp_gemm_workspace(const sfmp_layout_t* layout, int32_t M, int64_t* bytes);
+
+/* Device.  Zero-fills a workspace (a small fill kernel on hip_stream, safe under graph
+ * capture).  A workspace must be initialised once before its first use by sfmp_gemm; every
+ * sfmp_gemm call leaves it ready for the next one.  One workspace serves one stream at a
+ * time: two calls that overlap on the same workspace race. */
+int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream);
+
+/* Device.  The mixed-precision product of Fig. 3(c):
+ *   X         fp16 [M, K] row-major, ORIGINAL column order.
+ *   col_perm  int32 [K]; the kernel reads X[m, col_perm[j]] for reordered column j
+ *             (Section 3.4: the weight's column permutation applied to the activation);
+ *             NULL = identity.
+ *   layout, s2, s3, s4, index   a matrix packed by sfmp_pack, uploaded unchanged.
+ *   scales, zeros  fp16 [K/128, N] (group-major): w_hat = s*q + z (Appendix B Eq. 11).
+ *   bitmap    int8 [N/128, K/128] (device); must be the bitmap the matrix was packed with.
+ *   row_perm  int32 [N]; output feature i of the reordered product is stored at column
+ *             row_perm[i] of Y (undoing P_row of Eq. 9); NULL = leave the rows reordered.
+ *   Y         fp16 [M, N] row-major; fully overwritten.  fp32 accumulation, one
+ *             round-to-nearest-even conversion at the end.
+ *   workspace device memory of at least sfmp_gemm_workspace() bytes, 256-byte aligned,
+ *             initialised once by sfmp_workspace_init.
+ * M <= 16 runs the bandwidth-bound decode kernel; larger M runs the MFMA prefill kernel.
+ * Asynchronous on hip_stream; holds no global state.  The permutations are not checked for
+ * being bijections (out-of-range entries are the caller's error; use sfmp_check_perm). */
+int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
+              const void* s2_dev, const void* s3_dev, const void* s4_dev, const int32_t* index_dev,
+              const void* scales_dev, const void* zeros_dev, const int8_t* bitmap_dev,
+              const int32_t* row_perm_dev, void* Y_dev, void* workspace_dev, int64_t workspace_bytes,
+              void* hip_stream);
+
+/* Host only.  SFMP_OK if perm_host[0..n) is a permutation of 0..n-1, else SFMP_ERR_PERM. */
+int sfmp_check_perm(const int32_t* perm_host, int32_t n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SFMP_H */

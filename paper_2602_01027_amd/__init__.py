@@ -1,0 +1,21 @@
+"""MI355X-native SFMP mixed-precision GEMM/GEMV: thin Python binding over the C ABI (libsfmp.so).
+
+Argument marshalling only; every step of the path runs in the HIP kernels of the library.
+The names mirror include/sfmp.h.
+"""
+from .binding import (  # noqa: F401
+    SfmpError,
+    SfmpLayout,
+    DevicePacked,
+    lib_path,
+    load_library,
+    sfmp_strerror,
+    sfmp_pack_query,
+    sfmp_pack,
+    sfmp_unpack,
+    sfmp_gemm_workspace,
+    sfmp_workspace_init,
+    sfmp_gemm,
+    sfmp_check_perm,
+    upload_packed,
+)

@@ -1,0 +1,171 @@
+"""ctypes binding of libsfmp.so.  Host buffers are numpy arrays, device buffers are torch tensors
+(torch only owns device memory and streams here).  No fallback: a missing library raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class SfmpError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"sfmp error {code}: {text}")
+        self.code = code
+
+
+class SfmpLayout(C.Structure):
+    _fields_ = [
+        ("N", C.c_int32), ("K", C.c_int32), ("tile", C.c_int32), ("group", C.c_int32),
+        ("count2", C.c_int32), ("count3", C.c_int32), ("count4", C.c_int32), ("index_words", C.c_int32),
+        ("bytes_s2", C.c_int64), ("bytes_s3", C.c_int64), ("bytes_s4", C.c_int64), ("bytes_index", C.c_int64),
+    ]
+
+
+EXPORTS = ("sfmp_strerror", "sfmp_pack_query", "sfmp_pack", "sfmp_unpack", "sfmp_gemm_workspace",
+           "sfmp_workspace_init", "sfmp_gemm", "sfmp_check_perm")
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libsfmp.so")
+
+
+def load_library():
+    """Loads the in-tree libsfmp.so; raises if it has not been built (there is no other path)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} is missing: build it with `python -m paper_2602_01027_amd.build` "
+                                "(or __graft_entry__.build()); there is no CPU fallback")
+    lib = C.CDLL(path)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    LP = C.POINTER(SfmpLayout)
+    lib.sfmp_strerror.restype = C.c_char_p
+    lib.sfmp_strerror.argtypes = [C.c_int]
+    lib.sfmp_pack_query.argtypes = [vp, i32, i32, LP]
+    lib.sfmp_pack.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, LP]
+    lib.sfmp_unpack.argtypes = [LP, vp, vp, vp, vp, vp, vp]
+    lib.sfmp_gemm_workspace.argtypes = [LP, i32, C.POINTER(i64)]
+    lib.sfmp_workspace_init.argtypes = [vp, i64, vp]
+    lib.sfmp_gemm.argtypes = [vp, i32, vp, LP, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.sfmp_check_perm.argtypes = [vp, i32]
+    for name in EXPORTS:
+        if name != "sfmp_strerror":
+            getattr(lib, name).restype = C.c_int
+    _LIB = lib
+    return lib
+
+
+def sfmp_strerror(code: int) -> str:
+    return load_library().sfmp_strerror(int(code)).decode()
+
+
+def _check(code: int) -> None:
+    if code != 0:
+        raise SfmpError(code, sfmp_strerror(code))
+
+
+def _host_ptr(a: Optional[np.ndarray]):
+    if a is None or a.size == 0:
+        return None
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _dev_ptr(t):
+    if t is None:
+        return None
+    if t.numel() == 0:
+        return None
+    assert t.is_cuda and t.is_contiguous()
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def sfmp_pack_query(bitmap: np.ndarray, N: int, K: int) -> SfmpLayout:
+    L = SfmpLayout()
+    bm = np.ascontiguousarray(bitmap, dtype=np.int8)
+    _check(load_library().sfmp_pack_query(_host_ptr(bm), N, K, C.byref(L)))
+    return L
+
+
+def sfmp_pack(codes: np.ndarray, bitmap: np.ndarray):
+    """Host packer.  Returns (layout, s2, s3, s4, index) with numpy uint8 / int32 host arrays."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    bm = np.ascontiguousarray(bitmap, dtype=np.int8)
+    N, K = codes.shape
+    L = sfmp_pack_query(bm, N, K)
+    s2 = np.empty(L.bytes_s2, dtype=np.uint8)
+    s3 = np.empty(L.bytes_s3, dtype=np.uint8)
+    s4 = np.empty(L.bytes_s4, dtype=np.uint8)
+    index = np.empty(L.index_words, dtype=np.int32)
+    out = SfmpLayout()
+    _check(load_library().sfmp_pack(_host_ptr(codes), _host_ptr(bm), N, K, _host_ptr(s2), _host_ptr(s3),
+                                    _host_ptr(s4), _host_ptr(index), C.byref(out)))
+    return out, s2, s3, s4, index
+
+
+def sfmp_check_perm(perm: np.ndarray) -> int:
+    p = np.ascontiguousarray(perm, dtype=np.int32)
+    return int(load_library().sfmp_check_perm(_host_ptr(p), int(p.size)))
+
+
+@dataclass
+class DevicePacked:
+    """Device-resident packed matrix (torch tensors own the memory)."""
+    layout: SfmpLayout
+    s2: object
+    s3: object
+    s4: object
+    index: object
+    scales: object
+    zeros: object
+    bitmap: object
+
+
+def upload_packed(layout, s2, s3, s4, index, scales, zeros, bitmap, device="cuda:0") -> DevicePacked:
+    import torch
+
+    def up(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+    return DevicePacked(layout, up(s2), up(s3), up(s4), up(index), up(scales.view(np.float16)),
+                        up(zeros.view(np.float16)), up(bitmap.astype(np.int8)))
+
+
+def sfmp_unpack(layout: SfmpLayout, s2, s3, s4, index, codes_out, stream=None) -> None:
+    _check(load_library().sfmp_unpack(C.byref(layout), _dev_ptr(s2), _dev_ptr(s3), _dev_ptr(s4), _dev_ptr(index),
+                                      _dev_ptr(codes_out), _stream_ptr(stream)))
+
+
+def sfmp_gemm_workspace(layout: SfmpLayout, M: int) -> int:
+    n = C.c_int64(0)
+    _check(load_library().sfmp_gemm_workspace(C.byref(layout), int(M), C.byref(n)))
+    return int(n.value)
+
+
+def sfmp_workspace_init(workspace, stream=None) -> None:
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load_library().sfmp_workspace_init(_dev_ptr(workspace), nbytes, _stream_ptr(stream)))
+
+
+def sfmp_gemm(X, col_perm, layout: SfmpLayout, s2, s3, s4, index, scales, zeros, bitmap, row_perm, Y, workspace,
+              stream=None) -> None:
+    M = int(X.shape[0])
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load_library().sfmp_gemm(_dev_ptr(X), M, _dev_ptr(col_perm), C.byref(layout), _dev_ptr(s2), _dev_ptr(s3),
+                                    _dev_ptr(s4), _dev_ptr(index), _dev_ptr(scales), _dev_ptr(zeros),
+                                    _dev_ptr(bitmap), _dev_ptr(row_perm), _dev_ptr(Y), _dev_ptr(workspace), nbytes,
+                                    _stream_ptr(stream)))

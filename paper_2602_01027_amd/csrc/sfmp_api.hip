@@ -1,0 +1,79 @@
+// extern "C" device entry points: argument checks, workspace sizing, path selection.
+#include <hip/hip_runtime.h>
+
+#include "sfmp_internal.h"
+
+using namespace sfmp;
+
+static bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+extern "C" {
+
+int sfmp_unpack(const sfmp_layout_t* layout, const void* s2_dev, const void* s3_dev, const void* s4_dev,
+                const int32_t* index_dev, uint8_t* codes_dev, void* hip_stream) {
+  if (int e = check_layout(layout)) return e;
+  if (!index_dev || !codes_dev) return SFMP_ERR_NULL;
+  if ((layout->count2 && !s2_dev) || (layout->count3 && !s3_dev) || (layout->count4 && !s4_dev)) return SFMP_ERR_NULL;
+  if (!aligned(s2_dev, 16) || !aligned(s3_dev, 16) || !aligned(s4_dev, 16) || !aligned(codes_dev, 8) ||
+      !aligned(index_dev, 4))
+    return SFMP_ERR_SHAPE;
+  return launch_unpack(layout, (const uint8_t*)s2_dev, (const uint8_t*)s3_dev, (const uint8_t*)s4_dev, index_dev,
+                       codes_dev, hip_stream);
+}
+
+int sfmp_gemm_workspace(const sfmp_layout_t* layout, int32_t M, int64_t* bytes) {
+  if (!bytes) return SFMP_ERR_NULL;
+  if (int e = check_layout(layout)) return e;
+  if (M < 1) return SFMP_ERR_SHAPE;
+  if (M <= kDecodeMaxM) {
+    const DecodePlan d = make_decode_plan(layout->N, layout->K, M);
+    *bytes = d.counter_bytes + d.partial_bytes;
+  } else {
+    const PrefillPlan d = make_prefill_plan(layout->N, layout->K, M);
+    *bytes = d.xperm_bytes;
+  }
+  if (*bytes < 256) *bytes = 256;
+  return SFMP_OK;
+}
+
+int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream) {
+  if (!workspace_dev) return SFMP_ERR_NULL;
+  if (bytes < 0 || (bytes % 16) != 0 || !aligned(workspace_dev, 256)) return SFMP_ERR_WORKSPACE;
+  return launch_fill_zero(workspace_dev, bytes, hip_stream);
+}
+
+int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
+              const void* s2_dev, const void* s3_dev, const void* s4_dev, const int32_t* index_dev,
+              const void* scales_dev, const void* zeros_dev, const int8_t* bitmap_dev, const int32_t* row_perm_dev,
+              void* Y_dev, void* workspace_dev, int64_t workspace_bytes, void* hip_stream) {
+  if (int e = check_layout(layout)) return e;
+  if (M < 1) return SFMP_ERR_SHAPE;
+  if (!X_dev || !index_dev || !scales_dev || !zeros_dev || !bitmap_dev || !Y_dev) return SFMP_ERR_NULL;
+  if ((layout->count2 && !s2_dev) || (layout->count3 && !s3_dev) || (layout->count4 && !s4_dev)) return SFMP_ERR_NULL;
+  if (!aligned(s2_dev, 16) || !aligned(s3_dev, 16) || !aligned(s4_dev, 16) || !aligned(scales_dev, 16) ||
+      !aligned(zeros_dev, 16) || !aligned(X_dev, 16) || !aligned(Y_dev, 2) || !aligned(col_perm_dev, 16) ||
+      !aligned(row_perm_dev, 4) || !aligned(index_dev, 4))
+    return SFMP_ERR_SHAPE;
+  int64_t need = 0;
+  if (int e = sfmp_gemm_workspace(layout, M, &need)) return e;
+  if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < need) return SFMP_ERR_WORKSPACE;
+  GemmArgs a;
+  a.X = X_dev;
+  a.M = M;
+  a.col_perm = col_perm_dev;
+  a.L = layout;
+  a.s2 = (const uint8_t*)s2_dev;
+  a.s3 = (const uint8_t*)s3_dev;
+  a.s4 = (const uint8_t*)s4_dev;
+  a.index = index_dev;
+  a.scales = scales_dev;
+  a.zeros = zeros_dev;
+  a.bitmap = bitmap_dev;
+  a.row_perm = row_perm_dev;
+  a.Y = Y_dev;
+  a.workspace = workspace_dev;
+  a.workspace_bytes = workspace_bytes;
+  return M <= kDecodeMaxM ? launch_decode(a, hip_stream) : launch_prefill(a, hip_stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,181 @@
+// Host side of the library: argument validation, layout query, the offline packer and the
+// error strings.  Plain C++ (no device code); runs without a GPU.
+#include "sfmp_internal.h"
+
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+namespace sfmp {
+
+thread_local char g_hip_error_text[256] = {0};
+
+void note_hip_error(const char* what, const char* text) {
+  std::snprintf(g_hip_error_text, sizeof(g_hip_error_text), "%s: %s", what, text ? text : "?");
+}
+
+int check_shape(int32_t N, int32_t K) {
+  if (N <= 0 || K <= 0 || (N % SFMP_TILE) != 0 || (K % SFMP_TILE) != 0) return SFMP_ERR_SHAPE;
+  return SFMP_OK;
+}
+
+int check_layout(const sfmp_layout_t* L) {
+  if (!L) return SFMP_ERR_NULL;
+  if (check_shape(L->N, L->K) != SFMP_OK) return SFMP_ERR_SHAPE;
+  if (L->tile != SFMP_TILE || L->group != SFMP_GROUP) return SFMP_ERR_LAYOUT;
+  const int64_t ntr = L->N / SFMP_TILE, ntc = L->K / SFMP_TILE, nt = ntr * ntc;
+  if (L->count2 < 0 || L->count3 < 0 || L->count4 < 0) return SFMP_ERR_LAYOUT;
+  if ((int64_t)L->count2 + L->count3 + L->count4 != nt) return SFMP_ERR_LAYOUT;
+  if (L->bytes_s2 != (int64_t)L->count2 * 4096 || L->bytes_s3 != (int64_t)L->count3 * 6144 ||
+      L->bytes_s4 != (int64_t)L->count4 * 8192)
+    return SFMP_ERR_LAYOUT;
+  if (L->index_words != 3 + nt + 3 * (ntr + 1) + nt || L->bytes_index != 4 * (int64_t)L->index_words)
+    return SFMP_ERR_LAYOUT;
+  return SFMP_OK;
+}
+
+// Bit position (inside the tile's byte string) of bit 0 of the code at (r, c) for widths 2 and 4,
+// and of each bit separately for width 3 (its 16th pair is spread over three words).
+static inline uint32_t word_byte_offset(int b, int lane, int slab, int word) {
+  const int d = slab * b + word;
+  return (uint32_t)(d / 4) * 1024u + (uint32_t)lane * 16u + (uint32_t)(d % 4) * 4u;
+}
+
+static void pack_one_tile(const uint8_t* codes, int64_t ld, int b, uint8_t* out) {
+  uint32_t* words = reinterpret_cast<uint32_t*>(out);  // streams are written on a little-endian host
+  std::memset(out, 0, (size_t)2048 * b);
+  for (int r = 0; r < SFMP_TILE; ++r) {
+    const int slab = r % 8;
+    const uint8_t* row = codes + (int64_t)r * ld;
+    for (int c = 0; c < SFMP_TILE; ++c) {
+      const uint32_t q = row[c];
+      const int lane = 16 * ((c % 32) / 8) + r / 8;
+      const int kappa = c / 32, v = c % 8, pair = v / 2, half = v % 2;
+      if (b == 4) {
+        words[word_byte_offset(4, lane, slab, kappa) / 4] |= q << (16 * half + 4 * pair);
+      } else if (b == 2) {
+        words[word_byte_offset(2, lane, slab, kappa / 2) / 4] |= q << (16 * half + 2 * (4 * (kappa % 2) + pair));
+      } else {
+        const int pi = 4 * kappa + pair;
+        if (pi < 15) {
+          words[word_byte_offset(3, lane, slab, pi / 5) / 4] |= q << (16 * half + 3 * (pi % 5));
+        } else {
+          for (int t = 0; t < 3; ++t)
+            words[word_byte_offset(3, lane, slab, t) / 4] |= ((q >> t) & 1u) << (16 * half + 15);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace sfmp
+
+using namespace sfmp;
+
+extern "C" {
+
+const char* sfmp_strerror(int code) {
+  static thread_local char buf[320];
+  switch (code) {
+    case SFMP_OK: return "ok";
+    case SFMP_ERR_NULL: return "a required pointer is NULL";
+    case SFMP_ERR_SHAPE: return "bad shape: N and K must be positive multiples of 128 and M >= 1";
+    case SFMP_ERR_BITWIDTH: return "bitmap entry is not 2, 3 or 4";
+    case SFMP_ERR_CODE_RANGE: return "code out of range for its tile's bit-width";
+    case SFMP_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
+    case SFMP_ERR_HIP:
+      std::snprintf(buf, sizeof(buf), "HIP error (%s)", g_hip_error_text[0] ? g_hip_error_text : "no detail");
+      return buf;
+    case SFMP_ERR_PERM: return "not a permutation of 0..n-1";
+    case SFMP_ERR_LAYOUT: return "layout struct is inconsistent";
+    default: return "unknown sfmp error code";
+  }
+}
+
+int sfmp_pack_query(const int8_t* bitmap_host, int32_t N, int32_t K, sfmp_layout_t* out) {
+  if (!bitmap_host || !out) return SFMP_ERR_NULL;
+  if (int e = check_shape(N, K)) return e;
+  const int64_t ntr = N / SFMP_TILE, ntc = K / SFMP_TILE, nt = ntr * ntc;
+  int64_t cnt[5] = {0, 0, 0, 0, 0};
+  for (int64_t i = 0; i < nt; ++i) {
+    const int b = bitmap_host[i];
+    if (b < 2 || b > 4) return SFMP_ERR_BITWIDTH;
+    ++cnt[b];
+  }
+  std::memset(out, 0, sizeof(*out));
+  out->N = N;
+  out->K = K;
+  out->tile = SFMP_TILE;
+  out->group = SFMP_GROUP;
+  out->count2 = (int32_t)cnt[2];
+  out->count3 = (int32_t)cnt[3];
+  out->count4 = (int32_t)cnt[4];
+  out->index_words = (int32_t)(3 + nt + 3 * (ntr + 1) + nt);
+  out->bytes_s2 = cnt[2] * 4096;
+  out->bytes_s3 = cnt[3] * 6144;
+  out->bytes_s4 = cnt[4] * 8192;
+  out->bytes_index = 4 * (int64_t)out->index_words;
+  return SFMP_OK;
+}
+
+int sfmp_pack(const uint8_t* codes_host, const int8_t* bitmap_host, int32_t N, int32_t K, uint8_t* s2_host,
+              uint8_t* s3_host, uint8_t* s4_host, int32_t* index_host, sfmp_layout_t* out) {
+  if (!codes_host || !bitmap_host || !index_host || !out) return SFMP_ERR_NULL;
+  sfmp_layout_t L;
+  if (int e = sfmp_pack_query(bitmap_host, N, K, &L)) return e;
+  if ((L.count2 && !s2_host) || (L.count3 && !s3_host) || (L.count4 && !s4_host)) return SFMP_ERR_NULL;
+  const int64_t ntr = N / SFMP_TILE, ntc = K / SFMP_TILE, nt = ntr * ntc;
+
+  // range check first, so that nothing is written on failure
+  for (int64_t tr = 0; tr < ntr; ++tr)
+    for (int64_t r = 0; r < SFMP_TILE; ++r) {
+      const uint8_t* row = codes_host + (tr * SFMP_TILE + r) * (int64_t)K;
+      for (int64_t tc = 0; tc < ntc; ++tc) {
+        const uint8_t limit = (uint8_t)(1u << bitmap_host[tr * ntc + tc]);
+        const uint8_t* p = row + tc * SFMP_TILE;
+        uint8_t mx = 0;
+        for (int c = 0; c < SFMP_TILE; ++c) mx = p[c] > mx ? p[c] : mx;
+        if (mx >= limit) return SFMP_ERR_CODE_RANGE;
+      }
+    }
+
+  uint8_t* streams[5] = {nullptr, nullptr, s2_host, s3_host, s4_host};
+  int32_t next_slot[5] = {0, 0, 0, 0, 0};
+  int32_t* tile_desc = index_host + 3;
+  int32_t* row_ptr[5] = {nullptr, nullptr, index_host + 3 + nt, index_host + 3 + nt + (ntr + 1),
+                         index_host + 3 + nt + 2 * (ntr + 1)};
+  int32_t* col_idx[5] = {nullptr, nullptr, index_host + 3 + nt + 3 * (ntr + 1),
+                         index_host + 3 + nt + 3 * (ntr + 1) + L.count2,
+                         index_host + 3 + nt + 3 * (ntr + 1) + L.count2 + L.count3};
+  index_host[0] = L.count2;
+  index_host[1] = L.count3;
+  index_host[2] = L.count4;
+  for (int b = 2; b <= 4; ++b) row_ptr[b][0] = 0;
+  for (int64_t tr = 0; tr < ntr; ++tr) {
+    for (int64_t tc = 0; tc < ntc; ++tc) {
+      const int b = bitmap_host[tr * ntc + tc];
+      const int32_t slot = next_slot[b]++;
+      tile_desc[tr * ntc + tc] = (slot << 2) | (b - 2);
+      col_idx[b][slot] = (int32_t)tc;
+      pack_one_tile(codes_host + tr * SFMP_TILE * (int64_t)K + tc * SFMP_TILE, K, b,
+                    streams[b] + (int64_t)slot * 2048 * b);
+    }
+    for (int b = 2; b <= 4; ++b) row_ptr[b][tr + 1] = next_slot[b];
+  }
+  *out = L;
+  return SFMP_OK;
+}
+
+int sfmp_check_perm(const int32_t* perm_host, int32_t n) {
+  if (!perm_host) return SFMP_ERR_NULL;
+  if (n <= 0) return SFMP_ERR_SHAPE;
+  std::vector<uint8_t> seen((size_t)n, 0);
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t v = perm_host[i];
+    if (v < 0 || v >= n || seen[(size_t)v]) return SFMP_ERR_PERM;
+    seen[(size_t)v] = 1;
+  }
+  return SFMP_OK;
+}
+
+}  // extern "C"

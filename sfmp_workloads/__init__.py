@@ -28,6 +28,7 @@ from .generators import (  # noqa: F401
     quantize_minmax,
     random_quantized,
     make_problem,
+    with_activations,
     config_cases,
     algorithmic_bytes,
     metadata_bits_per_weight,

@@ -93,6 +93,11 @@ def _rng(seed: int) -> np.random.Generator:
     return np.random.Generator(np.random.PCG64(int(seed)))
 
 
+def _rng_x(seed: int, M: int) -> np.random.Generator:
+    """Activations come from their own stream, so problems that differ only in M share weights."""
+    return np.random.Generator(np.random.PCG64([int(seed), int(M), 0x5F3]))
+
+
 def make_bitmap(ntr: int, ntc: int, fractions: Optional[Dict[int, float]], rng: np.random.Generator) -> np.ndarray:
     """Bit-width of every tile.
 
@@ -254,7 +259,7 @@ def make_problem(label: str, K: int, N: int, M: int, seed: int, *, w_std: float 
         bitmap = make_bitmap(ntr, ntc, fractions, rng)
     col_perm = make_perm(K, rng) if use_col_perm else None
     row_perm = make_perm(N, rng) if use_row_perm else None
-    X = make_activations(M, K, rng, outliers=outliers)
+    X = make_activations(M, K, _rng_x(seed, M), outliers=outliers)
     W = Wt = None
     if fast_codes:
         codes, scales, zeros = random_quantized(N, K, bitmap, w_std, rng)
@@ -273,6 +278,12 @@ def make_problem(label: str, K: int, N: int, M: int, seed: int, *, w_std: float 
     return Problem(label=label, N=N, K=K, M=M, X=X, bitmap=bitmap, codes=codes, scales=scales, zeros=zeros,
                    col_perm=col_perm, row_perm=row_perm, W=W if keep_weights else None,
                    Wt=Wt if keep_weights else None, seed=seed)
+
+
+def with_activations(p: "Problem", M: int, outliers: bool) -> "Problem":
+    """The same weights, bitmap and permutations with a fresh activation block of M rows."""
+    import dataclasses
+    return dataclasses.replace(p, M=M, X=make_activations(M, p.K, _rng_x(p.seed, M), outliers=outliers))
 
 
 def config_cases(cid: int) -> Iterator[Tuple[str, int, int, int, int, dict]]:

@@ -1,0 +1,203 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Integer work (packed bytes, unpacked codes) must match bit for bit; fp16 outputs must be within
+a relative Frobenius error of 2e-3 of the float64 oracle (the stated acceptance bound).
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from oracle import sfmp_oracle as O
+import sfmp_workloads as W
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (no fallback path exists)")
+    return torch
+
+
+def _check(p, Y, rows=None):
+    """Compare Y (fp16 [M,N]) with the oracle; `rows` = sampled reordered rows for big layers."""
+    assert np.isfinite(Y.astype(np.float32)).all()
+    if rows is None:
+        ref = O.gemm(p.X, p.col_perm, p.codes, p.scales, p.zeros, p.row_perm)
+        err = O.rel_frobenius(Y, ref)
+    else:
+        ref = O.gemm_rows(p.X, p.col_perm, p.codes, p.scales, p.zeros, rows)
+        cols = rows if p.row_perm is None else p.row_perm[rows]
+        err = O.rel_frobenius(Y[:, cols], ref)
+    assert err <= TOL, err
+    return err
+
+
+# ---------------------------------------------------------------------------------------------
+# unpack: bit-exact
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("case", ["tiny", "all2", "all3", "all4", "ragged"])
+def test_unpack_bit_exact(torch_cuda, case):
+    import paper_2602_01027_amd as S
+    from gpu_util import device_problem
+    torch = torch_cuda
+    if case == "tiny":
+        p = W.make_problem("tiny", 512, 512, 1, 1000)
+    elif case == "ragged":
+        p = W.make_problem("r", 640, 384, 1, 77)
+    else:
+        b = int(case[-1])
+        p = W.make_problem(case, 384, 256, 1, 80 + b, bitmap=np.full((2, 3), b, dtype=np.int8))
+    # codes that exercise every bit of every field: replace by uniform random codes of the tile's width
+    rng = np.random.default_rng(5)
+    bm = np.repeat(np.repeat(p.bitmap, 128, axis=0), 128, axis=1)
+    p = dataclasses.replace(p, codes=(rng.integers(0, 16, size=bm.shape) % (1 << bm)).astype(np.uint8))
+    dp, _, _ = device_problem(p)
+    out = torch.full((p.N, p.K), 255, dtype=torch.uint8, device="cuda:0")
+    S.sfmp_unpack(dp.layout, dp.s2, dp.s3, dp.s4, dp.index, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.array_equal(got, p.codes)
+    # and the oracle's own unpack of the library's packed bytes agrees (bytes <-> codes both ways)
+    assert np.array_equal(O.unpack(p.N, p.K, dp.s2.cpu().numpy(), dp.s3.cpu().numpy(), dp.s4.cpu().numpy(),
+                                   dp.index.cpu().numpy()), p.codes)
+
+
+# ---------------------------------------------------------------------------------------------
+# config 1 and small edge cases
+# ---------------------------------------------------------------------------------------------
+def test_config1_tiny(torch_cuda):
+    from gpu_util import run_gemm
+    for label, K, N, M, seed, kw in W.config_cases(1):
+        p = W.make_problem(label, K, N, M, seed, **kw)
+        _check(p, run_gemm(p))
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 15, 16, 17, 63, 64, 65, 130])
+def test_edge_M_ragged_shape(torch_cuda, M):
+    # N = 640 = 5 tile rows (ragged last workgroup of 4 tile rows), K = 896 = 7 tiles (ragged last K chunk)
+    from gpu_util import run_gemm
+    p = W.make_problem("edge", 896, 640, M, 4242, fractions=None, outliers=True)
+    _check(p, run_gemm(p))
+
+
+@pytest.mark.parametrize("variant", ["all2", "all3", "all4", "clustered", "no_perm", "col_only", "row_only"])
+@pytest.mark.parametrize("M", [1, 7, 48])
+def test_bitmap_and_permutation_variants(torch_cuda, variant, M):
+    from gpu_util import run_gemm
+    K, N = 1024, 512
+    kw = dict(fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3})
+    if variant.startswith("all"):
+        kw["bitmap"] = np.full((N // 128, K // 128), int(variant[-1]), dtype=np.int8)
+    elif variant == "clustered":
+        kw["bitmap"] = W.clustered_bitmap(N // 128, K // 128, {2: 0.5, 3: 0.25, 4: 0.25})
+    elif variant == "no_perm":
+        kw.update(use_col_perm=False, use_row_perm=False)
+    elif variant == "col_only":
+        kw.update(use_row_perm=False)
+    elif variant == "row_only":
+        kw.update(use_col_perm=False)
+    p = W.make_problem(variant, K, N, M, 99, **kw)
+    _check(p, run_gemm(p))
+
+
+def test_workspace_is_reusable_and_result_deterministic(torch_cuda):
+    from gpu_util import device_problem, make_workspace, run_gemm
+    p = W.make_problem("reuse", 2048, 1024, 4, 31337, fractions={2: 0.5, 3: 0.5}, outliers=True)
+    dp, cp, rp = device_problem(p)
+    ws = make_workspace(dp.layout, p.M)
+    y1 = run_gemm(p, dp, cp, rp, ws)
+    y2 = run_gemm(p, dp, cp, rp, ws)
+    _check(p, y1)
+    assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+    # a second, smaller M through the same (larger) workspace
+    p1 = W.with_activations(p, 1, outliers=True)
+    _check(p1, run_gemm(p1, dp, cp, rp, ws))
+
+
+def test_gemm_argument_errors(torch_cuda):
+    import ctypes as C
+    import paper_2602_01027_amd as S
+    from gpu_util import device_problem
+    torch = torch_cuda
+    p = W.make_problem("err", 256, 256, 1, 3)
+    dp, cp, rp = device_problem(p)
+    X = torch.from_numpy(p.X).to("cuda:0")
+    Y = torch.empty((1, p.N), dtype=torch.float16, device="cuda:0")
+    small = torch.zeros(256, dtype=torch.uint8, device="cuda:0")
+    need = S.sfmp_gemm_workspace(dp.layout, 1)
+    assert need > 256
+    with pytest.raises(S.SfmpError) as ei:
+        S.sfmp_gemm(X, cp, dp.layout, dp.s2, dp.s3, dp.s4, dp.index, dp.scales, dp.zeros, dp.bitmap, rp, Y, small)
+    assert ei.value.code == -5
+
+
+# ---------------------------------------------------------------------------------------------
+# the benchmark configurations at full size
+# ---------------------------------------------------------------------------------------------
+_CACHE = {}
+
+
+def _config_problem(cid, si):
+    """Weights / bitmap / permutations of shape si of config cid (shared by all its M values)."""
+    key = (cid, si)
+    if key not in _CACHE:
+        _CACHE.clear()  # keep one big layer in host memory at a time
+        spec = W.CONFIGS[cid]
+        label, K, N = spec.shapes[si]
+        p = W.make_problem(label, K, N, 1, 1000 * cid + si, w_std=spec.w_std[si], fractions=spec.fractions,
+                           outliers=spec.outliers, use_col_perm=spec.col_perm, use_row_perm=spec.row_perm[si])
+        _CACHE[key] = p
+    return _CACHE[key]
+
+
+def _distinct_shapes(cid):
+    seen, out = set(), []
+    for si, (label, K, N) in enumerate(W.CONFIGS[cid].shapes):
+        if (K, N) not in seen:
+            seen.add((K, N))
+            out.append(si)
+    return out
+
+
+def _run_config_shape(cid, si, sample_rows):
+    from gpu_util import device_problem, run_gemm
+    spec = W.CONFIGS[cid]
+    base = _config_problem(cid, si)
+    dp, cp, rp = device_problem(base)
+    rows = None
+    if sample_rows and base.N * base.K > 64 * 2 ** 20:
+        rng = np.random.default_rng(cid * 100 + si)
+        # sampled output features: every tile row is hit, the oracle computes them one by one
+        rows = np.sort(np.concatenate([np.arange(base.N // 128) * 128 + rng.integers(0, 128, base.N // 128),
+                                       rng.choice(base.N, size=256, replace=False)]))
+        rows = np.unique(rows)
+    errs = {}
+    for M in spec.Ms:
+        p = W.with_activations(base, M, outliers=spec.outliers)
+        errs[M] = _check(p, run_gemm(p, dp, cp, rp), rows)
+    print(f"config {cid} {base.label} K={base.K} N={base.N} avg_bits={base.avg_bits:.3f} rel_frob={errs}", flush=True)
+
+
+@pytest.mark.parametrize("si", _distinct_shapes(2))
+def test_config2_8b_decode(torch_cuda, si):
+    _run_config_shape(2, si, sample_rows=False)
+
+
+@pytest.mark.parametrize("si", _distinct_shapes(3))
+def test_config3_8b_fractional(torch_cuda, si):
+    _run_config_shape(3, si, sample_rows=False)
+
+
+@pytest.mark.parametrize("si", _distinct_shapes(4))
+def test_config4_70b_decode(torch_cuda, si):
+    _run_config_shape(4, si, sample_rows=True)
+
+
+@pytest.mark.parametrize("si", _distinct_shapes(5))
+def test_config5_prefill(torch_cuda, si):
+    _run_config_shape(5, si, sample_rows=True)
