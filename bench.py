@@ -1,0 +1,313 @@
+#!/usr/bin/env python3
+"""bench.py - one-GPU benchmark of the SFMP mixed-precision GEMM/GEMV hot path on MI355X.
+
+A "step" is one pass of the whole hot path over one batch: the seven projections
+(q, k, v, o, gate, up, down) of a Llama-3-8B-shaped decoder layer at M = 1, 128x128 tiles with
+one third each of 2/3/4-bit tiles (average 3.0 code bits), group 128, random column and row
+permutations - benchmark configs[1].  Inputs are synthetic and already resident in HBM.
+Weights are rotated over R device copies (R * layer bytes >= 1 GiB) so that neither the L2s nor
+the 256 MB Infinity Cache hold them between steps: the numbers are cold-cache numbers.
+
+Prints ONE JSON line (see the keys below); `value` is microseconds per layer (lower is better).
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+NCPU = len(os.sched_getaffinity(0))
+os.environ.setdefault("OMP_NUM_THREADS", str(NCPU))
+os.environ.setdefault("OPENBLAS_NUM_THREADS", str(NCPU))
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 matrix peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=240)
+    ap.add_argument("--warmup", type=int, default=24)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the per-shape / 70B / prefill side reports")
+    ap.add_argument("--eager", action="store_true", help="time eager launches instead of HIP-graph replays")
+    return ap.parse_args()
+
+
+class Layer:
+    """Device-resident projections of one decoder layer, replicated R times for cold-cache timing."""
+
+    def __init__(self, problems, replicas, device="cuda:0"):
+        import torch
+        import paper_2602_01027_amd as S
+        self.S = S
+        self.torch = torch
+        self.device = device
+        self.problems = problems
+        self.replicas = replicas
+        self.proj = []  # per projection: dict(layout, reps=[DevicePacked...], X, Y, cp, rp, ws, bytes)
+        for p in problems:
+            L, s2, s3, s4, index = S.sfmp_pack(p.codes, p.bitmap)
+            reps = [S.upload_packed(L, s2, s3, s4, index, p.scales, p.zeros, p.bitmap, device) for _ in range(replicas)]
+            cp = [torch.from_numpy(p.col_perm).to(device) for _ in range(replicas)] if p.col_perm is not None else None
+            rp = [torch.from_numpy(p.row_perm).to(device) for _ in range(replicas)] if p.row_perm is not None else None
+            X = torch.from_numpy(p.X).to(device)
+            Y = torch.empty((p.M, p.N), dtype=torch.float16, device=device)
+            ws = torch.empty(S.sfmp_gemm_workspace(L, p.M), dtype=torch.uint8, device=device)
+            S.sfmp_workspace_init(ws)
+            self.proj.append(dict(p=p, layout=L, reps=reps, cp=cp, rp=rp, X=X, Y=Y, ws=ws))
+        torch.cuda.synchronize()
+        self._args = {}
+
+    def _call_args(self, i, r, stream_ptr):
+        """Pre-marshalled ctypes arguments of sfmp_gemm for projection i, replica r."""
+        key = (i, r, stream_ptr)
+        if key not in self._args:
+            d = self.proj[i]
+            dp = d["reps"][r]
+
+            def ptr(t):
+                return C.c_void_p(t.data_ptr()) if t is not None and t.numel() else None
+
+            self._args[key] = (ptr(d["X"]), C.c_int32(d["p"].M), ptr(d["cp"][r]) if d["cp"] else None,
+                               C.byref(dp.layout), ptr(dp.s2), ptr(dp.s3), ptr(dp.s4), ptr(dp.index), ptr(dp.scales),
+                               ptr(dp.zeros), ptr(dp.bitmap), ptr(d["rp"][r]) if d["rp"] else None, ptr(d["Y"]),
+                               ptr(d["ws"]), C.c_int64(d["ws"].numel()), C.c_void_p(stream_ptr))
+        return self._args[key]
+
+    def launch(self, i, r, stream_ptr):
+        rc = self.S.load_library().sfmp_gemm(*self._call_args(i, r, stream_ptr))
+        if rc != 0:
+            raise RuntimeError(self.S.sfmp_strerror(rc))
+
+    def step(self, r, stream_ptr):
+        for i in range(len(self.proj)):
+            self.launch(i, r, stream_ptr)
+
+    def bytes_per_proj(self, W):
+        out = []
+        for d in self.proj:
+            p = d["p"]
+            out.append(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, col_perm=p.col_perm is not None,
+                                           row_perm=p.row_perm is not None, index_words=p.bitmap.size))
+        return out
+
+
+def build_problems(W, cid, Ms=None, fast=False, only=None):
+    spec = W.CONFIGS[cid]
+    out = []
+    for si, (label, K, N) in enumerate(spec.shapes):
+        if only is not None and label not in only:
+            continue
+        M = (Ms or spec.Ms)[0]
+        out.append(W.make_problem(label, K, N, M, 1000 * cid + si, w_std=spec.w_std[si], fractions=spec.fractions,
+                                  outliers=spec.outliers, use_col_perm=spec.col_perm, use_row_perm=spec.row_perm[si],
+                                  fast_codes=fast))
+    return out
+
+
+def time_steps(torch, layer, steps, warmup, use_graph):
+    """Times `steps` steps after `warmup`; returns (ms_per_step from HIP events, wall ms_per_step)."""
+    R = layer.replicas
+    stream = torch.cuda.current_stream()
+    graphs = None
+    if use_graph:
+        graphs = []
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            for r in range(R):  # eager warm-up on the capture stream (module load, first-touch)
+                layer.step(r, side.cuda_stream)
+        side.synchronize()
+        for r in range(R):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                layer.step(r, torch.cuda.current_stream().cuda_stream)
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+    def run(i):
+        if graphs is not None:
+            graphs[i % R].replay()
+        else:
+            layer.step(i % R, stream.cuda_stream)
+
+    for i in range(warmup):
+        run(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        run(warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return e0.elapsed_time(e1) / steps, wall
+
+
+def time_each_projection(torch, layer, launches=60):
+    """Average microseconds per launch of every projection alone (back-to-back launches, rotating replicas)."""
+    out = []
+    stream = torch.cuda.current_stream()
+    R = layer.replicas
+    for i in range(len(layer.proj)):
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            layer.launch(i, 0, side.cuda_stream)
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for j in range(launches):
+                layer.launch(i, j % R, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        g.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        out.append(e0.elapsed_time(e1) * 1e3 / launches)
+    return out
+
+
+def cpu_baseline(problems):
+    """The CPU oracle, as it stands, on the same layer: one pass over all projections."""
+    from oracle import sfmp_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
+    except Exception:
+        threads = NCPU
+    t0 = time.perf_counter()
+    for p in problems:
+        O.gemm(p.X, p.col_perm, p.codes, p.scales, p.zeros, p.row_perm)
+    dt = time.perf_counter() - t0
+    return dict(value=dt * 1e6, unit="us/layer", cores=int(threads), kind="oracle",
+                sample="the full 8B layer (7 projections, M=1), one pass of oracle.gemm (fp64 dequant + matmul); "
+                       f"host has {NCPU} usable cores")
+
+
+def load_traffic():
+    path = os.path.join(ROOT, "profiles", "decode_traffic.json")
+    if os.path.exists(path):
+        try:
+            return json.load(open(path)).get("bytes_per_launch")
+        except Exception:
+            return None
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import sfmp_workloads as W
+    import paper_2602_01027_amd as S
+    S.load_library()  # fails loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    problems = build_problems(W, 2)
+    layer_bytes = sum(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, index_words=p.bitmap.size) for p in problems)
+    R = int(np.ceil(2 ** 30 / layer_bytes))
+    layer = Layer(problems, R)
+    per_proj_bytes = layer.bytes_per_proj(W)
+
+    ms_step, wall_ms = time_steps(torch, layer, args.steps, args.warmup, use_graph=not args.eager)
+    us_layer = ms_step * 1e3
+    gbps = layer_bytes / (ms_step * 1e-3) / 1e9
+    n_launch = len(problems)
+
+    result = {
+        "metric": "us_per_layer_M1 (Llama-3-8B-shaped decoder layer, 7 mixed 2/3/4-bit projections, avg 3.0 bits)",
+        "value": round(us_layer, 3),
+        "unit": "us/layer",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 (fp16 activations/scales, 2/3/4-bit codes, fp32 accumulate)",
+        "data": "synthetic (seeded Gaussian weights, min-max group quantised; cold cache: weights rotated over "
+                f"{R} device copies)",
+        "config": {"workload": "configs[1]: 8B decode layer, M=1, q/k/v/o/gate/up/down, 128x128 tiles 1/3 each "
+                               "2/3/4-bit, group 128, random col+row perms",
+                   "launch": "eager" if args.eager else "hip-graph replay of the 7 launches",
+                   "replicas": R, "layer_bytes": int(layer_bytes)},
+        "effective_GBps": round(gbps, 1),
+        "pct_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
+        "wall_ms_per_step": round(wall_ms, 6),
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "sfmp::decode_kernel<1>",
+            "achieved": round(gbps, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(gbps / HBM_PEAK_GBPS, 4),
+            "traffic": load_traffic(),
+            "bytes_per_launch_avg": int(layer_bytes / n_launch),
+            "avg_launch_us": round(us_layer / n_launch, 3),
+            "note": "achieved = algorithmic bytes of the 7 launches of a step / HIP-event time of the step "
+                    "(launch gaps included), averaged over the timed region",
+        },
+    }
+
+    if not args.no_extra:
+        extra = {}
+        per = time_each_projection(torch, layer)
+        extra["per_projection_8b_M1"] = [
+            dict(shape=f"{d['p'].K}->{d['p'].N}", label=d["p"].label, us=round(t, 3), MB=round(b / 1e6, 3),
+                 GBps=round(b / t / 1e3, 1), pct_hbm_peak=round(100 * b / t / 1e3 / HBM_PEAK_GBPS, 2))
+            for d, t, b in zip(layer.proj, per, per_proj_bytes)]
+        del layer
+        torch.cuda.empty_cache()
+        # 70B-shaped decode layer (configs[3]) at M = 1, codes drawn directly (timing only)
+        p70 = build_problems(W, 4, Ms=(1,), fast=True)
+        b70 = sum(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, index_words=p.bitmap.size) for p in p70)
+        l70 = Layer(p70, int(np.ceil(2 ** 30 / b70)))
+        ms70, _ = time_steps(torch, l70, 60, 6, use_graph=not args.eager)
+        per70 = time_each_projection(torch, l70, launches=24)
+        b70p = l70.bytes_per_proj(W)
+        extra["layer_70b_M1"] = dict(us_per_layer=round(ms70 * 1e3, 2), MB=round(b70 / 1e6, 1),
+                                     GBps=round(b70 / ms70 / 1e6, 1),
+                                     pct_hbm_peak=round(100 * b70 / ms70 / 1e6 / HBM_PEAK_GBPS, 2),
+                                     per_projection=[dict(shape=f"{d['p'].K}->{d['p'].N}", us=round(t, 2),
+                                                          GBps=round(b / t / 1e3, 1))
+                                                     for d, t, b in zip(l70.proj, per70, b70p)])
+        del l70, p70
+        torch.cuda.empty_cache()
+        # prefill (configs[4]) at M = 2048 on the 8B gate shape, codes drawn directly (timing only)
+        pp = build_problems(W, 5, fast=True, only=("8b.gate", "8b.q"))
+        lp = Layer(pp, 2)
+        perp = time_each_projection(torch, lp, launches=6)
+        extra["prefill_M2048"] = [
+            dict(shape=f"{d['p'].K}->{d['p'].N}", us=round(t, 1),
+                 TFLOPs=round(2.0 * d["p"].M * d["p"].N * d["p"].K / t / 1e6, 1),
+                 pct_mfma_peak=round(100 * 2.0 * d["p"].M * d["p"].N * d["p"].K / t / 1e6 / MFMA_F16_PEAK_TFLOPS, 2))
+            for d, t in zip(lp.proj, perp)]
+        del lp, pp
+        result["extra"] = extra
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(problems)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -23,21 +23,29 @@
  * Packed format (what sfmp_pack writes and the kernels read)
  *   Three byte streams S2, S3, S4.  Stream S_b holds all tiles of width b in ascending
  *   (tile row, tile column) order; a tile of width b occupies exactly 2048*b bytes.
- *   A tile is seen as 64 lanes that each own 8*b little-endian 32-bit words; word d of lane
- *   l is at byte offset (d/4)*1024 + l*16 + (d%4)*4 of the tile, so one 16-byte load per
- *   lane of a 64-wide wavefront reads 1024 contiguous bytes.
+ *   A tile is 8 slabs of 256*b bytes; slab sigma holds the tile rows {8i + sigma}.  Inside a
+ *   slab each of 64 lanes owns b consecutive little-endian 32-bit words: word w of lane l of
+ *   slab sigma is at byte offset sigma*256*b + l*4*b + 4*w of the tile, so one load of 4*b
+ *   bytes per lane of a 64-wide wavefront reads 256*b contiguous bytes, and a 16-row slab of
+ *   a tile can be fetched on its own.
  *   Element (r, c) of the tile (r = row, c = column inside the tile) belongs to
  *       lane  l     = 16*((c%32)/8) + r/8
- *       slab  sigma = r%8      (lane words [sigma*b, sigma*b+b) hold the slab's 32 codes)
- *       step  kappa = c/32,  slot v = c%8,  pair = v/2,  half = v%2
- *   and its bits sit inside the slab's b words at
- *       b=4: word kappa,     bits [16*half + 4*pair, +4)
- *       b=2: word kappa/2,   bits [16*half + 2*(4*(kappa%2) + pair), +2)
- *       b=3: pi = 4*kappa + pair.  pi < 15: word pi/5, bits [16*half + 3*(pi%5), +3);
- *            pi = 15: bit t of the code is bit 16*half + 15 of word t (t = 0,1,2).
- *   With this placement the two codes of a (pair) share one 32-bit mask, land inside the
- *   fp16 mantissa window of the two halves, and the 8 slots of a lane are exactly the 8
- *   k-values that lane feeds to a 16x16x32 fp16 matrix instruction.
+ *       slab  sigma = r%8
+ *       step  kappa = c/32,  slot v = c%8,  reg = v/2,  half = v%2
+ *   and its bits sit inside the lane's b words of that slab at
+ *       b=4: word reg,     bits [16*half + 4*kappa, +4)
+ *       b=2: word reg%2,   bits [16*half + 8*(reg/2) + 2*kappa, +2)
+ *       b=3: every 16-bit half of a word holds five 3-bit fields j=0..4 at bits [3j, 3j+3) and
+ *            one spare bit 15; (kappa, reg) -> (word, field):
+ *                kappa 0: (0,0) (1,0) (2,0) (0,3)
+ *                kappa 1: (0,1) (1,1) (2,1) (0,4)
+ *                kappa 2: (0,2) (1,2) (2,2) SPARE
+ *                kappa 3: (1,3) (2,3) (1,4) (2,4)
+ *            SPARE: bit t of the code is the spare bit (bit 16*half + 15) of word t, t = 0,1,2.
+ *   With this placement the two codes of a register (slots 2*reg, 2*reg+1) share one 32-bit
+ *   mask and land inside the fp16 mantissa window of the two halves, the four registers of a
+ *   k-step share one field position, and the 8 slots of a lane are exactly the 8 k-values that
+ *   lane feeds to a 16x16x32 fp16 matrix instruction.
  *
  *   Block-index table (int32 words), replacing any run-time offset computation
  *   (Appendix H attributes a <=3 % cost to computing block offsets at run time):

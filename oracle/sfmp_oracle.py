@@ -131,20 +131,35 @@ def rel_frobenius(Y: np.ndarray, Y_ref: np.ndarray) -> float:
 # ======================================================================================
 # Part 2 - the packed byte format, written from its description
 # ======================================================================================
-# A tile is 128 rows x 128 columns of b-bit codes and occupies exactly 2048*b bytes, seen as
-# 64 "lanes" that each own 8*b little-endian 32-bit words.  Word d of lane l sits at byte
-# offset (d // 4) * 1024 + l * 16 + (d % 4) * 4 of the tile.
+# A tile is 128 rows x 128 columns of b-bit codes and occupies exactly 2048*b bytes: 8 "slabs"
+# of 256*b bytes.  Inside a slab each of 64 "lanes" owns b consecutive little-endian 32-bit
+# words: word w of lane l of slab sigma sits at byte offset sigma*256*b + l*4*b + 4*w.
 #
 # Element (r, c) of the tile (r = row in tile, c = column in tile) belongs to
 #     lane   l     = 16 * ((c % 32) // 8) + r // 8
-#     slab   sigma = r % 8               (8 slabs; lane words [sigma*b, sigma*b + b) form the slab)
+#     slab   sigma = r % 8
 #     step   kappa = c // 32             (4 steps of 32 columns)
-#     slot   v     = c % 8,  pair = v // 2,  half = v % 2  (half selects bits 0-15 / 16-31 of a word)
-# and its bits are placed inside the slab's b words as follows:
-#     b = 4: word kappa,       bits [16*half + 4*pair, +4)
-#     b = 2: word kappa // 2,  bits [16*half + 2*(4*(kappa % 2) + pair), +2)
-#     b = 3: pi = 4*kappa + pair (0..15).  pi < 15: word pi // 5, bits [16*half + 3*(pi % 5), +3).
-#            pi = 15: bit t of the code is bit 16*half + 15 of word t  (t = 0, 1, 2).
+#     slot   v     = c % 8,  reg = v // 2,  half = v % 2  (half selects bits 0-15 / 16-31 of a word)
+# and its bits are placed inside the lane's b words of that slab as follows:
+#     b = 4: word reg,      bits [16*half + 4*kappa, +4)
+#     b = 2: word reg % 2,  bits [16*half + 8*(reg // 2) + 2*kappa, +2)
+#     b = 3: each 16-bit half of a word has five 3-bit fields j = 0..4 at bits [3j, 3j+3) and one
+#            spare bit 15.  (kappa, reg) -> (word, field j) by the table below; the entry SPARE
+#            spreads the code over the three spare bits: bit t of the code is bit 16*half + 15 of
+#            word t.
+#                kappa 0: (0,0) (1,0) (2,0) (0,3)
+#                kappa 1: (0,1) (1,1) (2,1) (0,4)
+#                kappa 2: (0,2) (1,2) (2,2) SPARE
+#                kappa 3: (1,3) (2,3) (1,4) (2,4)
+_SPARE = None
+_FIELD3 = (
+    ((0, 0), (1, 0), (2, 0), (0, 3)),
+    ((0, 1), (1, 1), (2, 1), (0, 4)),
+    ((0, 2), (1, 2), (2, 2), _SPARE),
+    ((1, 3), (2, 3), (1, 4), (2, 4)),
+)
+
+
 def tile_bytes(b: int) -> int:
     return 2048 * b
 
@@ -160,19 +175,18 @@ def code_bit_position(b: int, r: int, c: int, t: int) -> int:
     slab = r % 8
     kappa = c // 32
     v = c % 8
-    pair, half = v // 2, v % 2
+    reg, half = v // 2, v % 2
     if b == 4:
-        word, bit = kappa, 16 * half + 4 * pair + t
+        word, bit = reg, 16 * half + 4 * kappa + t
     elif b == 2:
-        word, bit = kappa // 2, 16 * half + 2 * (4 * (kappa % 2) + pair) + t
+        word, bit = reg % 2, 16 * half + 8 * (reg // 2) + 2 * kappa + t
     else:
-        pi = 4 * kappa + pair
-        if pi < 15:
-            word, bit = pi // 5, 16 * half + 3 * (pi % 5) + t
-        else:
+        entry = _FIELD3[kappa][reg]
+        if entry is _SPARE:
             word, bit = t, 16 * half + 15
-    d = slab * b + word
-    byte_off = (d // 4) * 1024 + lane * 16 + (d % 4) * 4
+        else:
+            word, bit = entry[0], 16 * half + 3 * entry[1] + t
+    byte_off = slab * 256 * b + lane * 4 * b + 4 * word
     return 8 * byte_off + bit
 
 

@@ -1,30 +1,207 @@
-// Decode path (M <= 16): bandwidth-bound mixed-precision GEMV / skinny GEMM for gfx950.
+// Decode path (M <= 16): bandwidth-bound mixed-precision GEMV (M = 1) and skinny GEMM
+// (2 <= M <= 16) for gfx950.
 //
-// Work split.  A workgroup is 4 wavefronts; wavefront w owns tile row 4*rowgroup + w and
-// walks `tiles_per_chunk` consecutive 128x128 tiles of that row (one K chunk).  The tile's
-// bit-width is read from the block-index table and selects, wavefront-uniformly, one of
-// three specialised bodies: there is no divergence inside a wavefront.  The four tile rows
-// of a workgroup share the K chunk, so the activation slice X[:, col_perm[chunk]] is
-// gathered once per workgroup into LDS (the permutation is fused into this load).
+// Common arithmetic.  Codes are masked out of the packed words as fp16 denormals q*2^(p-24)
+// and contracted against the fp16 activations by MFMA 16x16x32 (activations = A operand, 16
+// rows of which at most M are non-zero; 16 weight rows = B operand).  The matrix pipe is the
+// MAC engine of a memory-bound kernel: at HBM speed only 2-4 VALU lane-ops per weight are
+// available and they are spent on the unpack (about 0.6 per weight); the MFMA cost is
+// independent of M.  One accumulator per field position p; per 128-column group the result is
+// scaled in fp32:  y += s * sum_p 2^(24-p) C_p + z * sum(x)      (Appendix B Eq. 11, re-associated).
 //
-// Per tile and lane: 2*B 16-byte loads (1 KiB contiguous per wavefront per load), one
-// v_and_b32 per code pair (codes become fp16 denormals q*2^(p-24)), and 32 MFMA
-// 16x16x32 instructions that contract the tile against the LDS-resident activations, whose
-// slots were pre-multiplied by 2^(h-p).  The matrix pipe is used as the MAC engine of a
-// memory-bound kernel: the VALU budget per weight at HBM speed (2-4 lane-ops) is spent on
-// the unpack, and the MFMA cost does not grow with M up to 16.  Per 128-column group the
-// fp32 MFMA result is scaled: acc += s*2^(24-h) * sum(q*x) + z * sum(x)   (Appendix B Eq. 11,
-// re-associated per group), sum(x) coming from one extra MFMA against a vector of ones.
+// GEMV (M = 1): one workgroup owns one 16-row slab of a tile row over the WHOLE K range, so a
+// result never leaves the workgroup: no global partial sums, no atomics, no fences.  The
+// activation vector is copied to LDS with coalesced loads and permuted there (the column
+// permutation is fused into this load); wavefront w walks the tiles w, w+NW, ... of the tile
+// row, 4 slab loads in flight per lane; per-wavefront sums are combined through LDS and the 16
+// outputs are scattered through row_perm.  Workgroups are numbered so that the 8 slabs of a
+// tile row run on the same XCD (they share scale/zero cache lines and the index table).
 //
-// K reduction.  Each wavefront stores its 128 x M fp32 partial; an arrival counter per tile
-// row lets the last wavefront of a row add the partials in chunk order (deterministic),
-// convert to fp16 (RNE) and scatter the row through row_perm.  Counters are left at zero.
+// Skinny GEMM (2..16): a wavefront owns a tile row and walks a chunk of tiles of that row; the
+// four tile rows of a workgroup share the gathered activation chunk in LDS.  Partial sums go to
+// the workspace with device-scope atomic stores; an arrival counter per tile row lets the last
+// wavefront add them in chunk order (deterministic), convert and scatter.  No cache-wide fence
+// is used: ordering comes from s_waitcnt on the atomic stores before the counter increment.
 #include "sfmp_device.h"
 #include "sfmp_internal.h"
 
 namespace sfmp {
 
-struct DecodeParams {
+// sum over the slab's 128 columns of q * x for the 16 rows of the slab (lane%16) and the 16
+// activation rows (4*(lane/16) + r), scaled to plain integers-times-x.
+template <int B>
+__device__ __forceinline__ floatx4 slab_dot(const uint32_t* w, const half8 (&a)[4]) {
+  uint32_t op[4][4];
+  unpack_slab<B>(w, op);
+  floatx4 c[num_classes<B>()];
+#pragma unroll
+  for (int i = 0; i < num_classes<B>(); ++i) c[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kappa = 0; kappa < 4; ++kappa)
+    c[step_class<B>(kappa)] =
+        __builtin_amdgcn_mfma_f32_16x16x32_f16(a[kappa], as_half8(op[kappa]), c[step_class<B>(kappa)], 0, 0, 0);
+  floatx4 t = c[0] * pow2f(24 - class_pos<B>(0));
+#pragma unroll
+  for (int i = 1; i < num_classes<B>(); ++i) t += c[i] * pow2f(24 - class_pos<B>(i));
+  return t;
+}
+
+// ============================================================================================
+// GEMV, M = 1
+// ============================================================================================
+struct GemvParams {
+  const _Float16* X;
+  const int32_t* col_perm;
+  const uint8_t* s2;
+  const uint8_t* s3;
+  const uint8_t* s4;
+  const int32_t* tile_desc;
+  const _Float16* scales;
+  const _Float16* zeros;
+  const int32_t* row_perm;
+  _Float16* Y;
+  int32_t N, K, ntr, ntc;
+};
+
+constexpr int kGemvWaves = 8;
+constexpr int kGemvBatch = 4;
+
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void gemv_kernel(const GemvParams p) {
+  constexpr int NT = NW * 64;
+  constexpr int U = kGemvBatch;
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  _Float16* Xs = reinterpret_cast<_Float16*>(lds_raw);                       // [K] permuted activations
+  float* Sx = reinterpret_cast<float*>(lds_raw + (size_t)p.K * 2);           // [ntc] group sums of x
+  float* red = Sx + p.ntc;                                                   // [NW][16]
+  _Float16* Xraw = reinterpret_cast<_Float16*>(lds_raw + (((size_t)p.K * 2 + (size_t)p.ntc * 4 + NW * 64 + 15) & ~(size_t)15));
+
+  const int tid = threadIdx.x;
+  const int lane = tid % kWave;
+  const int wave = tid / kWave;
+  // 8*ntr slabs; block b runs on XCD b%8: give each XCD a contiguous range of ntr slabs
+  const int slab = (int)(blockIdx.x % 8) * p.ntr + (int)(blockIdx.x / 8);
+  const int tr = slab / 8, sigma = slab % 8;
+  const int64_t n = (int64_t)tr * kTile + 8 * (lane % 16) + sigma;  // weight row of this lane
+
+  // descriptors of this wavefront's tiles tc = wave + NW*i: lane i keeps descriptor i
+  const int my_cnt = p.ntc > wave ? (p.ntc - wave + NW - 1) / NW : 0;
+  int32_t desc_v = 0;
+  if (lane < my_cnt) desc_v = p.tile_desc[(int64_t)tr * p.ntc + wave + NW * lane];
+
+  // raw activation copy (coalesced 16-byte loads) and the first permutation indices
+  const int units = p.K / 8;
+  _Float16* stage = p.col_perm ? Xraw : Xs;
+  for (int i = tid; i < units; i += NT)
+    reinterpret_cast<uint4*>(stage)[i] = reinterpret_cast<const uint4*>(p.X)[i];
+  int4 c0 = make_int4(0, 0, 0, 0), c1 = c0;
+  if (p.col_perm && tid < units) {
+    c0 = reinterpret_cast<const int4*>(p.col_perm)[2 * tid];
+    c1 = reinterpret_cast<const int4*>(p.col_perm)[2 * tid + 1];
+  }
+
+  uint32_t wq[U][4];
+  _Float16 sv[U], zv[U];
+  int32_t dsc[U];
+  auto issue = [&](int base) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int idx = base + u;
+      dsc[u] = 0;
+      if (idx < my_cnt) {
+        const int32_t d = __builtin_amdgcn_readlane(desc_v, idx);
+        dsc[u] = d;
+        const int tc = wave + NW * idx;
+        const int64_t slot = d >> 2;
+        switch (d & 3) {
+          case 0: load_slab_words<2>(p.s2 + slot * 4096, sigma, lane, wq[u]); break;
+          case 1: load_slab_words<3>(p.s3 + slot * 6144, sigma, lane, wq[u]); break;
+          default: load_slab_words<4>(p.s4 + slot * 8192, sigma, lane, wq[u]); break;
+        }
+        sv[u] = p.scales[(int64_t)tc * p.N + n];
+        zv[u] = p.zeros[(int64_t)tc * p.N + n];
+      }
+    }
+  };
+  issue(0);  // the first slabs are in flight while the activations are staged
+
+  __syncthreads();
+  if (p.col_perm) {
+    for (int i = tid; i < units; i += NT) {
+      if (i != tid) {
+        c0 = reinterpret_cast<const int4*>(p.col_perm)[2 * i];
+        c1 = reinterpret_cast<const int4*>(p.col_perm)[2 * i + 1];
+      }
+      union {
+        _Float16 h[8];
+        uint4 u;
+      } v;
+      v.h[0] = Xraw[c0.x];
+      v.h[1] = Xraw[c0.y];
+      v.h[2] = Xraw[c0.z];
+      v.h[3] = Xraw[c0.w];
+      v.h[4] = Xraw[c1.x];
+      v.h[5] = Xraw[c1.y];
+      v.h[6] = Xraw[c1.z];
+      v.h[7] = Xraw[c1.w];
+      reinterpret_cast<uint4*>(Xs)[i] = v.u;
+    }
+    __syncthreads();
+  }
+  for (int tc = tid; tc < p.ntc; tc += NT) {
+    float s = 0.f;
+    for (int i = 0; i < 16; ++i) {
+      const half8 v = *reinterpret_cast<const half8*>(Xs + tc * kTile + 8 * i);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += (float)v[e];
+    }
+    Sx[tc] = s;
+  }
+  __syncthreads();
+
+  float acc = 0.f;
+  half8 a[4];
+#pragma unroll
+  for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+  for (int base = 0; base < my_cnt; base += U) {
+    if (base > 0) issue(base);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int idx = base + u;
+      if (idx < my_cnt) {
+        const int tc = wave + NW * idx;
+        if ((lane & 15) == 0) {  // only activation row 0 exists: lanes 0,16,32,48 feed it
+#pragma unroll
+          for (int kappa = 0; kappa < 4; ++kappa)
+            a[kappa] = *reinterpret_cast<const half8*>(Xs + tc * kTile + 32 * kappa + 8 * (lane / 16));
+        }
+        floatx4 t;
+        switch (dsc[u] & 3) {
+          case 0: t = slab_dot<2>(wq[u], a); break;
+          case 1: t = slab_dot<3>(wq[u], a); break;
+          default: t = slab_dot<4>(wq[u], a); break;
+        }
+        acc += (float)sv[u] * t[0] + (float)zv[u] * Sx[tc];
+      }
+    }
+  }
+
+  if (lane < 16) red[wave * 16 + lane] = acc;
+  __syncthreads();
+  if (tid < 16) {
+    float s = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) s += red[w * 16 + tid];
+    const int64_t row = (int64_t)tr * kTile + 8 * tid + sigma;
+    const int64_t col = p.row_perm ? p.row_perm[row] : row;
+    p.Y[col] = (_Float16)s;
+  }
+}
+
+// ============================================================================================
+// skinny GEMM, 2 <= M <= 16
+// ============================================================================================
+struct SkinnyParams {
   const _Float16* X;
   const int32_t* col_perm;
   const uint8_t* s2;
@@ -40,66 +217,32 @@ struct DecodeParams {
   int32_t M, N, K, ntr, ntc, tiles_per_chunk, nchunk;
 };
 
-__host__ __device__ constexpr float pow2f(int e) {
-  float v = 1.0f;
-  for (int i = 0; i < e; ++i) v *= 2.0f;
-  for (int i = 0; i < -e; ++i) v *= 0.5f;
-  return v;
-}
-
-// Activation pre-scale for k-step kappa: slot v gets 2^(h - p(kappa, v/2)).
-template <int B>
-__device__ __forceinline__ half8 prescale(int kappa) {
-  half8 f;
-#pragma unroll
-  for (int v = 0; v < 8; ++v) f[v] = (_Float16)pow2f(prescale_exp<B>() - field_pos<B>(kappa, v / 2));
-  return f;
-}
-
 template <int B>
 __device__ __forceinline__ void issue_tile_loads(const uint8_t* tile, int lane, uint32_t (&w)[32]) {
-  const u32x4* src = reinterpret_cast<const u32x4*>(tile) + lane;
 #pragma unroll
-  for (int c = 0; c < 2 * B; ++c) {
-    const u32x4 v = __builtin_nontemporal_load(src + c * 64);
-    w[4 * c + 0] = v[0];
-    w[4 * c + 1] = v[1];
-    w[4 * c + 2] = v[2];
-    w[4 * c + 3] = v[3];
-  }
+  for (int sigma = 0; sigma < 8; ++sigma) load_slab_words<B>(tile, sigma, lane, &w[sigma * B]);
 }
 
-template <int B, int MR>
+template <int B>
 __device__ __forceinline__ void contract_tile(const uint32_t (&w)[32], const half8 (&a)[4], const floatx4& sx,
-                                              const u32x4& sraw, const u32x4& zraw, float (&acc)[8][MR]) {
-  half8 ap[4];
-#pragma unroll
-  for (int kappa = 0; kappa < 4; ++kappa) ap[kappa] = a[kappa] * prescale<B>(kappa);
+                                              const u32x4& sraw, const u32x4& zraw, float (&acc)[8][4]) {
   union {
     u32x4 u;
     half8 h;
   } sc, zr;
   sc.u = sraw;
   zr.u = zraw;
-  constexpr float kFix = pow2f(24 - prescale_exp<B>());
 #pragma unroll
   for (int sigma = 0; sigma < 8; ++sigma) {
-    uint32_t op[4][4];
-    unpack_slab<B>(&w[sigma * B], op);
-    floatx4 c = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kappa = 0; kappa < 4; ++kappa)
-      c = __builtin_amdgcn_mfma_f32_16x16x32_f16(ap[kappa], as_half8(op[kappa][0], op[kappa][1], op[kappa][2], op[kappa][3]),
-                                                 c, 0, 0, 0);
-    const float s = (float)sc.h[sigma] * kFix;
+    const floatx4 t = slab_dot<B>(&w[sigma * B], a);
+    const float s = (float)sc.h[sigma];
     const float z = (float)zr.h[sigma];
 #pragma unroll
-    for (int r = 0; r < MR; ++r) acc[sigma][r] += s * c[r] + z * sx[r];
+    for (int r = 0; r < 4; ++r) acc[sigma][r] += s * t[r] + z * sx[r];
   }
 }
 
-template <int MR>
-__global__ __launch_bounds__(256) void decode_kernel(const DecodeParams p) {
+__global__ __launch_bounds__(256) void skinny_kernel(const SkinnyParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   _Float16* Xs = reinterpret_cast<_Float16*>(lds_raw);  // [tile*16 + kblock][M][8]
 
@@ -114,24 +257,25 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecodeParams p) {
   const int ntile = min(p.tiles_per_chunk, p.ntc - tc0);
   const int M = p.M;
 
-  // ---- first tile: descriptor, packed words, scales and zeros are requested before anything else
+  // first tile: descriptor, packed words, scales and zeros are requested before anything else
   uint32_t w[32];
   u32x4 sraw = {0, 0, 0, 0}, zraw = {0, 0, 0, 0};
   int32_t desc = 0;
   const int64_t sz_lane_off = (int64_t)(active ? tr : 0) * kTile + 8 * (lane % 16);
-  if (active) {
-    desc = __builtin_amdgcn_readfirstlane(p.tile_desc[(int64_t)tr * p.ntc + tc0]);
+  auto issue = [&](int t) {
+    desc = __builtin_amdgcn_readfirstlane(p.tile_desc[(int64_t)tr * p.ntc + tc0 + t]);
     const int64_t slot = desc >> 2;
     switch (desc & 3) {
       case 0: issue_tile_loads<2>(p.s2 + slot * 4096, lane, w); break;
       case 1: issue_tile_loads<3>(p.s3 + slot * 6144, lane, w); break;
       default: issue_tile_loads<4>(p.s4 + slot * 8192, lane, w); break;
     }
-    sraw = *reinterpret_cast<const u32x4*>(p.scales + (int64_t)tc0 * p.N + sz_lane_off);
-    zraw = *reinterpret_cast<const u32x4*>(p.zeros + (int64_t)tc0 * p.N + sz_lane_off);
-  }
+    sraw = *reinterpret_cast<const u32x4*>(p.scales + (int64_t)(tc0 + t) * p.N + sz_lane_off);
+    zraw = *reinterpret_cast<const u32x4*>(p.zeros + (int64_t)(tc0 + t) * p.N + sz_lane_off);
+  };
+  if (active) issue(0);
 
-  // ---- gather the activation slice of this K chunk into LDS (column permutation fused here)
+  // gather the activation slice of this K chunk into LDS (column permutation fused here)
   {
     const int kspan = ntile * kTile;
     const int total = kspan * M;
@@ -146,11 +290,11 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecodeParams p) {
   __syncthreads();
   if (!active) return;
 
-  float acc[8][MR];
+  float acc[8][4];
 #pragma unroll
   for (int s = 0; s < 8; ++s)
 #pragma unroll
-    for (int r = 0; r < MR; ++r) acc[s][r] = 0.f;
+    for (int r = 0; r < 4; ++r) acc[s][r] = 0.f;
 
   const int mrow = lane % 16;  // activation row this lane feeds to the MFMA A operand
   half8 ones;
@@ -158,18 +302,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecodeParams p) {
   for (int v = 0; v < 8; ++v) ones[v] = (_Float16)1.0f;
 
   for (int t = 0; t < ntile; ++t) {
-    if (t > 0) {
-      desc = __builtin_amdgcn_readfirstlane(p.tile_desc[(int64_t)tr * p.ntc + tc0 + t]);
-      const int64_t slot = desc >> 2;
-      switch (desc & 3) {
-        case 0: issue_tile_loads<2>(p.s2 + slot * 4096, lane, w); break;
-        case 1: issue_tile_loads<3>(p.s3 + slot * 6144, lane, w); break;
-        default: issue_tile_loads<4>(p.s4 + slot * 8192, lane, w); break;
-      }
-      sraw = *reinterpret_cast<const u32x4*>(p.scales + (int64_t)(tc0 + t) * p.N + sz_lane_off);
-      zraw = *reinterpret_cast<const u32x4*>(p.zeros + (int64_t)(tc0 + t) * p.N + sz_lane_off);
-    }
-    // activation operand of the 4 k-steps of this tile and the per-row sums of x over the group
+    if (t > 0) issue(t);
     half8 a[4];
     floatx4 sx = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -180,19 +313,19 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecodeParams p) {
       sx = __builtin_amdgcn_mfma_f32_16x16x32_f16(v, ones, sx, 0, 0, 0);
     }
     switch (desc & 3) {
-      case 0: contract_tile<2, MR>(w, a, sx, sraw, zraw, acc); break;
-      case 1: contract_tile<3, MR>(w, a, sx, sraw, zraw, acc); break;
-      default: contract_tile<4, MR>(w, a, sx, sraw, zraw, acc); break;
+      case 0: contract_tile<2>(w, a, sx, sraw, zraw, acc); break;
+      case 1: contract_tile<3>(w, a, sx, sraw, zraw, acc); break;
+      default: contract_tile<4>(w, a, sx, sraw, zraw, acc); break;
     }
   }
 
-  // ---- K reduction and epilogue.  Lane (j = lane%16, g = lane/16) holds, for r < MR, the outputs
-  // of activation row m = 4g + r and weight rows n = 128*tr + 8j + sigma.
+  // Lane (j = lane%16, g = lane/16) holds, for r < 4, the outputs of activation row m = 4g + r and
+  // weight rows n = 128*tr + 8j + sigma.
   const int j = lane % 16, g = lane / 16;
   const int64_t n0 = (int64_t)tr * kTile + 8 * j;
   if (p.nchunk == 1) {
 #pragma unroll
-    for (int r = 0; r < MR; ++r) {
+    for (int r = 0; r < 4; ++r) {
       const int m = 4 * g + r;
       if (m < M) {
 #pragma unroll
@@ -206,20 +339,20 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecodeParams p) {
     return;
   }
 #pragma unroll
-  for (int r = 0; r < MR; ++r) {
+  for (int r = 0; r < 4; ++r) {
     const int m = 4 * g + r;
     if (m < M) {
       float* dst = p.partial + ((int64_t)chunk * M + m) * p.N + n0;
-      reinterpret_cast<float4*>(dst)[0] = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
-      reinterpret_cast<float4*>(dst)[1] = make_float4(acc[4][r], acc[5][r], acc[6][r], acc[7][r]);
+#pragma unroll
+      for (int sigma = 0; sigma < 8; ++sigma)
+        __hip_atomic_store(dst + sigma, acc[sigma][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
-  __threadfence();  // release this wavefront's partial before announcing it
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the partial has left before it is announced
   int old = 0;
-  if (lane == 0) old = atomicAdd(p.counters + tr, 1);
+  if (lane == 0) old = __hip_atomic_fetch_add(p.counters + tr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   old = __builtin_amdgcn_readfirstlane(old);
   if (old != p.nchunk - 1) return;
-  __threadfence();  // acquire the other wavefronts' partials
   const int64_t n = (int64_t)tr * kTile + 2 * lane;
   int64_t c0 = n, c1 = n + 1;
   if (p.row_perm) {
@@ -230,23 +363,36 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecodeParams p) {
     float s0 = 0.f, s1 = 0.f;
     const float* src = p.partial + (int64_t)m * p.N + n;
     for (int c = 0; c < p.nchunk; ++c) {
-      const float2 v = *reinterpret_cast<const float2*>(src + (int64_t)c * M * p.N);
-      s0 += v.x;
-      s1 += v.y;
+      s0 += __hip_atomic_load(src + (int64_t)c * M * p.N, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s1 += __hip_atomic_load(src + (int64_t)c * M * p.N + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     p.Y[(int64_t)m * p.N + c0] = (_Float16)s0;
     p.Y[(int64_t)m * p.N + c1] = (_Float16)s1;
   }
-  if (lane == 0) p.counters[tr] = 0;  // ready for the next call
+  if (lane == 0) __hip_atomic_store(p.counters + tr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// ============================================================================================
+// host side
+// ============================================================================================
 DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
   DecodePlan d;
   const int32_t ntr = N / kTile, ntc = K / kTile;
+  const int64_t gemv_base = ((int64_t)K * 2 + (int64_t)ntc * 4 + kGemvWaves * 64 + 15) / 16 * 16;
+  d.gemv = M == 1 && ntc <= 64 * kGemvWaves && gemv_base + (int64_t)K * 2 <= 160 * 1024;
+  if (d.gemv) {  // GEMV: whole K per workgroup, nothing in the workspace
+    d.tiles_per_chunk = ntc;
+    d.nchunk = 1;
+    d.row_groups = 8 * ntr;
+    d.counter_bytes = 0;
+    d.partial_bytes = 0;
+    d.lds_bytes = (int32_t)(gemv_base + (int64_t)K * 2);
+    return d;
+  }
   // Few, long chunks keep the partial-sum traffic (128*M fp32 per wavefront, written and read
   // once) small next to the tile bytes; many chunks keep all 256 CUs busy.  Start from a chunk
   // length that grows with M and shorten it until about 2048 wavefronts exist.
-  int32_t tpc = M <= 1 ? 4 : M <= 4 ? 4 : 8;
+  int32_t tpc = M <= 4 ? 4 : 8;
   while (tpc > 1 && (int64_t)ntr * ((ntc + tpc - 1) / tpc) < 2048) tpc /= 2;
   while (tpc * M > 128) tpc /= 2;  // LDS: tpc * M * 256 bytes <= 32 KiB
   if (tpc < 1) tpc = 1;
@@ -259,10 +405,49 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
   return d;
 }
 
+static int after_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    note_hip_error(what, hipGetErrorString(e));
+    return SFMP_ERR_HIP;
+  }
+  return SFMP_OK;
+}
+
 int launch_decode(const GemmArgs& a, void* stream) {
   const sfmp_layout_t* L = a.L;
   const DecodePlan d = make_decode_plan(L->N, L->K, a.M);
-  DecodeParams p;
+  if (d.gemv) {
+    GemvParams p;
+    p.X = (const _Float16*)a.X;
+    p.col_perm = a.col_perm;
+    p.s2 = a.s2;
+    p.s3 = a.s3;
+    p.s4 = a.s4;
+    p.tile_desc = a.index + 3;
+    p.scales = (const _Float16*)a.scales;
+    p.zeros = (const _Float16*)a.zeros;
+    p.row_perm = a.row_perm;
+    p.Y = (_Float16*)a.Y;
+    p.N = L->N;
+    p.K = L->K;
+    p.ntr = L->N / kTile;
+    p.ntc = L->K / kTile;
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e != hipSuccess) {
+        note_hip_error("hipFuncSetAttribute(gemv)", hipGetErrorString(e));
+        return SFMP_ERR_HIP;
+      }
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(gemv_kernel<kGemvWaves>, dim3((unsigned)d.row_groups), dim3(kGemvWaves * 64),
+                       (size_t)d.lds_bytes, (hipStream_t)stream, p);
+    return after_launch("sfmp_gemm gemv launch");
+  }
+  SkinnyParams p;
   p.X = (const _Float16*)a.X;
   p.col_perm = a.col_perm;
   p.s2 = a.s2;
@@ -282,17 +467,9 @@ int launch_decode(const GemmArgs& a, void* stream) {
   p.ntc = L->K / kTile;
   p.tiles_per_chunk = d.tiles_per_chunk;
   p.nchunk = d.nchunk;
-  const dim3 grid((unsigned)(d.row_groups * d.nchunk));
-  if (a.M == 1)
-    hipLaunchKernelGGL(decode_kernel<1>, grid, dim3(256), (size_t)d.lds_bytes, (hipStream_t)stream, p);
-  else
-    hipLaunchKernelGGL(decode_kernel<4>, grid, dim3(256), (size_t)d.lds_bytes, (hipStream_t)stream, p);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) {
-    note_hip_error("sfmp_gemm decode launch", hipGetErrorString(e));
-    return SFMP_ERR_HIP;
-  }
-  return SFMP_OK;
+  hipLaunchKernelGGL(skinny_kernel, dim3((unsigned)(d.row_groups * d.nchunk)), dim3(256), (size_t)d.lds_bytes,
+                     (hipStream_t)stream, p);
+  return after_launch("sfmp_gemm skinny launch");
 }
 
 }  // namespace sfmp

@@ -34,12 +34,18 @@ int check_layout(const sfmp_layout_t* L) {
   return SFMP_OK;
 }
 
-// Bit position (inside the tile's byte string) of bit 0 of the code at (r, c) for widths 2 and 4,
-// and of each bit separately for width 3 (its 16th pair is spread over three words).
-static inline uint32_t word_byte_offset(int b, int lane, int slab, int word) {
-  const int d = slab * b + word;
-  return (uint32_t)(d / 4) * 1024u + (uint32_t)lane * 16u + (uint32_t)(d % 4) * 4u;
+// Word index (32-bit, inside the tile) of word `word` of lane `lane` of slab `slab`.
+static inline uint32_t word_index(int b, int lane, int slab, int word) {
+  return (uint32_t)(slab * 64 * b + lane * b + word);
 }
+
+// (kappa, reg) -> (word, field) of the 3-bit format; field -1 marks the spare-bit code.
+static const int8_t kField3[4][4][2] = {
+    {{0, 0}, {1, 0}, {2, 0}, {0, 3}},
+    {{0, 1}, {1, 1}, {2, 1}, {0, 4}},
+    {{0, 2}, {1, 2}, {2, 2}, {0, -1}},
+    {{1, 3}, {2, 3}, {1, 4}, {2, 4}},
+};
 
 static void pack_one_tile(const uint8_t* codes, int64_t ld, int b, uint8_t* out) {
   uint32_t* words = reinterpret_cast<uint32_t*>(out);  // streams are written on a little-endian host
@@ -50,18 +56,17 @@ static void pack_one_tile(const uint8_t* codes, int64_t ld, int b, uint8_t* out)
     for (int c = 0; c < SFMP_TILE; ++c) {
       const uint32_t q = row[c];
       const int lane = 16 * ((c % 32) / 8) + r / 8;
-      const int kappa = c / 32, v = c % 8, pair = v / 2, half = v % 2;
+      const int kappa = c / 32, v = c % 8, reg = v / 2, half = v % 2;
       if (b == 4) {
-        words[word_byte_offset(4, lane, slab, kappa) / 4] |= q << (16 * half + 4 * pair);
+        words[word_index(4, lane, slab, reg)] |= q << (16 * half + 4 * kappa);
       } else if (b == 2) {
-        words[word_byte_offset(2, lane, slab, kappa / 2) / 4] |= q << (16 * half + 2 * (4 * (kappa % 2) + pair));
+        words[word_index(2, lane, slab, reg % 2)] |= q << (16 * half + 8 * (reg / 2) + 2 * kappa);
       } else {
-        const int pi = 4 * kappa + pair;
-        if (pi < 15) {
-          words[word_byte_offset(3, lane, slab, pi / 5) / 4] |= q << (16 * half + 3 * (pi % 5));
+        const int8_t* e = kField3[kappa][reg];
+        if (e[1] >= 0) {
+          words[word_index(3, lane, slab, e[0])] |= q << (16 * half + 3 * e[1]);
         } else {
-          for (int t = 0; t < 3; ++t)
-            words[word_byte_offset(3, lane, slab, t) / 4] |= ((q >> t) & 1u) << (16 * half + 15);
+          for (int t = 0; t < 3; ++t) words[word_index(3, lane, slab, t)] |= ((q >> t) & 1u) << (16 * half + 15);
         }
       }
     }

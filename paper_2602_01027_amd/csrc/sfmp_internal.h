@@ -13,6 +13,7 @@ void note_hip_error(const char* what, const char* text);
 // How the decode kernel (M <= 16) splits a matrix: a wavefront walks `tiles_per_chunk`
 // consecutive tiles of one tile row; `nchunk` chunks cover the K direction.
 struct DecodePlan {
+  bool gemv;  // M == 1 and K small enough for the whole activation vector to sit in LDS
   int32_t tiles_per_chunk;
   int32_t nchunk;
   int32_t row_groups;  // workgroups along N (4 tile rows each)

@@ -8,7 +8,7 @@
 //
 // Step 2: workgroup = 128 (M) x 128 (N, one tile row) output block, 4 wavefronts in a 2x2
 // arrangement of 64x64 sub-blocks, K walked one 128x128 weight tile (= one quantisation
-// group) at a time.  Per step the packed tile (4-8 KiB) is loaded with 16-byte lane loads,
+// group) at a time.  Per step the packed tile (4-8 KiB) is loaded slab by slab (4*b bytes per lane),
 // unpacked with the shared routines, dequantised exactly to fp16 (w = fp16(s*q + z), one
 // rounding, Appendix B Eq. 11) and stored to LDS; the activation block is copied to LDS; both
 // are then read as 16x16x32 MFMA operands (fp32 accumulate).  Rows of both LDS blocks are
@@ -73,36 +73,6 @@ constexpr int kBM = 128;
 
 __device__ __forceinline__ int swz(int row, int unit) { return unit ^ ((row & 15) ^ ((row >> 4) & 7)); }
 
-// Words of slabs 2*wave and 2*wave+1 of one lane: words [2*wave*B, 2*wave*B + 2B) of the lane,
-// fetched as whole 16-byte chunks (plus one 8-byte half chunk for the 3-bit format).
-template <int B>
-__device__ __forceinline__ void load_two_slabs(const uint8_t* tile, int lane, int wave, uint32_t (&w)[8]) {
-  const uint8_t* base = tile + lane * 16;
-  if (B == 4) {
-    const u32x4 v0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (2 * wave) * 1024));
-    const u32x4 v1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (2 * wave + 1) * 1024));
-    w[0] = v0[0]; w[1] = v0[1]; w[2] = v0[2]; w[3] = v0[3];
-    w[4] = v1[0]; w[5] = v1[1]; w[6] = v1[2]; w[7] = v1[3];
-  } else if (B == 2) {
-    const u32x4 v0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + wave * 1024));
-    w[0] = v0[0]; w[1] = v0[1]; w[2] = v0[2]; w[3] = v0[3];
-  } else {
-    // words 6*wave .. 6*wave+5: wave even -> chunk 3*(wave/2) whole, then the low half of the next;
-    // wave odd -> the high half of chunk 3*(wave/2)+1, then chunk 3*(wave/2)+2 whole.
-    const int c = 3 * (wave / 2);
-    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-    if ((wave & 1) == 0) {
-      const u32x4 v0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + c * 1024));
-      const u32x2 v1 = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + (c + 1) * 1024));
-      w[0] = v0[0]; w[1] = v0[1]; w[2] = v0[2]; w[3] = v0[3]; w[4] = v1[0]; w[5] = v1[1];
-    } else {
-      const u32x2 v0 = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + (c + 1) * 1024 + 8));
-      const u32x4 v1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (c + 2) * 1024));
-      w[0] = v0[0]; w[1] = v0[1]; w[2] = v1[0]; w[3] = v1[1]; w[4] = v1[2]; w[5] = v1[3];
-    }
-  }
-}
-
 // Exact fp16 dequantisation of one slab and store to the LDS weight block.
 template <int B>
 __device__ __forceinline__ void dequant_slab_to_lds(const uint32_t* w, _Float16 s, _Float16 z, _Float16* Ws, int row,
@@ -112,23 +82,23 @@ __device__ __forceinline__ void dequant_slab_to_lds(const uint32_t* w, _Float16 
   const half2_ s2 = {s, s}, z2 = {z, z};
 #pragma unroll
   for (int kappa = 0; kappa < 4; ++kappa) {
+    const int p = step_pos<B>(kappa);
+    const _Float16 inv = (_Float16)(1.0f / (float)(1 << p));
+    const _Float16 off = (_Float16)(-1024.0f / (float)(1 << p));
+    const half2_ inv2 = {inv, inv}, off2 = {off, off};
     union {
       half2_ h[4];
       uint4 u;
     } out;
 #pragma unroll
-    for (int pair = 0; pair < 4; ++pair) {
-      const int p = field_pos<B>(kappa, pair);
+    for (int reg = 0; reg < 4; ++reg) {
       union {
         uint32_t u;
         half2_ h;
       } t;
-      t.u = op[kappa][pair] | 0x64006400u;  // 1024 + q*2^p in both halves
-      const _Float16 inv = (_Float16)(1.0f / (float)(1 << p));
-      const _Float16 off = (_Float16)(-1024.0f / (float)(1 << p));
-      const half2_ inv2 = {inv, inv}, off2 = {off, off};
+      t.u = op[kappa][reg] | 0x64006400u;                           // 1024 + q*2^p in both halves
       const half2_ q = __builtin_elementwise_fma(t.h, inv2, off2);  // exact: q in [0, 15]
-      out.h[pair] = __builtin_elementwise_fma(q, s2, z2);           // one rounding
+      out.h[reg] = __builtin_elementwise_fma(q, s2, z2);            // one rounding
     }
     const int unit = 4 * kappa + kb;
     *reinterpret_cast<uint4*>(Ws + row * 128 + swz(row, unit) * 8) = out.u;
@@ -178,10 +148,19 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p) {
     }
     desc = __builtin_amdgcn_readfirstlane(p.tile_desc[(int64_t)tr * p.ntc + tc]);
     const int64_t slot = desc >> 2;
-    switch (desc & 3) {
-      case 0: load_two_slabs<2>(p.s2 + slot * 4096, lane, wave, wreg); break;
-      case 1: load_two_slabs<3>(p.s3 + slot * 6144, lane, wave, wreg); break;
-      default: load_two_slabs<4>(p.s4 + slot * 8192, lane, wave, wreg); break;
+    switch (desc & 3) {  // slabs 2*wave and 2*wave+1 of this lane
+      case 0:
+        load_slab_words<2>(p.s2 + slot * 4096, 2 * wave, lane, wreg);
+        load_slab_words<2>(p.s2 + slot * 4096, 2 * wave + 1, lane, wreg + 2);
+        break;
+      case 1:
+        load_slab_words<3>(p.s3 + slot * 6144, 2 * wave, lane, wreg);
+        load_slab_words<3>(p.s3 + slot * 6144, 2 * wave + 1, lane, wreg + 3);
+        break;
+      default:
+        load_slab_words<4>(p.s4 + slot * 8192, 2 * wave, lane, wreg);
+        load_slab_words<4>(p.s4 + slot * 8192, 2 * wave + 1, lane, wreg + 4);
+        break;
     }
     const int64_t off = (int64_t)tc * p.N + (int64_t)tr * 128 + nloc;
     szreg[0] = *reinterpret_cast<const uint32_t*>(p.scales + off);

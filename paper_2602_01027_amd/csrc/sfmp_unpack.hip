@@ -7,25 +7,25 @@ namespace sfmp {
 
 template <int B>
 __device__ __forceinline__ void unpack_tile_to_codes(const uint8_t* tile, int lane, uint8_t* dst, int64_t ld) {
-  uint32_t w[8 * B];
-  load_tile_words<B>(tile, lane, w);
   const int i = lane % 16, kb = lane / 16;
 #pragma unroll
   for (int sigma = 0; sigma < 8; ++sigma) {
+    uint32_t w[B];
+    load_slab_words<B>(tile, sigma, lane, w);
     uint32_t op[4][4];
-    unpack_slab<B>(&w[sigma * B], op);
+    unpack_slab<B>(w, op);
     uint8_t* row = dst + (int64_t)(8 * i + sigma) * ld + 8 * kb;
 #pragma unroll
     for (int kappa = 0; kappa < 4; ++kappa) {
+      const int p = step_pos<B>(kappa);
       uint32_t lo = 0, hi = 0;  // 8 codes of this lane and k-step as two little-endian words
 #pragma unroll
-      for (int pair = 0; pair < 4; ++pair) {
-        const int p = field_pos<B>(kappa, pair);
-        const uint32_t f = op[kappa][pair];
+      for (int reg = 0; reg < 4; ++reg) {
+        const uint32_t f = op[kappa][reg];
         const uint32_t q0 = (f >> p) & ((1u << B) - 1u);
         const uint32_t q1 = (f >> (16 + p)) & ((1u << B) - 1u);
         const uint32_t two = q0 | (q1 << 8);
-        if (pair < 2) lo |= two << (16 * pair); else hi |= two << (16 * (pair - 2));
+        if (reg < 2) lo |= two << (16 * reg); else hi |= two << (16 * (reg - 2));
       }
       uint2 v;
       v.x = lo;

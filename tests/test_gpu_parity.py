@@ -124,12 +124,12 @@ def test_gemm_argument_errors(torch_cuda):
     import paper_2602_01027_amd as S
     from gpu_util import device_problem
     torch = torch_cuda
-    p = W.make_problem("err", 256, 256, 1, 3)
+    p = W.make_problem("err", 1024, 256, 4, 3)
     dp, cp, rp = device_problem(p)
     X = torch.from_numpy(p.X).to("cuda:0")
-    Y = torch.empty((1, p.N), dtype=torch.float16, device="cuda:0")
+    Y = torch.empty((4, p.N), dtype=torch.float16, device="cuda:0")
     small = torch.zeros(256, dtype=torch.uint8, device="cuda:0")
-    need = S.sfmp_gemm_workspace(dp.layout, 1)
+    need = S.sfmp_gemm_workspace(dp.layout, 4)
     assert need > 256
     with pytest.raises(S.SfmpError) as ei:
         S.sfmp_gemm(X, cp, dp.layout, dp.s2, dp.s3, dp.s4, dp.index, dp.scales, dp.zeros, dp.bitmap, rp, Y, small)

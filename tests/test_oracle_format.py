@@ -36,16 +36,17 @@ def test_single_code_sets_exactly_its_bits(b, golden):
         assert words[bit_index // 32] == np.uint32(1) << np.uint32(bit_index % 32)
 
 
-def test_lane_words_are_16_byte_chunks():
-    # every lane's 4 consecutive words d = 4i..4i+3 are contiguous 16 bytes at i*1024 + lane*16
+def test_slab_major_layout():
+    # slab sigma = rows {8i + sigma} occupies bytes [sigma*256b, (sigma+1)*256b); inside it lane l owns the
+    # 4b contiguous bytes at l*4b, so one load of 4b bytes per lane reads a contiguous 256b-byte segment
     for b in (2, 3, 4):
         pos = O.tile_bit_positions(b)
         byte = pos // 8
-        lane_of = (16 * ((np.arange(128)[None, :] % 32) // 8) + np.arange(128)[:, None] // 8)[:, :, None]
-        chunk = byte // 1024
-        within = byte % 1024
-        assert np.array_equal(within // 16, np.broadcast_to(lane_of, byte.shape))
-        assert chunk.max() == 2 * b - 1
+        r = np.arange(128)[:, None, None]
+        c = np.arange(128)[None, :, None]
+        lane_of = 16 * ((c % 32) // 8) + r // 8
+        assert np.array_equal(byte // (256 * b), np.broadcast_to(r % 8, byte.shape))
+        assert np.array_equal((byte % (256 * b)) // (4 * b), np.broadcast_to(lane_of, byte.shape))
 
 
 @settings(max_examples=25, deadline=None)
