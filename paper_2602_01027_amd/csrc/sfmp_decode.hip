@@ -60,139 +60,216 @@ struct GemvParams {
   const _Float16* zeros;
   const int32_t* row_perm;
   _Float16* Y;
-  int32_t N, K, ntr, ntc;
+  int32_t N, K, ntr, ntc, nslab;
+  int32_t slots;       // ring slots per wavefront
+  int32_t max_slabs;   // slabs per workgroup (upper bound), sizes the reduction buffer
+#ifdef SFMP_EXPERIMENT
+  int32_t dbg;
+#endif
 };
+#ifdef SFMP_EXPERIMENT
+#define SFMP_DBG(p, bit) (((p).dbg & (bit)) != 0)
+int g_sfmp_debug = 0;
+extern "C" void sfmp_debug_set(int v) { g_sfmp_debug = v; }
+#else
+#define SFMP_DBG(p, bit) false
+#endif
 
-constexpr int kGemvWaves = 8;
-constexpr int kGemvBatch = 4;
+constexpr int kGemvWaves = 16;       // wavefronts per workgroup; one workgroup per CU
+constexpr int kGemvMaxGrid = 256;    // persistent grid: at most one workgroup per CU
+constexpr int kGemvMaxSlots = 8;
+constexpr int kSlotBytes = 1024 + 64 + 64;  // slab bytes (<= 1 KiB) + 16 scale dwords + 16 zero dwords
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// sum of the 8 halves of a 16-byte unit, then over the 16 lanes (= 128 columns = one group)
+__device__ __forceinline__ float unit_group_sum(const half8& v) {
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s += (float)v[e];
+  s += __shfl_xor(s, 8, 16);
+  s += __shfl_xor(s, 4, 16);
+  s += __shfl_xor(s, 2, 16);
+  s += __shfl_xor(s, 1, 16);
+  return s;
+}
+
+template <int B>
+__device__ __forceinline__ float gemv_item(const unsigned char* slot, int lane, const half8 (&a)[4]) {
+  uint32_t w[B];
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(slot + lane * (4 * B));
+#pragma unroll
+  for (int i = 0; i < B; ++i) w[i] = src[i];
+  return slab_dot<B>(w, a)[0];
+}
 
 template <int NW>
 __global__ __launch_bounds__(NW * 64) void gemv_kernel(const GemvParams p) {
   constexpr int NT = NW * 64;
-  constexpr int U = kGemvBatch;
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  _Float16* Xs = reinterpret_cast<_Float16*>(lds_raw);                       // [K] permuted activations
-  float* Sx = reinterpret_cast<float*>(lds_raw + (size_t)p.K * 2);           // [ntc] group sums of x
-  float* red = Sx + p.ntc;                                                   // [NW][16]
-  _Float16* Xraw = reinterpret_cast<_Float16*>(lds_raw + (((size_t)p.K * 2 + (size_t)p.ntc * 4 + NW * 64 + 15) & ~(size_t)15));
+  // LDS: Xs [K] fp16 | Sx [ntc] f32 | red [max_slabs][NW][16] f32 | rings [NW][slots][kSlotBytes]
+  // (the raw activation copy used while permuting aliases the rings: they are idle until then)
+  _Float16* Xs = reinterpret_cast<_Float16*>(lds_raw);
+  float* Sx = reinterpret_cast<float*>(lds_raw + (size_t)p.K * 2);
+  float* red = Sx + p.ntc;
+  unsigned char* rings =
+      lds_raw + (((size_t)p.K * 2 + (size_t)p.ntc * 4 + (size_t)p.max_slabs * NW * 64 + 15) & ~(size_t)15);
+  _Float16* Xraw = reinterpret_cast<_Float16*>(rings);
 
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
   const int wave = tid / kWave;
-  // 8*ntr slabs; block b runs on XCD b%8: give each XCD a contiguous range of ntr slabs
-  const int slab = (int)(blockIdx.x % 8) * p.ntr + (int)(blockIdx.x / 8);
-  const int tr = slab / 8, sigma = slab % 8;
-  const int64_t n = (int64_t)tr * kTile + 8 * (lane % 16) + sigma;  // weight row of this lane
+  const int G = gridDim.x;
+  // Virtual slab index v = blockIdx + G*j (G is a multiple of 8, block b runs on XCD b%8): XCD x gets
+  // the contiguous slab range [x*ntr, (x+1)*ntr), so the 8 slabs of a tile row run on one XCD.
+  const int nj = (p.nslab - (int)blockIdx.x + G - 1) / G;              // slabs of this workgroup
+  const int my_cnt = p.ntc > wave ? (p.ntc - wave + NW - 1) / NW : 0;  // tiles per slab of this wavefront
+  const int E = nj * my_cnt;                                           // items of this wavefront
+  const int slots = p.slots;
 
-  // descriptors of this wavefront's tiles tc = wave + NW*i: lane i keeps descriptor i
-  const int my_cnt = p.ntc > wave ? (p.ntc - wave + NW - 1) / NW : 0;
-  int32_t desc_v = 0;
-  if (lane < my_cnt) desc_v = p.tile_desc[(int64_t)tr * p.ntc + wave + NW * lane];
-
-  // raw activation copy (coalesced 16-byte loads) and the first permutation indices
-  const int units = p.K / 8;
-  _Float16* stage = p.col_perm ? Xraw : Xs;
-  for (int i = tid; i < units; i += NT)
-    reinterpret_cast<uint4*>(stage)[i] = reinterpret_cast<const uint4*>(p.X)[i];
-  int4 c0 = make_int4(0, 0, 0, 0), c1 = c0;
-  if (p.col_perm && tid < units) {
-    c0 = reinterpret_cast<const int4*>(p.col_perm)[2 * tid];
-    c1 = reinterpret_cast<const int4*>(p.col_perm)[2 * tid + 1];
-  }
-
-  uint32_t wq[U][4];
-  _Float16 sv[U], zv[U];
-  int32_t dsc[U];
-  auto issue = [&](int base) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int idx = base + u;
-      dsc[u] = 0;
-      if (idx < my_cnt) {
-        const int32_t d = __builtin_amdgcn_readlane(desc_v, idx);
-        dsc[u] = d;
-        const int tc = wave + NW * idx;
-        const int64_t slot = d >> 2;
-        switch (d & 3) {
-          case 0: load_slab_words<2>(p.s2 + slot * 4096, sigma, lane, wq[u]); break;
-          case 1: load_slab_words<3>(p.s3 + slot * 6144, sigma, lane, wq[u]); break;
-          default: load_slab_words<4>(p.s4 + slot * 8192, sigma, lane, wq[u]); break;
-        }
-        sv[u] = p.scales[(int64_t)tc * p.N + n];
-        zv[u] = p.zeros[(int64_t)tc * p.N + n];
-      }
+  // descriptor of item e = j*my_cnt + i: tile (tr(j), wave + NW*i).  Lane s of a batch loads its own.
+  auto item_desc = [&](int e) {
+    int32_t d = 0;
+    if (e < E) {
+      const int j = e / my_cnt, i = e - j * my_cnt;
+      const int v = (int)blockIdx.x + G * j;
+      const int slab = (v % 8) * p.ntr + v / 8;
+      d = p.tile_desc[(int64_t)(slab / 8) * p.ntc + wave + NW * i];
     }
+    return d;
   };
-  issue(0);  // the first slabs are in flight while the activations are staged
+  int32_t desc_cur = lane < slots ? item_desc(lane) : 0;
 
-  __syncthreads();
+  // ---- stage the activation vector once per workgroup: raw copy, then permute inside LDS
+  const int units = p.K / 8;
   if (p.col_perm) {
+    for (int i = tid; i < units; i += NT)
+      reinterpret_cast<uint4*>(Xraw)[i] = reinterpret_cast<const uint4*>(p.X)[i];
+    int4 c0 = make_int4(0, 0, 0, 0), c1 = c0;
+    if (tid < units) {
+      c0 = reinterpret_cast<const int4*>(p.col_perm)[2 * tid];
+      c1 = reinterpret_cast<const int4*>(p.col_perm)[2 * tid + 1];
+    }
+    __syncthreads();
     for (int i = tid; i < units; i += NT) {
       if (i != tid) {
         c0 = reinterpret_cast<const int4*>(p.col_perm)[2 * i];
         c1 = reinterpret_cast<const int4*>(p.col_perm)[2 * i + 1];
       }
+      half8 v;
+      v[0] = Xraw[c0.x];
+      v[1] = Xraw[c0.y];
+      v[2] = Xraw[c0.z];
+      v[3] = Xraw[c0.w];
+      v[4] = Xraw[c1.x];
+      v[5] = Xraw[c1.y];
+      v[6] = Xraw[c1.z];
+      v[7] = Xraw[c1.w];
+      *reinterpret_cast<half8*>(Xs + 8 * i) = v;
+      const float s = unit_group_sum(v);
+      if ((lane & 15) == 0) Sx[i / 16] = s;
+    }
+  } else {
+    for (int i = tid; i < units; i += NT) {
       union {
-        _Float16 h[8];
         uint4 u;
+        half8 h;
       } v;
-      v.h[0] = Xraw[c0.x];
-      v.h[1] = Xraw[c0.y];
-      v.h[2] = Xraw[c0.z];
-      v.h[3] = Xraw[c0.w];
-      v.h[4] = Xraw[c1.x];
-      v.h[5] = Xraw[c1.y];
-      v.h[6] = Xraw[c1.z];
-      v.h[7] = Xraw[c1.w];
-      reinterpret_cast<uint4*>(Xs)[i] = v.u;
+      v.u = reinterpret_cast<const uint4*>(p.X)[i];
+      *reinterpret_cast<half8*>(Xs + 8 * i) = v.h;
+      const float s = unit_group_sum(v.h);
+      if ((lane & 15) == 0) Sx[i / 16] = s;
     }
-    __syncthreads();
   }
-  for (int tc = tid; tc < p.ntc; tc += NT) {
-    float s = 0.f;
-    for (int i = 0; i < 16; ++i) {
-      const half8 v = *reinterpret_cast<const half8*>(Xs + tc * kTile + 8 * i);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) s += (float)v[e];
-    }
-    Sx[tc] = s;
-  }
-  __syncthreads();
+  __syncthreads();  // Xs and Sx are complete; the raw copy is dead and the rings may be filled
 
-  float acc = 0.f;
+  unsigned char* ring = rings + (size_t)wave * slots * kSlotBytes;
   half8 a[4];
 #pragma unroll
   for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = half8{0, 0, 0, 0, 0, 0, 0, 0};
-  for (int base = 0; base < my_cnt; base += U) {
-    if (base > 0) issue(base);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int idx = base + u;
-      if (idx < my_cnt) {
-        const int tc = wave + NW * idx;
-        if ((lane & 15) == 0) {  // only activation row 0 exists: lanes 0,16,32,48 feed it
-#pragma unroll
-          for (int kappa = 0; kappa < 4; ++kappa)
-            a[kappa] = *reinterpret_cast<const half8*>(Xs + tc * kTile + 32 * kappa + 8 * (lane / 16));
+  float acc = 0.f;
+  int j = 0, i = 0;  // slab index within this workgroup / tile index within the slab, of the next item
+  for (int e0 = 0; e0 < E; e0 += slots) {
+    const int nb = min(slots, E - e0);
+    // descriptors of the next batch are requested before this batch is waited for
+    const int32_t desc_next = lane < slots ? item_desc(e0 + slots + lane) : 0;
+    // ---- issue: one direct global->LDS copy of the slab and of its 16 scales / zeros per item
+    {
+      int jj = j, ii = i;
+      for (int s = 0; s < nb; ++s) {
+        const int32_t d = __builtin_amdgcn_readlane(desc_cur, s);
+        const int v = (int)blockIdx.x + G * jj;
+        const int slab = (v % 8) * p.ntr + v / 8;
+        const int tr = slab / 8, sigma = slab % 8;
+        const int tc = wave + NW * ii;
+        const int bm2 = d & 3;  // bit-width - 2
+        const uint8_t* base = bm2 == 0 ? p.s2 : bm2 == 1 ? p.s3 : p.s4;
+        const int64_t slab_bytes = 256 * (bm2 + 2);
+        const uint8_t* g = base + (int64_t)(d >> 2) * (8 * slab_bytes) + sigma * slab_bytes + lane * 16;
+        unsigned char* slot = ring + s * kSlotBytes;
+        if (lane * 16 < slab_bytes) __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)slot, 16, 0, 0);
+        if (lane < 16) {
+          // the aligned dword that contains the fp16 of row n = 128*tr + 8*lane + sigma
+          const int64_t off = ((int64_t)tc * p.N + (int64_t)tr * kTile + 8 * lane + (sigma & ~1)) * 2;
+          __builtin_amdgcn_global_load_lds((gptr_t)((const char*)p.scales + off), (lptr_t)(slot + 1024), 4, 0, 0);
+          __builtin_amdgcn_global_load_lds((gptr_t)((const char*)p.zeros + off), (lptr_t)(slot + 1088), 4, 0, 0);
         }
-        floatx4 t;
-        switch (dsc[u] & 3) {
-          case 0: t = slab_dot<2>(wq[u], a); break;
-          case 1: t = slab_dot<3>(wq[u], a); break;
-          default: t = slab_dot<4>(wq[u], a); break;
+        if (++ii == my_cnt) {
+          ii = 0;
+          ++jj;
         }
-        acc += (float)sv[u] * t[0] + (float)zv[u] * Sx[tc];
       }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // ---- consume
+    for (int s = 0; s < nb; ++s) {
+      const int32_t d = __builtin_amdgcn_readlane(desc_cur, s);
+      const int v = (int)blockIdx.x + G * j;
+      const int slab = (v % 8) * p.ntr + v / 8;
+      const int sigma = slab % 8;
+      const int tc = wave + NW * i;
+      const unsigned char* slot = ring + s * kSlotBytes;
+      if ((lane & 15) == 0) {  // only activation row 0 exists: lanes 0,16,32,48 feed it
+#pragma unroll
+        for (int kappa = 0; kappa < 4; ++kappa)
+          a[kappa] = *reinterpret_cast<const half8*>(Xs + tc * kTile + 32 * kappa + 8 * (lane / 16));
+      }
+      float t;
+      switch (d & 3) {
+        case 0: t = gemv_item<2>(slot, lane, a); break;
+        case 1: t = gemv_item<3>(slot, lane, a); break;
+        default: t = gemv_item<4>(slot, lane, a); break;
+      }
+      union {
+        uint32_t u;
+        half2_ h;
+      } sc, zr;
+      sc.u = *reinterpret_cast<const uint32_t*>(slot + 1024 + (lane & 15) * 4);
+      zr.u = *reinterpret_cast<const uint32_t*>(slot + 1088 + (lane & 15) * 4);
+      const float sf = (sigma & 1) ? (float)sc.h[1] : (float)sc.h[0];
+      const float zf = (sigma & 1) ? (float)zr.h[1] : (float)zr.h[0];
+      acc += sf * t + zf * Sx[tc];
+      if (++i == my_cnt) {  // this wavefront's share of slab j is complete
+        if (lane < 16) red[(j * NW + wave) * 16 + lane] = acc;
+        acc = 0.f;
+        i = 0;
+        ++j;
+      }
+    }
+    desc_cur = desc_next;
   }
-
-  if (lane < 16) red[wave * 16 + lane] = acc;
+  if (my_cnt == 0 && lane < 16)
+    for (int jj = 0; jj < nj; ++jj) red[(jj * NW + wave) * 16 + lane] = 0.f;
   __syncthreads();
-  if (tid < 16) {
+  for (int o = tid; o < nj * 16; o += NT) {
+    const int jj = o / 16, r16 = o % 16;
     float s = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) s += red[w * 16 + tid];
-    const int64_t row = (int64_t)tr * kTile + 8 * tid + sigma;
+    for (int w = 0; w < NW; ++w) s += red[(jj * NW + w) * 16 + r16];
+    const int v = (int)blockIdx.x + G * jj;
+    const int slab = (v % 8) * p.ntr + v / 8;
+    const int64_t row = (int64_t)(slab / 8) * kTile + 8 * r16 + (slab % 8);
     const int64_t col = p.row_perm ? p.row_perm[row] : row;
     p.Y[col] = (_Float16)s;
   }
@@ -378,16 +455,28 @@ __global__ __launch_bounds__(256) void skinny_kernel(const SkinnyParams p) {
 DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
   DecodePlan d;
   const int32_t ntr = N / kTile, ntc = K / kTile;
-  const int64_t gemv_base = ((int64_t)K * 2 + (int64_t)ntc * 4 + kGemvWaves * 64 + 15) / 16 * 16;
-  d.gemv = M == 1 && ntc <= 64 * kGemvWaves && gemv_base + (int64_t)K * 2 <= 160 * 1024;
-  if (d.gemv) {  // GEMV: whole K per workgroup, nothing in the workspace
-    d.tiles_per_chunk = ntc;
-    d.nchunk = 1;
-    d.row_groups = 8 * ntr;
-    d.counter_bytes = 0;
-    d.partial_bytes = 0;
-    d.lds_bytes = (int32_t)(gemv_base + (int64_t)K * 2);
-    return d;
+  // GEMV: persistent grid of at most 256 workgroups (multiple of 8), 16 wavefronts each; LDS holds the
+  // permuted activation vector, the group sums, the reduction buffer and the per-wavefront rings.
+  {
+    const int32_t nslab = 8 * ntr;
+    const int32_t grid = nslab < kGemvMaxGrid ? nslab : kGemvMaxGrid;
+    const int32_t max_slabs = (nslab + grid - 1) / grid;
+    const int64_t fixed = ((int64_t)K * 2 + (int64_t)ntc * 4 + (int64_t)max_slabs * kGemvWaves * 64 + 15) / 16 * 16;
+    int64_t slots = (160 * 1024 - fixed) / ((int64_t)kGemvWaves * kSlotBytes);
+    if (slots > kGemvMaxSlots) slots = kGemvMaxSlots;
+    const int64_t ring_bytes = slots * kGemvWaves * kSlotBytes;
+    d.gemv = M == 1 && slots >= 2 && (int64_t)K * 2 <= ring_bytes;  // the raw activation copy aliases the rings
+    if (d.gemv) {
+      d.tiles_per_chunk = ntc;
+      d.nchunk = 1;
+      d.row_groups = grid;
+      d.counter_bytes = 0;
+      d.partial_bytes = 0;
+      d.lds_bytes = (int32_t)(fixed + ring_bytes);
+      d.gemv_slots = (int32_t)slots;
+      d.gemv_max_slabs = max_slabs;
+      return d;
+    }
   }
   // Few, long chunks keep the partial-sum traffic (128*M fp32 per wavefront, written and read
   // once) small next to the tile bytes; many chunks keep all 256 CUs busy.  Start from a chunk
@@ -433,6 +522,9 @@ int launch_decode(const GemmArgs& a, void* stream) {
     p.K = L->K;
     p.ntr = L->N / kTile;
     p.ntc = L->K / kTile;
+    p.nslab = 8 * p.ntr;
+    p.slots = d.gemv_slots;
+    p.max_slabs = d.gemv_max_slabs;
     static bool attr_set = false;
     if (!attr_set) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves>),
@@ -443,7 +535,11 @@ int launch_decode(const GemmArgs& a, void* stream) {
       }
       attr_set = true;
     }
-    hipLaunchKernelGGL(gemv_kernel<kGemvWaves>, dim3((unsigned)d.row_groups), dim3(kGemvWaves * 64),
+    const unsigned grid = (unsigned)d.row_groups;
+#ifdef SFMP_EXPERIMENT
+    p.dbg = g_sfmp_debug;
+#endif
+    hipLaunchKernelGGL(gemv_kernel<kGemvWaves>, dim3(grid), dim3(kGemvWaves * 64),
                        (size_t)d.lds_bytes, (hipStream_t)stream, p);
     return after_launch("sfmp_gemm gemv launch");
   }

@@ -20,6 +20,7 @@ struct DecodePlan {
   int64_t counter_bytes;
   int64_t partial_bytes;
   int32_t lds_bytes;
+  int32_t gemv_slots, gemv_max_slabs;
 };
 DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M);
 
