@@ -61,10 +61,10 @@ struct GemvParams {
   const int32_t* row_perm;
   _Float16* Y;
   int32_t N, K, ntr, ntc, nslab;
-  int32_t slots;       // ring slots per wavefront
-  int32_t max_slabs;   // slabs per workgroup (upper bound), sizes the reduction buffer
+  int32_t max_slabs;  // slabs per workgroup (upper bound), sizes the reduction buffer
 #ifdef SFMP_EXPERIMENT
   int32_t dbg;
+  int32_t dbg_count[3];
 #endif
 };
 #ifdef SFMP_EXPERIMENT
@@ -77,8 +77,11 @@ extern "C" void sfmp_debug_set(int v) { g_sfmp_debug = v; }
 
 constexpr int kGemvWaves = 16;       // wavefronts per workgroup; one workgroup per CU
 constexpr int kGemvMaxGrid = 256;    // persistent grid: at most one workgroup per CU
-constexpr int kGemvMaxSlots = 8;
-constexpr int kSlotBytes = 1024 + 64 + 64;  // slab bytes (<= 1 KiB) + 16 scale dwords + 16 zero dwords
+constexpr int kGemvMaxSlots = 8;     // ring slots per wavefront (compile-time variants 4..8)
+constexpr int kGemvMinSlots = 4;
+constexpr int kGemvMaxSlabs = 16;    // slabs per workgroup kept in register accumulators
+constexpr int kGemvMaxItems = 64;    // items per wavefront: one lane of the item registers each
+constexpr int kSlotBytes = 1024 + 128;  // slab bytes (<= 1 KiB) + 16 scale dwords + 16 zero dwords
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -104,11 +107,17 @@ __device__ __forceinline__ float gemv_item(const unsigned char* slot, int lane, 
   return slab_dot<B>(w, a)[0];
 }
 
-template <int NW>
+// NW wavefronts per workgroup, S ring slots per wavefront.
+//
+// A wavefront's work is a list of at most 64 "items" (one 16-row slab of one tile each).  Everything
+// an item needs (packed-slab address, scale address, tile column, flags) is computed once, by lane e
+// for item e, and later broadcast with v_readlane: the steady-state loop does no address arithmetic.
+// The ring is refilled item by item, so S-1 copies per wavefront are always in flight.
+template <int NW, int S>
 __global__ __launch_bounds__(NW * 64) void gemv_kernel(const GemvParams p) {
   constexpr int NT = NW * 64;
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  // LDS: Xs [K] fp16 | Sx [ntc] f32 | red [max_slabs][NW][16] f32 | rings [NW][slots][kSlotBytes]
+  // LDS: Xs [K] fp16 | Sx [ntc] f32 | red [max_slabs][NW][16] f32 | rings [NW][S][kSlotBytes]
   // (the raw activation copy used while permuting aliases the rings: they are idle until then)
   _Float16* Xs = reinterpret_cast<_Float16*>(lds_raw);
   float* Sx = reinterpret_cast<float*>(lds_raw + (size_t)p.K * 2);
@@ -119,27 +128,41 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const GemvParams p) {
 
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
-  const int wave = tid / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int G = gridDim.x;
   // Virtual slab index v = blockIdx + G*j (G is a multiple of 8, block b runs on XCD b%8): XCD x gets
   // the contiguous slab range [x*ntr, (x+1)*ntr), so the 8 slabs of a tile row run on one XCD.
   const int nj = (p.nslab - (int)blockIdx.x + G - 1) / G;              // slabs of this workgroup
   const int my_cnt = p.ntc > wave ? (p.ntc - wave + NW - 1) / NW : 0;  // tiles per slab of this wavefront
-  const int E = nj * my_cnt;                                           // items of this wavefront
-  const int slots = p.slots;
+  const int E = nj * my_cnt;                                           // items of this wavefront (<= 64)
 
-  // descriptor of item e = j*my_cnt + i: tile (tr(j), wave + NW*i).  Lane s of a batch loads its own.
-  auto item_desc = [&](int e) {
-    int32_t d = 0;
-    if (e < E) {
-      const int j = e / my_cnt, i = e - j * my_cnt;
-      const int v = (int)blockIdx.x + G * j;
-      const int slab = (v % 8) * p.ntr + v / 8;
-      d = p.tile_desc[(int64_t)(slab / 8) * p.ntc + wave + NW * i];
-    }
-    return d;
-  };
-  int32_t desc_cur = lane < slots ? item_desc(lane) : 0;
+  // ---- per-item registers: lane e describes item e = j*my_cnt + i (tile column wave + NW*i of slab j)
+  uint32_t it_alo = 0, it_ahi = 0, it_slo = 0, it_shi = 0, it_misc = 0;
+  if (lane < E) {
+    const int j = lane / my_cnt, i = lane - j * my_cnt;
+    const int v = (int)blockIdx.x + G * j;
+    const int slab = (v % 8) * p.ntr + v / 8;
+    const int tr = slab / 8, sigma = slab % 8;
+    const int tc = wave + NW * i;
+    const int32_t d = p.tile_desc[(int64_t)tr * p.ntc + tc];
+    const int bm2 = d & 3;  // bit-width - 2
+    const uint8_t* base = bm2 == 0 ? p.s2 : bm2 == 1 ? p.s3 : p.s4;
+    const int64_t slab_bytes = 256 * (bm2 + 2);
+    const uint64_t a = (uint64_t)(base + (int64_t)(d >> 2) * (8 * slab_bytes) + sigma * slab_bytes);
+    // address of the aligned dword holding the fp16 scale of row 128*tr + sigma (rows 8*l + sigma are
+    // 16 bytes apart); direct-to-LDS copies need dword-aligned addresses, the wanted fp16 is the
+    // low half for even sigma and the high half for odd sigma
+    const uint64_t sa = (uint64_t)(p.scales + (int64_t)tc * p.N + (int64_t)tr * kTile + (sigma & ~1));
+    it_alo = (uint32_t)a;
+    it_ahi = (uint32_t)(a >> 32);
+    it_slo = (uint32_t)sa;
+    it_shi = (uint32_t)(sa >> 32);
+    it_misc = (uint32_t)tc | ((i == my_cnt - 1) ? 0x10000u : 0u) | ((uint32_t)j << 17) | ((uint32_t)bm2 << 24) |
+              ((uint32_t)(sigma & 1) << 26);
+  }
+  // per-lane parts of the two copies of an item
+  const uint32_t data_voff = lane * 16;
+  const int64_t sz_voff = (int64_t)(lane & 15) * 16 + (lane < 16 ? (int64_t)0 : (int64_t)((const char*)p.zeros - (const char*)p.scales));
 
   // ---- stage the activation vector once per workgroup: raw copy, then permute inside LDS
   const int units = p.K / 8;
@@ -184,59 +207,50 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const GemvParams p) {
   }
   __syncthreads();  // Xs and Sx are complete; the raw copy is dead and the rings may be filled
 
-  unsigned char* ring = rings + (size_t)wave * slots * kSlotBytes;
+  // Issue item e into ring slot s: exactly two direct global->LDS copies, the slab (16 B per lane,
+  // 32/48/64 lanes) and its 16 scale + 16 zero dwords (lanes 0-15 / 16-31).
+  unsigned char* ring = rings + (size_t)wave * S * kSlotBytes;
+  auto issue_item = [&](int e, int s) {
+    // (v_readlane returns a signed int: go through uint32_t, or the low word would be sign-extended)
+    const uint64_t a = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_ahi, e) << 32) |
+                       (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_alo, e);
+    const uint64_t sa = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_shi, e) << 32) |
+                        (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_slo, e);
+    const uint32_t slab_bytes = 256u * ((((uint32_t)__builtin_amdgcn_readlane((int)it_misc, e) >> 24) & 3u) + 2u);
+    unsigned char* slot = ring + s * kSlotBytes;
+    if (data_voff < slab_bytes)
+      __builtin_amdgcn_global_load_lds((gptr_t)((const char*)a + data_voff), (lptr_t)slot, 16, 0, 0);
+    if (lane < 32 && !SFMP_DBG(p, 2))
+      __builtin_amdgcn_global_load_lds((gptr_t)((const char*)sa + sz_voff), (lptr_t)(slot + 1024), 4, 0, 0);
+  };
+
+  // ---- prologue: fill the ring
+  const int npro = min(S, E);
+  for (int e = 0; e < npro; ++e) issue_item(e, e);
+
   half8 a[4];
 #pragma unroll
   for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+  // One fp32 sum per slab of this workgroup, kept in registers: an LDS store inside the loop would
+  // make the compiler wait for every outstanding global->LDS copy (it cannot tell them apart).
+  float accs[kGemvMaxSlabs];
+#pragma unroll
+  for (int q = 0; q < kGemvMaxSlabs; ++q) accs[q] = 0.f;
   float acc = 0.f;
-  int j = 0, i = 0;  // slab index within this workgroup / tile index within the slab, of the next item
-  for (int e0 = 0; e0 < E; e0 += slots) {
-    const int nb = min(slots, E - e0);
-    // descriptors of the next batch are requested before this batch is waited for
-    const int32_t desc_next = lane < slots ? item_desc(e0 + slots + lane) : 0;
-    // ---- issue: one direct global->LDS copy of the slab and of its 16 scales / zeros per item
-    {
-      int jj = j, ii = i;
-      for (int s = 0; s < nb; ++s) {
-        const int32_t d = __builtin_amdgcn_readlane(desc_cur, s);
-        const int v = (int)blockIdx.x + G * jj;
-        const int slab = (v % 8) * p.ntr + v / 8;
-        const int tr = slab / 8, sigma = slab % 8;
-        const int tc = wave + NW * ii;
-        const int bm2 = d & 3;  // bit-width - 2
-        const uint8_t* base = bm2 == 0 ? p.s2 : bm2 == 1 ? p.s3 : p.s4;
-        const int64_t slab_bytes = 256 * (bm2 + 2);
-        const uint8_t* g = base + (int64_t)(d >> 2) * (8 * slab_bytes) + sigma * slab_bytes + lane * 16;
-        unsigned char* slot = ring + s * kSlotBytes;
-        if (lane * 16 < slab_bytes) __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)slot, 16, 0, 0);
-        if (lane < 16) {
-          // the aligned dword that contains the fp16 of row n = 128*tr + 8*lane + sigma
-          const int64_t off = ((int64_t)tc * p.N + (int64_t)tr * kTile + 8 * lane + (sigma & ~1)) * 2;
-          __builtin_amdgcn_global_load_lds((gptr_t)((const char*)p.scales + off), (lptr_t)(slot + 1024), 4, 0, 0);
-          __builtin_amdgcn_global_load_lds((gptr_t)((const char*)p.zeros + off), (lptr_t)(slot + 1088), 4, 0, 0);
-        }
-        if (++ii == my_cnt) {
-          ii = 0;
-          ++jj;
-        }
-      }
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    // ---- consume
-    for (int s = 0; s < nb; ++s) {
-      const int32_t d = __builtin_amdgcn_readlane(desc_cur, s);
-      const int v = (int)blockIdx.x + G * j;
-      const int slab = (v % 8) * p.ntr + v / 8;
-      const int sigma = slab % 8;
-      const int tc = wave + NW * i;
-      const unsigned char* slot = ring + s * kSlotBytes;
+
+  auto consume = [&](int e, int s) {
+    const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
+    const int tc = misc & 0xFFFF;
+    const unsigned char* slot = ring + s * kSlotBytes;
+    if (!SFMP_DBG(p, 8)) {
       if ((lane & 15) == 0) {  // only activation row 0 exists: lanes 0,16,32,48 feed it
 #pragma unroll
         for (int kappa = 0; kappa < 4; ++kappa)
           a[kappa] = *reinterpret_cast<const half8*>(Xs + tc * kTile + 32 * kappa + 8 * (lane / 16));
       }
+      const float sx = Sx[tc];
       float t;
-      switch (d & 3) {
+      switch ((misc >> 24) & 3) {
         case 0: t = gemv_item<2>(slot, lane, a); break;
         case 1: t = gemv_item<3>(slot, lane, a); break;
         default: t = gemv_item<4>(slot, lane, a); break;
@@ -247,31 +261,57 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const GemvParams p) {
       } sc, zr;
       sc.u = *reinterpret_cast<const uint32_t*>(slot + 1024 + (lane & 15) * 4);
       zr.u = *reinterpret_cast<const uint32_t*>(slot + 1088 + (lane & 15) * 4);
-      const float sf = (sigma & 1) ? (float)sc.h[1] : (float)sc.h[0];
-      const float zf = (sigma & 1) ? (float)zr.h[1] : (float)zr.h[0];
-      acc += sf * t + zf * Sx[tc];
-      if (++i == my_cnt) {  // this wavefront's share of slab j is complete
-        if (lane < 16) red[(j * NW + wave) * 16 + lane] = acc;
-        acc = 0.f;
-        i = 0;
-        ++j;
-      }
+      const bool odd = (misc >> 26) & 1;
+      const float sf = odd ? (float)sc.h[1] : (float)sc.h[0];
+      const float zf = odd ? (float)zr.h[1] : (float)zr.h[0];
+      acc += sf * t + zf * sx;
     }
-    desc_cur = desc_next;
+    if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
+      switch ((misc >> 17) & 0x7F) {
+#define SFMP_CASE(q) case q: accs[q] = acc; break;
+        SFMP_CASE(0) SFMP_CASE(1) SFMP_CASE(2) SFMP_CASE(3) SFMP_CASE(4) SFMP_CASE(5) SFMP_CASE(6) SFMP_CASE(7)
+        SFMP_CASE(8) SFMP_CASE(9) SFMP_CASE(10) SFMP_CASE(11) SFMP_CASE(12) SFMP_CASE(13) SFMP_CASE(14)
+        SFMP_CASE(15)
+#undef SFMP_CASE
+        default: break;
+      }
+      acc = 0.f;
+    }
+  };
+
+  // ---- steady state: item e has landed once at most the S-1 younger items (2 copies each) are
+  // outstanding; consume it and refill its slot with item e + S
+  int s = 0;
+  int e = 0;
+  for (; e + S < E; ++e) {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (S - 1)) : "memory");
+    consume(e, s);
+    issue_item(e + S, s);
+    if (++s == S) s = 0;
   }
-  if (my_cnt == 0 && lane < 16)
-    for (int jj = 0; jj < nj; ++jj) red[(jj * NW + wave) * 16 + lane] = 0.f;
+  // ---- tail: nothing left to issue
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  for (; e < E; ++e) {
+    consume(e, s);
+    if (++s == S) s = 0;
+  }
+
+  if (lane < 16) {
+#pragma unroll
+    for (int q = 0; q < kGemvMaxSlabs; ++q)
+      if (q < nj) red[(q * NW + wave) * 16 + lane] = accs[q];
+  }
   __syncthreads();
   for (int o = tid; o < nj * 16; o += NT) {
     const int jj = o / 16, r16 = o % 16;
-    float s = 0.f;
+    float sum = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) s += red[(jj * NW + w) * 16 + r16];
+    for (int w = 0; w < NW; ++w) sum += red[(jj * NW + w) * 16 + r16];
     const int v = (int)blockIdx.x + G * jj;
     const int slab = (v % 8) * p.ntr + v / 8;
     const int64_t row = (int64_t)(slab / 8) * kTile + 8 * r16 + (slab % 8);
     const int64_t col = p.row_perm ? p.row_perm[row] : row;
-    p.Y[col] = (_Float16)s;
+    p.Y[col] = (_Float16)sum;
   }
 }
 
@@ -465,7 +505,10 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
     int64_t slots = (160 * 1024 - fixed) / ((int64_t)kGemvWaves * kSlotBytes);
     if (slots > kGemvMaxSlots) slots = kGemvMaxSlots;
     const int64_t ring_bytes = slots * kGemvWaves * kSlotBytes;
-    d.gemv = M == 1 && slots >= 2 && (int64_t)K * 2 <= ring_bytes;  // the raw activation copy aliases the rings
+    const int64_t items = (int64_t)max_slabs * ((ntc + kGemvWaves - 1) / kGemvWaves);
+    // the raw activation copy used while permuting aliases the rings (they are idle until then)
+    d.gemv = M == 1 && slots >= kGemvMinSlots && max_slabs <= kGemvMaxSlabs && items <= kGemvMaxItems &&
+             (int64_t)K * 2 <= ring_bytes;
     if (d.gemv) {
       d.tiles_per_chunk = ntc;
       d.nchunk = 1;
@@ -523,24 +566,39 @@ int launch_decode(const GemmArgs& a, void* stream) {
     p.ntr = L->N / kTile;
     p.ntc = L->K / kTile;
     p.nslab = 8 * p.ntr;
-    p.slots = d.gemv_slots;
     p.max_slabs = d.gemv_max_slabs;
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-      if (e != hipSuccess) {
-        note_hip_error("hipFuncSetAttribute(gemv)", hipGetErrorString(e));
-        return SFMP_ERR_HIP;
-      }
-      attr_set = true;
-    }
     const unsigned grid = (unsigned)d.row_groups;
 #ifdef SFMP_EXPERIMENT
     p.dbg = g_sfmp_debug;
+    p.dbg_count[0] = L->count2 > 0 ? L->count2 : 1;
+    p.dbg_count[1] = L->count3 > 0 ? L->count3 : 1;
+    p.dbg_count[2] = L->count4 > 0 ? L->count4 : 1;
 #endif
-    hipLaunchKernelGGL(gemv_kernel<kGemvWaves>, dim3(grid), dim3(kGemvWaves * 64),
-                       (size_t)d.lds_bytes, (hipStream_t)stream, p);
+    const void* fn = nullptr;
+    switch (d.gemv_slots) {
+#define SFMP_GEMV_CASE(S_)                                                                                  \
+  case S_: {                                                                                                \
+    static bool attr_set = false;                                                                           \
+    fn = reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, S_>);                                       \
+    if (!attr_set) {                                                                                        \
+      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);       \
+      if (e != hipSuccess) {                                                                                \
+        note_hip_error("hipFuncSetAttribute(gemv)", hipGetErrorString(e));                                  \
+        return SFMP_ERR_HIP;                                                                                \
+      }                                                                                                     \
+      attr_set = true;                                                                                      \
+    }                                                                                                       \
+    hipLaunchKernelGGL((gemv_kernel<kGemvWaves, S_>), dim3(grid), dim3(kGemvWaves * 64), (size_t)d.lds_bytes, \
+                       (hipStream_t)stream, p);                                                             \
+  } break;
+      SFMP_GEMV_CASE(4)
+      SFMP_GEMV_CASE(5)
+      SFMP_GEMV_CASE(6)
+      SFMP_GEMV_CASE(7)
+      SFMP_GEMV_CASE(8)
+#undef SFMP_GEMV_CASE
+      default: return SFMP_ERR_SHAPE;
+    }
     return after_launch("sfmp_gemm gemv launch");
   }
   SkinnyParams p;
