@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-shape / 70B / prefill side reports")
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of HIP-graph replays")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (known size) so that rocprofv3 --pmc FETCH_SIZE / "
+                         "WRITE_SIZE readings can be scaled")
     return ap.parse_args()
 
 
@@ -227,6 +230,13 @@ def main():
     layer = Layer(problems, R)
     per_proj_bytes = layer.bytes_per_proj(W)
 
+    if args.pmc_calibration:
+        src = torch.empty(256 * 2 ** 20, dtype=torch.uint8, device="cuda:0").fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)  # reads 256 MiB and writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     ms_step, wall_ms = time_steps(torch, layer, args.steps, args.warmup, use_graph=not args.eager)
     us_layer = ms_step * 1e3
     gbps = layer_bytes / (ms_step * 1e-3) / 1e9
@@ -255,7 +265,7 @@ def main():
         "wall_ms_per_step": round(wall_ms, 6),
         "roofline": {
             "bound": "hbm",
-            "kernel": "sfmp::decode_kernel<1>",
+            "kernel": "sfmp::gemv_kernel<16, S>",
             "achieved": round(gbps, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
