@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-shape / 70B / prefill side reports")
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of HIP-graph replays")
+    ap.add_argument("--separate", action="store_true",
+                    help="one launch per projection (7) instead of q|k|v, o, gate|up, down sharing launches (4)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (known size) so that rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE readings can be scaled")
@@ -97,6 +99,23 @@ class Layer:
         for i in range(len(self.proj)):
             self.launch(i, r, stream_ptr)
 
+    def step_fused(self, r, stream_ptr, groups):
+        """The same projections as `step`, independent ones sharing a launch (sfmp_gemv_batched)."""
+        lib = self.S.load_library()
+        for gi, idxs in enumerate(groups):
+            key = ("fused", gi, r)
+            if key not in self._args:
+                batch = []
+                for i in idxs:
+                    d = self.proj[i]
+                    batch.append((d["X"], d["cp"][r] if d["cp"] else None, d["reps"][r],
+                                  d["rp"][r] if d["rp"] else None, d["Y"]))
+                self._args[key] = self.S.make_gemv_batch(batch)
+            arr, _keep = self._args[key]
+            rc = lib.sfmp_gemv_batched(C.cast(arr, C.c_void_p), len(idxs), C.c_void_p(stream_ptr))
+            if rc != 0:
+                raise RuntimeError(self.S.sfmp_strerror(rc))
+
     def bytes_per_proj(self, W):
         out = []
         for d in self.proj:
@@ -119,9 +138,21 @@ def build_problems(W, cid, Ms=None, fast=False, only=None):
     return out
 
 
-def time_steps(torch, layer, steps, warmup, use_graph):
-    """Times `steps` steps after `warmup`; returns (ms_per_step from HIP events, wall ms_per_step)."""
+FUSED_GROUPS = [[0, 1, 2], [3], [4, 5], [6]]  # q|k|v, o, gate|up, down: what a decoder layer can run together
+
+
+def time_steps(torch, layer, steps, warmup, use_graph, groups=None):
+    """Times `steps` steps after `warmup`; returns (ms_per_step from HIP events, wall ms_per_step).
+
+    groups None: one launch per projection; else independent projections share a launch."""
     R = layer.replicas
+
+    def do_step(r, sp):
+        if groups is None:
+            layer.step(r, sp)
+        else:
+            layer.step_fused(r, sp, groups)
+
     stream = torch.cuda.current_stream()
     graphs = None
     if use_graph:
@@ -130,12 +161,12 @@ def time_steps(torch, layer, steps, warmup, use_graph):
         side.wait_stream(stream)
         with torch.cuda.stream(side):
             for r in range(R):  # eager warm-up on the capture stream (module load, first-touch)
-                layer.step(r, side.cuda_stream)
+                do_step(r, side.cuda_stream)
         side.synchronize()
         for r in range(R):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=side):
-                layer.step(r, torch.cuda.current_stream().cuda_stream)
+                do_step(r, torch.cuda.current_stream().cuda_stream)
             graphs.append(g)
         torch.cuda.synchronize()
 
@@ -143,7 +174,7 @@ def time_steps(torch, layer, steps, warmup, use_graph):
         if graphs is not None:
             graphs[i % R].replay()
         else:
-            layer.step(i % R, stream.cuda_stream)
+            do_step(i % R, stream.cuda_stream)
 
     for i in range(warmup):
         run(i)
@@ -237,10 +268,11 @@ def main():
             dst.copy_(src)  # reads 256 MiB and writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
-    ms_step, wall_ms = time_steps(torch, layer, args.steps, args.warmup, use_graph=not args.eager)
+    groups = None if args.separate else FUSED_GROUPS
+    ms_step, wall_ms = time_steps(torch, layer, args.steps, args.warmup, use_graph=not args.eager, groups=groups)
     us_layer = ms_step * 1e3
     gbps = layer_bytes / (ms_step * 1e-3) / 1e9
-    n_launch = len(problems)
+    n_launch = len(problems) if groups is None else len(groups)
 
     result = {
         "metric": "us_per_layer_M1 (Llama-3-8B-shaped decoder layer, 7 mixed 2/3/4-bit projections, avg 3.0 bits)",
@@ -258,14 +290,16 @@ def main():
                 f"{R} device copies)",
         "config": {"workload": "configs[1]: 8B decode layer, M=1, q/k/v/o/gate/up/down, 128x128 tiles 1/3 each "
                                "2/3/4-bit, group 128, random col+row perms",
-                   "launch": "eager" if args.eager else "hip-graph replay of the 7 launches",
+                   "launch": ("eager" if args.eager else "hip-graph replay") + (
+                       ", one launch per projection (7)" if groups is None else
+                       ", 4 launches: q|k|v, o, gate|up, down (independent projections share a launch)"),
                    "replicas": R, "layer_bytes": int(layer_bytes)},
         "effective_GBps": round(gbps, 1),
         "pct_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "wall_ms_per_step": round(wall_ms, 6),
         "roofline": {
             "bound": "hbm",
-            "kernel": "sfmp::gemv_kernel<16, S>",
+            "kernel": "sfmp::gemv_batched_kernel<16, S> / gemv_kernel<16, S> (same body)",
             "achieved": round(gbps, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
@@ -273,13 +307,16 @@ def main():
             "traffic": load_traffic(),
             "bytes_per_launch_avg": int(layer_bytes / n_launch),
             "avg_launch_us": round(us_layer / n_launch, 3),
-            "note": "achieved = algorithmic bytes of the 7 launches of a step / HIP-event time of the step "
+            "note": "achieved = algorithmic bytes of all launches of a step / HIP-event time of the step "
                     "(launch gaps included), averaged over the timed region",
         },
     }
 
     if not args.no_extra:
         extra = {}
+        if groups is not None:
+            ms7, _ = time_steps(torch, layer, args.steps, args.warmup, use_graph=not args.eager, groups=None)
+            extra["seven_separate_launches_us_per_layer"] = round(ms7 * 1e3, 3)
         per = time_each_projection(torch, layer)
         extra["per_projection_8b_M1"] = [
             dict(shape=f"{d['p'].K}->{d['p'].N}", label=d["p"].label, us=round(t, 3), MB=round(b / 1e6, 3),

@@ -144,6 +144,30 @@ int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const s
               const int32_t* row_perm_dev, void* Y_dev, void* workspace_dev, int64_t workspace_bytes,
               void* hip_stream);
 
+/* One M = 1 problem of a batched launch: the arguments of sfmp_gemm without M and workspace. */
+typedef struct sfmp_gemv_problem {
+  const void* X_dev;             /* fp16 [1, K] */
+  const int32_t* col_perm_dev;   /* int32 [K] or NULL */
+  const sfmp_layout_t* layout;   /* host pointer; read during the call only */
+  const void* s2_dev;
+  const void* s3_dev;
+  const void* s4_dev;
+  const int32_t* index_dev;
+  const void* scales_dev;
+  const void* zeros_dev;
+  const int8_t* bitmap_dev;
+  const int32_t* row_perm_dev;   /* int32 [N] or NULL */
+  void* Y_dev;                   /* fp16 [1, N] */
+} sfmp_gemv_problem_t;
+
+/* Device.  Up to 8 independent M = 1 products (each exactly what sfmp_gemm computes, each with its
+ * own weights, permutations, X and Y) in ONE kernel launch: the launch and first-touch latency that
+ * bounds small decode layers is paid once for, say, the q, k and v projections of a decoder layer
+ * (Section 4 measures decode at batch 1, where every projection is a GEMV).  problems_host is a host
+ * array read during the call.  Needs no workspace.  SFMP_ERR_SHAPE if a problem cannot use the
+ * GEMV kernel (K above about 32k) - call sfmp_gemm per problem then. */
+int sfmp_gemv_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, void* hip_stream);
+
 /* Host only.  SFMP_OK if perm_host[0..n) is a permutation of 0..n-1, else SFMP_ERR_PERM. */
 int sfmp_check_perm(const int32_t* perm_host, int32_t n);
 

@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     sfmp_gemm_workspace,
     sfmp_workspace_init,
     sfmp_gemm,
+    sfmp_gemv_batched,
+    make_gemv_batch,
     sfmp_check_perm,
     upload_packed,
 )

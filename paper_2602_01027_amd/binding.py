@@ -27,8 +27,13 @@ class SfmpLayout(C.Structure):
     ]
 
 
+class SfmpGemvProblem(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("X", "col_perm", "layout", "s2", "s3", "s4", "index", "scales", "zeros",
+                                          "bitmap", "row_perm", "Y")]
+
+
 EXPORTS = ("sfmp_strerror", "sfmp_pack_query", "sfmp_pack", "sfmp_unpack", "sfmp_gemm_workspace",
-           "sfmp_workspace_init", "sfmp_gemm", "sfmp_check_perm")
+           "sfmp_workspace_init", "sfmp_gemm", "sfmp_gemv_batched", "sfmp_check_perm")
 
 
 def lib_path() -> str:
@@ -55,6 +60,7 @@ def load_library():
     lib.sfmp_gemm_workspace.argtypes = [LP, i32, C.POINTER(i64)]
     lib.sfmp_workspace_init.argtypes = [vp, i64, vp]
     lib.sfmp_gemm.argtypes = [vp, i32, vp, LP, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.sfmp_gemv_batched.argtypes = [vp, i32, vp]
     lib.sfmp_check_perm.argtypes = [vp, i32]
     for name in EXPORTS:
         if name != "sfmp_strerror":
@@ -169,3 +175,27 @@ def sfmp_gemm(X, col_perm, layout: SfmpLayout, s2, s3, s4, index, scales, zeros,
                                     _dev_ptr(s4), _dev_ptr(index), _dev_ptr(scales), _dev_ptr(zeros),
                                     _dev_ptr(bitmap), _dev_ptr(row_perm), _dev_ptr(Y), _dev_ptr(workspace), nbytes,
                                     _stream_ptr(stream)))
+
+
+def make_gemv_batch(problems):
+    """Marshal a list of (X, col_perm, DevicePacked, row_perm, Y) into a ctypes array for sfmp_gemv_batched.
+
+    Returns (array, keepalive); keep `keepalive` referenced for as long as the array is used."""
+    arr = (SfmpGemvProblem * len(problems))()
+    keep = []
+    for i, (X, cp, dp, rp, Y) in enumerate(problems):
+        def ptr(t):
+            return t.data_ptr() if t is not None and t.numel() else None
+        arr[i].X, arr[i].col_perm = ptr(X), ptr(cp)
+        arr[i].layout = C.addressof(dp.layout)
+        arr[i].s2, arr[i].s3, arr[i].s4, arr[i].index = ptr(dp.s2), ptr(dp.s3), ptr(dp.s4), ptr(dp.index)
+        arr[i].scales, arr[i].zeros, arr[i].bitmap = ptr(dp.scales), ptr(dp.zeros), ptr(dp.bitmap)
+        arr[i].row_perm, arr[i].Y = ptr(rp), ptr(Y)
+        keep.append((X, cp, dp, rp, Y))
+    return arr, keep
+
+
+def sfmp_gemv_batched(problems, stream=None) -> None:
+    """problems: list of (X [1,K] fp16, col_perm or None, DevicePacked, row_perm or None, Y [1,N] fp16)."""
+    arr, _keep = make_gemv_batch(problems)
+    _check(load_library().sfmp_gemv_batched(C.cast(arr, C.c_void_p), len(problems), _stream_ptr(stream)))

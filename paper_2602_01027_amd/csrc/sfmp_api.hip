@@ -42,18 +42,58 @@ int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream) {
   return launch_fill_zero(workspace_dev, bytes, hip_stream);
 }
 
-int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
-              const void* s2_dev, const void* s3_dev, const void* s4_dev, const int32_t* index_dev,
-              const void* scales_dev, const void* zeros_dev, const int8_t* bitmap_dev, const int32_t* row_perm_dev,
-              void* Y_dev, void* workspace_dev, int64_t workspace_bytes, void* hip_stream) {
+static int check_gemm_pointers(const void* X_dev, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
+                               const void* s2_dev, const void* s3_dev, const void* s4_dev, const int32_t* index_dev,
+                               const void* scales_dev, const void* zeros_dev, const int8_t* bitmap_dev,
+                               const int32_t* row_perm_dev, const void* Y_dev) {
   if (int e = check_layout(layout)) return e;
-  if (M < 1) return SFMP_ERR_SHAPE;
   if (!X_dev || !index_dev || !scales_dev || !zeros_dev || !bitmap_dev || !Y_dev) return SFMP_ERR_NULL;
   if ((layout->count2 && !s2_dev) || (layout->count3 && !s3_dev) || (layout->count4 && !s4_dev)) return SFMP_ERR_NULL;
   if (!aligned(s2_dev, 16) || !aligned(s3_dev, 16) || !aligned(s4_dev, 16) || !aligned(scales_dev, 16) ||
       !aligned(zeros_dev, 16) || !aligned(X_dev, 16) || !aligned(Y_dev, 2) || !aligned(col_perm_dev, 16) ||
       !aligned(row_perm_dev, 4) || !aligned(index_dev, 4))
     return SFMP_ERR_SHAPE;
+  return SFMP_OK;
+}
+
+int sfmp_gemv_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, void* hip_stream) {
+  if (!problems_host) return SFMP_ERR_NULL;
+  if (count < 1 || count > 8) return SFMP_ERR_SHAPE;
+  GemmArgs args[8];
+  for (int i = 0; i < count; ++i) {
+    const sfmp_gemv_problem_t& q = problems_host[i];
+    if (int e = check_gemm_pointers(q.X_dev, q.col_perm_dev, q.layout, q.s2_dev, q.s3_dev, q.s4_dev, q.index_dev,
+                                    q.scales_dev, q.zeros_dev, q.bitmap_dev, q.row_perm_dev, q.Y_dev))
+      return e;
+    GemmArgs& a = args[i];
+    a.X = q.X_dev;
+    a.M = 1;
+    a.col_perm = q.col_perm_dev;
+    a.L = q.layout;
+    a.s2 = (const uint8_t*)q.s2_dev;
+    a.s3 = (const uint8_t*)q.s3_dev;
+    a.s4 = (const uint8_t*)q.s4_dev;
+    a.index = q.index_dev;
+    a.scales = q.scales_dev;
+    a.zeros = q.zeros_dev;
+    a.bitmap = q.bitmap_dev;
+    a.row_perm = q.row_perm_dev;
+    a.Y = q.Y_dev;
+    a.workspace = nullptr;
+    a.workspace_bytes = 0;
+  }
+  return launch_gemv_batched(args, count, hip_stream);
+}
+
+int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
+              const void* s2_dev, const void* s3_dev, const void* s4_dev, const int32_t* index_dev,
+              const void* scales_dev, const void* zeros_dev, const int8_t* bitmap_dev, const int32_t* row_perm_dev,
+              void* Y_dev, void* workspace_dev, int64_t workspace_bytes, void* hip_stream) {
+  if (int e = check_layout(layout)) return e;
+  if (M < 1) return SFMP_ERR_SHAPE;
+  if (int e = check_gemm_pointers(X_dev, col_perm_dev, layout, s2_dev, s3_dev, s4_dev, index_dev, scales_dev,
+                                  zeros_dev, bitmap_dev, row_perm_dev, Y_dev))
+    return e;
   int64_t need = 0;
   if (int e = sfmp_gemm_workspace(layout, M, &need)) return e;
   if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < need) return SFMP_ERR_WORKSPACE;

@@ -114,9 +114,8 @@ __device__ __forceinline__ float gemv_item(const unsigned char* slot, int lane, 
 // for item e, and later broadcast with v_readlane: the steady-state loop does no address arithmetic.
 // The ring is refilled item by item, so S-1 copies per wavefront are always in flight.
 template <int NW, int S>
-__global__ __launch_bounds__(NW * 64) void gemv_kernel(const GemvParams p) {
+__device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, const int G, unsigned char* lds_raw) {
   constexpr int NT = NW * 64;
-  extern __shared__ __align__(16) unsigned char lds_raw[];
   // LDS: Xs [K] fp16 | Sx [ntc] f32 | red [max_slabs][NW][16] f32 | rings [NW][S][kSlotBytes]
   // (the raw activation copy used while permuting aliases the rings: they are idle until then)
   _Float16* Xs = reinterpret_cast<_Float16*>(lds_raw);
@@ -129,10 +128,9 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const GemvParams p) {
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-  const int G = gridDim.x;
-  // Virtual slab index v = blockIdx + G*j (G is a multiple of 8, block b runs on XCD b%8): XCD x gets
+  // Virtual slab index v = bid + G*j (G is a multiple of 8, block b runs on XCD b%8): XCD x gets
   // the contiguous slab range [x*ntr, (x+1)*ntr), so the 8 slabs of a tile row run on one XCD.
-  const int nj = (p.nslab - (int)blockIdx.x + G - 1) / G;              // slabs of this workgroup
+  const int nj = (p.nslab - bid + G - 1) / G;                           // slabs of this workgroup
   const int my_cnt = p.ntc > wave ? (p.ntc - wave + NW - 1) / NW : 0;  // tiles per slab of this wavefront
   const int E = nj * my_cnt;                                           // items of this wavefront (<= 64)
 
@@ -140,7 +138,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const GemvParams p) {
   uint32_t it_alo = 0, it_ahi = 0, it_slo = 0, it_shi = 0, it_misc = 0;
   if (lane < E) {
     const int j = lane / my_cnt, i = lane - j * my_cnt;
-    const int v = (int)blockIdx.x + G * j;
+    const int v = bid + G * j;
     const int slab = (v % 8) * p.ntr + v / 8;
     const int tr = slab / 8, sigma = slab % 8;
     const int tc = wave + NW * i;
@@ -307,12 +305,36 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const GemvParams p) {
     float sum = 0.f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) sum += red[(jj * NW + w) * 16 + r16];
-    const int v = (int)blockIdx.x + G * jj;
+    const int v = bid + G * jj;
     const int slab = (v % 8) * p.ntr + v / 8;
     const int64_t row = (int64_t)(slab / 8) * kTile + 8 * r16 + (slab % 8);
     const int64_t col = p.row_perm ? p.row_perm[row] : row;
     p.Y[col] = (_Float16)sum;
   }
+}
+
+template <int NW, int S>
+__global__ __launch_bounds__(NW * 64) void gemv_kernel(const GemvParams p) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  gemv_body<NW, S>(p, (int)blockIdx.x, (int)gridDim.x, lds_raw);
+}
+
+// Several independent M = 1 problems in one launch (for example q, k and v, or gate and up of a
+// decoder layer): the persistent grid is split between the problems in proportion to their bytes;
+// workgroups [first[i], first[i+1]) run problem i exactly as a launch of that size would.
+constexpr int kGemvMaxBatch = 8;
+struct GemvBatch {
+  GemvParams p[kGemvMaxBatch];
+  int32_t first[kGemvMaxBatch + 1];
+  int32_t count;
+};
+
+template <int NW, int S>
+__global__ __launch_bounds__(NW * 64) void gemv_batched_kernel(const GemvBatch b) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  int i = 0;
+  while (i + 1 < b.count && (int)blockIdx.x >= b.first[i + 1]) ++i;
+  gemv_body<NW, S>(b.p[i], (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
 }
 
 // ============================================================================================
@@ -492,32 +514,56 @@ __global__ __launch_bounds__(256) void skinny_kernel(const SkinnyParams p) {
 // ============================================================================================
 // host side
 // ============================================================================================
+static int after_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    note_hip_error(what, hipGetErrorString(e));
+    return SFMP_ERR_HIP;
+  }
+  return SFMP_OK;
+}
+
+// Does an M = 1 problem fit the GEMV kernel when `grid` workgroups (a multiple of 8) work on it?  LDS holds
+// the permuted activation vector, the group sums, the reduction buffer and the per-wavefront rings; the
+// raw activation copy used while permuting aliases the rings (they are idle until then).
+struct GemvFit {
+  bool ok;
+  int32_t slots, max_slabs, lds_bytes;
+};
+static GemvFit gemv_fit(int32_t N, int32_t K, int32_t grid) {
+  GemvFit f;
+  const int32_t ntr = N / kTile, ntc = K / kTile, nslab = 8 * ntr;
+  f.max_slabs = (nslab + grid - 1) / grid;
+  const int64_t fixed = ((int64_t)K * 2 + (int64_t)ntc * 4 + (int64_t)f.max_slabs * kGemvWaves * 64 + 15) / 16 * 16;
+  int64_t slots = (160 * 1024 - fixed) / ((int64_t)kGemvWaves * kSlotBytes);
+  if (slots > kGemvMaxSlots) slots = kGemvMaxSlots;
+  const int64_t ring_bytes = slots * kGemvWaves * kSlotBytes;
+  const int64_t items = (int64_t)f.max_slabs * ((ntc + kGemvWaves - 1) / kGemvWaves);
+  f.ok = grid >= 8 && grid % 8 == 0 && grid <= nslab && slots >= kGemvMinSlots && f.max_slabs <= kGemvMaxSlabs &&
+         items <= kGemvMaxItems && (int64_t)K * 2 <= ring_bytes;
+  f.slots = (int32_t)slots;
+  f.lds_bytes = (int32_t)(fixed + ring_bytes);
+  return f;
+}
+
 DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
   DecodePlan d;
   const int32_t ntr = N / kTile, ntc = K / kTile;
-  // GEMV: persistent grid of at most 256 workgroups (multiple of 8), 16 wavefronts each; LDS holds the
-  // permuted activation vector, the group sums, the reduction buffer and the per-wavefront rings.
+  // GEMV: persistent grid of at most 256 workgroups (multiple of 8), 16 wavefronts each.
   {
     const int32_t nslab = 8 * ntr;
     const int32_t grid = nslab < kGemvMaxGrid ? nslab : kGemvMaxGrid;
-    const int32_t max_slabs = (nslab + grid - 1) / grid;
-    const int64_t fixed = ((int64_t)K * 2 + (int64_t)ntc * 4 + (int64_t)max_slabs * kGemvWaves * 64 + 15) / 16 * 16;
-    int64_t slots = (160 * 1024 - fixed) / ((int64_t)kGemvWaves * kSlotBytes);
-    if (slots > kGemvMaxSlots) slots = kGemvMaxSlots;
-    const int64_t ring_bytes = slots * kGemvWaves * kSlotBytes;
-    const int64_t items = (int64_t)max_slabs * ((ntc + kGemvWaves - 1) / kGemvWaves);
-    // the raw activation copy used while permuting aliases the rings (they are idle until then)
-    d.gemv = M == 1 && slots >= kGemvMinSlots && max_slabs <= kGemvMaxSlabs && items <= kGemvMaxItems &&
-             (int64_t)K * 2 <= ring_bytes;
+    GemvFit f = gemv_fit(N, K, grid);
+    d.gemv = M == 1 && f.ok;
     if (d.gemv) {
       d.tiles_per_chunk = ntc;
       d.nchunk = 1;
       d.row_groups = grid;
       d.counter_bytes = 0;
       d.partial_bytes = 0;
-      d.lds_bytes = (int32_t)(fixed + ring_bytes);
-      d.gemv_slots = (int32_t)slots;
-      d.gemv_max_slabs = max_slabs;
+      d.lds_bytes = f.lds_bytes;
+      d.gemv_slots = f.slots;
+      d.gemv_max_slabs = f.max_slabs;
       return d;
     }
   }
@@ -537,69 +583,130 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
   return d;
 }
 
-static int after_launch(const char* what) {
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) {
-    note_hip_error(what, hipGetErrorString(e));
-    return SFMP_ERR_HIP;
+static GemvParams gemv_params(const GemmArgs& a, int32_t max_slabs) {
+  const sfmp_layout_t* L = a.L;
+  GemvParams p;
+  p.X = (const _Float16*)a.X;
+  p.col_perm = a.col_perm;
+  p.s2 = a.s2;
+  p.s3 = a.s3;
+  p.s4 = a.s4;
+  p.tile_desc = a.index + 3;
+  p.scales = (const _Float16*)a.scales;
+  p.zeros = (const _Float16*)a.zeros;
+  p.row_perm = a.row_perm;
+  p.Y = (_Float16*)a.Y;
+  p.N = L->N;
+  p.K = L->K;
+  p.ntr = L->N / kTile;
+  p.ntc = L->K / kTile;
+  p.nslab = 8 * p.ntr;
+  p.max_slabs = max_slabs;
+#ifdef SFMP_EXPERIMENT
+  p.dbg = g_sfmp_debug;
+  p.dbg_count[0] = L->count2 > 0 ? L->count2 : 1;
+  p.dbg_count[1] = L->count3 > 0 ? L->count3 : 1;
+  p.dbg_count[2] = L->count4 > 0 ? L->count4 : 1;
+#endif
+  return p;
+}
+
+// Launches gemv_kernel / gemv_batched_kernel instantiated for S ring slots.
+template <typename KernelArg>
+static int launch_gemv_variant(int slots, bool batched, const KernelArg& arg, unsigned grid, size_t lds_bytes,
+                               void* stream) {
+  switch (slots) {
+#define SFMP_GEMV_CASE(S_)                                                                                     \
+  case S_: {                                                                                                   \
+    static bool attr_set[2] = {false, false};                                                                  \
+    const void* fn = batched ? reinterpret_cast<const void*>(&gemv_batched_kernel<kGemvWaves, S_>)             \
+                             : reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, S_>);                    \
+    if (!attr_set[batched]) {                                                                                  \
+      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);          \
+      if (e != hipSuccess) {                                                                                   \
+        note_hip_error("hipFuncSetAttribute(gemv)", hipGetErrorString(e));                                     \
+        return SFMP_ERR_HIP;                                                                                   \
+      }                                                                                                        \
+      attr_set[batched] = true;                                                                                \
+    }                                                                                                          \
+    void* kargs[] = {const_cast<KernelArg*>(&arg)};                                                            \
+    hipError_t e = hipLaunchKernel(fn, dim3(grid), dim3(kGemvWaves * 64), kargs, lds_bytes, (hipStream_t)stream); \
+    if (e != hipSuccess) {                                                                                     \
+      note_hip_error("sfmp gemv launch", hipGetErrorString(e));                                                \
+      return SFMP_ERR_HIP;                                                                                     \
+    }                                                                                                          \
+  } break;
+    SFMP_GEMV_CASE(4)
+    SFMP_GEMV_CASE(5)
+    SFMP_GEMV_CASE(6)
+    SFMP_GEMV_CASE(7)
+    SFMP_GEMV_CASE(8)
+#undef SFMP_GEMV_CASE
+    default: return SFMP_ERR_SHAPE;
   }
-  return SFMP_OK;
+  return after_launch("sfmp gemv launch");
+}
+
+int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
+  if (count < 1 || count > kGemvMaxBatch) return SFMP_ERR_SHAPE;
+  // split the 256 workgroups in units of 8 (one per XCD), greedily to the problem with the most packed bytes
+  // per workgroup, never giving a problem more workgroups than it has slabs
+  int32_t g[kGemvMaxBatch];
+  int64_t bytes[kGemvMaxBatch];
+  int32_t total = 0;
+  for (int i = 0; i < count; ++i) {
+    const sfmp_layout_t* L = probs[i].L;
+    bytes[i] = L->bytes_s2 + L->bytes_s3 + L->bytes_s4 + (int64_t)L->N * (L->K / kTile) * 4;
+    g[i] = 8;
+    total += 8;
+  }
+  if (total > kGemvMaxGrid) return SFMP_ERR_SHAPE;
+  while (total + 8 <= kGemvMaxGrid) {
+    int best = -1;
+    double best_load = 0.0;
+    for (int i = 0; i < count; ++i) {
+      if (g[i] + 8 > 8 * (probs[i].L->N / kTile)) continue;
+      const double load = (double)bytes[i] / g[i];
+      if (load > best_load) {
+        best_load = load;
+        best = i;
+      }
+    }
+    if (best < 0) break;
+    g[best] += 8;
+    total += 8;
+  }
+  GemvBatch b;
+  b.count = count;
+  int32_t slots = kGemvMaxSlots, lds = 0, first = 0;
+  for (int i = 0; i < count; ++i) {
+    const GemvFit f = gemv_fit(probs[i].L->N, probs[i].L->K, g[i]);
+    if (!f.ok) return SFMP_ERR_SHAPE;
+    slots = f.slots < slots ? f.slots : slots;
+    b.p[i] = gemv_params(probs[i], f.max_slabs);
+    b.first[i] = first;
+    first += g[i];
+  }
+  b.first[count] = first;
+  for (int i = count + 1; i <= kGemvMaxBatch; ++i) b.first[i] = first;
+  // with fewer slots than a problem could use alone its LDS footprint only shrinks: size for the largest
+  for (int i = 0; i < count; ++i) {
+    const sfmp_layout_t* L = probs[i].L;
+    const int64_t fixed =
+        ((int64_t)L->K * 2 + (int64_t)(L->K / kTile) * 4 + (int64_t)b.p[i].max_slabs * kGemvWaves * 64 + 15) / 16 * 16;
+    const int64_t need = fixed + (int64_t)slots * kGemvWaves * kSlotBytes;
+    if ((int64_t)L->K * 2 > (int64_t)slots * kGemvWaves * kSlotBytes) return SFMP_ERR_SHAPE;
+    lds = need > lds ? (int32_t)need : lds;
+  }
+  return launch_gemv_variant(slots, true, b, (unsigned)first, (size_t)lds, stream);
 }
 
 int launch_decode(const GemmArgs& a, void* stream) {
   const sfmp_layout_t* L = a.L;
   const DecodePlan d = make_decode_plan(L->N, L->K, a.M);
   if (d.gemv) {
-    GemvParams p;
-    p.X = (const _Float16*)a.X;
-    p.col_perm = a.col_perm;
-    p.s2 = a.s2;
-    p.s3 = a.s3;
-    p.s4 = a.s4;
-    p.tile_desc = a.index + 3;
-    p.scales = (const _Float16*)a.scales;
-    p.zeros = (const _Float16*)a.zeros;
-    p.row_perm = a.row_perm;
-    p.Y = (_Float16*)a.Y;
-    p.N = L->N;
-    p.K = L->K;
-    p.ntr = L->N / kTile;
-    p.ntc = L->K / kTile;
-    p.nslab = 8 * p.ntr;
-    p.max_slabs = d.gemv_max_slabs;
-    const unsigned grid = (unsigned)d.row_groups;
-#ifdef SFMP_EXPERIMENT
-    p.dbg = g_sfmp_debug;
-    p.dbg_count[0] = L->count2 > 0 ? L->count2 : 1;
-    p.dbg_count[1] = L->count3 > 0 ? L->count3 : 1;
-    p.dbg_count[2] = L->count4 > 0 ? L->count4 : 1;
-#endif
-    const void* fn = nullptr;
-    switch (d.gemv_slots) {
-#define SFMP_GEMV_CASE(S_)                                                                                  \
-  case S_: {                                                                                                \
-    static bool attr_set = false;                                                                           \
-    fn = reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, S_>);                                       \
-    if (!attr_set) {                                                                                        \
-      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);       \
-      if (e != hipSuccess) {                                                                                \
-        note_hip_error("hipFuncSetAttribute(gemv)", hipGetErrorString(e));                                  \
-        return SFMP_ERR_HIP;                                                                                \
-      }                                                                                                     \
-      attr_set = true;                                                                                      \
-    }                                                                                                       \
-    hipLaunchKernelGGL((gemv_kernel<kGemvWaves, S_>), dim3(grid), dim3(kGemvWaves * 64), (size_t)d.lds_bytes, \
-                       (hipStream_t)stream, p);                                                             \
-  } break;
-      SFMP_GEMV_CASE(4)
-      SFMP_GEMV_CASE(5)
-      SFMP_GEMV_CASE(6)
-      SFMP_GEMV_CASE(7)
-      SFMP_GEMV_CASE(8)
-#undef SFMP_GEMV_CASE
-      default: return SFMP_ERR_SHAPE;
-    }
-    return after_launch("sfmp_gemm gemv launch");
+    const GemvParams p = gemv_params(a, d.gemv_max_slabs);
+    return launch_gemv_variant(d.gemv_slots, false, p, (unsigned)d.row_groups, (size_t)d.lds_bytes, stream);
   }
   SkinnyParams p;
   p.X = (const _Float16*)a.X;

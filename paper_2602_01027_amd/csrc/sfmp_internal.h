@@ -61,5 +61,6 @@ int launch_unpack(const sfmp_layout_t* L, const uint8_t* s2, const uint8_t* s3, 
                   const int32_t* index, uint8_t* codes, void* stream);
 int launch_fill_zero(void* ptr, int64_t bytes, void* stream);
 int launch_decode(const GemmArgs& a, void* stream);
+int launch_gemv_batched(const GemmArgs* problems, int count, void* stream);
 int launch_prefill(const GemmArgs& a, void* stream);
 }  // namespace sfmp

@@ -201,3 +201,32 @@ def test_config4_70b_decode(torch_cuda, si):
 @pytest.mark.parametrize("si", _distinct_shapes(5))
 def test_config5_prefill(torch_cuda, si):
     _run_config_shape(5, si, sample_rows=True)
+
+
+# ---------------------------------------------------------------------------------------------
+# several M = 1 problems in one launch
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("shapes", [[(512, 512)], [(896, 640), (512, 1024), (1024, 256)],
+                                    [(4096, 4096), (4096, 1024), (4096, 1024)], [(4096, 14336), (4096, 14336)]])
+def test_gemv_batched(torch_cuda, shapes):
+    import paper_2602_01027_amd as S
+    from gpu_util import device_problem
+    torch = torch_cuda
+    probs, batch = [], []
+    for i, (K, N) in enumerate(shapes):
+        p = W.make_problem(f"b{i}", K, N, 1, 7000 + 13 * i + K, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3},
+                           use_row_perm=(i % 2 == 0), use_col_perm=(i != 1))
+        dp, cp, rp = device_problem(p)
+        X = torch.from_numpy(p.X).to("cuda:0")
+        Y = torch.full((1, N), float("nan"), dtype=torch.float16, device="cuda:0")
+        probs.append(p)
+        batch.append((X, cp, dp, rp, Y))
+    S.sfmp_gemv_batched(batch)
+    torch.cuda.synchronize()
+    for p, (_, _, _, _, Y) in zip(probs, batch):
+        _check(p, Y.cpu().numpy())
+    # the batched launch computes exactly what separate launches compute
+    from gpu_util import run_gemm
+    for p, (_, cp, dp, rp, Y) in zip(probs, batch):
+        y_single = run_gemm(p, dp, cp, rp)
+        assert np.array_equal(y_single.view(np.uint16), Y.cpu().numpy().view(np.uint16))
