@@ -30,7 +30,7 @@ int sfmp_gemm_workspace(const sfmp_layout_t* layout, int32_t M, int64_t* bytes) 
     *bytes = d.counter_bytes + d.partial_bytes;
   } else {
     const PrefillPlan d = make_prefill_plan(layout->N, layout->K, M);
-    *bytes = d.xperm_bytes;
+    *bytes = d.xperm_bytes + d.ytmp_bytes;
   }
   if (*bytes < 256) *bytes = 256;
   return SFMP_OK;
@@ -51,7 +51,7 @@ static int check_gemm_pointers(const void* X_dev, const int32_t* col_perm_dev, c
   if ((layout->count2 && !s2_dev) || (layout->count3 && !s3_dev) || (layout->count4 && !s4_dev)) return SFMP_ERR_NULL;
   if (!aligned(s2_dev, 16) || !aligned(s3_dev, 16) || !aligned(s4_dev, 16) || !aligned(scales_dev, 16) ||
       !aligned(zeros_dev, 16) || !aligned(X_dev, 16) || !aligned(Y_dev, 2) || !aligned(col_perm_dev, 16) ||
-      !aligned(row_perm_dev, 4) || !aligned(index_dev, 4))
+      !aligned(row_perm_dev, 16) || !aligned(index_dev, 4))
     return SFMP_ERR_SHAPE;
   return SFMP_OK;
 }

@@ -26,7 +26,8 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M);
 
 // Prefill path (M > 16): workspace holds the column-gathered activation.
 struct PrefillPlan {
-  int64_t xperm_bytes;
+  int64_t xperm_bytes;  // column-gathered activation copy
+  int64_t ytmp_bytes;   // product in reordered row order, before the row un-permute pass
 };
 PrefillPlan make_prefill_plan(int32_t N, int32_t K, int32_t M);
 
