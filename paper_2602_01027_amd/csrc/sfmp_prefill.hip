@@ -7,19 +7,23 @@
 //     the N/128 workgroups that need it; doing it once costs 4*M*K bytes of streaming traffic.
 //  2. prefill_kernel: workgroup = 128 (M) x 128 (N, one tile row) output block, 4 wavefronts in a
 //     2x2 arrangement of 64x64 sub-blocks, two workgroups per CU.  K is walked one 128x128 weight
-//     tile (= one quantisation group) per step: packed slabs -> shared unpack routines -> exact q
-//     (0x6400 magic + one exact FMA) -> fp16(s*q + z) with one FMA (Appendix B Eq. 11) -> LDS; the
-//     activation block is copied to LDS; both are read as 16x16x32 MFMA operands (fp32 accumulate).
-//     LDS rows are 256 bytes with 16-byte units XOR-swizzled by (row%16)^(row/16), so operand reads
-//     (16 consecutive rows) and dequant writes (rows 8 apart) are bank-conflict free.  Weight loads
-//     run TWO steps ahead of their use (two register sets, loop unrolled by two), activation
-//     loads one step; the tile descriptors are read once into LDS.  With the descriptor load and one
-//     step of look-ahead inside the loop every step waited a full memory latency (about 3000 cycles
-//     against about 1000 cycles of MFMA work).
+//     tile (= one quantisation group) per step.  A packed slab is already laid out as an MFMA B
+//     operand (lane = weight row-in-16 x k-block of 8), so the weights never touch LDS: each wavefront
+//     loads the four slabs of its 64 output columns, unpacks them with the shared routines and
+//     dequantises in registers (exact q from the 0x6400 magic, then fp16(s*q + z) with one FMA,
+//     Appendix B Eq. 11) straight into the B operands of v_mfma_f32_16x16x32_f16.  Only the activation
+//     block goes through LDS (double-buffered, 256-byte rows, 16-byte units XOR-swizzled by
+//     (row%16)^(row/16): conflict-free operand reads), one barrier per step.  The version that staged
+//     dequantised weights in LDS was bound by LDS bandwidth (192 KiB per step against 96 KiB now).
+//     Weight loads run two steps ahead (three rotating register sets), activation loads one step; tile
+//     descriptors are read once into LDS; the load sequence is the same for every width so that the
+//     compiler can keep younger loads in flight (exact s_waitcnt counts).
 //  3. scatter_cols_kernel (only with a row permutation): the GEMM writes the product in reordered
 //     row order with coalesced stores into the workspace, then Y[m, row_perm[i]] = Yt[m, i] is done
 //     one row through LDS.  Scattering 2-byte results straight from the GEMM epilogue leaves
 //     half-written cache lines all over Y and doubled the kernel time.
+#include <type_traits>
+
 #include "sfmp_device.h"
 #include "sfmp_internal.h"
 
@@ -95,54 +99,80 @@ struct PrefillParams {
   const uint8_t* s2;
   const uint8_t* s3;
   const uint8_t* s4;
-  const int32_t* tile_desc;
+  const int32_t* index;  // the whole block-index table
   const _Float16* scales;
   const _Float16* zeros;
   _Float16* Yt;  // [M, N], rows of Wt in reordered order
   int32_t M, N, K, ntr, ntc, n_mtiles;
 };
 
-constexpr int kBM = 128;
 constexpr int kPrefillMaxTiles = 224 * 2;  // K <= 57344
 
-__device__ __forceinline__ int swz(int row, int unit) { return unit ^ ((row & 15) ^ ((row >> 4) & 7)); }
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
 
-// Exact fp16 dequantisation of one slab and store to the LDS weight block.
-template <int B>
-__device__ __forceinline__ void dequant_slab_to_lds(const uint32_t* w, _Float16 s, _Float16 z, _Float16* Ws, int row,
-                                                    int kb) {
-  uint32_t op[4][4];
-  unpack_slab<B>(w, op);
-  const half2_ s2 = {s, s}, z2 = {z, z};
-#pragma unroll
-  for (int kappa = 0; kappa < 4; ++kappa) {
-    const int p = step_pos<B>(kappa);
-    const _Float16 inv = (_Float16)(1.0f / (float)(1 << p));
-    const _Float16 off = (_Float16)(-1024.0f / (float)(1 << p));
-    const half2_ inv2 = {inv, inv}, off2 = {off, off};
-    union {
-      half2_ h[4];
-      uint4 u;
-    } out;
-#pragma unroll
-    for (int reg = 0; reg < 4; ++reg) {
-      union {
-        uint32_t u;
-        half2_ h;
-      } t;
-      t.u = op[kappa][reg] | 0x64006400u;                           // 1024 + q*2^p in both halves
-      const half2_ q = __builtin_elementwise_fma(t.h, inv2, off2);  // exact: q in [0, 15]
-      out.h[reg] = __builtin_elementwise_fma(q, s2, z2);            // one rounding
-    }
-    const int unit = 4 * kappa + kb;
-    *reinterpret_cast<uint4*>(Ws + row * 128 + swz(row, unit) * 8) = out.u;
-  }
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16*lane.  Written as inline
+// assembly so that the compiler's wait-count bookkeeping does not see it: the kernel orders these
+// loads itself (they complete in issue order with the ordinary loads around them).
+__device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t byte_offset, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(base), "v"(byte_offset), "s"(lds_base)
+               : "memory", "m0");
 }
 
-__global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p) {
-  __shared__ __align__(16) _Float16 Xs[kBM * 128];
-  __shared__ __align__(16) _Float16 Ws[128 * 128];
-  __shared__ int32_t descs[kPrefillMaxTiles];
+// 256-byte LDS rows of the activation block: 16-byte unit u of row r is stored at position u ^ (r % 16).  The 16
+// rows that one quarter of a wavefront reads for an MFMA operand then hit 16 different positions (all 64
+// banks once), and the position does not depend on the 16-row block, so operand addresses of a lane differ
+// by multiples of 4096 bytes: immediate offsets.
+__device__ __forceinline__ int swz(int row, int unit) { return unit ^ (row & 15); }
+
+// One MFMA B operand in registers: the 16 weight rows {8i + sigma} x the 32 columns of k-step KAPPA of a
+// slab, dequantised exactly: q from the 0x6400 magic (1024 + q*2^p) by one exact FMA, then
+// fp16(s*q + z) by one FMA (Appendix B Eq. 11, a single rounding).  `magic` is 0x64006400 held in a
+// vector register so that mask-and-or is one instruction (two literals do not fit into one).
+template <int B, int KAPPA>
+__device__ __forceinline__ half8 dequant_operand(const uint32_t* w, half2_ s2, half2_ z2, uint32_t magic) {
+  uint32_t op[4][4];
+  unpack_slab<B>(w, op);  // the other k-steps are dead code here and shared between the four calls
+  constexpr int p = step_pos<B>(KAPPA);
+  const _Float16 inv = (_Float16)(1.0f / (float)(1 << p));
+  const _Float16 off = (_Float16)(-1024.0f / (float)(1 << p));
+  const half2_ inv2 = {inv, inv}, off2 = {off, off};
+  union {
+    half2_ h[4];
+    half8 v;
+  } out;
+#pragma unroll
+  for (int reg = 0; reg < 4; ++reg) {
+    union {
+      uint32_t u;
+      half2_ h;
+    } t;
+    t.u = op[KAPPA][reg] | magic;
+    const half2_ q = __builtin_elementwise_fma(t.h, inv2, off2);  // exact: q in [0, 15]
+    out.h[reg] = __builtin_elementwise_fma(q, s2, z2);            // one rounding
+  }
+  return out.v;
+}
+
+// Workgroup = BM x 128 output block, WM x WN wavefronts, wavefront tile (BM/WM) x (128/WN): MI = BM/WM/16
+// row blocks x NS = 8/WN slabs.  A dequantised B operand feeds MI MFMAs, so the dequantisation cost per
+// MFMA falls with MI; the activation operand reads from LDS grow with WN.
+template <int BM, int WM, int WN>
+struct PrefillShape {
+  static constexpr int kThreads = 64 * WM * WN;
+  static constexpr int kMI = BM / WM / 16;
+  static constexpr int kNS = 8 / WN;
+  static constexpr int kRowsPerPass = kThreads / 16;
+  static constexpr int kPasses = BM / kRowsPerPass;
+};
+
+template <int BM, int WM, int WN>
+__global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) / 4)) void prefill_kernel(const PrefillParams p) {
+  using S = PrefillShape<BM, WM, WN>;
+  constexpr int MI = S::kMI, NS = S::kNS;
+  constexpr uint32_t kBufBytes = BM * 256;
+  __shared__ __align__(16) unsigned char Xs[2 * kBufBytes];  // activation block, double-buffered
+  __shared__ int32_t seq[kPrefillMaxTiles];                  // (slot << 9) | tc of this tile row, width-sorted
 
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
@@ -154,141 +184,280 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p) {
   const int mt = xcd + 8 * (within / p.ntr);
   const int tr = within % p.ntr;
   if (mt >= p.n_mtiles) return;
-  const int m0 = mt * kBM;
+  const int m0 = mt * BM;
 
-  const int wm = wave / 2, wn = wave % 2;
-  floatx4 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-  const int xrow = tid / 16, xunit = tid % 16;  // + 16*pass rows
-  const int i16 = lane % 16, kb = lane / 16;
-  const int nloc = 8 * i16 + 2 * wave;  // weight row (in tile) of slab 2*wave for this lane
-
-  // descriptors of this tile row, fetched once (a load of the descriptor inside the K loop would put
-  // a dependent memory round trip in front of every step's weight loads)
-  for (int i = tid; i < p.ntc; i += 256) descs[i] = p.tile_desc[(int64_t)tr * p.ntc + i];
+  // The K reduction runs over the tiles of this tile row sorted by width (first all 2-bit tiles, then
+  // the 3-bit, then the 4-bit ones; the order of a sum is free): three loops, each with a straight-line
+  // body for its width.  The CSR part of the block-index table lists exactly these runs: the i-th
+  // width-b tile of row tr is tile number row_ptr_b[tr] + i of stream S_b, in tile column
+  // col_idx_b[row_ptr_b[tr] + i].
+  const int32_t* row_ptr = p.index + 3 + p.ntr * p.ntc;
+  const int32_t* col_idx = row_ptr + 3 * (p.ntr + 1);
+  const int32_t first2 = row_ptr[tr], first3 = row_ptr[(p.ntr + 1) + tr], first4 = row_ptr[2 * (p.ntr + 1) + tr];
+  const int end2 = row_ptr[tr + 1] - first2;
+  const int end3 = end2 + row_ptr[(p.ntr + 1) + tr + 1] - first3;
+  const int32_t total2 = p.index[0], total3 = p.index[1];
+  for (int e = tid; e < p.ntc; e += S::kThreads) {
+    // position in its stream, and position of that stream's column list
+    const int32_t slot = e < end2 ? first2 + e : e < end3 ? first3 + (e - end2) : first4 + (e - end3);
+    const int32_t cols = e < end2 ? 0 : e < end3 ? total2 : total2 + total3;
+    seq[e] = (slot << 9) | col_idx[cols + slot];
+  }
   __syncthreads();
 
-  // (clang vector types, not HIP uint4: arrays or structs of the HIP type stayed in scratch memory)
-  struct XRegs {
-    u32x4 v0, v1, v2, v3, v4, v5, v6, v7;
-  };
-#define SFMP_FOR8(M) M(0) M(1) M(2) M(3) M(4) M(5) M(6) M(7)
-  auto issue_x = [&](int tc, XRegs& xr) __attribute__((always_inline)) {
-    // rows past M re-read the last row (never stored): no branch, so the load count is fixed
-#define SFMP_LDX(i)                                                                                             \
-  xr.v##i = *reinterpret_cast<const u32x4*>(p.Xp + (int64_t)min(m0 + xrow + 16 * i, p.M - 1) * p.K + tc * 128 + \
-                                            xunit * 8);
-    SFMP_FOR8(SFMP_LDX)
-#undef SFMP_LDX
-  };
-  // Same instruction sequence for every width (the compiler can then count outstanding loads exactly and
-  // let younger loads stay in flight): four dword loads per slab; the words a narrower width does not
-  // have re-read its last word.
-  auto issue_w = [&](int tc, uint32_t (&rw)[8], uint32_t (&rsz)[2], int32_t& rdesc) __attribute__((always_inline)) {
-    rdesc = __builtin_amdgcn_readfirstlane(descs[tc]);
-    const int bw = (rdesc & 3) + 2;
-    const uint8_t* stream = bw == 2 ? p.s2 : bw == 3 ? p.s3 : p.s4;
-    const uint8_t* tile = stream + (int64_t)(rdesc >> 2) * (2048 * bw);
+  const int wm = wave / WN, wn = wave % WN;  // this wavefront: rows 16*MI*wm.., slabs NS*wn .. NS*wn+NS-1
+  floatx4 acc[MI][NS];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const uint32_t* src = reinterpret_cast<const uint32_t*>(tile + (2 * wave + q) * (256 * bw) + lane * (4 * bw));
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) rw[4 * q + i] = __builtin_nontemporal_load(src + (i < bw ? i : bw - 1));
+    for (int j = 0; j < NS; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const int xrow = tid / 16, xunit = tid % 16;  // + kRowsPerPass*pass rows
+  const int i16 = lane % 16, kb = lane / 16;
+  uint32_t magic;
+  asm volatile("v_mov_b32 %0, 0x64006400" : "=v"(magic));
+
+  // The activation block goes from global memory straight into LDS (no staging registers).  A 16-byte
+  // LDS-DMA load of a wavefront fills 1024 contiguous bytes = four 256-byte rows, lane l -> row l/16,
+  // 16-byte position l%16; the swizzle is applied on the global side: position u of row r receives
+  // unit u ^ (r%16).  Rows past M re-read row M-1 (never stored), so the load count is fixed.
+  uint32_t xoff[S::kPasses];  // byte offsets from Xp + m0*K + tc*128
+#pragma unroll
+  for (int i = 0; i < S::kPasses; ++i) {
+    const int row = xrow + S::kRowsPerPass * i;
+    xoff[i] = 2u * (uint32_t)((min(m0 + row, p.M - 1) - m0) * p.K + swz(row, xunit) * 8);
+  }
+  const _Float16* xbase = p.Xp + (int64_t)m0 * p.K;
+  const uint32_t xs_base = (uint32_t)(uintptr_t)(lptr_t)Xs;
+  auto issue_x = [&](int e) __attribute__((always_inline)) {
+    const int tc = __builtin_amdgcn_readfirstlane(seq[e]) & 511;
+    const uint32_t dst = xs_base + (e & 1) * kBufBytes + wave * 1024;
+    const _Float16* src = xbase + tc * 128;
+#pragma unroll
+    for (int i = 0; i < S::kPasses; ++i) load_to_lds_16(src, xoff[i], dst + i * (S::kRowsPerPass * 256));
+  };
+  // operand read addresses: row 16*(MI*wm + i) + i16, unit 4*kappa + kb -> byte offset aoff[kappa] + 4096*i
+  uint32_t aoff[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) aoff[k] = (uint32_t)((16 * MI * wm + i16) * 256 + swz(i16, 4 * k + kb) * 16);
+
+  // Packed weights of one tile for this wavefront: one load of 4*b bytes per slab and lane, whatever the
+  // width (equal load counts on the three paths keep the compiler's wait counts exact), plus NS
+  // consecutive fp16 scales and zeros (rows 8*i16 + NS*wn + 0..NS-1 of the tile).
+  struct SZ {
+    uint32_t s[NS / 2], z[NS / 2];
+  };
+  auto issue_sz = [&](int tc, SZ& rsz) __attribute__((always_inline)) {
+    const int64_t off = (int64_t)tc * p.N + (int64_t)tr * 128 + 8 * i16 + NS * wn;
+#pragma unroll
+    for (int q = 0; q < NS / 2; ++q) {
+      rsz.s[q] = reinterpret_cast<const uint32_t*>(p.scales + off)[q];
+      rsz.z[q] = reinterpret_cast<const uint32_t*>(p.zeros + off)[q];
     }
-    const int64_t off = (int64_t)tc * p.N + (int64_t)tr * 128 + nloc;
-    rsz[0] = *reinterpret_cast<const uint32_t*>(p.scales + off);
-    rsz[1] = *reinterpret_cast<const uint32_t*>(p.zeros + off);
+  };
+  // width known at compile time (the next tile belongs to the same run): no branch around the loads, so
+  // they land in place and nothing waits for them before the next step
+  auto issue_w_static = [&](auto btag, int e, u32x4 (&rw)[NS], SZ& rsz) __attribute__((always_inline)) {
+    constexpr int B = decltype(btag)::value;
+    const int32_t d = __builtin_amdgcn_readfirstlane(seq[e]);
+    const uint8_t* stream = B == 2 ? p.s2 : B == 3 ? p.s3 : p.s4;
+    const uint8_t* src = stream + (int64_t)(d >> 9) * (2048 * B) + (NS * wn) * (256 * B) + lane * (4 * B);
+#pragma unroll
+    for (int q = 0; q < NS; ++q) {
+      if constexpr (B == 4) {
+        rw[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + q * 1024));
+      } else if constexpr (B == 3) {
+        const uint32_t* s3 = reinterpret_cast<const uint32_t*>(src + q * 768);  // 4-byte aligned: three dwords, merged
+        rw[q][0] = __builtin_nontemporal_load(s3);
+        rw[q][1] = __builtin_nontemporal_load(s3 + 1);
+        rw[q][2] = __builtin_nontemporal_load(s3 + 2);
+      } else {
+        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src + q * 512));
+        rw[q][0] = v[0];
+        rw[q][1] = v[1];
+      }
+    }
+    issue_sz(d & 511, rsz);
+  };
+  // width decided at run time (last tile of a run: the next one has another width)
+  auto issue_w_dynamic = [&](int e, u32x4 (&rw)[NS], SZ& rsz) __attribute__((always_inline)) {
+    if (e < end2)
+      issue_w_static(std::integral_constant<int, 2>{}, e, rw, rsz);
+    else if (e < end3)
+      issue_w_static(std::integral_constant<int, 3>{}, e, rw, rsz);
+    else
+      issue_w_static(std::integral_constant<int, 4>{}, e, rw, rsz);
   };
 
-  // One K step.  r holds the weights of tile tc and xr its activations.  Afterwards xr is refilled with
-  // step tc+1 (mostly L2 hits: the M block is shared by all tile rows on this XCD) and r with step
-  // tc+2 (first touch of a weight tile goes to HBM: it needs the longer look-ahead).  Loads past the
-  // end re-read the last tile: unconditional, so that the counts stay exact.
-  auto step = [&](int tc, XRegs& xr, uint32_t (&rw)[8], uint32_t (&rsz)[2], int32_t& rdesc) __attribute__((always_inline)) {
-    __syncthreads();  // previous step's MFMA reads of LDS are done
-#define SFMP_STX(i)                                                                 \
-  {                                                                                 \
-    const int row = xrow + 16 * i;                                                  \
-    *reinterpret_cast<u32x4*>(Xs + row * 128 + swz(row, xunit) * 8) = xr.v##i;      \
-  }
-    SFMP_FOR8(SFMP_STX)
-#undef SFMP_STX
+  u32x4 fw[NS];  // landing registers of the next tile's packed words
+#pragma unroll
+  for (int q = 0; q < NS; ++q) fw[q] = u32x4{0u, 0u, 0u, 0u};
+  SZ fsz;
+
+  // One K step of width B.  The weights never touch LDS: a slab is already laid out as an MFMA B operand
+  // (lane = row-in-16 x k-block), so each wavefront dequantises the slabs of its own output columns in
+  // registers.
+  auto step = [&](auto btag, auto same_run, int e) __attribute__((always_inline)) {
+    constexpr int B = decltype(btag)::value;
+    // Loads complete in issue order, and the previous step issued X(e) before W(e): the wait the compiler
+    // puts in front of these moves (the landing registers then receive tile e+1) also covers the LDS-DMA
+    // loads of block e.  After the barrier every wavefront's part of the block is there, and the other
+    // buffer is free.
+    u32x4 w[NS];
+    SZ rsz;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+      w[i] = fw[i];
+      asm volatile("" : "+v"(w[i]));
+    }
+#pragma unroll
+    for (int i = 0; i < NS / 2; ++i) {
+      rsz.s[i] = fsz.s[i];
+      rsz.z[i] = fsz.z[i];
+      asm volatile("" : "+v"(rsz.s[i]), "+v"(rsz.z[i]));
+    }
+    // no operand read of the previous step may still be in the LDS queue when the barrier opens the
+    // other buffer for overwriting
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    // the last step re-issues its own tile into the idle buffer and the landing registers: same load
+    // count on every path
+    const int nxt = min(e + 1, p.ntc - 1);
     {
+      const int tc = __builtin_amdgcn_readfirstlane(seq[nxt]) & 511;
+      const uint32_t dst = xs_base + ((e + 1) & 1) * kBufBytes + wave * 1024;
+      const _Float16* src = xbase + tc * 128;
+#pragma unroll
+      for (int i = 0; i < S::kPasses; ++i) load_to_lds_16(src, xoff[i], dst + i * (S::kRowsPerPass * 256));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (decltype(same_run)::value)
+      issue_w_static(btag, nxt, fw, fsz);
+    else
+      issue_w_dynamic(nxt, fw, fsz);
+    __builtin_amdgcn_sched_barrier(0);
+    half2_ s2[NS], z2[NS];
+#pragma unroll
+    for (int j = 0; j < NS; ++j) {
       union {
         uint32_t u;
-        half2_ h;
-      } s, z;
-      s.u = rsz[0];
-      z.u = rsz[1];
-      switch (rdesc & 3) {
-        case 0:
-          dequant_slab_to_lds<2>(&rw[0], s.h[0], z.h[0], Ws, nloc, kb);
-          dequant_slab_to_lds<2>(&rw[4], s.h[1], z.h[1], Ws, nloc + 1, kb);
-          break;
-        case 1:
-          dequant_slab_to_lds<3>(&rw[0], s.h[0], z.h[0], Ws, nloc, kb);
-          dequant_slab_to_lds<3>(&rw[4], s.h[1], z.h[1], Ws, nloc + 1, kb);
-          break;
-        default:
-          dequant_slab_to_lds<4>(&rw[0], s.h[0], z.h[0], Ws, nloc, kb);
-          dequant_slab_to_lds<4>(&rw[4], s.h[1], z.h[1], Ws, nloc + 1, kb);
-          break;
-      }
+        _Float16 h[2];
+      } sv, zv;
+      sv.u = rsz.s[j / 2];
+      zv.u = rsz.z[j / 2];
+      s2[j] = half2_{sv.h[j % 2], sv.h[j % 2]};
+      z2[j] = half2_{zv.h[j % 2], zv.h[j % 2]};
     }
-    __syncthreads();
-    issue_x(min(tc + 1, p.ntc - 1), xr);
-    issue_w(min(tc + 2, p.ntc - 1), rw, rsz, rdesc);
-#pragma unroll 1
-    for (int kappa = 0; kappa < 4; ++kappa) {
-      half8 a[4], b[4];
-      const int unit = 4 * kappa + kb;
+    // Software pipeline over the four k-steps: while the MFMAs of k-step kappa run, the activation
+    // operands of kappa+1 are read from LDS and the weight operands of kappa+1 are dequantised; the
+    // scheduling groups spread those between the MFMAs (an MFMA occupies the matrix pipe for 16 cycles
+    // but the issue port for 4).
+    const unsigned char* Xb = Xs + (e & 1) * kBufBytes;
+    half8 a0[MI], a1[MI], b0[NS], b1[NS];
+    auto read_a = [&](auto ktag, half8(&a)[MI]) __attribute__((always_inline)) {
+      const unsigned char* base = Xb + aoff[decltype(ktag)::value];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = 64 * wm + 16 * i + i16;
-        a[i] = *reinterpret_cast<const half8*>(Xs + row * 128 + swz(row, unit) * 8);
+      for (int i = 0; i < MI; ++i) a[i] = *reinterpret_cast<const half8*>(base + i * 4096);
+    };
+    auto make_b = [&](auto ktag, half8(&b)[NS]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int j = 0; j < NS; ++j) {
+        const uint32_t words[4] = {w[j][0], w[j][1], w[j][2], w[j][3]};
+        b[j] = dequant_operand<B, decltype(ktag)::value>(words, s2[j], z2[j], magic);
       }
+    };
+    auto mfmas = [&](const half8(&a)[MI], const half8(&b)[NS]) __attribute__((always_inline)) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int row = 64 * wn + 16 * j + i16;
-        b[j] = *reinterpret_cast<const half8*>(Ws + row * 128 + swz(row, unit) * 8);
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NS; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+    };
+    auto interleave = [&]() __attribute__((always_inline)) {
+#pragma unroll
+      for (int g = 0; g < MI * NS; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // VALU
       }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
+    };
+    const std::integral_constant<int, 0> k0;
+    const std::integral_constant<int, 1> k1;
+    const std::integral_constant<int, 2> k2;
+    const std::integral_constant<int, 3> k3;
+    read_a(k0, a0);
+    make_b(k0, b0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(a0, b0);
+    read_a(k1, a1);
+    make_b(k1, b1);
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(a1, b1);
+    read_a(k2, a0);
+    make_b(k2, b0);
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(a0, b0);
+    read_a(k3, a1);
+    make_b(k3, b1);
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(a1, b1);
   };
 
-  uint32_t w0[8], w1[8], sz0[2], sz1[2];
-  int32_t d0, d1;
-  issue_w(0, w0, sz0, d0);
-  issue_w(min(1, p.ntc - 1), w1, sz1, d1);
-  XRegs xr;  // 8 rows x 16 bytes of the activation block of the next step
-  issue_x(0, xr);
-  int tc = 0;
-  for (; tc + 1 < p.ntc; tc += 2) {
-    step(tc, xr, w0, sz0, d0);
-    step(tc + 1, xr, w1, sz1, d1);
-  }
-  if (tc < p.ntc) step(tc, xr, w0, sz0, d0);
+  issue_x(0);
+  __builtin_amdgcn_sched_barrier(0);
+  issue_w_dynamic(0, fw, fsz);
+  __builtin_amdgcn_sched_barrier(0);
+  const std::integral_constant<bool, true> same_run;
+  const std::integral_constant<bool, false> run_ends;
+  const std::integral_constant<int, 2> b2;
+  const std::integral_constant<int, 3> b3;
+  const std::integral_constant<int, 4> b4;
+  int e = 0;
+  for (; e + 1 < end2; ++e) step(b2, same_run, e);
+  if (e < end2) step(b2, run_ends, e++);
+  for (; e + 1 < end3; ++e) step(b3, same_run, e);
+  if (e < end3) step(b3, run_ends, e++);
+  for (; e + 1 < p.ntc; ++e) step(b4, same_run, e);
+  if (e < p.ntc) step(b4, run_ends, e++);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the idle re-issue of the last step
 
-  // epilogue: acc[i][j][r] = C[m0 + 64wm + 16i + 4*kb + r][128tr + 64wn + 16j + i16]; 16 lanes write 32
-  // contiguous bytes of one row
+  // epilogue: acc[i][j][r] = C[m0 + 16*MI*wm + 16i + 4kb + r][128tr + 8*i16 + NS*wn + j]: the NS values j
+  // of a lane are consecutive output columns -> one 2*NS-byte store
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int64_t n = (int64_t)tr * 128 + 64 * wn + 16 * j + i16;
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int r = 0; r < 4; ++r) {
+      const int m = m0 + 16 * MI * wm + 16 * i + 4 * kb + r;
+      union {
+        _Float16 h[NS];
+        uint32_t u[NS / 2];
+      } o;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int m = m0 + 64 * wm + 16 * i + 4 * kb + r;
-        if (m < p.M) p.Yt[(int64_t)m * p.N + n] = (_Float16)acc[i][j][r];
+      for (int j = 0; j < NS; ++j) o.h[j] = (_Float16)acc[i][j][r];
+      if (m < p.M) {
+        uint32_t* dst = reinterpret_cast<uint32_t*>(p.Yt + (int64_t)m * p.N + (int64_t)tr * 128 + 8 * i16 + NS * wn);
+        if constexpr (NS == 4) {
+          *reinterpret_cast<u32x2*>(dst) = u32x2{o.u[0], o.u[1]};
+        } else {
+#pragma unroll
+          for (int q = 0; q < NS / 2; ++q) dst[q] = o.u[q];
+        }
       }
-  }
+    }
+}
+
+#ifdef SFMP_EXPERIMENT
+extern int g_sfmp_debug;
+#endif
+
+template <int BM, int WM, int WN>
+static void launch_prefill_shape(PrefillParams p, int M, hipStream_t stream) {
+  p.n_mtiles = (M + BM - 1) / BM;
+  const unsigned grid = 8u * (unsigned)((p.n_mtiles + 7) / 8) * (unsigned)p.ntr;
+  hipLaunchKernelGGL((prefill_kernel<BM, WM, WN>), dim3(grid), dim3(64 * WM * WN), 0, stream, p);
 }
 
 PrefillPlan make_prefill_plan(int32_t N, int32_t K, int32_t M) {
@@ -340,7 +509,7 @@ int launch_prefill(const GemmArgs& a, void* stream) {
   p.s2 = a.s2;
   p.s3 = a.s3;
   p.s4 = a.s4;
-  p.tile_desc = a.index + 3;
+  p.index = a.index;
   p.scales = (const _Float16*)a.scales;
   p.zeros = (const _Float16*)a.zeros;
   p.Yt = Yt;
@@ -349,9 +518,18 @@ int launch_prefill(const GemmArgs& a, void* stream) {
   p.K = L->K;
   p.ntr = L->N / kTile;
   p.ntc = L->K / kTile;
-  p.n_mtiles = (a.M + kBM - 1) / kBM;
-  const unsigned grid = 8u * (unsigned)((p.n_mtiles + 7) / 8) * (unsigned)p.ntr;
-  hipLaunchKernelGGL(prefill_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, p);
+  p.n_mtiles = 0;
+#ifdef SFMP_EXPERIMENT
+  switch (g_sfmp_debug & 7) {
+    case 1: launch_prefill_shape<128, 1, 4>(p, a.M, (hipStream_t)stream); break;
+    case 2: launch_prefill_shape<256, 2, 2>(p, a.M, (hipStream_t)stream); break;
+    case 3: launch_prefill_shape<256, 1, 4>(p, a.M, (hipStream_t)stream); break;
+    case 4: launch_prefill_shape<256, 2, 4>(p, a.M, (hipStream_t)stream); break;
+    default: launch_prefill_shape<128, 2, 2>(p, a.M, (hipStream_t)stream); break;
+  }
+#else
+  launch_prefill_shape<128, 1, 4>(p, a.M, (hipStream_t)stream);
+#endif
   if (int e = check_launch("sfmp_gemm prefill launch")) return e;
   if (a.row_perm) {
     hipLaunchKernelGGL(scatter_cols_kernel, dim3((unsigned)a.M), dim3(256), (size_t)L->N * 2, (hipStream_t)stream,
