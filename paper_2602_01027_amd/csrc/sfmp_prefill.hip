@@ -1,27 +1,27 @@
-// Prefill path (M > 16): dequantise-to-LDS + fp16 MFMA GEMM for gfx950.
+// Prefill path (M > 16): fp16 MFMA GEMM with the weights dequantised in registers, for gfx950.
 //
 // Three kernels on one stream:
 //  1. gather_cols_kernel (only with a column permutation): Xp[m, j] = X[m, col_perm[j]], one row
 //     through LDS per workgroup (coalesced read, coalesced 16-byte writes).  A random column gather
 //     inside the GEMM would turn every 2-byte element into its own cache-line request for each of
 //     the N/128 workgroups that need it; doing it once costs 4*M*K bytes of streaming traffic.
-//  2. prefill_kernel: workgroup = 128 (M) x 128 (N, one tile row) output block, 4 wavefronts in a
-//     2x2 arrangement of 64x64 sub-blocks, two workgroups per CU.  K is walked one 128x128 weight
-//     tile (= one quantisation group) per step.  A packed slab is already laid out as an MFMA B
-//     operand (lane = weight row-in-16 x k-block of 8), so the weights never touch LDS: each wavefront
-//     loads the four slabs of its 64 output columns, unpacks them with the shared routines and
-//     dequantises in registers (exact q from the 0x6400 magic, then fp16(s*q + z) with one FMA,
-//     Appendix B Eq. 11) straight into the B operands of v_mfma_f32_16x16x32_f16.  Only the activation
-//     block goes through LDS (double-buffered, 256-byte rows, 16-byte units XOR-swizzled by
-//     (row%16)^(row/16): conflict-free operand reads), one barrier per step.  The version that staged
-//     dequantised weights in LDS was bound by LDS bandwidth (192 KiB per step against 96 KiB now).
-//     Weight loads run two steps ahead (three rotating register sets), activation loads one step; tile
-//     descriptors are read once into LDS; the load sequence is the same for every width so that the
-//     compiler can keep younger loads in flight (exact s_waitcnt counts).
+//  2. prefill_kernel: workgroup = 128 (M) x 128 (N, one tile row) output block, 4 wavefronts, each
+//     128 rows x 32 columns (two slabs), two workgroups per CU.  K is walked one 128x128 weight tile
+//     (= one quantisation group) per step, the tiles of the tile row sorted by width (the order of a
+//     sum is free, and the CSR part of the block-index table lists exactly these runs): three loops,
+//     each with a straight-line body for its width.  A packed slab is already laid out as an MFMA B
+//     operand (lane = weight row-in-16 x k-block of 8), so the weights never touch LDS: each
+//     wavefront loads the slabs of its own output columns and dequantises them in registers (mask-or
+//     into the 0x6400 magic, exact q, then fp16(s*q + z) with one FMA, Appendix B Eq. 11) straight
+//     into the B operands of v_mfma_f32_16x16x32_f16; every operand feeds eight MFMAs.  The activation
+//     block goes from global memory directly into LDS (LDS-DMA, double-buffered, 256-byte rows,
+//     16-byte units XOR-swizzled by row%16: conflict-free operand reads whose addresses differ by
+//     immediates).  A step is software-pipelined over its four k-steps and into the next step; one
+//     barrier per step.  The product leaves through LDS in whole 256-byte row segments.
 //  3. scatter_cols_kernel (only with a row permutation): the GEMM writes the product in reordered
-//     row order with coalesced stores into the workspace, then Y[m, row_perm[i]] = Yt[m, i] is done
-//     one row through LDS.  Scattering 2-byte results straight from the GEMM epilogue leaves
-//     half-written cache lines all over Y and doubled the kernel time.
+//     row order into the workspace, then Y[m, row_perm[i]] = Yt[m, i] is done one row through LDS.
+//     Scattering 2-byte results straight from the GEMM epilogue leaves half-written cache lines all
+//     over Y and doubled the kernel time.
 #include <type_traits>
 
 #include "sfmp_device.h"
@@ -114,10 +114,13 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 // 16 bytes per lane from global memory straight into LDS at lds_base + 16*lane.  Written as inline
 // assembly so that the compiler's wait-count bookkeeping does not see it: the kernel orders these
 // loads itself (they complete in issue order with the ordinary loads around them).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"  // m0 is named as clobbered on purpose
 __device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t byte_offset, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(base), "v"(byte_offset), "s"(lds_base)
                : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // 256-byte LDS rows of the activation block: 16-byte unit u of row r is stored at position u ^ (r % 16).  The 16
 // rows that one quarter of a wavefront reads for an MFMA operand then hit 16 different positions (all 64
@@ -166,7 +169,7 @@ struct PrefillShape {
   static constexpr int kPasses = BM / kRowsPerPass;
 };
 
-template <int BM, int WM, int WN>
+template <int BM, int WM, int WN, int IL = 2>
 __global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) / 4)) void prefill_kernel(const PrefillParams p) {
   using S = PrefillShape<BM, WM, WN>;
   constexpr int MI = S::kMI, NS = S::kNS;
@@ -198,8 +201,14 @@ __global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) 
   const int end3 = end2 + row_ptr[(p.ntr + 1) + tr + 1] - first3;
   const int32_t total2 = p.index[0], total3 = p.index[1];
   for (int e = tid; e < p.ntc; e += S::kThreads) {
-    // position in its stream, and position of that stream's column list
-    const int32_t slot = e < end2 ? first2 + e : e < end3 ? first3 + (e - end2) : first4 + (e - end3);
+    // Position in its stream, and position of that stream's column list.  Each tile row walks its runs
+    // from a different starting point: the workgroups of one XCD all read the same activation rows, and
+    // 256-byte pieces at the same tile column of rows K*2 bytes apart sit in the same L2 channel, so
+    // workgroups marching in step would all queue at one channel.
+    const int32_t lo = e < end2 ? 0 : e < end3 ? end2 : end3;
+    const int32_t n = (e < end2 ? end2 : e < end3 ? end3 : p.ntc) - lo;
+    const int32_t i = (e - lo + tr * 5) % n;
+    const int32_t slot = (e < end2 ? first2 : e < end3 ? first3 : first4) + i;
     const int32_t cols = e < end2 ? 0 : e < end3 ? total2 : total2 + total3;
     seq[e] = (slot << 9) | col_idx[cols + slot];
   }
@@ -229,9 +238,11 @@ __global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) 
   }
   const _Float16* xbase = p.Xp + (int64_t)m0 * p.K;
   const uint32_t xs_base = (uint32_t)(uintptr_t)(lptr_t)Xs;
-  auto issue_x = [&](int e) __attribute__((always_inline)) {
+  // block of tile position e into the buffer that block `like` uses (like = e mod 2, except for the idle
+  // loads past the end)
+  auto issue_x = [&](int e, int like) __attribute__((always_inline)) {
     const int tc = __builtin_amdgcn_readfirstlane(seq[e]) & 511;
-    const uint32_t dst = xs_base + (e & 1) * kBufBytes + wave * 1024;
+    const uint32_t dst = xs_base + (like & 1) * kBufBytes + wave * 1024;
     const _Float16* src = xbase + tc * 128;
 #pragma unroll
     for (int i = 0; i < S::kPasses; ++i) load_to_lds_16(src, xoff[i], dst + i * (S::kRowsPerPass * 256));
@@ -279,14 +290,22 @@ __global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) 
     }
     issue_sz(d & 511, rsz);
   };
-  // width decided at run time (last tile of a run: the next one has another width)
-  auto issue_w_dynamic = [&](int e, u32x4 (&rw)[NS], SZ& rsz) __attribute__((always_inline)) {
-    if (e < end2)
-      issue_w_static(std::integral_constant<int, 2>{}, e, rw, rsz);
-    else if (e < end3)
-      issue_w_static(std::integral_constant<int, 3>{}, e, rw, rsz);
-    else
-      issue_w_static(std::integral_constant<int, 4>{}, e, rw, rsz);
+  // width decided at run time (near the end of a run, where the tile two steps ahead has another width):
+  // the same load sequence for every width, the words a narrower width does not have re-read its last
+  // word.  No branch around the loads, so they land in place.
+  auto issue_w_generic = [&](int e, u32x4 (&rw)[NS], SZ& rsz) __attribute__((always_inline)) {
+    const int32_t d = __builtin_amdgcn_readfirstlane(seq[e]);
+    const int bw = e < end2 ? 2 : e < end3 ? 3 : 4;
+    const uint8_t* stream = bw == 2 ? p.s2 : bw == 3 ? p.s3 : p.s4;
+    const uint8_t* src = stream + (int64_t)(d >> 9) * (2048 * bw) + (NS * wn) * (256 * bw) + lane * (4 * bw);
+#pragma unroll
+    for (int q = 0; q < NS; ++q) {
+      const uint32_t* s = reinterpret_cast<const uint32_t*>(src + q * (256 * bw));
+      const uint32_t v0 = __builtin_nontemporal_load(s), v1 = __builtin_nontemporal_load(s + 1),
+                     v2 = __builtin_nontemporal_load(s + min(2, bw - 1)), v3 = __builtin_nontemporal_load(s + bw - 1);
+      rw[q] = u32x4{v0, v1, v2, v3};
+    }
+    issue_sz(d & 511, rsz);
   };
 
   u32x4 fw[NS];  // landing registers of the next tile's packed words
@@ -294,16 +313,59 @@ __global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) 
   for (int q = 0; q < NS; ++q) fw[q] = u32x4{0u, 0u, 0u, 0u};
   SZ fsz;
 
-  // One K step of width B.  The weights never touch LDS: a slab is already laid out as an MFMA B operand
-  // (lane = row-in-16 x k-block), so each wavefront dequantises the slabs of its own output columns in
-  // registers.
-  auto step = [&](auto btag, auto same_run, int e) __attribute__((always_inline)) {
-    constexpr int B = decltype(btag)::value;
-    // Loads complete in issue order, and the previous step issued X(e) before W(e): the wait the compiler
-    // puts in front of these moves (the landing registers then receive tile e+1) also covers the LDS-DMA
-    // loads of block e.  After the barrier every wavefront's part of the block is there, and the other
-    // buffer is free.
-    u32x4 w[NS];
+  // ---- the software pipeline -------------------------------------------------------------------------
+  // State between steps: w / s2 / z2 = packed words, scales, zeros of tile e; a0 / b0 = the MFMA operands
+  // of its k-step 0; in flight: activation block e+1 (into the other LDS buffer) and the weights of tile
+  // e+1 (into fw).  A step runs four groups; in each the MFMAs of one k-step are interleaved with the LDS
+  // reads and the dequantisation of the next one (an MFMA occupies the matrix pipe for 16 cycles but the
+  // issue port for 4).  Between the third and the fourth group sits the only synchronisation point: all
+  // operand reads of block e have returned, block e+1 and tile e+1 have landed, a barrier, and the loads of
+  // e+2 start; the fourth group then already prepares k-step 0 of tile e+1.
+  u32x4 w[NS];
+  half2_ s2[NS], z2[NS];
+  half8 a0[MI], a1[MI], b0[NS], b1[NS];
+
+  auto read_a = [&](int e, auto ktag, half8(&a)[MI]) __attribute__((always_inline)) {
+    const unsigned char* base = Xs + (e & 1) * kBufBytes + aoff[decltype(ktag)::value];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) a[i] = *reinterpret_cast<const half8*>(base + i * 4096);
+  };
+  auto make_b = [&](auto btag, auto ktag, half8(&b)[NS]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < NS; ++j) {
+      const uint32_t words[4] = {w[j][0], w[j][1], w[j][2], w[j][3]};
+      b[j] = dequant_operand<decltype(btag)::value, decltype(ktag)::value>(words, s2[j], z2[j], magic);
+    }
+  };
+  auto make_b_any = [&](int e, auto ktag, half8(&b)[NS]) __attribute__((always_inline)) {
+    if (e < end2)
+      make_b(std::integral_constant<int, 2>{}, ktag, b);
+    else if (e < end3)
+      make_b(std::integral_constant<int, 3>{}, ktag, b);
+    else
+      make_b(std::integral_constant<int, 4>{}, ktag, b);
+  };
+  auto mfmas = [&](const half8(&a)[MI], const half8(&b)[NS]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NS; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+  };
+  auto interleave = [&]() __attribute__((always_inline)) {
+    if constexpr (IL > 0) {
+#pragma unroll
+      for (int g = 0; g < MI * NS; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+        __builtin_amdgcn_sched_group_barrier(0x002, IL, 0);  // VALU
+      }
+    }
+  };
+  // Synchronisation point.  Loads complete in issue order and X(e+1) was issued before W(e+1): the wait
+  // the compiler puts in front of the moves out of the landing registers also covers the LDS-DMA loads of
+  // block e+1.  No operand read may still be in the LDS queue when the barrier opens this step's buffer
+  // for overwriting.
+  auto sync_and_issue = [&](int e, auto in_run, auto btag) __attribute__((always_inline)) {
     SZ rsz;
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
@@ -316,28 +378,6 @@ __global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) 
       rsz.z[i] = fsz.z[i];
       asm volatile("" : "+v"(rsz.s[i]), "+v"(rsz.z[i]));
     }
-    // no operand read of the previous step may still be in the LDS queue when the barrier opens the
-    // other buffer for overwriting
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    // the last step re-issues its own tile into the idle buffer and the landing registers: same load
-    // count on every path
-    const int nxt = min(e + 1, p.ntc - 1);
-    {
-      const int tc = __builtin_amdgcn_readfirstlane(seq[nxt]) & 511;
-      const uint32_t dst = xs_base + ((e + 1) & 1) * kBufBytes + wave * 1024;
-      const _Float16* src = xbase + tc * 128;
-#pragma unroll
-      for (int i = 0; i < S::kPasses; ++i) load_to_lds_16(src, xoff[i], dst + i * (S::kRowsPerPass * 256));
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (decltype(same_run)::value)
-      issue_w_static(btag, nxt, fw, fsz);
-    else
-      issue_w_dynamic(nxt, fw, fsz);
-    __builtin_amdgcn_sched_barrier(0);
-    half2_ s2[NS], z2[NS];
 #pragma unroll
     for (int j = 0; j < NS; ++j) {
       union {
@@ -349,115 +389,120 @@ __global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) 
       s2[j] = half2_{sv.h[j % 2], sv.h[j % 2]};
       z2[j] = half2_{zv.h[j % 2], zv.h[j % 2]};
     }
-    // Software pipeline over the four k-steps: while the MFMAs of k-step kappa run, the activation
-    // operands of kappa+1 are read from LDS and the weight operands of kappa+1 are dequantised; the
-    // scheduling groups spread those between the MFMAs (an MFMA occupies the matrix pipe for 16 cycles
-    // but the issue port for 4).
-    const unsigned char* Xb = Xs + (e & 1) * kBufBytes;
-    half8 a0[MI], a1[MI], b0[NS], b1[NS];
-    auto read_a = [&](auto ktag, half8(&a)[MI]) __attribute__((always_inline)) {
-      const unsigned char* base = Xb + aoff[decltype(ktag)::value];
-#pragma unroll
-      for (int i = 0; i < MI; ++i) a[i] = *reinterpret_cast<const half8*>(base + i * 4096);
-    };
-    auto make_b = [&](auto ktag, half8(&b)[NS]) __attribute__((always_inline)) {
-#pragma unroll
-      for (int j = 0; j < NS; ++j) {
-        const uint32_t words[4] = {w[j][0], w[j][1], w[j][2], w[j][3]};
-        b[j] = dequant_operand<B, decltype(ktag)::value>(words, s2[j], z2[j], magic);
-      }
-    };
-    auto mfmas = [&](const half8(&a)[MI], const half8(&b)[NS]) __attribute__((always_inline)) {
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NS; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], b[j], acc[i][j], 0, 0, 0);
-    };
-    auto interleave = [&]() __attribute__((always_inline)) {
-#pragma unroll
-      for (int g = 0; g < MI * NS; ++g) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
-        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // VALU
-      }
-    };
-    const std::integral_constant<int, 0> k0;
-    const std::integral_constant<int, 1> k1;
-    const std::integral_constant<int, 2> k2;
-    const std::integral_constant<int, 3> k3;
-    read_a(k0, a0);
-    make_b(k0, b0);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    // past the end the last tile is loaded again, into the idle buffer and the landing registers: same
+    // load count on every path
+    const int nn = min(e + 2, p.ntc - 1);
+    issue_x(nn, e);
     __builtin_amdgcn_sched_barrier(0);
+    if constexpr (decltype(in_run)::value)
+      issue_w_static(btag, nn, fw, fsz);
+    else
+      issue_w_generic(nn, fw, fsz);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  const std::integral_constant<int, 0> k0;
+  const std::integral_constant<int, 1> k1;
+  const std::integral_constant<int, 2> k2;
+  const std::integral_constant<int, 3> k3;
+
+  // in_run: tiles e+1 and e+2 have the same width B as tile e
+  auto step = [&](auto btag, auto in_run, int e) __attribute__((always_inline)) {
     mfmas(a0, b0);
-    read_a(k1, a1);
-    make_b(k1, b1);
+    read_a(e, k1, a1);
+    make_b(btag, k1, b1);
     interleave();
     __builtin_amdgcn_sched_barrier(0);
     mfmas(a1, b1);
-    read_a(k2, a0);
-    make_b(k2, b0);
+    read_a(e, k2, a0);
+    make_b(btag, k2, b0);
     interleave();
     __builtin_amdgcn_sched_barrier(0);
     mfmas(a0, b0);
-    read_a(k3, a1);
-    make_b(k3, b1);
+    read_a(e, k3, a1);
+    make_b(btag, k3, b1);
     interleave();
     __builtin_amdgcn_sched_barrier(0);
+    sync_and_issue(e, in_run, btag);
     mfmas(a1, b1);
+    read_a(e + 1, k0, a0);
+    if constexpr (decltype(in_run)::value) {
+      make_b(btag, k0, b0);
+      interleave();
+      __builtin_amdgcn_sched_barrier(0);
+    } else {
+      interleave();
+      __builtin_amdgcn_sched_barrier(0);
+      make_b_any(min(e + 1, p.ntc - 1), k0, b0);
+    }
   };
 
-  issue_x(0);
+  // prologue: tile 0 lands, then its k-step 0 is prepared while tile 1 is on its way
+  issue_x(0, 0);
   __builtin_amdgcn_sched_barrier(0);
-  issue_w_dynamic(0, fw, fsz);
+  issue_w_generic(0, fw, fsz);
   __builtin_amdgcn_sched_barrier(0);
-  const std::integral_constant<bool, true> same_run;
+  sync_and_issue(-1, std::integral_constant<bool, false>{}, k0);
+  read_a(0, k0, a0);
+  make_b_any(0, k0, b0);
+  __builtin_amdgcn_sched_barrier(0);
+
+  const std::integral_constant<bool, true> in_run;
   const std::integral_constant<bool, false> run_ends;
   const std::integral_constant<int, 2> b2;
   const std::integral_constant<int, 3> b3;
   const std::integral_constant<int, 4> b4;
   int e = 0;
-  for (; e + 1 < end2; ++e) step(b2, same_run, e);
-  if (e < end2) step(b2, run_ends, e++);
-  for (; e + 1 < end3; ++e) step(b3, same_run, e);
-  if (e < end3) step(b3, run_ends, e++);
-  for (; e + 1 < p.ntc; ++e) step(b4, same_run, e);
-  if (e < p.ntc) step(b4, run_ends, e++);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the idle re-issue of the last step
+  for (; e + 2 < end2; ++e) step(b2, in_run, e);
+  for (; e < end2; ++e) step(b2, run_ends, e);
+  for (; e + 2 < end3; ++e) step(b3, in_run, e);
+  for (; e < end3; ++e) step(b3, run_ends, e);
+  for (; e + 2 < p.ntc; ++e) step(b4, in_run, e);
+  for (; e < p.ntc; ++e) step(b4, run_ends, e);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the idle loads of the last two steps
 
-  // epilogue: acc[i][j][r] = C[m0 + 16*MI*wm + 16i + 4kb + r][128tr + 8*i16 + NS*wn + j]: the NS values j
-  // of a lane are consecutive output columns -> one 2*NS-byte store
+  // epilogue: the block goes through LDS (the activation buffers are free now) so that it leaves in whole
+  // 256-byte row segments: acc[i][j][r] = C[16*MI*wm + 16i + 4kb + r][8*i16 + NS*wn + j], the NS values j of
+  // a lane being consecutive columns.
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();  // every wavefront's idle loads have landed and its operand reads returned
+  asm volatile("" ::: "memory");
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int m = m0 + 16 * MI * wm + 16 * i + 4 * kb + r;
+      const int row = 16 * MI * wm + 16 * i + 4 * kb + r;
       union {
         _Float16 h[NS];
         uint32_t u[NS / 2];
       } o;
 #pragma unroll
       for (int j = 0; j < NS; ++j) o.h[j] = (_Float16)acc[i][j][r];
-      if (m < p.M) {
-        uint32_t* dst = reinterpret_cast<uint32_t*>(p.Yt + (int64_t)m * p.N + (int64_t)tr * 128 + 8 * i16 + NS * wn);
-        if constexpr (NS == 4) {
-          *reinterpret_cast<u32x2*>(dst) = u32x2{o.u[0], o.u[1]};
-        } else {
+      uint32_t* dst = reinterpret_cast<uint32_t*>(Xs + row * 256 + (8 * i16 + NS * wn) * 2);
 #pragma unroll
-          for (int q = 0; q < NS / 2; ++q) dst[q] = o.u[q];
-        }
-      }
+      for (int q = 0; q < NS / 2; ++q) dst[q] = o.u[q];
     }
+  __syncthreads();
+  _Float16* ybase = p.Yt + (int64_t)m0 * p.N + (int64_t)tr * 128;
+#pragma unroll
+  for (int i = 0; i < S::kPasses; ++i) {
+    const int row = xrow + S::kRowsPerPass * i;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(Xs + row * 256 + xunit * 16);
+    if (m0 + row < p.M) *reinterpret_cast<u32x4*>(ybase + (int64_t)row * p.N + xunit * 8) = v;
+  }
 }
 
 #ifdef SFMP_EXPERIMENT
 extern int g_sfmp_debug;
 #endif
 
-template <int BM, int WM, int WN>
+template <int BM, int WM, int WN, int IL = 2>
 static void launch_prefill_shape(PrefillParams p, int M, hipStream_t stream) {
   p.n_mtiles = (M + BM - 1) / BM;
   const unsigned grid = 8u * (unsigned)((p.n_mtiles + 7) / 8) * (unsigned)p.ntr;
-  hipLaunchKernelGGL((prefill_kernel<BM, WM, WN>), dim3(grid), dim3(64 * WM * WN), 0, stream, p);
+  hipLaunchKernelGGL((prefill_kernel<BM, WM, WN, IL>), dim3(grid), dim3(64 * WM * WN), 0, stream, p);
 }
 
 PrefillPlan make_prefill_plan(int32_t N, int32_t K, int32_t M) {
