@@ -27,7 +27,7 @@ int sfmp_gemm_workspace(const sfmp_layout_t* layout, int32_t M, int64_t* bytes) 
   if (M < 1) return SFMP_ERR_SHAPE;
   if (M <= kDecodeMaxM) {
     const DecodePlan d = make_decode_plan(layout->N, layout->K, M);
-    *bytes = d.counter_bytes + d.partial_bytes;
+    *bytes = d.workspace_bytes;
   } else {
     const PrefillPlan d = make_prefill_plan(layout->N, layout->K, M);
     *bytes = d.xperm_bytes + d.ytmp_bytes;

@@ -512,6 +512,242 @@ __global__ __launch_bounds__(256) void skinny_kernel(const SkinnyParams p) {
 }
 
 // ============================================================================================
+// skinny GEMM through the rings, 2 <= M <= 16
+// ============================================================================================
+// The GEMV scheme carried over to a few activation rows: a workgroup owns whole 16-row slabs over the
+// whole K range (no partial sums leave it), its wavefronts walk the tile columns, and everything an
+// item needs arrives in a ring slot by direct global->LDS copies.  With M rows the activation vector no
+// longer fits in LDS beside the rings, so the activations of an item's tile column (MB rows x 128
+// columns, MB = 4, 8 or 16 >= M) travel through the ring slot as well; a small pass before the GEMM
+// writes them into the workspace per tile column, column permutation applied, rows >= M zero, 16-byte
+// units of row m stored at position u ^ m (conflict-free MFMA operand reads).  These copies hit in L2.
+// The group sums of the activations come from one more MFMA against a vector of ones.
+struct RSkinnyParams {
+  const unsigned char* xblk;  // [ntc][MB][256 bytes], swizzled
+  const uint8_t* s2;
+  const uint8_t* s3;
+  const uint8_t* s4;
+  const int32_t* tile_desc;
+  const _Float16* scales;
+  const _Float16* zeros;
+  const int32_t* row_perm;
+  _Float16* Y;
+  int32_t M, N, K, ntr, ntc, nslab, max_slabs;
+};
+
+// one workgroup per tile column; thread (m, u) gathers the 8 columns of unit u' = u ^ m of row m
+template <int MB>
+__global__ __launch_bounds__(MB * 16) void stage_rows_kernel(const _Float16* __restrict__ X,
+                                                            const int32_t* __restrict__ col_perm, unsigned char* xblk,
+                                                            int M, int K) {
+  const int tc = blockIdx.x;
+  const int m = threadIdx.x / 16, pos = threadIdx.x % 16;
+  const int unit = pos ^ m;
+  half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (m < M) {
+    const int k0 = tc * kTile + unit * 8;
+    if (col_perm) {
+      const int4 c0 = reinterpret_cast<const int4*>(col_perm + k0)[0];
+      const int4 c1 = reinterpret_cast<const int4*>(col_perm + k0)[1];
+      const _Float16* row = X + (int64_t)m * K;
+      v[0] = row[c0.x];
+      v[1] = row[c0.y];
+      v[2] = row[c0.z];
+      v[3] = row[c0.w];
+      v[4] = row[c1.x];
+      v[5] = row[c1.y];
+      v[6] = row[c1.z];
+      v[7] = row[c1.w];
+    } else {
+      v = *reinterpret_cast<const half8*>(X + (int64_t)m * K + k0);
+    }
+  }
+  *reinterpret_cast<half8*>(xblk + ((int64_t)tc * MB + m) * 256 + pos * 16) = v;
+}
+
+template <int MB>
+constexpr int rskinny_slot_bytes() { return kSlotBytes + MB * 256; }
+
+template <int NW, int S, int MB>
+__global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  constexpr int NT = NW * 64;
+  constexpr int kSlot = rskinny_slot_bytes<MB>();
+  constexpr int kCopies = 2 + MB / 4;  // direct copies per item: slab, scales+zeros, MB/4 x 1 KiB of activations
+  // LDS: red [max_slabs][4][64] f32 | rings [NW][S][kSlot]
+  float* red = reinterpret_cast<float*>(lds_raw);
+  unsigned char* rings = lds_raw + (size_t)p.max_slabs * 1024;
+
+  const int tid = threadIdx.x;
+  const int lane = tid % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int bid = blockIdx.x, G = gridDim.x;
+  const int i16 = lane % 16, kb = lane / 16;
+  // same slab numbering as the GEMV kernel: the 8 slabs of a tile row run on one XCD
+  const int nj = (p.nslab - bid + G - 1) / G;
+  const int my_cnt = p.ntc > wave ? (p.ntc - wave + NW - 1) / NW : 0;
+  const int E = nj * my_cnt;  // items of this wavefront (<= 64)
+
+  uint32_t it_alo = 0, it_ahi = 0, it_slo = 0, it_shi = 0, it_misc = 0;
+  if (lane < E) {
+    const int j = lane / my_cnt, i = lane - j * my_cnt;
+    const int v = bid + G * j;
+    const int slab = (v % 8) * p.ntr + v / 8;
+    const int tr = slab / 8, sigma = slab % 8;
+    const int tc = wave + NW * i;
+    const int32_t d = p.tile_desc[(int64_t)tr * p.ntc + tc];
+    const int bm2 = d & 3;
+    const uint8_t* base = bm2 == 0 ? p.s2 : bm2 == 1 ? p.s3 : p.s4;
+    const int64_t slab_bytes = 256 * (bm2 + 2);
+    const uint64_t a = (uint64_t)(base + (int64_t)(d >> 2) * (8 * slab_bytes) + sigma * slab_bytes);
+    const uint64_t sa = (uint64_t)(p.scales + (int64_t)tc * p.N + (int64_t)tr * kTile + (sigma & ~1));
+    it_alo = (uint32_t)a;
+    it_ahi = (uint32_t)(a >> 32);
+    it_slo = (uint32_t)sa;
+    it_shi = (uint32_t)(sa >> 32);
+    it_misc = (uint32_t)tc | ((i == my_cnt - 1) ? 0x10000u : 0u) | ((uint32_t)j << 17) | ((uint32_t)bm2 << 24) |
+              ((uint32_t)(sigma & 1) << 26);
+  }
+  const uint32_t data_voff = lane * 16;
+  const int64_t sz_voff =
+      (int64_t)(lane & 15) * 16 + (lane < 16 ? (int64_t)0 : (int64_t)((const char*)p.zeros - (const char*)p.scales));
+
+  unsigned char* ring = rings + (size_t)wave * S * kSlot;
+  auto issue_item = [&](int e, int s) {
+    const uint64_t a = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_ahi, e) << 32) |
+                       (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_alo, e);
+    const uint64_t sa = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_shi, e) << 32) |
+                        (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_slo, e);
+    const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
+    const uint32_t slab_bytes = 256u * (((misc >> 24) & 3u) + 2u);
+    unsigned char* slot = ring + s * kSlot;
+    if (data_voff < slab_bytes)
+      __builtin_amdgcn_global_load_lds((gptr_t)((const char*)a + data_voff), (lptr_t)slot, 16, 0, 0);
+    if (lane < 32) __builtin_amdgcn_global_load_lds((gptr_t)((const char*)sa + sz_voff), (lptr_t)(slot + 1024), 4, 0, 0);
+    const unsigned char* xsrc = p.xblk + (int64_t)(misc & 0xFFFF) * (MB * 256) + data_voff;
+#pragma unroll
+    for (int c = 0; c < MB / 4; ++c)
+      __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + c * 1024), (lptr_t)(slot + kSlotBytes + c * 1024), 16, 0, 0);
+  };
+
+  const int npro = min(S, E);
+  for (int e = 0; e < npro; ++e) issue_item(e, e);
+
+  half8 ones;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) ones[v] = (_Float16)1.0f;
+  half8 a[4];
+#pragma unroll
+  for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+  // operand addresses inside a slot: activation row i16, unit 4*kappa + kb at position unit ^ i16
+  uint32_t a_off[4];
+#pragma unroll
+  for (int kappa = 0; kappa < 4; ++kappa) a_off[kappa] = kSlotBytes + i16 * 256 + (((4 * kappa + kb) ^ i16) * 16);
+
+  floatx4 accs[kGemvMaxSlabs];
+#pragma unroll
+  for (int q = 0; q < kGemvMaxSlabs; ++q) accs[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+  floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+
+  auto consume = [&](int e, int s) {
+    const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
+    const unsigned char* slot = ring + s * kSlot;
+    if (MB == 16 || i16 < MB) {
+#pragma unroll
+      for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = *reinterpret_cast<const half8*>(slot + a_off[kappa]);
+    }
+    floatx4 sx = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kappa = 0; kappa < 4; ++kappa) sx = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[kappa], ones, sx, 0, 0, 0);
+    floatx4 t;
+    {
+      uint32_t w[4];
+      const uint32_t* src;
+      switch ((misc >> 24) & 3) {
+        case 0:
+          src = reinterpret_cast<const uint32_t*>(slot + lane * 8);
+          w[0] = src[0], w[1] = src[1];
+          t = slab_dot<2>(w, a);
+          break;
+        case 1:
+          src = reinterpret_cast<const uint32_t*>(slot + lane * 12);
+          w[0] = src[0], w[1] = src[1], w[2] = src[2];
+          t = slab_dot<3>(w, a);
+          break;
+        default:
+          src = reinterpret_cast<const uint32_t*>(slot + lane * 16);
+          w[0] = src[0], w[1] = src[1], w[2] = src[2], w[3] = src[3];
+          t = slab_dot<4>(w, a);
+          break;
+      }
+    }
+    union {
+      uint32_t u;
+      half2_ h;
+    } sc, zr;
+    sc.u = *reinterpret_cast<const uint32_t*>(slot + 1024 + (lane & 15) * 4);
+    zr.u = *reinterpret_cast<const uint32_t*>(slot + 1088 + (lane & 15) * 4);
+    const bool odd = (misc >> 26) & 1;
+    const float sf = odd ? (float)sc.h[1] : (float)sc.h[0];
+    const float zf = odd ? (float)zr.h[1] : (float)zr.h[0];
+    acc += sf * t + zf * sx;
+    if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
+      switch ((misc >> 17) & 0x7F) {
+#define SFMP_CASE(q) case q: accs[q] = acc; break;
+        SFMP_CASE(0) SFMP_CASE(1) SFMP_CASE(2) SFMP_CASE(3) SFMP_CASE(4) SFMP_CASE(5) SFMP_CASE(6) SFMP_CASE(7)
+        SFMP_CASE(8) SFMP_CASE(9) SFMP_CASE(10) SFMP_CASE(11) SFMP_CASE(12) SFMP_CASE(13) SFMP_CASE(14)
+        SFMP_CASE(15)
+#undef SFMP_CASE
+        default: break;
+      }
+      acc = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+  };
+
+  int s = 0;
+  int e = 0;
+  for (; e + S < E; ++e) {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies * (S - 1)) : "memory");
+    consume(e, s);
+    issue_item(e + S, s);
+    if (++s == S) s = 0;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  for (; e < E; ++e) {
+    consume(e, s);
+    if (++s == S) s = 0;
+  }
+
+  // the wavefronts add their sums one after the other: a fixed order, so results repeat bit for bit
+  for (int w = 0; w < NW; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int q = 0; q < kGemvMaxSlabs; ++q)
+        if (q < nj) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            float* dst = red + (q * 4 + r) * 64 + lane;
+            *dst = (w == 0 ? 0.f : *dst) + accs[q][r];
+          }
+        }
+    }
+    __syncthreads();
+  }
+  for (int o = tid; o < nj * 256; o += NT) {
+    const int jj = o / 256, rem = o % 256;
+    const int r = rem / 64, l = rem % 64;
+    const int m = 4 * (l / 16) + r;
+    if (m < p.M) {
+      const int v = bid + G * jj;
+      const int slab = (v % 8) * p.ntr + v / 8;
+      const int64_t row = (int64_t)(slab / 8) * kTile + 8 * (l % 16) + (slab % 8);
+      const int64_t col = p.row_perm ? p.row_perm[row] : row;
+      p.Y[(int64_t)m * p.N + col] = (_Float16)red[o];
+    }
+  }
+}
+
+// ============================================================================================
 // host side
 // ============================================================================================
 static int after_launch(const char* what) {
@@ -546,8 +782,22 @@ static GemvFit gemv_fit(int32_t N, int32_t K, int32_t grid) {
   return f;
 }
 
+// ring-skinny variants: activation rows padded to MB, NW wavefronts, S ring slots
+struct RSkinnyShape {
+  int32_t mb, nw, slots;
+};
+static RSkinnyShape rskinny_shape(int32_t M) {
+  if (M <= 4) return {4, 8, 8};
+  if (M <= 8) return {8, 8, 5};
+  return {16, 8, 3};
+}
+
 DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
   DecodePlan d;
+  d.rskinny = false;
+  d.mb = 0;
+  d.xblk_bytes = 0;
+  d.workspace_bytes = 0;
   const int32_t ntr = N / kTile, ntc = K / kTile;
   // GEMV: persistent grid of at most 256 workgroups (multiple of 8), 16 wavefronts each.
   {
@@ -567,6 +817,30 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
       return d;
     }
   }
+  if (M >= 2) {
+    const RSkinnyShape sh = rskinny_shape(M);
+    const int32_t nslab = 8 * ntr;
+    const int32_t grid = nslab < kGemvMaxGrid ? nslab : kGemvMaxGrid;
+    const int32_t max_slabs = (nslab + grid - 1) / grid;
+    const int64_t items = (int64_t)max_slabs * ((ntc + sh.nw - 1) / sh.nw);
+    const int64_t lds = (int64_t)max_slabs * 1024 + (int64_t)sh.nw * sh.slots * (kSlotBytes + sh.mb * 256);
+    if (max_slabs <= kGemvMaxSlabs && items <= kGemvMaxItems && lds <= 160 * 1024) {
+      d.rskinny = true;
+      d.gemv = false;
+      d.mb = sh.mb;
+      d.tiles_per_chunk = ntc;
+      d.nchunk = 1;
+      d.row_groups = grid;
+      d.counter_bytes = 0;
+      d.partial_bytes = 0;
+      d.lds_bytes = (int32_t)lds;
+      d.gemv_slots = sh.slots;
+      d.gemv_max_slabs = max_slabs;
+      d.xblk_bytes = round_up_256((int64_t)ntc * sh.mb * 256);
+      d.workspace_bytes = d.xblk_bytes;
+      return d;
+    }
+  }
   // Few, long chunks keep the partial-sum traffic (128*M fp32 per wavefront, written and read
   // once) small next to the tile bytes; many chunks keep all 256 CUs busy.  Start from a chunk
   // length that grows with M and shorten it until about 2048 wavefronts exist.
@@ -580,6 +854,7 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
   d.counter_bytes = round_up_256((int64_t)ntr * 4);
   d.partial_bytes = d.nchunk > 1 ? round_up_256((int64_t)d.nchunk * M * N * 4) : 0;
   d.lds_bytes = tpc * M * 256;
+  d.workspace_bytes = d.counter_bytes + d.partial_bytes;
   return d;
 }
 
@@ -701,6 +976,57 @@ int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
   return launch_gemv_variant(slots, true, b, (unsigned)first, (size_t)lds, stream);
 }
 
+template <int NW, int S, int MB>
+static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* stream) {
+  const sfmp_layout_t* L = a.L;
+  static bool attr_set = false;
+  const void* fn = reinterpret_cast<const void*>(&rskinny_kernel<NW, S, MB>);
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) {
+      note_hip_error("hipFuncSetAttribute(skinny)", hipGetErrorString(e));
+      return SFMP_ERR_HIP;
+    }
+    attr_set = true;
+  }
+  const int32_t ntc = L->K / kTile;
+  hipLaunchKernelGGL((stage_rows_kernel<MB>), dim3((unsigned)ntc), dim3(MB * 16), 0, (hipStream_t)stream,
+                     (const _Float16*)a.X, a.col_perm, (unsigned char*)a.workspace, (int)a.M, (int)L->K);
+  if (int e = after_launch("sfmp_gemm activation staging launch")) return e;
+  RSkinnyParams p;
+  p.xblk = (const unsigned char*)a.workspace;
+  p.s2 = a.s2;
+  p.s3 = a.s3;
+  p.s4 = a.s4;
+  p.tile_desc = a.index + 3;
+  p.scales = (const _Float16*)a.scales;
+  p.zeros = (const _Float16*)a.zeros;
+  p.row_perm = a.row_perm;
+  p.Y = (_Float16*)a.Y;
+  p.M = a.M;
+  p.N = L->N;
+  p.K = L->K;
+  p.ntr = L->N / kTile;
+  p.ntc = ntc;
+  p.nslab = 8 * p.ntr;
+  p.max_slabs = d.gemv_max_slabs;
+  void* kargs[] = {&p};
+  hipError_t e = hipLaunchKernel(fn, dim3((unsigned)d.row_groups), dim3(NW * 64), kargs, (size_t)d.lds_bytes, (hipStream_t)stream);
+  if (e != hipSuccess) {
+    note_hip_error("sfmp_gemm skinny launch", hipGetErrorString(e));
+    return SFMP_ERR_HIP;
+  }
+  return after_launch("sfmp_gemm skinny launch");
+}
+
+static int launch_rskinny(const GemmArgs& a, const DecodePlan& d, void* stream) {
+  switch (d.mb) {
+    case 4: return launch_rskinny_variant<8, 8, 4>(a, d, stream);
+    case 8: return launch_rskinny_variant<8, 5, 8>(a, d, stream);
+    default: return launch_rskinny_variant<8, 3, 16>(a, d, stream);
+  }
+}
+
 int launch_decode(const GemmArgs& a, void* stream) {
   const sfmp_layout_t* L = a.L;
   const DecodePlan d = make_decode_plan(L->N, L->K, a.M);
@@ -708,6 +1034,7 @@ int launch_decode(const GemmArgs& a, void* stream) {
     const GemvParams p = gemv_params(a, d.gemv_max_slabs);
     return launch_gemv_variant(d.gemv_slots, false, p, (unsigned)d.row_groups, (size_t)d.lds_bytes, stream);
   }
+  if (d.rskinny) return launch_rskinny(a, d, stream);
   SkinnyParams p;
   p.X = (const _Float16*)a.X;
   p.col_perm = a.col_perm;

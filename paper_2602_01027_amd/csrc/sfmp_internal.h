@@ -21,6 +21,11 @@ struct DecodePlan {
   int64_t partial_bytes;
   int32_t lds_bytes;
   int32_t gemv_slots, gemv_max_slabs;
+  // 2 <= M <= 16 through the rings: activation rows padded to mb, staged per tile column in the workspace
+  bool rskinny;
+  int32_t mb;
+  int64_t xblk_bytes;
+  int64_t workspace_bytes;  // what sfmp_gemm needs for this plan
 };
 DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M);
 
