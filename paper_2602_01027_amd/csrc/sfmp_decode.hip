@@ -17,11 +17,9 @@
 // outputs are scattered through row_perm.  Workgroups are numbered so that the 8 slabs of a
 // tile row run on the same XCD (they share scale/zero cache lines and the index table).
 //
-// Skinny GEMM (2..16): a wavefront owns a tile row and walks a chunk of tiles of that row; the
-// four tile rows of a workgroup share the gathered activation chunk in LDS.  Partial sums go to
-// the workspace with device-scope atomic stores; an arrival counter per tile row lets the last
-// wavefront add them in chunk order (deterministic), convert and scatter.  No cache-wide fence
-// is used: ordering comes from s_waitcnt on the atomic stores before the counter increment.
+// Skinny GEMM (2..16), and any M = 1 problem whose activation vector does not fit in LDS beside the
+// rings: the same scheme with the activations of each tile column travelling through the ring slots
+// (see rskinny_kernel).
 #include "sfmp_device.h"
 #include "sfmp_internal.h"
 
@@ -338,180 +336,6 @@ __global__ __launch_bounds__(NW * 64) void gemv_batched_kernel(const GemvBatch b
 }
 
 // ============================================================================================
-// skinny GEMM, 2 <= M <= 16
-// ============================================================================================
-struct SkinnyParams {
-  const _Float16* X;
-  const int32_t* col_perm;
-  const uint8_t* s2;
-  const uint8_t* s3;
-  const uint8_t* s4;
-  const int32_t* tile_desc;
-  const _Float16* scales;
-  const _Float16* zeros;
-  const int32_t* row_perm;
-  _Float16* Y;
-  float* partial;
-  int32_t* counters;
-  int32_t M, N, K, ntr, ntc, tiles_per_chunk, nchunk;
-};
-
-template <int B>
-__device__ __forceinline__ void issue_tile_loads(const uint8_t* tile, int lane, uint32_t (&w)[32]) {
-#pragma unroll
-  for (int sigma = 0; sigma < 8; ++sigma) load_slab_words<B>(tile, sigma, lane, &w[sigma * B]);
-}
-
-template <int B>
-__device__ __forceinline__ void contract_tile(const uint32_t (&w)[32], const half8 (&a)[4], const floatx4& sx,
-                                              const u32x4& sraw, const u32x4& zraw, float (&acc)[8][4]) {
-  union {
-    u32x4 u;
-    half8 h;
-  } sc, zr;
-  sc.u = sraw;
-  zr.u = zraw;
-#pragma unroll
-  for (int sigma = 0; sigma < 8; ++sigma) {
-    const floatx4 t = slab_dot<B>(&w[sigma * B], a);
-    const float s = (float)sc.h[sigma];
-    const float z = (float)zr.h[sigma];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) acc[sigma][r] += s * t[r] + z * sx[r];
-  }
-}
-
-__global__ __launch_bounds__(256) void skinny_kernel(const SkinnyParams p) {
-  extern __shared__ __align__(16) unsigned char lds_raw[];
-  _Float16* Xs = reinterpret_cast<_Float16*>(lds_raw);  // [tile*16 + kblock][M][8]
-
-  const int tid = threadIdx.x;
-  const int lane = tid % kWave;
-  const int wave = tid / kWave;
-  const int chunk = blockIdx.x % p.nchunk;
-  const int rowgroup = blockIdx.x / p.nchunk;
-  const int tr = rowgroup * 4 + wave;
-  const bool active = tr < p.ntr;
-  const int tc0 = chunk * p.tiles_per_chunk;
-  const int ntile = min(p.tiles_per_chunk, p.ntc - tc0);
-  const int M = p.M;
-
-  // first tile: descriptor, packed words, scales and zeros are requested before anything else
-  uint32_t w[32];
-  u32x4 sraw = {0, 0, 0, 0}, zraw = {0, 0, 0, 0};
-  int32_t desc = 0;
-  const int64_t sz_lane_off = (int64_t)(active ? tr : 0) * kTile + 8 * (lane % 16);
-  auto issue = [&](int t) {
-    desc = __builtin_amdgcn_readfirstlane(p.tile_desc[(int64_t)tr * p.ntc + tc0 + t]);
-    const int64_t slot = desc >> 2;
-    switch (desc & 3) {
-      case 0: issue_tile_loads<2>(p.s2 + slot * 4096, lane, w); break;
-      case 1: issue_tile_loads<3>(p.s3 + slot * 6144, lane, w); break;
-      default: issue_tile_loads<4>(p.s4 + slot * 8192, lane, w); break;
-    }
-    sraw = *reinterpret_cast<const u32x4*>(p.scales + (int64_t)(tc0 + t) * p.N + sz_lane_off);
-    zraw = *reinterpret_cast<const u32x4*>(p.zeros + (int64_t)(tc0 + t) * p.N + sz_lane_off);
-  };
-  if (active) issue(0);
-
-  // gather the activation slice of this K chunk into LDS (column permutation fused here)
-  {
-    const int kspan = ntile * kTile;
-    const int total = kspan * M;
-    for (int idx = tid; idx < total; idx += 256) {
-      const int m = idx / kspan;
-      const int kl = idx - m * kspan;
-      const int k = tc0 * kTile + kl;
-      const int src = p.col_perm ? p.col_perm[k] : k;
-      Xs[((kl >> 3) * M + m) * 8 + (kl & 7)] = p.X[(int64_t)m * p.K + src];
-    }
-  }
-  __syncthreads();
-  if (!active) return;
-
-  float acc[8][4];
-#pragma unroll
-  for (int s = 0; s < 8; ++s)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) acc[s][r] = 0.f;
-
-  const int mrow = lane % 16;  // activation row this lane feeds to the MFMA A operand
-  half8 ones;
-#pragma unroll
-  for (int v = 0; v < 8; ++v) ones[v] = (_Float16)1.0f;
-
-  for (int t = 0; t < ntile; ++t) {
-    if (t > 0) issue(t);
-    half8 a[4];
-    floatx4 sx = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kappa = 0; kappa < 4; ++kappa) {
-      half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (mrow < M) v = *reinterpret_cast<const half8*>(Xs + ((t * 16 + kappa * 4 + lane / 16) * M + mrow) * 8);
-      a[kappa] = v;
-      sx = __builtin_amdgcn_mfma_f32_16x16x32_f16(v, ones, sx, 0, 0, 0);
-    }
-    switch (desc & 3) {
-      case 0: contract_tile<2>(w, a, sx, sraw, zraw, acc); break;
-      case 1: contract_tile<3>(w, a, sx, sraw, zraw, acc); break;
-      default: contract_tile<4>(w, a, sx, sraw, zraw, acc); break;
-    }
-  }
-
-  // Lane (j = lane%16, g = lane/16) holds, for r < 4, the outputs of activation row m = 4g + r and
-  // weight rows n = 128*tr + 8j + sigma.
-  const int j = lane % 16, g = lane / 16;
-  const int64_t n0 = (int64_t)tr * kTile + 8 * j;
-  if (p.nchunk == 1) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int m = 4 * g + r;
-      if (m < M) {
-#pragma unroll
-        for (int sigma = 0; sigma < 8; ++sigma) {
-          const int64_t n = n0 + sigma;
-          const int64_t col = p.row_perm ? p.row_perm[n] : n;
-          p.Y[(int64_t)m * p.N + col] = (_Float16)acc[sigma][r];
-        }
-      }
-    }
-    return;
-  }
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int m = 4 * g + r;
-    if (m < M) {
-      float* dst = p.partial + ((int64_t)chunk * M + m) * p.N + n0;
-#pragma unroll
-      for (int sigma = 0; sigma < 8; ++sigma)
-        __hip_atomic_store(dst + sigma, acc[sigma][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-  }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the partial has left before it is announced
-  int old = 0;
-  if (lane == 0) old = __hip_atomic_fetch_add(p.counters + tr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  old = __builtin_amdgcn_readfirstlane(old);
-  if (old != p.nchunk - 1) return;
-  const int64_t n = (int64_t)tr * kTile + 2 * lane;
-  int64_t c0 = n, c1 = n + 1;
-  if (p.row_perm) {
-    c0 = p.row_perm[n];
-    c1 = p.row_perm[n + 1];
-  }
-  for (int m = 0; m < M; ++m) {
-    float s0 = 0.f, s1 = 0.f;
-    const float* src = p.partial + (int64_t)m * p.N + n;
-    for (int c = 0; c < p.nchunk; ++c) {
-      s0 += __hip_atomic_load(src + (int64_t)c * M * p.N, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      s1 += __hip_atomic_load(src + (int64_t)c * M * p.N + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    p.Y[(int64_t)m * p.N + c0] = (_Float16)s0;
-    p.Y[(int64_t)m * p.N + c1] = (_Float16)s1;
-  }
-  if (lane == 0) __hip_atomic_store(p.counters + tr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// ============================================================================================
 // skinny GEMM through the rings, 2 <= M <= 16
 // ============================================================================================
 // The GEMV scheme carried over to a few activation rows: a workgroup owns whole 16-row slabs over the
@@ -586,28 +410,31 @@ __global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p)
   // same slab numbering as the GEMV kernel: the 8 slabs of a tile row run on one XCD
   const int nj = (p.nslab - bid + G - 1) / G;
   const int my_cnt = p.ntc > wave ? (p.ntc - wave + NW - 1) / NW : 0;
-  const int E = nj * my_cnt;  // items of this wavefront (<= 64)
+  const int E = nj * my_cnt;  // items of this wavefront, handled in batches of 64 (one lane describes one item)
 
   uint32_t it_alo = 0, it_ahi = 0, it_slo = 0, it_shi = 0, it_misc = 0;
-  if (lane < E) {
-    const int j = lane / my_cnt, i = lane - j * my_cnt;
-    const int v = bid + G * j;
-    const int slab = (v % 8) * p.ntr + v / 8;
-    const int tr = slab / 8, sigma = slab % 8;
-    const int tc = wave + NW * i;
-    const int32_t d = p.tile_desc[(int64_t)tr * p.ntc + tc];
-    const int bm2 = d & 3;
-    const uint8_t* base = bm2 == 0 ? p.s2 : bm2 == 1 ? p.s3 : p.s4;
-    const int64_t slab_bytes = 256 * (bm2 + 2);
-    const uint64_t a = (uint64_t)(base + (int64_t)(d >> 2) * (8 * slab_bytes) + sigma * slab_bytes);
-    const uint64_t sa = (uint64_t)(p.scales + (int64_t)tc * p.N + (int64_t)tr * kTile + (sigma & ~1));
-    it_alo = (uint32_t)a;
-    it_ahi = (uint32_t)(a >> 32);
-    it_slo = (uint32_t)sa;
-    it_shi = (uint32_t)(sa >> 32);
-    it_misc = (uint32_t)tc | ((i == my_cnt - 1) ? 0x10000u : 0u) | ((uint32_t)j << 17) | ((uint32_t)bm2 << 24) |
-              ((uint32_t)(sigma & 1) << 26);
-  }
+  auto describe = [&](int e0, int Eb) {
+    if (lane < Eb) {
+      const int ge = e0 + lane;
+      const int j = ge / my_cnt, i = ge - j * my_cnt;
+      const int v = bid + G * j;
+      const int slab = (v % 8) * p.ntr + v / 8;
+      const int tr = slab / 8, sigma = slab % 8;
+      const int tc = wave + NW * i;
+      const int32_t d = p.tile_desc[(int64_t)tr * p.ntc + tc];
+      const int bm2 = d & 3;
+      const uint8_t* base = bm2 == 0 ? p.s2 : bm2 == 1 ? p.s3 : p.s4;
+      const int64_t slab_bytes = 256 * (bm2 + 2);
+      const uint64_t a = (uint64_t)(base + (int64_t)(d >> 2) * (8 * slab_bytes) + sigma * slab_bytes);
+      const uint64_t sa = (uint64_t)(p.scales + (int64_t)tc * p.N + (int64_t)tr * kTile + (sigma & ~1));
+      it_alo = (uint32_t)a;
+      it_ahi = (uint32_t)(a >> 32);
+      it_slo = (uint32_t)sa;
+      it_shi = (uint32_t)(sa >> 32);
+      it_misc = (uint32_t)tc | ((i == my_cnt - 1) ? 0x10000u : 0u) | ((uint32_t)j << 17) | ((uint32_t)bm2 << 24) |
+                ((uint32_t)(sigma & 1) << 26);
+    }
+  };
   const uint32_t data_voff = lane * 16;
   const int64_t sz_voff =
       (int64_t)(lane & 15) * 16 + (lane < 16 ? (int64_t)0 : (int64_t)((const char*)p.zeros - (const char*)p.scales));
@@ -629,9 +456,6 @@ __global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p)
     for (int c = 0; c < MB / 4; ++c)
       __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + c * 1024), (lptr_t)(slot + kSlotBytes + c * 1024), 16, 0, 0);
   };
-
-  const int npro = min(S, E);
-  for (int e = 0; e < npro; ++e) issue_item(e, e);
 
   half8 ones;
 #pragma unroll
@@ -704,18 +528,24 @@ __global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p)
     }
   };
 
-  int s = 0;
-  int e = 0;
-  for (; e + S < E; ++e) {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies * (S - 1)) : "memory");
-    consume(e, s);
-    issue_item(e + S, s);
-    if (++s == S) s = 0;
-  }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  for (; e < E; ++e) {
-    consume(e, s);
-    if (++s == S) s = 0;
+  for (int e0 = 0; e0 < E; e0 += 64) {
+    const int Eb = min(64, E - e0);
+    describe(e0, Eb);
+    const int npro = min(S, Eb);
+    for (int e = 0; e < npro; ++e) issue_item(e, e);
+    int s = 0;
+    int e = 0;
+    for (; e + S < Eb; ++e) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies * (S - 1)) : "memory");
+      consume(e, s);
+      issue_item(e + S, s);
+      if (++s == S) s = 0;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    for (; e < Eb; ++e) {
+      consume(e, s);
+      if (++s == S) s = 0;
+    }
   }
 
   // the wavefronts add their sums one after the other: a fixed order, so results repeat bit for bit
@@ -794,67 +624,34 @@ static RSkinnyShape rskinny_shape(int32_t M) {
 
 DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
   DecodePlan d;
-  d.rskinny = false;
-  d.mb = 0;
-  d.xblk_bytes = 0;
-  d.workspace_bytes = 0;
-  const int32_t ntr = N / kTile, ntc = K / kTile;
+  const int32_t ntr = N / kTile, ntc = K / kTile, nslab = 8 * ntr;
   // GEMV: persistent grid of at most 256 workgroups (multiple of 8), 16 wavefronts each.
-  {
-    const int32_t nslab = 8 * ntr;
+  if (M == 1) {
     const int32_t grid = nslab < kGemvMaxGrid ? nslab : kGemvMaxGrid;
-    GemvFit f = gemv_fit(N, K, grid);
-    d.gemv = M == 1 && f.ok;
-    if (d.gemv) {
-      d.tiles_per_chunk = ntc;
-      d.nchunk = 1;
-      d.row_groups = grid;
-      d.counter_bytes = 0;
-      d.partial_bytes = 0;
+    const GemvFit f = gemv_fit(N, K, grid);
+    if (f.ok) {
+      d.gemv = true;
+      d.grid = grid;
       d.lds_bytes = f.lds_bytes;
-      d.gemv_slots = f.slots;
-      d.gemv_max_slabs = f.max_slabs;
+      d.slots = f.slots;
+      d.max_slabs = f.max_slabs;
+      d.mb = 1;
+      d.workspace_bytes = 0;
       return d;
     }
   }
-  if (M >= 2) {
-    const RSkinnyShape sh = rskinny_shape(M);
-    const int32_t nslab = 8 * ntr;
-    const int32_t grid = nslab < kGemvMaxGrid ? nslab : kGemvMaxGrid;
-    const int32_t max_slabs = (nslab + grid - 1) / grid;
-    const int64_t items = (int64_t)max_slabs * ((ntc + sh.nw - 1) / sh.nw);
-    const int64_t lds = (int64_t)max_slabs * 1024 + (int64_t)sh.nw * sh.slots * (kSlotBytes + sh.mb * 256);
-    if (max_slabs <= kGemvMaxSlabs && items <= kGemvMaxItems && lds <= 160 * 1024) {
-      d.rskinny = true;
-      d.gemv = false;
-      d.mb = sh.mb;
-      d.tiles_per_chunk = ntc;
-      d.nchunk = 1;
-      d.row_groups = grid;
-      d.counter_bytes = 0;
-      d.partial_bytes = 0;
-      d.lds_bytes = (int32_t)lds;
-      d.gemv_slots = sh.slots;
-      d.gemv_max_slabs = max_slabs;
-      d.xblk_bytes = round_up_256((int64_t)ntc * sh.mb * 256);
-      d.workspace_bytes = d.xblk_bytes;
-      return d;
-    }
-  }
-  // Few, long chunks keep the partial-sum traffic (128*M fp32 per wavefront, written and read
-  // once) small next to the tile bytes; many chunks keep all 256 CUs busy.  Start from a chunk
-  // length that grows with M and shorten it until about 2048 wavefronts exist.
-  int32_t tpc = M <= 4 ? 4 : 8;
-  while (tpc > 1 && (int64_t)ntr * ((ntc + tpc - 1) / tpc) < 2048) tpc /= 2;
-  while (tpc * M > 128) tpc /= 2;  // LDS: tpc * M * 256 bytes <= 32 KiB
-  if (tpc < 1) tpc = 1;
-  d.tiles_per_chunk = tpc;
-  d.nchunk = (ntc + tpc - 1) / tpc;
-  d.row_groups = (ntr + 3) / 4;
-  d.counter_bytes = round_up_256((int64_t)ntr * 4);
-  d.partial_bytes = d.nchunk > 1 ? round_up_256((int64_t)d.nchunk * M * N * 4) : 0;
-  d.lds_bytes = tpc * M * 256;
-  d.workspace_bytes = d.counter_bytes + d.partial_bytes;
+  // Everything else goes through the ring-skinny kernel: one workgroup per CU while a workgroup's share
+  // stays within 16 slabs (N <= 65536), more workgroups beyond that.
+  const RSkinnyShape sh = rskinny_shape(M);
+  int32_t grid = nslab < kGemvMaxGrid ? nslab : kGemvMaxGrid;
+  if ((nslab + grid - 1) / grid > kGemvMaxSlabs) grid = ((nslab + kGemvMaxSlabs - 1) / kGemvMaxSlabs + 7) / 8 * 8;
+  d.gemv = false;
+  d.grid = grid;
+  d.max_slabs = (nslab + grid - 1) / grid;
+  d.slots = sh.slots;
+  d.mb = sh.mb;
+  d.lds_bytes = d.max_slabs * 1024 + sh.nw * sh.slots * (kSlotBytes + sh.mb * 256);
+  d.workspace_bytes = round_up_256((int64_t)ntc * sh.mb * 256);
   return d;
 }
 
@@ -1009,9 +806,9 @@ static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* 
   p.ntr = L->N / kTile;
   p.ntc = ntc;
   p.nslab = 8 * p.ntr;
-  p.max_slabs = d.gemv_max_slabs;
+  p.max_slabs = d.max_slabs;
   void* kargs[] = {&p};
-  hipError_t e = hipLaunchKernel(fn, dim3((unsigned)d.row_groups), dim3(NW * 64), kargs, (size_t)d.lds_bytes, (hipStream_t)stream);
+  hipError_t e = hipLaunchKernel(fn, dim3((unsigned)d.grid), dim3(NW * 64), kargs, (size_t)d.lds_bytes, (hipStream_t)stream);
   if (e != hipSuccess) {
     note_hip_error("sfmp_gemm skinny launch", hipGetErrorString(e));
     return SFMP_ERR_HIP;
@@ -1031,33 +828,10 @@ int launch_decode(const GemmArgs& a, void* stream) {
   const sfmp_layout_t* L = a.L;
   const DecodePlan d = make_decode_plan(L->N, L->K, a.M);
   if (d.gemv) {
-    const GemvParams p = gemv_params(a, d.gemv_max_slabs);
-    return launch_gemv_variant(d.gemv_slots, false, p, (unsigned)d.row_groups, (size_t)d.lds_bytes, stream);
+    const GemvParams p = gemv_params(a, d.max_slabs);
+    return launch_gemv_variant(d.slots, false, p, (unsigned)d.grid, (size_t)d.lds_bytes, stream);
   }
-  if (d.rskinny) return launch_rskinny(a, d, stream);
-  SkinnyParams p;
-  p.X = (const _Float16*)a.X;
-  p.col_perm = a.col_perm;
-  p.s2 = a.s2;
-  p.s3 = a.s3;
-  p.s4 = a.s4;
-  p.tile_desc = a.index + 3;
-  p.scales = (const _Float16*)a.scales;
-  p.zeros = (const _Float16*)a.zeros;
-  p.row_perm = a.row_perm;
-  p.Y = (_Float16*)a.Y;
-  p.counters = (int32_t*)a.workspace;
-  p.partial = (float*)((char*)a.workspace + d.counter_bytes);
-  p.M = a.M;
-  p.N = L->N;
-  p.K = L->K;
-  p.ntr = L->N / kTile;
-  p.ntc = L->K / kTile;
-  p.tiles_per_chunk = d.tiles_per_chunk;
-  p.nchunk = d.nchunk;
-  hipLaunchKernelGGL(skinny_kernel, dim3((unsigned)(d.row_groups * d.nchunk)), dim3(256), (size_t)d.lds_bytes,
-                     (hipStream_t)stream, p);
-  return after_launch("sfmp_gemm skinny launch");
+  return launch_rskinny(a, d, stream);
 }
 
 }  // namespace sfmp

@@ -10,22 +10,15 @@ int check_shape(int32_t N, int32_t K);
 int check_layout(const sfmp_layout_t* L);
 void note_hip_error(const char* what, const char* text);
 
-// How the decode kernel (M <= 16) splits a matrix: a wavefront walks `tiles_per_chunk`
-// consecutive tiles of one tile row; `nchunk` chunks cover the K direction.
+// How the decode path (M <= 16) runs a problem.
 struct DecodePlan {
-  bool gemv;  // M == 1 and K small enough for the whole activation vector to sit in LDS
-  int32_t tiles_per_chunk;
-  int32_t nchunk;
-  int32_t row_groups;  // workgroups along N (4 tile rows each)
-  int64_t counter_bytes;
-  int64_t partial_bytes;
+  bool gemv;         // M == 1 with the whole activation vector in LDS; otherwise the ring-skinny kernel
+  int32_t grid;      // workgroups
   int32_t lds_bytes;
-  int32_t gemv_slots, gemv_max_slabs;
-  // 2 <= M <= 16 through the rings: activation rows padded to mb, staged per tile column in the workspace
-  bool rskinny;
-  int32_t mb;
-  int64_t xblk_bytes;
-  int64_t workspace_bytes;  // what sfmp_gemm needs for this plan
+  int32_t slots;     // ring slots per wavefront
+  int32_t max_slabs; // 16-row slabs per workgroup (upper bound)
+  int32_t mb;        // activation rows padded to this (ring-skinny: 4, 8 or 16)
+  int64_t workspace_bytes;  // staged activations of the ring-skinny kernel
 };
 DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M);
 

@@ -105,6 +105,15 @@ def test_bitmap_and_permutation_variants(torch_cuda, variant, M):
     _check(p, run_gemm(p))
 
 
+@pytest.mark.parametrize("K,N,M", [(66560, 256, 1), (66560, 256, 3), (66560, 256, 16), (128, 66048, 2)])
+def test_decode_extreme_aspect(torch_cuda, K, N, M):
+    # K = 520 tiles: more than 64 work items per wavefront, and an activation vector too long for the M = 1
+    # kernel's LDS; N = 516 tile rows: more than 16 slabs per workgroup with one workgroup per CU
+    from gpu_util import run_gemm
+    p = W.make_problem("aspect", K, N, M, 777, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, fast_codes=True)
+    _check(p, run_gemm(p))
+
+
 def test_workspace_is_reusable_and_result_deterministic(torch_cuda):
     from gpu_util import device_problem, make_workspace, run_gemm
     p = W.make_problem("reuse", 2048, 1024, 4, 31337, fractions={2: 0.5, 3: 0.5}, outliers=True)
