@@ -43,6 +43,10 @@ def parse_args():
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of HIP-graph replays")
     ap.add_argument("--separate", action="store_true",
                     help="one launch per projection (7) instead of q|k|v, o, gate|up, down sharing launches (4)")
+    ap.add_argument("--section", choices=("all", "decode", "batch", "prefill"), default="all",
+                    help="which side reports to run after the headline measurement (for profiling one kernel "
+                         "family at a time): decode = per-projection and 70B M=1, batch = M in {4, 16}, prefill = "
+                         "M=2048; with batch or prefill the headline region runs 2 steps only")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (known size) so that rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE readings can be scaled")
@@ -269,6 +273,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     groups = None if args.separate else FUSED_GROUPS
+    if args.section in ("batch", "prefill"):
+        args.steps, args.warmup = 2, 1
     ms_step, wall_ms = time_steps(torch, layer, args.steps, args.warmup, use_graph=not args.eager, groups=groups)
     us_layer = ms_step * 1e3
     gbps = layer_bytes / (ms_step * 1e-3) / 1e9
@@ -314,41 +320,59 @@ def main():
 
     if not args.no_extra:
         extra = {}
-        if groups is not None:
-            ms7, _ = time_steps(torch, layer, args.steps, args.warmup, use_graph=not args.eager, groups=None)
-            extra["seven_separate_launches_us_per_layer"] = round(ms7 * 1e3, 3)
-        per = time_each_projection(torch, layer)
-        extra["per_projection_8b_M1"] = [
-            dict(shape=f"{d['p'].K}->{d['p'].N}", label=d["p"].label, us=round(t, 3), MB=round(b / 1e6, 3),
-                 GBps=round(b / t / 1e3, 1), pct_hbm_peak=round(100 * b / t / 1e3 / HBM_PEAK_GBPS, 2))
-            for d, t, b in zip(layer.proj, per, per_proj_bytes)]
+        if args.section in ("all", "decode"):
+            if groups is not None:
+                ms7, _ = time_steps(torch, layer, args.steps, args.warmup, use_graph=not args.eager, groups=None)
+                extra["seven_separate_launches_us_per_layer"] = round(ms7 * 1e3, 3)
+            per = time_each_projection(torch, layer)
+            extra["per_projection_8b_M1"] = [
+                dict(shape=f"{d['p'].K}->{d['p'].N}", label=d["p"].label, us=round(t, 3), MB=round(b / 1e6, 3),
+                     GBps=round(b / t / 1e3, 1), pct_hbm_peak=round(100 * b / t / 1e3 / HBM_PEAK_GBPS, 2))
+                for d, t, b in zip(layer.proj, per, per_proj_bytes)]
         del layer
         torch.cuda.empty_cache()
-        # 70B-shaped decode layer (configs[3]) at M = 1, codes drawn directly (timing only)
-        p70 = build_problems(W, 4, Ms=(1,), fast=True)
-        b70 = sum(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, index_words=p.bitmap.size) for p in p70)
-        l70 = Layer(p70, int(np.ceil(2 ** 30 / b70)))
-        ms70, _ = time_steps(torch, l70, 60, 6, use_graph=not args.eager)
-        per70 = time_each_projection(torch, l70, launches=24)
-        b70p = l70.bytes_per_proj(W)
-        extra["layer_70b_M1"] = dict(us_per_layer=round(ms70 * 1e3, 2), MB=round(b70 / 1e6, 1),
-                                     GBps=round(b70 / ms70 / 1e6, 1),
-                                     pct_hbm_peak=round(100 * b70 / ms70 / 1e6 / HBM_PEAK_GBPS, 2),
-                                     per_projection=[dict(shape=f"{d['p'].K}->{d['p'].N}", us=round(t, 2),
-                                                          GBps=round(b / t / 1e3, 1))
-                                                     for d, t, b in zip(l70.proj, per70, b70p)])
-        del l70, p70
-        torch.cuda.empty_cache()
-        # prefill (configs[4]) at M = 2048 on the 8B gate shape, codes drawn directly (timing only)
-        pp = build_problems(W, 5, fast=True, only=("8b.gate", "8b.q"))
-        lp = Layer(pp, 2)
-        perp = time_each_projection(torch, lp, launches=6)
-        extra["prefill_M2048"] = [
-            dict(shape=f"{d['p'].K}->{d['p'].N}", us=round(t, 1),
-                 TFLOPs=round(2.0 * d["p"].M * d["p"].N * d["p"].K / t / 1e6, 1),
-                 pct_mfma_peak=round(100 * 2.0 * d["p"].M * d["p"].N * d["p"].K / t / 1e6 / MFMA_F16_PEAK_TFLOPS, 2))
-            for d, t in zip(lp.proj, perp)]
-        del lp, pp
+        if args.section in ("all", "decode"):
+            # 70B-shaped decode layer (configs[3]) at M = 1, codes drawn directly (timing only)
+            p70 = build_problems(W, 4, Ms=(1,), fast=True)
+            b70 = sum(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, index_words=p.bitmap.size) for p in p70)
+            l70 = Layer(p70, int(np.ceil(2 ** 30 / b70)))
+            ms70, _ = time_steps(torch, l70, 60, 6, use_graph=not args.eager)
+            per70 = time_each_projection(torch, l70, launches=24)
+            b70p = l70.bytes_per_proj(W)
+            extra["layer_70b_M1"] = dict(us_per_layer=round(ms70 * 1e3, 2), MB=round(b70 / 1e6, 1),
+                                         GBps=round(b70 / ms70 / 1e6, 1),
+                                         pct_hbm_peak=round(100 * b70 / ms70 / 1e6 / HBM_PEAK_GBPS, 2),
+                                         per_projection=[dict(shape=f"{d['p'].K}->{d['p'].N}", us=round(t, 2),
+                                                              GBps=round(b / t / 1e3, 1))
+                                                         for d, t, b in zip(l70.proj, per70, b70p)])
+            del l70, p70
+            torch.cuda.empty_cache()
+        if args.section in ("all", "batch"):
+            # small batches (configs[2]: 50 % 2-bit / 50 % 3-bit) through the ring-skinny kernel, 7 launches
+            rows = []
+            for M in (4, 16):
+                pb = build_problems(W, 3, Ms=(M,), fast=True)
+                bb = sum(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, index_words=p.bitmap.size) for p in pb)
+                lb = Layer(pb, int(np.ceil(2 ** 30 / bb)))
+                msb, _ = time_steps(torch, lb, 60, 6, use_graph=not args.eager)
+                rows.append(dict(M=M, us_per_layer=round(msb * 1e3, 2), MB=round(bb / 1e6, 1),
+                                 GBps=round(bb / msb / 1e6, 1),
+                                 pct_hbm_peak=round(100 * bb / msb / 1e6 / HBM_PEAK_GBPS, 2)))
+                del lb, pb
+                torch.cuda.empty_cache()
+            extra["layer_8b_small_batch"] = rows
+        if args.section in ("all", "prefill"):
+            # prefill (configs[4]) at M = 2048 on two 8B shapes, codes drawn directly (timing only)
+            pp = build_problems(W, 5, fast=True, only=("8b.gate", "8b.q"))
+            lp = Layer(pp, 2)
+            perp = time_each_projection(torch, lp, launches=24)
+            extra["prefill_M2048"] = [
+                dict(shape=f"{d['p'].K}->{d['p'].N}", us=round(t, 1),
+                     TFLOPs=round(2.0 * d["p"].M * d["p"].N * d["p"].K / t / 1e6, 1),
+                     pct_mfma_peak=round(100 * 2.0 * d["p"].M * d["p"].N * d["p"].K / t / 1e6 / MFMA_F16_PEAK_TFLOPS,
+                                         2))
+                for d, t in zip(lp.proj, perp)]
+            del lp, pp
         result["extra"] = extra
 
     if not args.no_cpu_baseline:

@@ -116,9 +116,10 @@ int sfmp_unpack(const sfmp_layout_t* layout, const void* s2_dev, const void* s3_
 int sfmp_gemm_workspace(const sfmp_layout_t* layout, int32_t M, int64_t* bytes);
 
 /* Device.  Zero-fills a workspace (a small fill kernel on hip_stream, safe under graph
- * capture).  A workspace must be initialised once before its first use by sfmp_gemm; every
- * sfmp_gemm call leaves it ready for the next one.  One workspace serves one stream at a
- * time: two calls that overlap on the same workspace race. */
+ * capture).  Optional: sfmp_gemm writes every workspace byte it later reads (staged or gathered
+ * activations, the product before the row un-permute), so an uninitialised workspace is fine.
+ * One workspace serves one stream at a time: two calls that overlap on the same workspace
+ * race. */
 int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream);
 
 /* Device.  The mixed-precision product of Fig. 3(c):
@@ -133,9 +134,11 @@ int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream);
  *             row_perm[i] of Y (undoing P_row of Eq. 9); NULL = leave the rows reordered.
  *   Y         fp16 [M, N] row-major; fully overwritten.  fp32 accumulation, one
  *             round-to-nearest-even conversion at the end.
- *   workspace device memory of at least sfmp_gemm_workspace() bytes, 256-byte aligned,
- *             initialised once by sfmp_workspace_init.
- * M <= 16 runs the bandwidth-bound decode kernel; larger M runs the MFMA prefill kernel.
+ *   workspace device memory of at least sfmp_gemm_workspace() bytes, 256-byte aligned; contents
+ *             on entry are irrelevant, contents on return are unspecified.
+ * M = 1 runs the bandwidth-bound GEMV kernel, 2 <= M <= 16 (and M = 1 with K above about 32k) the
+ * same scheme with the activations staged per tile column, larger M the MFMA prefill kernels
+ * (SFMP_ERR_SHAPE there if K > 57344, or with a permutation whose vector exceeds 160 KiB of fp16).
  * Asynchronous on hip_stream; holds no global state.  The permutations are not checked for
  * being bijections (out-of-range entries are the caller's error; use sfmp_check_perm). */
 int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
