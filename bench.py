@@ -104,8 +104,10 @@ class Layer:
             self.launch(i, r, stream_ptr)
 
     def step_fused(self, r, stream_ptr, groups):
-        """The same projections as `step`, independent ones sharing a launch (sfmp_gemv_batched)."""
+        """The same projections as `step`, independent ones sharing a launch (sfmp_gemv_batched at M = 1,
+        sfmp_gemm_batched for small batches)."""
         lib = self.S.load_library()
+        M = self.problems[0].M
         for gi, idxs in enumerate(groups):
             key = ("fused", gi, r)
             if key not in self._args:
@@ -114,9 +116,21 @@ class Layer:
                     d = self.proj[i]
                     batch.append((d["X"], d["cp"][r] if d["cp"] else None, d["reps"][r],
                                   d["rp"][r] if d["rp"] else None, d["Y"]))
-                self._args[key] = self.S.make_gemv_batch(batch)
-            arr, _keep = self._args[key]
-            rc = lib.sfmp_gemv_batched(C.cast(arr, C.c_void_p), len(idxs), C.c_void_p(stream_ptr))
+                arr, keep = self.S.make_gemv_batch(batch)
+                ws = None
+                if M > 1:
+                    wkey = ("fused_ws", gi)
+                    if wkey not in self._args:
+                        self._args[wkey] = self.torch.empty(self.S.sfmp_gemm_batched_workspace(batch, M),
+                                                            dtype=self.torch.uint8, device=self.device)
+                    ws = self._args[wkey]
+                self._args[key] = (arr, keep, ws)
+            arr, _keep, ws = self._args[key]
+            if M == 1:
+                rc = lib.sfmp_gemv_batched(C.cast(arr, C.c_void_p), len(idxs), C.c_void_p(stream_ptr))
+            else:
+                rc = lib.sfmp_gemm_batched(C.cast(arr, C.c_void_p), len(idxs), C.c_int32(M), C.c_void_p(ws.data_ptr()),
+                                           C.c_int64(ws.numel()), C.c_void_p(stream_ptr))
             if rc != 0:
                 raise RuntimeError(self.S.sfmp_strerror(rc))
 
@@ -348,15 +362,17 @@ def main():
             del l70, p70
             torch.cuda.empty_cache()
         if args.section in ("all", "batch"):
-            # small batches (configs[2]: 50 % 2-bit / 50 % 3-bit) through the ring-skinny kernel, 7 launches
+            # small batches (configs[2]: 50 % 2-bit / 50 % 3-bit) through the ring-skinny kernel: 4 batched calls
+            # (q|k|v, o, gate|up, down: 8 kernels) and, for comparison, 7 separate calls (14 kernels)
             rows = []
             for M in (4, 16):
                 pb = build_problems(W, 3, Ms=(M,), fast=True)
                 bb = sum(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, index_words=p.bitmap.size) for p in pb)
                 lb = Layer(pb, int(np.ceil(2 ** 30 / bb)))
-                msb, _ = time_steps(torch, lb, 60, 6, use_graph=not args.eager)
-                rows.append(dict(M=M, us_per_layer=round(msb * 1e3, 2), MB=round(bb / 1e6, 1),
-                                 GBps=round(bb / msb / 1e6, 1),
+                msb, _ = time_steps(torch, lb, 60, 6, use_graph=not args.eager, groups=FUSED_GROUPS)
+                ms7, _ = time_steps(torch, lb, 60, 6, use_graph=not args.eager)
+                rows.append(dict(M=M, us_per_layer=round(msb * 1e3, 2), seven_separate_calls_us=round(ms7 * 1e3, 2),
+                                 MB=round(bb / 1e6, 1), GBps=round(bb / msb / 1e6, 1),
                                  pct_hbm_peak=round(100 * bb / msb / 1e6 / HBM_PEAK_GBPS, 2)))
                 del lb, pb
                 torch.cuda.empty_cache()

@@ -147,9 +147,9 @@ int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const s
               const int32_t* row_perm_dev, void* Y_dev, void* workspace_dev, int64_t workspace_bytes,
               void* hip_stream);
 
-/* One M = 1 problem of a batched launch: the arguments of sfmp_gemm without M and workspace. */
+/* One problem of a batched launch: the arguments of sfmp_gemm without M and workspace. */
 typedef struct sfmp_gemv_problem {
-  const void* X_dev;             /* fp16 [1, K] */
+  const void* X_dev;             /* fp16 [M, K] */
   const int32_t* col_perm_dev;   /* int32 [K] or NULL */
   const sfmp_layout_t* layout;   /* host pointer; read during the call only */
   const void* s2_dev;
@@ -160,7 +160,7 @@ typedef struct sfmp_gemv_problem {
   const void* zeros_dev;
   const int8_t* bitmap_dev;
   const int32_t* row_perm_dev;   /* int32 [N] or NULL */
-  void* Y_dev;                   /* fp16 [1, N] */
+  void* Y_dev;                   /* fp16 [M, N] */
 } sfmp_gemv_problem_t;
 
 /* Device.  Up to 8 independent M = 1 products (each exactly what sfmp_gemm computes, each with its
@@ -170,6 +170,18 @@ typedef struct sfmp_gemv_problem {
  * array read during the call.  Needs no workspace.  SFMP_ERR_SHAPE if a problem cannot use the
  * GEMV kernel (K above about 32k) - call sfmp_gemm per problem then. */
 int sfmp_gemv_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, void* hip_stream);
+
+/* The same for a small batch: up to 8 independent products with a common M, 1 <= M <= 16 (each exactly what
+ * sfmp_gemm computes; X_dev of a problem is fp16 [M, K], Y_dev fp16 [M, N]), in one launch of the GEMM kernel plus,
+ * for M >= 2, one launch of the activation staging kernel.  Problems that pass the same X_dev, col_perm_dev and K
+ * (q, k and v; gate and up) share one staged copy of the activations.  M = 1 is sfmp_gemv_batched.
+ * sfmp_gemm_batched_workspace (host only) gives the workspace size for these problems and this M (never 0);
+ * the workspace is device memory, 256-byte aligned, contents irrelevant on entry and unspecified on return.
+ * SFMP_ERR_SHAPE if M is outside 1..16 or a problem would put more than 16 slabs on a workgroup (N above about
+ * 65536 times its share of the grid) - call sfmp_gemm per problem then. */
+int sfmp_gemm_batched_workspace(const sfmp_gemv_problem_t* problems_host, int32_t count, int32_t M, int64_t* bytes);
+int sfmp_gemm_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, int32_t M, void* workspace_dev,
+                      int64_t workspace_bytes, void* hip_stream);
 
 /* Host only.  SFMP_OK if perm_host[0..n) is a permutation of 0..n-1, else SFMP_ERR_PERM. */
 int sfmp_check_perm(const int32_t* perm_host, int32_t n);

@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     sfmp_workspace_init,
     sfmp_gemm,
     sfmp_gemv_batched,
+    sfmp_gemm_batched,
+    sfmp_gemm_batched_workspace,
     make_gemv_batch,
     sfmp_check_perm,
     upload_packed,

@@ -33,7 +33,8 @@ class SfmpGemvProblem(C.Structure):
 
 
 EXPORTS = ("sfmp_strerror", "sfmp_pack_query", "sfmp_pack", "sfmp_unpack", "sfmp_gemm_workspace",
-           "sfmp_workspace_init", "sfmp_gemm", "sfmp_gemv_batched", "sfmp_check_perm")
+           "sfmp_workspace_init", "sfmp_gemm", "sfmp_gemv_batched", "sfmp_gemm_batched_workspace",
+           "sfmp_gemm_batched", "sfmp_check_perm")
 
 
 def lib_path() -> str:
@@ -199,3 +200,20 @@ def sfmp_gemv_batched(problems, stream=None) -> None:
     """problems: list of (X [1,K] fp16, col_perm or None, DevicePacked, row_perm or None, Y [1,N] fp16)."""
     arr, _keep = make_gemv_batch(problems)
     _check(load_library().sfmp_gemv_batched(C.cast(arr, C.c_void_p), len(problems), _stream_ptr(stream)))
+
+
+def sfmp_gemm_batched_workspace(problems, M: int) -> int:
+    """Workspace bytes for sfmp_gemm_batched on these problems (tuples as for sfmp_gemv_batched, X [M,K], Y [M,N])."""
+    arr, _keep = make_gemv_batch(problems)
+    out = C.c_int64(0)
+    _check(load_library().sfmp_gemm_batched_workspace(C.cast(arr, C.c_void_p), len(problems), C.c_int32(M),
+                                                      C.byref(out)))
+    return int(out.value)
+
+
+def sfmp_gemm_batched(problems, M: int, workspace, stream=None) -> None:
+    """Up to 8 independent products with a common M <= 16 in one launch (plus one staging launch for M >= 2)."""
+    arr, _keep = make_gemv_batch(problems)
+    _check(load_library().sfmp_gemm_batched(C.cast(arr, C.c_void_p), len(problems), C.c_int32(M),
+                                            C.c_void_p(workspace.data_ptr()), C.c_int64(workspace.numel()),
+                                            _stream_ptr(stream)))

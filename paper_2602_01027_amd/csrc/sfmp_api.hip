@@ -56,10 +56,9 @@ static int check_gemm_pointers(const void* X_dev, const int32_t* col_perm_dev, c
   return SFMP_OK;
 }
 
-int sfmp_gemv_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, void* hip_stream) {
+static int marshal_batch(const sfmp_gemv_problem_t* problems_host, int32_t count, GemmArgs* args) {
   if (!problems_host) return SFMP_ERR_NULL;
   if (count < 1 || count > 8) return SFMP_ERR_SHAPE;
-  GemmArgs args[8];
   for (int i = 0; i < count; ++i) {
     const sfmp_gemv_problem_t& q = problems_host[i];
     if (int e = check_gemm_pointers(q.X_dev, q.col_perm_dev, q.layout, q.s2_dev, q.s3_dev, q.s4_dev, q.index_dev,
@@ -82,7 +81,36 @@ int sfmp_gemv_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, v
     a.workspace = nullptr;
     a.workspace_bytes = 0;
   }
+  return SFMP_OK;
+}
+
+int sfmp_gemv_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, void* hip_stream) {
+  GemmArgs args[8];
+  if (int e = marshal_batch(problems_host, count, args)) return e;
   return launch_gemv_batched(args, count, hip_stream);
+}
+
+int sfmp_gemm_batched_workspace(const sfmp_gemv_problem_t* problems_host, int32_t count, int32_t M, int64_t* bytes) {
+  if (!bytes) return SFMP_ERR_NULL;
+  if (M < 1 || M > kDecodeMaxM) return SFMP_ERR_SHAPE;
+  GemmArgs args[8];
+  if (int e = marshal_batch(problems_host, count, args)) return e;
+  *bytes = batched_workspace_bytes(args, count, M);
+  if (*bytes < 256) *bytes = 256;
+  return SFMP_OK;
+}
+
+int sfmp_gemm_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, int32_t M, void* workspace_dev,
+                      int64_t workspace_bytes, void* hip_stream) {
+  if (M < 1 || M > kDecodeMaxM) return SFMP_ERR_SHAPE;
+  GemmArgs args[8];
+  if (int e = marshal_batch(problems_host, count, args)) return e;
+  if (M > 1) {
+    const int64_t need = batched_workspace_bytes(args, count, M);
+    if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < need) return SFMP_ERR_WORKSPACE;
+  }
+  for (int i = 0; i < count; ++i) args[i].M = M;
+  return launch_decode_batched(args, count, M, workspace_dev, hip_stream);
 }
 
 int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,

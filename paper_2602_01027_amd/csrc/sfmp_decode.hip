@@ -361,10 +361,8 @@ struct RSkinnyParams {
 
 // one workgroup per tile column; thread (m, u) gathers the 8 columns of unit u' = u ^ m of row m
 template <int MB>
-__global__ __launch_bounds__(MB * 16) void stage_rows_kernel(const _Float16* __restrict__ X,
-                                                            const int32_t* __restrict__ col_perm, unsigned char* xblk,
-                                                            int M, int K) {
-  const int tc = blockIdx.x;
+__device__ __forceinline__ void stage_rows_tile(const _Float16* __restrict__ X, const int32_t* __restrict__ col_perm,
+                                                unsigned char* xblk, int M, int K, int tc) {
   const int m = threadIdx.x / 16, pos = threadIdx.x % 16;
   const int unit = pos ^ m;
   half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -390,11 +388,17 @@ __global__ __launch_bounds__(MB * 16) void stage_rows_kernel(const _Float16* __r
 }
 
 template <int MB>
+__global__ __launch_bounds__(MB * 16) void stage_rows_kernel(const _Float16* __restrict__ X,
+                                                            const int32_t* __restrict__ col_perm, unsigned char* xblk,
+                                                            int M, int K) {
+  stage_rows_tile<MB>(X, col_perm, xblk, M, K, (int)blockIdx.x);
+}
+
+template <int MB>
 constexpr int rskinny_slot_bytes() { return kSlotBytes + MB * 256; }
 
 template <int NW, int S, int MB>
-__global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p) {
-  extern __shared__ __align__(16) unsigned char lds_raw[];
+__device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int bid, const int G, unsigned char* lds_raw) {
   constexpr int NT = NW * 64;
   constexpr int kSlot = rskinny_slot_bytes<MB>();
   constexpr int kCopies = 2 + MB / 4;  // direct copies per item: slab, scales+zeros, MB/4 x 1 KiB of activations
@@ -405,7 +409,6 @@ __global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p)
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-  const int bid = blockIdx.x, G = gridDim.x;
   const int i16 = lane % 16, kb = lane / 16;
   // same slab numbering as the GEMV kernel: the 8 slabs of a tile row run on one XCD
   const int nj = (p.nslab - bid + G - 1) / G;
@@ -577,6 +580,45 @@ __global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p)
   }
 }
 
+template <int NW, int S, int MB>
+__global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  rskinny_body<NW, S, MB>(p, (int)blockIdx.x, (int)gridDim.x, lds_raw);
+}
+
+// Several independent problems with the same M in one launch (q, k and v, or gate and up of a decoder
+// layer): the grid is split between the problems as in gemv_batched_kernel.
+struct RSkinnyBatch {
+  RSkinnyParams p[kGemvMaxBatch];
+  int32_t first[kGemvMaxBatch + 1];
+  int32_t count;
+};
+
+template <int NW, int S, int MB>
+__global__ __launch_bounds__(NW * 64) void rskinny_batched_kernel(const RSkinnyBatch b) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  int i = 0;
+  while (i + 1 < b.count && (int)blockIdx.x >= b.first[i + 1]) ++i;
+  rskinny_body<NW, S, MB>(b.p[i], (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
+}
+
+// Staging for a batch: job j (one per distinct activation matrix) owns workgroups [first[j], first[j+1]).
+struct StageBatch {
+  const _Float16* X[kGemvMaxBatch];
+  const int32_t* col_perm[kGemvMaxBatch];
+  unsigned char* xblk[kGemvMaxBatch];
+  int32_t K[kGemvMaxBatch];
+  int32_t first[kGemvMaxBatch + 1];
+  int32_t count, M;
+};
+
+template <int MB>
+__global__ __launch_bounds__(MB * 16) void stage_rows_batched_kernel(const StageBatch b) {
+  int j = 0;
+  while (j + 1 < b.count && (int)blockIdx.x >= b.first[j + 1]) ++j;
+  stage_rows_tile<MB>(b.X[j], b.col_perm[j], b.xblk[j], b.M, b.K[j], (int)blockIdx.x - b.first[j]);
+}
+
 // ============================================================================================
 // host side
 // ============================================================================================
@@ -719,11 +761,9 @@ static int launch_gemv_variant(int slots, bool batched, const KernelArg& arg, un
   return after_launch("sfmp gemv launch");
 }
 
-int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
-  if (count < 1 || count > kGemvMaxBatch) return SFMP_ERR_SHAPE;
-  // split the 256 workgroups in units of 8 (one per XCD), greedily to the problem with the most packed bytes
-  // per workgroup, never giving a problem more workgroups than it has slabs
-  int32_t g[kGemvMaxBatch];
+// Splits the 256 workgroups of a persistent launch between `count` problems in units of 8 (one per XCD), greedily to
+// the problem with the most packed bytes per workgroup, never giving a problem more workgroups than it has slabs.
+static int split_grid(const GemmArgs* probs, int count, int32_t* g) {
   int64_t bytes[kGemvMaxBatch];
   int32_t total = 0;
   for (int i = 0; i < count; ++i) {
@@ -748,6 +788,13 @@ int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
     g[best] += 8;
     total += 8;
   }
+  return SFMP_OK;
+}
+
+int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
+  if (count < 1 || count > kGemvMaxBatch) return SFMP_ERR_SHAPE;
+  int32_t g[kGemvMaxBatch];
+  if (int e = split_grid(probs, count, g)) return e;
   GemvBatch b;
   b.count = count;
   int32_t slots = kGemvMaxSlots, lds = 0, first = 0;
@@ -821,6 +868,131 @@ static int launch_rskinny(const GemmArgs& a, const DecodePlan& d, void* stream) 
     case 4: return launch_rskinny_variant<8, 8, 4>(a, d, stream);
     case 8: return launch_rskinny_variant<8, 5, 8>(a, d, stream);
     default: return launch_rskinny_variant<8, 3, 16>(a, d, stream);
+  }
+}
+
+// ---- batched launch for 2 <= M <= 16 ---------------------------------------------------------------
+// Problems that read the same activation matrix through the same column permutation share one staged copy.
+struct BatchStagePlan {
+  int32_t job_of[kGemvMaxBatch];    // staging job of each problem
+  int32_t rep[kGemvMaxBatch];       // first problem of each job
+  int64_t offset[kGemvMaxBatch];    // workspace offset of each job's staged activations
+  int32_t njobs;
+  int64_t bytes;
+};
+static BatchStagePlan plan_batch_staging(const GemmArgs* probs, int count, int32_t mb) {
+  BatchStagePlan sp;
+  sp.njobs = 0;
+  sp.bytes = 0;
+  for (int i = 0; i < count; ++i) {
+    int j = 0;
+    for (; j < sp.njobs; ++j) {
+      const GemmArgs& r = probs[sp.rep[j]];
+      if (r.X == probs[i].X && r.col_perm == probs[i].col_perm && r.L->K == probs[i].L->K) break;
+    }
+    if (j == sp.njobs) {
+      sp.rep[j] = i;
+      sp.offset[j] = sp.bytes;
+      sp.bytes += round_up_256((int64_t)(probs[i].L->K / kTile) * mb * 256);
+      ++sp.njobs;
+    }
+    sp.job_of[i] = j;
+  }
+  return sp;
+}
+
+int64_t batched_workspace_bytes(const GemmArgs* probs, int count, int32_t M) {
+  if (M < 2) return 0;
+  return plan_batch_staging(probs, count, rskinny_shape(M).mb).bytes;
+}
+
+template <int NW, int S, int MB>
+static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int32_t M, void* workspace, void* stream) {
+  int32_t g[kGemvMaxBatch];
+  if (int e = split_grid(probs, count, g)) return e;
+  const BatchStagePlan sp = plan_batch_staging(probs, count, MB);
+  StageBatch sb;
+  sb.count = sp.njobs;
+  sb.M = M;
+  int32_t sfirst = 0;
+  for (int j = 0; j < sp.njobs; ++j) {
+    const GemmArgs& r = probs[sp.rep[j]];
+    sb.X[j] = (const _Float16*)r.X;
+    sb.col_perm[j] = r.col_perm;
+    sb.xblk[j] = (unsigned char*)workspace + sp.offset[j];
+    sb.K[j] = r.L->K;
+    sb.first[j] = sfirst;
+    sfirst += r.L->K / kTile;
+  }
+  for (int j = sp.njobs; j <= kGemvMaxBatch; ++j) sb.first[j] = sfirst;
+  for (int j = sp.njobs; j < kGemvMaxBatch; ++j) {
+    sb.X[j] = nullptr;
+    sb.col_perm[j] = nullptr;
+    sb.xblk[j] = nullptr;
+    sb.K[j] = 0;
+  }
+  RSkinnyBatch b;
+  b.count = count;
+  int32_t first = 0;
+  int64_t lds = 0;
+  for (int i = 0; i < count; ++i) {
+    const sfmp_layout_t* L = probs[i].L;
+    const int32_t nslab = 8 * (L->N / kTile);
+    const int32_t max_slabs = (nslab + g[i] - 1) / g[i];
+    if (max_slabs > kGemvMaxSlabs) return SFMP_ERR_SHAPE;
+    RSkinnyParams& p = b.p[i];
+    p.xblk = (const unsigned char*)workspace + sp.offset[sp.job_of[i]];
+    p.s2 = probs[i].s2;
+    p.s3 = probs[i].s3;
+    p.s4 = probs[i].s4;
+    p.tile_desc = probs[i].index + 3;
+    p.scales = (const _Float16*)probs[i].scales;
+    p.zeros = (const _Float16*)probs[i].zeros;
+    p.row_perm = probs[i].row_perm;
+    p.Y = (_Float16*)probs[i].Y;
+    p.M = M;
+    p.N = L->N;
+    p.K = L->K;
+    p.ntr = L->N / kTile;
+    p.ntc = L->K / kTile;
+    p.nslab = nslab;
+    p.max_slabs = max_slabs;
+    const int64_t need = (int64_t)max_slabs * 1024 + (int64_t)NW * S * rskinny_slot_bytes<MB>();
+    lds = need > lds ? need : lds;
+    b.first[i] = first;
+    first += g[i];
+  }
+  for (int i = count; i <= kGemvMaxBatch; ++i) b.first[i] = first;
+  for (int i = count; i < kGemvMaxBatch; ++i) b.p[i] = b.p[0];
+  if (lds > 160 * 1024) return SFMP_ERR_SHAPE;
+  static bool attr_set = false;
+  const void* fn = reinterpret_cast<const void*>(&rskinny_batched_kernel<NW, S, MB>);
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) {
+      note_hip_error("hipFuncSetAttribute(skinny batched)", hipGetErrorString(e));
+      return SFMP_ERR_HIP;
+    }
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((stage_rows_batched_kernel<MB>), dim3((unsigned)sfirst), dim3(MB * 16), 0, (hipStream_t)stream, sb);
+  if (int e = after_launch("sfmp_gemm_batched activation staging launch")) return e;
+  void* kargs[] = {&b};
+  hipError_t e = hipLaunchKernel(fn, dim3((unsigned)first), dim3(NW * 64), kargs, (size_t)lds, (hipStream_t)stream);
+  if (e != hipSuccess) {
+    note_hip_error("sfmp_gemm_batched launch", hipGetErrorString(e));
+    return SFMP_ERR_HIP;
+  }
+  return after_launch("sfmp_gemm_batched launch");
+}
+
+int launch_decode_batched(const GemmArgs* probs, int count, int32_t M, void* workspace, void* stream) {
+  if (count < 1 || count > kGemvMaxBatch || M < 1 || M > kDecodeMaxM) return SFMP_ERR_SHAPE;
+  if (M == 1) return launch_gemv_batched(probs, count, stream);
+  switch (rskinny_shape(M).mb) {
+    case 4: return launch_rskinny_batched_variant<8, 8, 4>(probs, count, M, workspace, stream);
+    case 8: return launch_rskinny_batched_variant<8, 5, 8>(probs, count, M, workspace, stream);
+    default: return launch_rskinny_batched_variant<8, 3, 16>(probs, count, M, workspace, stream);
   }
 }
 

@@ -61,5 +61,7 @@ int launch_unpack(const sfmp_layout_t* L, const uint8_t* s2, const uint8_t* s3, 
 int launch_fill_zero(void* ptr, int64_t bytes, void* stream);
 int launch_decode(const GemmArgs& a, void* stream);
 int launch_gemv_batched(const GemmArgs* problems, int count, void* stream);
+int launch_decode_batched(const GemmArgs* problems, int count, int32_t M, void* workspace, void* stream);
+int64_t batched_workspace_bytes(const GemmArgs* problems, int count, int32_t M);
 int launch_prefill(const GemmArgs& a, void* stream);
 }  // namespace sfmp

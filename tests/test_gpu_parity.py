@@ -239,3 +239,41 @@ def test_gemv_batched(torch_cuda, shapes):
     for p, (_, cp, dp, rp, Y) in zip(probs, batch):
         y_single = run_gemm(p, dp, cp, rp)
         assert np.array_equal(y_single.view(np.uint16), Y.cpu().numpy().view(np.uint16))
+
+
+@pytest.mark.parametrize("M", [1, 2, 4, 7, 16])
+def test_gemm_batched_shared_activations(torch_cuda, M):
+    # q|k|v-like: three matrices over the same activations and column permutation (one staged copy), plus a fourth
+    # problem with its own activations, K and no column permutation
+    import dataclasses
+    import paper_2602_01027_amd as S
+    from gpu_util import device_problem, run_gemm
+    torch = torch_cuda
+    base = W.make_problem("s0", 1024, 512, M, 8100, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, outliers=True)
+    probs = [base]
+    for i, N in enumerate((256, 384)):
+        q = W.make_problem(f"s{i + 1}", 1024, N, M, 8200 + i, fractions={2: 0.5, 3: 0.5}, use_row_perm=(i == 0))
+        probs.append(dataclasses.replace(q, X=base.X, col_perm=base.col_perm))
+    probs.append(W.make_problem("own", 896, 640, M, 8300, fractions=None, use_col_perm=False))
+    Xd = torch.from_numpy(base.X).to("cuda:0")
+    cpd = torch.from_numpy(base.col_perm).to("cuda:0")
+    batch, keep = [], []
+    for i, p in enumerate(probs):
+        dp, cp, rp = device_problem(p)
+        X = Xd if i < 3 else torch.from_numpy(p.X).to("cuda:0")
+        Y = torch.full((M, p.N), float("nan"), dtype=torch.float16, device="cuda:0")
+        batch.append((X, cpd if i < 3 else None, dp, rp, Y))
+        keep.append((dp, cp, rp))
+    need = S.sfmp_gemm_batched_workspace(batch, M)
+    shared = S.sfmp_gemm_batched_workspace(batch[:3], M)
+    single = S.sfmp_gemm_batched_workspace(batch[:1], M)
+    assert shared == single  # one staged copy for the three problems that share X and col_perm
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    S.sfmp_gemm_batched(batch, M, ws)
+    torch.cuda.synchronize()
+    for p, (_, _, _, _, Y), (dp, cp, rp) in zip(probs, batch, keep):
+        y = Y.cpu().numpy()
+        _check(p, y)
+        # the batched launch computes exactly what separate launches compute
+        assert np.array_equal(run_gemm(p, dp, cp, rp).view(np.uint16), y.view(np.uint16))
+
