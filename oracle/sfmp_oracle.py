@@ -9,7 +9,10 @@ What it computes (paper: Fig. 3(c); Section 3.4 Eq. 8-9; Appendix B Eq. 10-11;
 Section 4 "group quantization is applied along the n_b dimension within each block"):
 
     b        = bitmap[n // 128, k // 128]                      bit-width of the tile, in {2,3,4}
-    w_hat    = s[k // 128, n] * q[n, k] + z[k // 128, n]      z is an additive real zero-point
+    w_hat    = s[k // G, n] * q[n, k] + z[k // G, n]          z is an additive real zero-point; G = group
+                                                               length along K (128 by default; the ablation
+                                                               "Effect of n_b" also uses 256 and 512), read off
+                                                               the shape of s: G = K / s.shape[0]
     Xp[m, j] = X[m, col_perm[j]]                               the same permutation on the activation
     Yt       = Xp @ w_hat^T                                    float64
     Y[:, row_perm[i]] = Yt[:, i]                               undo the row reordering of the weight
@@ -29,7 +32,7 @@ from typing import Dict, Optional, Sequence
 import numpy as np
 
 TILE = 128  # tile edge (rows of Wt = output features, columns = input features)
-GROUP = 128  # quantisation group length along K
+GROUP = 128  # default quantisation group length along K
 WIDTHS = (2, 3, 4)
 
 
@@ -53,20 +56,30 @@ def codes_from_bit_planes(planes: Sequence[np.ndarray]) -> np.ndarray:
     return acc.astype(np.uint8)
 
 
-def dequant(codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray) -> np.ndarray:
-    """w_hat[n, k] = s[k // 128, n] * q[n, k] + z[k // 128, n]   (Appendix B, Eq. 11).
+def group_length(K: int, scales: np.ndarray) -> int:
+    """Group length G along K implied by a scale array of shape [K/G, N]."""
+    ng = scales.shape[0]
+    assert ng > 0 and K % ng == 0, (K, scales.shape)
+    return K // ng
 
-    codes uint8 [N, K]; scales, zeros fp16 (or any float) [K/128, N].  Returns float64 [N, K].
+
+def dequant(codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray) -> np.ndarray:
+    """w_hat[n, k] = s[k // G, n] * q[n, k] + z[k // G, n]   (Appendix B, Eq. 11; group quantisation along
+    the n_b dimension, Section 4 and the "Effect of n_b" ablation).
+
+    codes uint8 [N, K]; scales, zeros [K/G, N] in any float type whose values are the stored parameters
+    (fp16, or float32 holding bf16-representable numbers).  Returns float64 [N, K].
     """
     N, K = codes.shape
-    ng = K // GROUP
+    G = group_length(K, scales)
+    ng = K // G
     assert scales.shape == (ng, N) and zeros.shape == (ng, N)
     w_hat = np.empty((N, K), dtype=np.float64)
     for g in range(ng):
         s = scales[g].astype(np.float64)[:, None]  # one scale per row for this group
         z = zeros[g].astype(np.float64)[:, None]
-        q = codes[:, g * GROUP:(g + 1) * GROUP].astype(np.float64)
-        w_hat[:, g * GROUP:(g + 1) * GROUP] = s * q + z
+        q = codes[:, g * G:(g + 1) * G].astype(np.float64)
+        w_hat[:, g * G:(g + 1) * G] = s * q + z
     return w_hat
 
 
@@ -113,9 +126,10 @@ def dequant_rows(codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray, rows:
     """``dequant`` restricted to the given rows of Wt.  float64 [len(rows), K]."""
     rows = np.asarray(rows, dtype=np.int64)
     K = codes.shape[1]
+    G = group_length(K, scales)
     q = codes[rows].astype(np.float64)
-    s = np.repeat(scales[:, rows].astype(np.float64).T, GROUP, axis=1)[:, :K]
-    z = np.repeat(zeros[:, rows].astype(np.float64).T, GROUP, axis=1)[:, :K]
+    s = np.repeat(scales[:, rows].astype(np.float64).T, G, axis=1)
+    z = np.repeat(zeros[:, rows].astype(np.float64).T, G, axis=1)
     return s * q + z
 
 

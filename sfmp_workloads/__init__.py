@@ -21,6 +21,9 @@ from .generators import (  # noqa: F401
     CONFIGS,
     Problem,
     make_bitmap,
+    block_bitmap,
+    to_bf16,
+    param_bits,
     clustered_bitmap,
     make_weights,
     make_activations,

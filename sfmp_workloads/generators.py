@@ -9,8 +9,10 @@ that a weight matrix is stored [N, K] = [output features, input features]):
 * ``bitmap``   int8 ``[N/128, K/128]`` holding the literal bit-width 2, 3 or 4 of
   every 128x128 tile of ``Wt`` (Section 3.3 block-wise allocation; one int8
   per block as in the metadata paragraph of Section 4.3).
-* ``codes``    uint8 ``[N, K]`` integer codes of ``Wt``; ``scales`` / ``zeros`` fp16
-  ``[K/128, N]``: one (s, z) pair per row per group of 128 reordered columns.
+* ``codes``    uint8 ``[N, K]`` integer codes of ``Wt``; ``scales`` / ``zeros``
+  ``[K/G, N]``: one (s, z) pair per row per group of G reordered columns (G = 128 by
+  default; 256 and 512 as in the paper's ablation of the block width n_b, which is also its
+  group size), stored as fp16, or as bf16 (the paper's storage type) held in float32 arrays.
 """
 from __future__ import annotations
 
@@ -118,6 +120,49 @@ def make_bitmap(ntr: int, ntc: int, fractions: Optional[Dict[int, float]], rng: 
     return flat.reshape(ntr, ntc)
 
 
+def block_bitmap(ntr: int, ntc: int, fractions: Optional[Dict[int, float]], rng: np.random.Generator,
+                 mb_tiles: int = 4, nb_tiles: int = 1) -> np.ndarray:
+    """A bitmap whose widths are constant on blocks of (128*mb_tiles) x (128*nb_tiles) weights.
+
+    The paper allocates bit-widths per (m_b, n_b) block, (512, 128) in its experiments; a block is
+    a run of equal-width 128x128 tiles.  ``ntr`` and ``ntc`` must be multiples of the block.
+    """
+    assert ntr % mb_tiles == 0 and ntc % nb_tiles == 0
+    coarse = make_bitmap(ntr // mb_tiles, ntc // nb_tiles, fractions, rng)
+    return np.repeat(np.repeat(coarse, mb_tiles, axis=0), nb_tiles, axis=1).astype(np.int8)
+
+
+def to_bf16(x: np.ndarray) -> np.ndarray:
+    """Rounds to the nearest bf16 value (ties to even); returns float32 holding those values."""
+    bits = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    bits = (bits + 0x7FFF + ((bits >> 16) & 1)) >> 16
+    return (bits.astype(np.uint32) << 16).view(np.float32).reshape(np.shape(x))
+
+
+def param_bits(a: np.ndarray) -> np.ndarray:
+    """The 16 stored bits of every scale / zero: fp16 arrays as they are, bf16-in-float32 arrays by their top half."""
+    if a.dtype == np.float16:
+        return np.ascontiguousarray(a).view(np.uint16)
+    assert a.dtype == np.float32
+    return (np.ascontiguousarray(a).view(np.uint32) >> 16).astype(np.uint16)
+
+
+def _store(x: np.ndarray, scale_format: str) -> np.ndarray:
+    if scale_format == "fp16":
+        return x.astype(np.float16)
+    assert scale_format == "bf16"
+    return to_bf16(x.astype(np.float32))
+
+
+def _group_widths(bitmap: np.ndarray, group: int) -> np.ndarray:
+    """Width of every (tile row, group): all tiles under a group must agree."""
+    tpg = group // TILE
+    assert group % TILE == 0 and bitmap.shape[1] % tpg == 0
+    bg = bitmap.reshape(bitmap.shape[0], bitmap.shape[1] // tpg, tpg)
+    assert (bg == bg[:, :, :1]).all(), "tiles that share a quantisation group must have one width"
+    return bg[:, :, 0]
+
+
 def clustered_bitmap(ntr: int, ntc: int, fractions: Dict[int, float]) -> np.ndarray:
     """Widths sorted so that the widest tiles sit in the top-left corner.
 
@@ -158,34 +203,37 @@ def make_perm(n: int, rng: np.random.Generator) -> np.ndarray:
 # --------------------------------------------------------------------------------------
 # test-data quantiser (harness only; both the oracle and the HIP path consume its output)
 # --------------------------------------------------------------------------------------
-def quantize_minmax(Wt: np.ndarray, bitmap: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+def quantize_minmax(Wt: np.ndarray, bitmap: np.ndarray, group: int = GROUP,
+                    scale_format: str = "fp16") -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """Asymmetric min-max group quantisation of the reordered weight ``Wt`` [N, K].
 
-    Per row n and per group g of 128 consecutive reordered columns, at the width b of
-    the tile that holds the group: step ``s = fp16((max - min) / (2^b - 1))`` (the
-    uniform-quantiser step of the paper's Eq. 5), ``z = fp16(min)`` and
+    Per row n and per group g of ``group`` consecutive reordered columns, at the width b of
+    the tiles that hold the group: step ``s = store((max - min) / (2^b - 1))`` (the
+    uniform-quantiser step of the paper's Eq. 5), ``z = store(min)`` and
     ``q = clip(rint((w - z) / s), 0, 2^b - 1)`` evaluated in float64 with the
-    fp16-rounded s and z.  A group whose step rounds to zero gets ``s = 1, q = 0``.
-    Returns (codes uint8 [N,K], scales fp16 [K/128,N], zeros fp16 [K/128,N]).
+    stored (fp16- or bf16-rounded) s and z.  A group whose step rounds to zero gets ``s = 1, q = 0``.
+    Returns (codes uint8 [N,K], scales [K/group,N], zeros [K/group,N]).
     """
     N, K = Wt.shape
-    assert N % TILE == 0 and K % GROUP == 0
-    ng = K // GROUP
+    assert N % TILE == 0 and K % group == 0
+    ng = K // group
+    gw = _group_widths(bitmap, group)
+    sdt = np.float16 if scale_format == "fp16" else np.float32
     codes = np.empty((N, K), dtype=np.uint8)
-    scales = np.empty((ng, N), dtype=np.float16)
-    zeros = np.empty((ng, N), dtype=np.float16)
+    scales = np.empty((ng, N), dtype=sdt)
+    zeros = np.empty((ng, N), dtype=sdt)
     rows_per_step = TILE * max(1, (1 << 22) // (K * TILE) or 1)
     for r0 in range(0, N, rows_per_step):
         r1 = min(N, r0 + rows_per_step)
-        w = Wt[r0:r1].astype(np.float64).reshape(r1 - r0, ng, GROUP)
-        b = np.repeat(bitmap[r0 // TILE:(r1 + TILE - 1) // TILE].astype(np.int64), TILE, axis=0)[: r1 - r0]
+        w = Wt[r0:r1].astype(np.float64).reshape(r1 - r0, ng, group)
+        b = np.repeat(gw[r0 // TILE:(r1 + TILE - 1) // TILE].astype(np.int64), TILE, axis=0)[: r1 - r0]
         levels = (2.0 ** b - 1.0)  # [rows, ng]
         lo = w.min(axis=2)
         hi = w.max(axis=2)
-        s16 = ((hi - lo) / levels).astype(np.float16)
-        z16 = lo.astype(np.float16)
+        s16 = _store((hi - lo) / levels, scale_format)
+        z16 = _store(lo, scale_format)
         degenerate = (s16 == 0) | ~np.isfinite(s16)
-        s16 = np.where(degenerate, np.float16(1.0), s16)
+        s16 = np.where(degenerate, sdt(1.0), s16)
         s = s16.astype(np.float64)[:, :, None]
         z = z16.astype(np.float64)[:, :, None]
         q = np.clip(np.rint((w - z) / s), 0.0, levels[:, :, None])
@@ -196,21 +244,22 @@ def quantize_minmax(Wt: np.ndarray, bitmap: np.ndarray) -> Tuple[np.ndarray, np.
     return codes, scales, zeros
 
 
-def random_quantized(N: int, K: int, bitmap: np.ndarray, std: float,
-                     rng: np.random.Generator) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+def random_quantized(N: int, K: int, bitmap: np.ndarray, std: float, rng: np.random.Generator,
+                     group: int = GROUP, scale_format: str = "fp16") -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """Codes / scales / zeros with the value ranges of ``quantize_minmax`` but drawn directly.
 
     Used only where building and quantising a float weight would dominate the run
     (timing loops); codes are uniform in [0, 2^b), the group range is about 5 sigma.
     """
-    ng = K // GROUP
+    ng = K // group
+    gw = _group_widths(bitmap, group)
     bm = np.repeat(np.repeat(bitmap.astype(np.uint8), TILE, axis=0), TILE, axis=1)
     raw = rng.integers(0, 256, size=(N, K), dtype=np.uint8)
     codes = (raw & ((np.uint8(1) << bm) - np.uint8(1))).astype(np.uint8)
     span = (5.0 * std) * (1.0 + 0.1 * rng.standard_normal((ng, N)))
-    lv = (2.0 ** np.repeat(bitmap.astype(np.float64), TILE, axis=0).T - 1.0)  # [ng, N]
-    scales = (span / lv).astype(np.float16)
-    zeros = (-0.5 * span * (1.0 + 0.05 * rng.standard_normal((ng, N)))).astype(np.float16)
+    lv = (2.0 ** np.repeat(gw.astype(np.float64), TILE, axis=0).T - 1.0)  # [ng, N]
+    scales = _store(span / lv, scale_format)
+    zeros = _store(-0.5 * span * (1.0 + 0.05 * rng.standard_normal((ng, N))), scale_format)
     return codes, scales, zeros
 
 
@@ -228,14 +277,16 @@ class Problem:
     X: np.ndarray  # fp16 [M, K], original column order
     bitmap: np.ndarray  # int8 [N/128, K/128]
     codes: np.ndarray  # uint8 [N, K], reordered coordinates
-    scales: np.ndarray  # fp16 [K/128, N]
-    zeros: np.ndarray  # fp16 [K/128, N]
+    scales: np.ndarray  # [K/group, N]: fp16, or float32 holding bf16 values
+    zeros: np.ndarray  # same
     col_perm: Optional[np.ndarray]  # int32 [K] or None (identity)
     row_perm: Optional[np.ndarray]  # int32 [N] or None (leave rows reordered)
     W: Optional[np.ndarray] = None  # fp16 [N, K] original coordinates, if materialised
     Wt: Optional[np.ndarray] = None  # fp16 [N, K] reordered, if kept
     seed: int = 0
     meta: dict = field(default_factory=dict)
+    group: int = GROUP  # quantisation group length along K (128, 256 or 512)
+    scale_format: str = "fp16"  # storage type of scales and zeros: "fp16" or "bf16"
 
     @property
     def avg_bits(self) -> float:
@@ -245,7 +296,8 @@ class Problem:
 def make_problem(label: str, K: int, N: int, M: int, seed: int, *, w_std: float = 0.02,
                  fractions: Optional[Dict[int, float]] = None, outliers: bool = False,
                  use_col_perm: bool = True, use_row_perm: bool = True, bitmap: Optional[np.ndarray] = None,
-                 keep_weights: bool = False, from_original: bool = False, fast_codes: bool = False) -> Problem:
+                 keep_weights: bool = False, from_original: bool = False, fast_codes: bool = False,
+                 group: int = GROUP, scale_format: str = "fp16", block: Tuple[int, int] = (1, 1)) -> Problem:
     """Build one seeded problem.
 
     ``from_original`` draws W in original coordinates and reorders it with the two
@@ -256,13 +308,16 @@ def make_problem(label: str, K: int, N: int, M: int, seed: int, *, w_std: float 
     rng = _rng(seed)
     ntr, ntc = N // TILE, K // TILE
     if bitmap is None:
-        bitmap = make_bitmap(ntr, ntc, fractions, rng)
+        # ``block`` = (rows, columns) of a bit-allocation block in tiles; a group never spans blocks
+        nb = max(block[1], group // TILE)
+        bitmap = make_bitmap(ntr, ntc, fractions, rng) if (block[0], nb) == (1, 1) else \
+            block_bitmap(ntr, ntc, fractions, rng, block[0], nb)
     col_perm = make_perm(K, rng) if use_col_perm else None
     row_perm = make_perm(N, rng) if use_row_perm else None
     X = make_activations(M, K, _rng_x(seed, M), outliers=outliers)
     W = Wt = None
     if fast_codes:
-        codes, scales, zeros = random_quantized(N, K, bitmap, w_std, rng)
+        codes, scales, zeros = random_quantized(N, K, bitmap, w_std, rng, group, scale_format)
     else:
         if from_original:
             W = make_weights(N, K, w_std, rng)
@@ -274,10 +329,10 @@ def make_problem(label: str, K: int, N: int, M: int, seed: int, *, w_std: float 
             Wt = np.ascontiguousarray(Wt)
         else:
             Wt = make_weights(N, K, w_std, rng)
-        codes, scales, zeros = quantize_minmax(Wt, bitmap)
+        codes, scales, zeros = quantize_minmax(Wt, bitmap, group, scale_format)
     return Problem(label=label, N=N, K=K, M=M, X=X, bitmap=bitmap, codes=codes, scales=scales, zeros=zeros,
                    col_perm=col_perm, row_perm=row_perm, W=W if keep_weights else None,
-                   Wt=Wt if keep_weights else None, seed=seed)
+                   Wt=Wt if keep_weights else None, seed=seed, group=group, scale_format=scale_format)
 
 
 def with_activations(p: "Problem", M: int, outliers: bool) -> "Problem":
@@ -304,15 +359,15 @@ def config_cases(cid: int) -> Iterator[Tuple[str, int, int, int, int, dict]]:
 # byte accounting (what the method itself has to move)
 # --------------------------------------------------------------------------------------
 def algorithmic_bytes(N: int, K: int, M: int, bitmap: np.ndarray, *, col_perm: bool = True,
-                      row_perm: bool = True, index_words: int = 0) -> int:
+                      row_perm: bool = True, index_words: int = 0, group: int = GROUP) -> int:
     """Bytes one GEMM call must move at minimum.
 
-    codes: N*K*b/8 summed over tiles; fp16 scale+zero: 4 bytes per row per group;
+    codes: N*K*b/8 summed over tiles; 16-bit scale+zero: 4 bytes per row per group;
     X and Y in fp16; the two int32 permutation vectors; the int8 bitmap; optionally the
     block-index table words that replace a run-time offset computation.
     """
     code_bytes = int(bitmap.astype(np.int64).sum()) * (TILE * TILE // 8)
-    sz_bytes = N * (K // GROUP) * 4
+    sz_bytes = N * (K // group) * 4
     xy = 2 * M * K + 2 * M * N
     perms = 4 * K * int(col_perm) + 4 * N * int(row_perm)
     return code_bytes + sz_bytes + xy + perms + bitmap.size + 4 * index_words

@@ -182,3 +182,53 @@ def test_rel_frobenius_definition():
     b = np.array([[3.0, 0.0]])
     assert O.rel_frobenius(a, b) == pytest.approx(4.0 / 3.0)
     assert O.rel_frobenius(b, b) == 0.0
+
+
+# ---- group lengths beyond 128 and bf16 parameters ("Effect of n_b" ablation; Table 1 caption) -----------
+@pytest.mark.parametrize("group", [256, 512])
+def test_longer_groups_match_bruteforce_and_reduce_to_group_128(group):
+    p = _small_problem(seed=21, N=256, K=1024, fractions={2: 0.5, 4: 0.5}, group=group)
+    assert p.scales.shape == (p.K // group, p.N)
+    w_hat = O.dequant(p.codes, p.scales, p.zeros)
+    # brute force on a sample of elements, straight from the definition
+    rng = np.random.default_rng(3)
+    for n, k in zip(rng.integers(0, p.N, 200), rng.integers(0, p.K, 200)):
+        g = k // group
+        assert w_hat[n, k] == float(p.scales[g, n]) * float(p.codes[n, k]) + float(p.zeros[g, n])
+    # a parameter shared by `group` columns is the same as that parameter repeated for every 128 columns
+    rep = group // 128
+    w_128 = O.dequant(p.codes, np.repeat(p.scales, rep, axis=0), np.repeat(p.zeros, rep, axis=0))
+    assert np.array_equal(w_hat, w_128)
+    rows = np.array([0, 5, 130, 255])
+    assert np.array_equal(O.dequant_rows(p.codes, p.scales, p.zeros, rows), w_hat[rows])
+    # the quantiser used one width per group: its error stays within half a step
+    err = np.abs(w_hat - p.Wt.astype(np.float64))
+    step = np.repeat(p.scales.astype(np.float64).T, group, axis=1)
+    assert (err <= 0.5 * step * (1 + 1e-2) + 1e-3 * np.abs(p.Wt.astype(np.float64)) + 1e-6).all()
+
+
+def test_bf16_storage_values_and_bits():
+    # bf16 keeps the top 16 bits of the float32 pattern, rounded to nearest even
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 3.14159, -2.5e-3, 0.0], dtype=np.float32)
+    y = W.to_bf16(x)
+    assert y.tolist() == [1.0, 1.0, 1.015625, 3.140625, -0.00250244140625, 0.0]
+    assert W.param_bits(y).tolist() == [0x3F80, 0x3F80, 0x3F82, 0x4049, 0xBB24, 0x0000]
+    assert W.param_bits(np.array([1.0, -2.0], dtype=np.float16)).tolist() == [0x3C00, 0xC000]
+    p = _small_problem(seed=22, N=128, K=512, scale_format="bf16")
+    assert p.scales.dtype == np.float32 and np.array_equal(W.to_bf16(p.scales), p.scales)
+    w_hat = O.dequant(p.codes, p.scales, p.zeros)
+    assert w_hat[3, 200] == float(p.scales[1, 3]) * float(p.codes[3, 200]) + float(p.zeros[1, 3])
+    # the quantised weight tracks the original to within half a step plus the bf16 rounding of the zero-point
+    err = np.abs(w_hat - p.Wt.astype(np.float64))
+    step = np.repeat(p.scales.astype(np.float64).T, 128, axis=1)
+    zmag = np.repeat(np.abs(p.zeros.astype(np.float64)).T, 128, axis=1)
+    assert (err <= 0.5 * step * (1 + 1e-2) + zmag * 2.0 ** -8 + 1e-6).all()
+
+
+def test_block_bitmap_is_constant_on_blocks():
+    bm = W.block_bitmap(8, 6, {2: 0.5, 3: 0.25, 4: 0.25}, np.random.default_rng(0), mb_tiles=4, nb_tiles=2)
+    assert bm.shape == (8, 6)
+    for i in range(0, 8, 4):
+        for j in range(0, 6, 2):
+            assert (bm[i:i + 4, j:j + 2] == bm[i, j]).all()
+    assert sorted(np.unique(bm).tolist()) == [2, 3, 4]
