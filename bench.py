@@ -67,6 +67,7 @@ class Layer:
         self.proj = []  # per projection: dict(layout, reps=[DevicePacked...], X, Y, cp, rp, ws, bytes)
         for p in problems:
             L, s2, s3, s4, index = S.sfmp_pack(p.codes, p.bitmap)
+            S.sfmp_layout_set_quant(L, p.group, p.scale_format)
             reps = [S.upload_packed(L, s2, s3, s4, index, p.scales, p.zeros, p.bitmap, device) for _ in range(replicas)]
             cp = [torch.from_numpy(p.col_perm).to(device) for _ in range(replicas)] if p.col_perm is not None else None
             rp = [torch.from_numpy(p.row_perm).to(device) for _ in range(replicas)] if p.row_perm is not None else None
@@ -139,11 +140,12 @@ class Layer:
         for d in self.proj:
             p = d["p"]
             out.append(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, col_perm=p.col_perm is not None,
-                                           row_perm=p.row_perm is not None, index_words=p.bitmap.size))
+                                           row_perm=p.row_perm is not None, index_words=p.bitmap.size, group=p.group))
         return out
 
 
-def build_problems(W, cid, Ms=None, fast=False, only=None):
+def build_problems(W, cid, Ms=None, fast=False, only=None, **fmt):
+    """fmt: group / scale_format / block passed on to the generator (default: group 128, fp16, 128x128 blocks)."""
     spec = W.CONFIGS[cid]
     out = []
     for si, (label, K, N) in enumerate(spec.shapes):
@@ -152,7 +154,7 @@ def build_problems(W, cid, Ms=None, fast=False, only=None):
         M = (Ms or spec.Ms)[0]
         out.append(W.make_problem(label, K, N, M, 1000 * cid + si, w_std=spec.w_std[si], fractions=spec.fractions,
                                   outliers=spec.outliers, use_col_perm=spec.col_perm, use_row_perm=spec.row_perm[si],
-                                  fast_codes=fast))
+                                  fast_codes=fast, **fmt))
     return out
 
 
@@ -360,6 +362,18 @@ def main():
                                                               GBps=round(b / t / 1e3, 1))
                                                          for d, t, b in zip(l70.proj, per70, b70p)])
             del l70, p70
+            torch.cuda.empty_cache()
+        if args.section in ("all", "decode"):
+            # the paper's own parameter format on the 8B layer at M = 1: (512, 256) bit-allocation blocks, group 256,
+            # bf16 scales and zeros (its best setting at low bit budgets), same 1/3-each width mix, 4 launches
+            pf = build_problems(W, 2, fast=True, group=256, scale_format="bf16", block=(4, 2))
+            bf = sum(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, index_words=p.bitmap.size, group=p.group) for p in pf)
+            lf = Layer(pf, int(np.ceil(2 ** 30 / bf)))
+            msf, _ = time_steps(torch, lf, 120, 12, use_graph=not args.eager, groups=FUSED_GROUPS)
+            extra["layer_8b_M1_blocks512x256_group256_bf16"] = dict(
+                us_per_layer=round(msf * 1e3, 2), MB=round(bf / 1e6, 1), GBps=round(bf / msf / 1e6, 1),
+                pct_hbm_peak=round(100 * bf / msf / 1e6 / HBM_PEAK_GBPS, 2))
+            del lf, pf
             torch.cuda.empty_cache()
         if args.section in ("all", "batch"):
             # small batches (configs[2]: 50 % 2-bit / 50 % 3-bit) through the ring-skinny kernel: 4 batched calls

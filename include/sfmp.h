@@ -65,7 +65,9 @@ extern "C" {
 #endif
 
 #define SFMP_TILE 128
-#define SFMP_GROUP 128
+#define SFMP_GROUP 128        /* default quantisation group length along K */
+#define SFMP_SCALE_FP16 0     /* scales and zeros stored as IEEE fp16 */
+#define SFMP_SCALE_BF16 1     /* ... as bfloat16 (the storage type of the paper's Table 1) */
 
 #define SFMP_OK 0
 #define SFMP_ERR_NULL (-1)        /* a required pointer is NULL */
@@ -85,6 +87,8 @@ typedef struct sfmp_layout {
   int32_t count2, count3, count4;  /* tiles of each width */
   int32_t index_words;             /* length of the block-index table in int32 words */
   int64_t bytes_s2, bytes_s3, bytes_s4, bytes_index;
+  int32_t scale_format;            /* SFMP_SCALE_FP16 (default) or SFMP_SCALE_BF16 */
+  int32_t reserved;                /* 0 */
 } sfmp_layout_t;
 
 /* Text for an error code (static storage, never NULL).  For SFMP_ERR_HIP the text of the last
@@ -94,6 +98,13 @@ const char* sfmp_strerror(int code);
 /* Host only.  Sizes of the three streams and of the index table for a bitmap
  * (int8 [N/128, K/128], row-major, host).  Section 4.3 "Extra Metadata": one int8 per block. */
 int sfmp_pack_query(const int8_t* bitmap_host, int32_t N, int32_t K, sfmp_layout_t* out);
+
+/* Host only.  Chooses the quantisation-parameter format of a layout filled by sfmp_pack_query / sfmp_pack
+ * (which set group 128, fp16): group = 128, 256 or 512 columns per (scale, zero) pair, K a multiple of it
+ * (Appendix "Effect of n_b": the block width n_b is also the group size); scale_format = SFMP_SCALE_FP16 or
+ * SFMP_SCALE_BF16.  The packed streams and the index table do not depend on either.  scales and zeros are then
+ * [K/group, N] arrays of 16-bit values in that format.  SFMP_ERR_LAYOUT for any other value. */
+int sfmp_layout_set_quant(sfmp_layout_t* layout, int32_t group, int32_t scale_format);
 
 /* Host only.  Packs codes (uint8 [N, K] row-major, reordered coordinates, host) into the three
  * streams and writes the block-index table; all four outputs are host buffers of the sizes
@@ -128,7 +139,8 @@ int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream);
  *             (Section 3.4: the weight's column permutation applied to the activation);
  *             NULL = identity.
  *   layout, s2, s3, s4, index   a matrix packed by sfmp_pack, uploaded unchanged.
- *   scales, zeros  fp16 [K/128, N] (group-major): w_hat = s*q + z (Appendix B Eq. 11).
+ *   scales, zeros  16-bit [K/group, N] (group-major; group and storage type from the layout, fp16 and 128
+ *             unless sfmp_layout_set_quant said otherwise): w_hat = s*q + z (Appendix B Eq. 11).
  *   bitmap    int8 [N/128, K/128] (device); must be the bitmap the matrix was packed with.
  *   row_perm  int32 [N]; output feature i of the reordered product is stored at column
  *             row_perm[i] of Y (undoing P_row of Eq. 9); NULL = leave the rows reordered.

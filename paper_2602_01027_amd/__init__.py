@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     load_library,
     sfmp_strerror,
     sfmp_pack_query,
+    sfmp_layout_set_quant,
     sfmp_pack,
     sfmp_unpack,
     sfmp_gemm_workspace,

@@ -24,6 +24,7 @@ class SfmpLayout(C.Structure):
         ("N", C.c_int32), ("K", C.c_int32), ("tile", C.c_int32), ("group", C.c_int32),
         ("count2", C.c_int32), ("count3", C.c_int32), ("count4", C.c_int32), ("index_words", C.c_int32),
         ("bytes_s2", C.c_int64), ("bytes_s3", C.c_int64), ("bytes_s4", C.c_int64), ("bytes_index", C.c_int64),
+        ("scale_format", C.c_int32), ("reserved", C.c_int32),
     ]
 
 
@@ -32,7 +33,7 @@ class SfmpGemvProblem(C.Structure):
                                           "bitmap", "row_perm", "Y")]
 
 
-EXPORTS = ("sfmp_strerror", "sfmp_pack_query", "sfmp_pack", "sfmp_unpack", "sfmp_gemm_workspace",
+EXPORTS = ("sfmp_strerror", "sfmp_pack_query", "sfmp_layout_set_quant", "sfmp_pack", "sfmp_unpack", "sfmp_gemm_workspace",
            "sfmp_workspace_init", "sfmp_gemm", "sfmp_gemv_batched", "sfmp_gemm_batched_workspace",
            "sfmp_gemm_batched", "sfmp_check_perm")
 
@@ -148,8 +149,22 @@ def upload_packed(layout, s2, s3, s4, index, scales, zeros, bitmap, device="cuda
     def up(a):
         return torch.from_numpy(np.ascontiguousarray(a)).to(device)
 
-    return DevicePacked(layout, up(s2), up(s3), up(s4), up(index), up(scales.view(np.float16)),
-                        up(zeros.view(np.float16)), up(bitmap.astype(np.int8)))
+    def bits(a):
+        """The 16 stored bits of each parameter: fp16 arrays as they are, float32 arrays (bf16 values) by their top
+        half; handed to torch as float16 storage, which the library reads as raw 16-bit words."""
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.float32:
+            a = (a.view(np.uint32) >> 16).astype(np.uint16)
+        return a.view(np.float16)
+
+    return DevicePacked(layout, up(s2), up(s3), up(s4), up(index), up(bits(scales)), up(bits(zeros)),
+                        up(bitmap.astype(np.int8)))
+
+
+def sfmp_layout_set_quant(layout: SfmpLayout, group: int = 128, scale_format: str = "fp16") -> SfmpLayout:
+    """Sets the group length (128 / 256 / 512) and the storage type ("fp16" / "bf16") of scales and zeros."""
+    _check(load_library().sfmp_layout_set_quant(C.byref(layout), int(group), {"fp16": 0, "bf16": 1}[scale_format]))
+    return layout
 
 
 def sfmp_unpack(layout: SfmpLayout, s2, s3, s4, index, codes_out, stream=None) -> None:

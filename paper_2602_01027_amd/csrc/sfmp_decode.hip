@@ -60,6 +60,8 @@ struct GemvParams {
   _Float16* Y;
   int32_t N, K, ntr, ntc, nslab;
   int32_t max_slabs;  // slabs per workgroup (upper bound), sizes the reduction buffer
+  int32_t gshift;     // log2(group / 128): tile column tc uses parameter row tc >> gshift
+  int32_t bf16;       // scales and zeros are bfloat16 (else fp16)
 #ifdef SFMP_EXPERIMENT
   int32_t dbg;
   int32_t dbg_count[3];
@@ -84,7 +86,29 @@ constexpr int kSlotBytes = 1024 + 128;  // slab bytes (<= 1 KiB) + 16 scale dwor
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-// sum of the 8 halves of a 16-byte unit, then over the 16 lanes (= 128 columns = one group)
+// The scale and the zero of an item as floats.  Each sits in the low or the high half (shift = 0 or 16, the same
+// for the whole wavefront) of its dword, as IEEE fp16 or as bfloat16 (= the top half of a float).  `bf16` is
+// wave-uniform; the marker keeps the two formats on separate paths instead of computing both and selecting.
+__device__ __forceinline__ void params_to_float(uint32_t scale_dword, uint32_t zero_dword, uint32_t shift, bool bf16,
+                                                float& sf, float& zf) {
+  const uint32_t sb = scale_dword >> shift, zb = zero_dword >> shift;
+  if (bf16) {
+    asm volatile("; bfloat16 parameters");
+    sf = __uint_as_float(sb << 16);
+    zf = __uint_as_float(zb << 16);
+  } else {
+    union {
+      uint16_t u;
+      _Float16 h;
+    } a, b;
+    a.u = (uint16_t)sb;
+    b.u = (uint16_t)zb;
+    sf = (float)a.h;
+    zf = (float)b.h;
+  }
+}
+
+// sum of the 8 halves of a 16-byte unit, then over the 16 lanes (= 128 columns = one tile column)
 __device__ __forceinline__ float unit_group_sum(const half8& v) {
   float s = 0.f;
 #pragma unroll
@@ -148,7 +172,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
     // address of the aligned dword holding the fp16 scale of row 128*tr + sigma (rows 8*l + sigma are
     // 16 bytes apart); direct-to-LDS copies need dword-aligned addresses, the wanted fp16 is the
     // low half for even sigma and the high half for odd sigma
-    const uint64_t sa = (uint64_t)(p.scales + (int64_t)tc * p.N + (int64_t)tr * kTile + (sigma & ~1));
+    const uint64_t sa = (uint64_t)(p.scales + (int64_t)(tc >> p.gshift) * p.N + (int64_t)tr * kTile + (sigma & ~1));
     it_alo = (uint32_t)a;
     it_ahi = (uint32_t)(a >> 32);
     it_slo = (uint32_t)sa;
@@ -251,15 +275,10 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
         case 1: t = gemv_item<3>(slot, lane, a); break;
         default: t = gemv_item<4>(slot, lane, a); break;
       }
-      union {
-        uint32_t u;
-        half2_ h;
-      } sc, zr;
-      sc.u = *reinterpret_cast<const uint32_t*>(slot + 1024 + (lane & 15) * 4);
-      zr.u = *reinterpret_cast<const uint32_t*>(slot + 1088 + (lane & 15) * 4);
-      const bool odd = (misc >> 26) & 1;
-      const float sf = odd ? (float)sc.h[1] : (float)sc.h[0];
-      const float zf = odd ? (float)zr.h[1] : (float)zr.h[0];
+      const uint32_t scw = *reinterpret_cast<const uint32_t*>(slot + 1024 + (lane & 15) * 4);
+      const uint32_t zrw = *reinterpret_cast<const uint32_t*>(slot + 1088 + (lane & 15) * 4);
+      float sf, zf;
+      params_to_float(scw, zrw, (misc >> 22) & 16u, p.bf16 != 0, sf, zf);  // bit 26 of misc: odd sigma -> high half
       acc += sf * t + zf * sx;
     }
     if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
@@ -357,6 +376,7 @@ struct RSkinnyParams {
   const int32_t* row_perm;
   _Float16* Y;
   int32_t M, N, K, ntr, ntc, nslab, max_slabs;
+  int32_t gshift, bf16;  // as in GemvParams
 };
 
 // one workgroup per tile column; thread (m, u) gathers the 8 columns of unit u' = u ^ m of row m
@@ -429,7 +449,7 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
       const uint8_t* base = bm2 == 0 ? p.s2 : bm2 == 1 ? p.s3 : p.s4;
       const int64_t slab_bytes = 256 * (bm2 + 2);
       const uint64_t a = (uint64_t)(base + (int64_t)(d >> 2) * (8 * slab_bytes) + sigma * slab_bytes);
-      const uint64_t sa = (uint64_t)(p.scales + (int64_t)tc * p.N + (int64_t)tr * kTile + (sigma & ~1));
+      const uint64_t sa = (uint64_t)(p.scales + (int64_t)(tc >> p.gshift) * p.N + (int64_t)tr * kTile + (sigma & ~1));
       it_alo = (uint32_t)a;
       it_ahi = (uint32_t)(a >> 32);
       it_slo = (uint32_t)sa;
@@ -508,15 +528,10 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
           break;
       }
     }
-    union {
-      uint32_t u;
-      half2_ h;
-    } sc, zr;
-    sc.u = *reinterpret_cast<const uint32_t*>(slot + 1024 + (lane & 15) * 4);
-    zr.u = *reinterpret_cast<const uint32_t*>(slot + 1088 + (lane & 15) * 4);
-    const bool odd = (misc >> 26) & 1;
-    const float sf = odd ? (float)sc.h[1] : (float)sc.h[0];
-    const float zf = odd ? (float)zr.h[1] : (float)zr.h[0];
+    const uint32_t scw = *reinterpret_cast<const uint32_t*>(slot + 1024 + (lane & 15) * 4);
+    const uint32_t zrw = *reinterpret_cast<const uint32_t*>(slot + 1088 + (lane & 15) * 4);
+    float sf, zf;
+    params_to_float(scw, zrw, (misc >> 22) & 16u, p.bf16 != 0, sf, zf);  // bit 26 of misc: odd sigma -> high half
     acc += sf * t + zf * sx;
     if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
       switch ((misc >> 17) & 0x7F) {
@@ -716,6 +731,8 @@ static GemvParams gemv_params(const GemmArgs& a, int32_t max_slabs) {
   p.ntc = L->K / kTile;
   p.nslab = 8 * p.ntr;
   p.max_slabs = max_slabs;
+  p.gshift = L->group == 512 ? 2 : L->group == 256 ? 1 : 0;
+  p.bf16 = L->scale_format == SFMP_SCALE_BF16;
 #ifdef SFMP_EXPERIMENT
   p.dbg = g_sfmp_debug;
   p.dbg_count[0] = L->count2 > 0 ? L->count2 : 1;
@@ -768,7 +785,7 @@ static int split_grid(const GemmArgs* probs, int count, int32_t* g) {
   int32_t total = 0;
   for (int i = 0; i < count; ++i) {
     const sfmp_layout_t* L = probs[i].L;
-    bytes[i] = L->bytes_s2 + L->bytes_s3 + L->bytes_s4 + (int64_t)L->N * (L->K / kTile) * 4;
+    bytes[i] = L->bytes_s2 + L->bytes_s3 + L->bytes_s4 + (int64_t)L->N * (L->K / L->group) * 4;
     g[i] = 8;
     total += 8;
   }
@@ -854,6 +871,8 @@ static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* 
   p.ntc = ntc;
   p.nslab = 8 * p.ntr;
   p.max_slabs = d.max_slabs;
+  p.gshift = L->group == 512 ? 2 : L->group == 256 ? 1 : 0;
+  p.bf16 = L->scale_format == SFMP_SCALE_BF16;
   void* kargs[] = {&p};
   hipError_t e = hipLaunchKernel(fn, dim3((unsigned)d.grid), dim3(NW * 64), kargs, (size_t)d.lds_bytes, (hipStream_t)stream);
   if (e != hipSuccess) {
@@ -957,6 +976,8 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
     p.ntc = L->K / kTile;
     p.nslab = nslab;
     p.max_slabs = max_slabs;
+    p.gshift = L->group == 512 ? 2 : L->group == 256 ? 1 : 0;
+    p.bf16 = L->scale_format == SFMP_SCALE_BF16;
     const int64_t need = (int64_t)max_slabs * 1024 + (int64_t)NW * S * rskinny_slot_bytes<MB>();
     lds = need > lds ? need : lds;
     b.first[i] = first;

@@ -22,7 +22,9 @@ int check_shape(int32_t N, int32_t K) {
 int check_layout(const sfmp_layout_t* L) {
   if (!L) return SFMP_ERR_NULL;
   if (check_shape(L->N, L->K) != SFMP_OK) return SFMP_ERR_SHAPE;
-  if (L->tile != SFMP_TILE || L->group != SFMP_GROUP) return SFMP_ERR_LAYOUT;
+  if (L->tile != SFMP_TILE) return SFMP_ERR_LAYOUT;
+  if ((L->group != 128 && L->group != 256 && L->group != 512) || (L->K % L->group) != 0) return SFMP_ERR_LAYOUT;
+  if (L->scale_format != SFMP_SCALE_FP16 && L->scale_format != SFMP_SCALE_BF16) return SFMP_ERR_LAYOUT;
   const int64_t ntr = L->N / SFMP_TILE, ntc = L->K / SFMP_TILE, nt = ntr * ntc;
   if (L->count2 < 0 || L->count3 < 0 || L->count4 < 0) return SFMP_ERR_LAYOUT;
   if ((int64_t)L->count2 + L->count3 + L->count4 != nt) return SFMP_ERR_LAYOUT;
@@ -112,6 +114,7 @@ int sfmp_pack_query(const int8_t* bitmap_host, int32_t N, int32_t K, sfmp_layout
   out->K = K;
   out->tile = SFMP_TILE;
   out->group = SFMP_GROUP;
+  out->scale_format = SFMP_SCALE_FP16;
   out->count2 = (int32_t)cnt[2];
   out->count3 = (int32_t)cnt[3];
   out->count4 = (int32_t)cnt[4];
@@ -168,6 +171,16 @@ int sfmp_pack(const uint8_t* codes_host, const int8_t* bitmap_host, int32_t N, i
     for (int b = 2; b <= 4; ++b) row_ptr[b][tr + 1] = next_slot[b];
   }
   *out = L;
+  return SFMP_OK;
+}
+
+int sfmp_layout_set_quant(sfmp_layout_t* layout, int32_t group, int32_t scale_format) {
+  if (!layout) return SFMP_ERR_NULL;
+  sfmp_layout_t t = *layout;
+  t.group = group;
+  t.scale_format = scale_format;
+  if (int e = check_layout(&t)) return e;
+  *layout = t;
   return SFMP_OK;
 }
 

@@ -104,6 +104,8 @@ struct PrefillParams {
   const _Float16* zeros;
   _Float16* Yt;  // [M, N], rows of Wt in reordered order
   int32_t M, N, K, ntr, ntc, n_mtiles;
+  int32_t gshift;  // log2(group / 128): tile column tc uses parameter row tc >> gshift
+  int32_t bf16;    // scales and zeros are bfloat16 (else fp16)
 };
 
 constexpr int kPrefillMaxTiles = 224 * 2;  // K <= 57344
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) 
     uint32_t s[NS / 2], z[NS / 2];
   };
   auto issue_sz = [&](int tc, SZ& rsz) __attribute__((always_inline)) {
-    const int64_t off = (int64_t)tc * p.N + (int64_t)tr * 128 + 8 * i16 + NS * wn;
+    const int64_t off = (int64_t)(tc >> p.gshift) * p.N + (int64_t)tr * 128 + 8 * i16 + NS * wn;
 #pragma unroll
     for (int q = 0; q < NS / 2; ++q) {
       rsz.s[q] = reinterpret_cast<const uint32_t*>(p.scales + off)[q];
@@ -386,8 +388,13 @@ __global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) 
       } sv, zv;
       sv.u = rsz.s[j / 2];
       zv.u = rsz.z[j / 2];
-      s2[j] = half2_{sv.h[j % 2], sv.h[j % 2]};
-      z2[j] = half2_{zv.h[j % 2], zv.h[j % 2]};
+      _Float16 sh = sv.h[j % 2], zh = zv.h[j % 2];
+      if (p.bf16) {  // bfloat16 = top half of a float; the dequantisation runs in fp16
+        sh = (_Float16)__uint_as_float((j % 2 ? sv.u >> 16 : sv.u & 0xFFFFu) << 16);
+        zh = (_Float16)__uint_as_float((j % 2 ? zv.u >> 16 : zv.u & 0xFFFFu) << 16);
+      }
+      s2[j] = half2_{sh, sh};
+      z2[j] = half2_{zh, zh};
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
@@ -563,6 +570,8 @@ int launch_prefill(const GemmArgs& a, void* stream) {
   p.K = L->K;
   p.ntr = L->N / kTile;
   p.ntc = L->K / kTile;
+  p.gshift = L->group == 512 ? 2 : L->group == 256 ? 1 : 0;
+  p.bf16 = L->scale_format == SFMP_SCALE_BF16;
   p.n_mtiles = 0;
 #ifdef SFMP_EXPERIMENT
   switch (g_sfmp_debug & 7) {

@@ -7,6 +7,7 @@ def device_problem(p, device="cuda:0"):
     import paper_2602_01027_amd as S
 
     L, s2, s3, s4, index = S.sfmp_pack(p.codes, p.bitmap)
+    S.sfmp_layout_set_quant(L, p.group, p.scale_format)
     dp = S.upload_packed(L, s2, s3, s4, index, p.scales, p.zeros, p.bitmap, device)
     cp = torch.from_numpy(p.col_perm).to(device) if p.col_perm is not None else None
     rp = torch.from_numpy(p.row_perm).to(device) if p.row_perm is not None else None

@@ -277,3 +277,37 @@ def test_gemm_batched_shared_activations(torch_cuda, M):
         # the batched launch computes exactly what separate launches compute
         assert np.array_equal(run_gemm(p, dp, cp, rp).view(np.uint16), y.view(np.uint16))
 
+
+# ---------------------------------------------------------------------------------------------
+# group lengths 256 / 512, bf16 parameters, (m_b, n_b) bit-allocation blocks
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("M", [1, 5, 16, 48])
+@pytest.mark.parametrize("group,scale_format,block", [(128, "bf16", (4, 1)), (256, "fp16", (2, 2)),
+                                                      (256, "bf16", (4, 2)), (512, "bf16", (4, 4))])
+def test_group_length_and_parameter_format(torch_cuda, group, scale_format, block, M):
+    # K = 1536: 12 tile columns = 6 / 3 groups of 256 / 512; N = 1024: two (512 x n_b) block rows
+    from gpu_util import run_gemm
+    p = W.make_problem("fmt", 1536, 1024, M, 606 + group, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, outliers=True,
+                       group=group, scale_format=scale_format, block=block)
+    assert p.scales.shape == (1536 // group, 1024)
+    _check(p, run_gemm(p))
+
+
+def test_batched_launch_with_mixed_parameter_formats(torch_cuda):
+    import paper_2602_01027_amd as S
+    from gpu_util import device_problem
+    torch = torch_cuda
+    probs, batch = [], []
+    for i, (group, fmt) in enumerate([(128, "fp16"), (256, "bf16"), (512, "fp16")]):
+        p = W.make_problem(f"m{i}", 1024, 256 + 128 * i, 3, 900 + i, fractions={2: 0.5, 4: 0.5}, group=group,
+                           scale_format=fmt, block=(1, group // 128))
+        dp, cp, rp = device_problem(p)
+        X = torch.from_numpy(p.X).to("cuda:0")
+        Y = torch.full((3, p.N), float("nan"), dtype=torch.float16, device="cuda:0")
+        probs.append(p)
+        batch.append((X, cp, dp, rp, Y))
+    ws = torch.empty(S.sfmp_gemm_batched_workspace(batch, 3), dtype=torch.uint8, device="cuda:0")
+    S.sfmp_gemm_batched(batch, 3, ws)
+    torch.cuda.synchronize()
+    for p, (_, _, _, _, Y) in zip(probs, batch):
+        _check(p, Y.cpu().numpy())

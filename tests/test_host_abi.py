@@ -25,8 +25,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_layout_struct_matches_header_size():
-    # 8 int32 + 4 int64 = 64 bytes, no padding
-    assert C.sizeof(S.SfmpLayout) == 64
+    # 8 int32 + 4 int64 + 2 int32 = 72 bytes, no padding
+    assert C.sizeof(S.SfmpLayout) == 72
 
 
 @settings(max_examples=10, deadline=None)
@@ -102,3 +102,22 @@ def test_check_perm():
     assert S.sfmp_check_perm(np.array([2, 0, 2], dtype=np.int32)) == -7
     assert S.sfmp_check_perm(np.array([0, 3, 1], dtype=np.int32)) == -7
     assert S.sfmp_check_perm(np.array([0, -1, 1], dtype=np.int32)) == -7
+
+
+def test_layout_set_quant_accepts_the_documented_formats_only():
+    bitmap = np.full((1, 4), 3, dtype=np.int8)  # N = 128, K = 512
+    L = S.sfmp_pack_query(bitmap, 128, 512)
+    assert (L.group, L.scale_format) == (128, 0)
+    for group in (128, 256, 512):
+        for fmt, code in (("fp16", 0), ("bf16", 1)):
+            S.sfmp_layout_set_quant(L, group, fmt)
+            assert (L.group, L.scale_format) == (group, code)
+    S.sfmp_layout_set_quant(L, 128, "fp16")
+    lib = S.load_library()
+    for group, fmt in ((64, 0), (1024, 0), (384, 0), (128, 2), (256, -1)):
+        assert lib.sfmp_layout_set_quant(C.byref(L), group, fmt) == -8
+        assert (L.group, L.scale_format) == (128, 0)  # a rejected call leaves the layout alone
+    # K must be a multiple of the group
+    L3 = S.sfmp_pack_query(np.full((1, 3), 2, dtype=np.int8), 128, 384)
+    assert lib.sfmp_layout_set_quant(C.byref(L3), 256, 0) == -8
+    assert lib.sfmp_layout_set_quant(None, 128, 0) == -1
