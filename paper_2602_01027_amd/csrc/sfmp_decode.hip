@@ -62,18 +62,7 @@ struct GemvParams {
   int32_t max_slabs;  // slabs per workgroup (upper bound), sizes the reduction buffer
   int32_t gshift;     // log2(group / 128): tile column tc uses parameter row tc >> gshift
   int32_t bf16;       // scales and zeros are bfloat16 (else fp16)
-#ifdef SFMP_EXPERIMENT
-  int32_t dbg;
-  int32_t dbg_count[3];
-#endif
 };
-#ifdef SFMP_EXPERIMENT
-#define SFMP_DBG(p, bit) (((p).dbg & (bit)) != 0)
-int g_sfmp_debug = 0;
-extern "C" void sfmp_debug_set(int v) { g_sfmp_debug = v; }
-#else
-#define SFMP_DBG(p, bit) false
-#endif
 
 constexpr int kGemvWaves = 16;       // wavefronts per workgroup; one workgroup per CU
 constexpr int kGemvMaxGrid = 256;    // persistent grid: at most one workgroup per CU
@@ -240,7 +229,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
     unsigned char* slot = ring + s * kSlotBytes;
     if (data_voff < slab_bytes)
       __builtin_amdgcn_global_load_lds((gptr_t)((const char*)a + data_voff), (lptr_t)slot, 16, 0, 0);
-    if (lane < 32 && !SFMP_DBG(p, 2))
+    if (lane < 32)
       __builtin_amdgcn_global_load_lds((gptr_t)((const char*)sa + sz_voff), (lptr_t)(slot + 1024), 4, 0, 0);
   };
 
@@ -262,25 +251,24 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
     const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
     const int tc = misc & 0xFFFF;
     const unsigned char* slot = ring + s * kSlotBytes;
-    if (!SFMP_DBG(p, 8)) {
-      if ((lane & 15) == 0) {  // only activation row 0 exists: lanes 0,16,32,48 feed it
+    if ((lane & 15) == 0) {  // only activation row 0 exists: lanes 0,16,32,48 feed it
 #pragma unroll
-        for (int kappa = 0; kappa < 4; ++kappa)
-          a[kappa] = *reinterpret_cast<const half8*>(Xs + tc * kTile + 32 * kappa + 8 * (lane / 16));
-      }
-      const float sx = Sx[tc];
-      float t;
-      switch ((misc >> 24) & 3) {
-        case 0: t = gemv_item<2>(slot, lane, a); break;
-        case 1: t = gemv_item<3>(slot, lane, a); break;
-        default: t = gemv_item<4>(slot, lane, a); break;
-      }
-      const uint32_t scw = *reinterpret_cast<const uint32_t*>(slot + 1024 + (lane & 15) * 4);
-      const uint32_t zrw = *reinterpret_cast<const uint32_t*>(slot + 1088 + (lane & 15) * 4);
-      float sf, zf;
-      params_to_float(scw, zrw, (misc >> 22) & 16u, p.bf16 != 0, sf, zf);  // bit 26 of misc: odd sigma -> high half
-      acc += sf * t + zf * sx;
+      for (int kappa = 0; kappa < 4; ++kappa)
+        a[kappa] = *reinterpret_cast<const half8*>(Xs + tc * kTile + 32 * kappa + 8 * (lane / 16));
     }
+    const float sx = Sx[tc];
+    float t;
+    switch ((misc >> 24) & 3) {
+      case 0: t = gemv_item<2>(slot, lane, a); break;
+      case 1: t = gemv_item<3>(slot, lane, a); break;
+      default: t = gemv_item<4>(slot, lane, a); break;
+    }
+    const uint32_t scw = *reinterpret_cast<const uint32_t*>(slot + 1024 + (lane & 15) * 4);
+    const uint32_t zrw = *reinterpret_cast<const uint32_t*>(slot + 1088 + (lane & 15) * 4);
+    float sf, zf;
+    params_to_float(scw, zrw, (misc >> 22) & 16u, p.bf16 != 0, sf, zf);  // bit 26 of misc: odd sigma -> high half
+    acc += sf * t + zf * sx;
+  
     if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
       switch ((misc >> 17) & 0x7F) {
 #define SFMP_CASE(q) case q: accs[q] = acc; break;
@@ -733,12 +721,6 @@ static GemvParams gemv_params(const GemmArgs& a, int32_t max_slabs) {
   p.max_slabs = max_slabs;
   p.gshift = L->group == 512 ? 2 : L->group == 256 ? 1 : 0;
   p.bf16 = L->scale_format == SFMP_SCALE_BF16;
-#ifdef SFMP_EXPERIMENT
-  p.dbg = g_sfmp_debug;
-  p.dbg_count[0] = L->count2 > 0 ? L->count2 : 1;
-  p.dbg_count[1] = L->count3 > 0 ? L->count3 : 1;
-  p.dbg_count[2] = L->count4 > 0 ? L->count4 : 1;
-#endif
   return p;
 }
 

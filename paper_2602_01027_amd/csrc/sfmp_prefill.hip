@@ -501,10 +501,6 @@ __global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) 
   }
 }
 
-#ifdef SFMP_EXPERIMENT
-extern int g_sfmp_debug;
-#endif
-
 template <int BM, int WM, int WN, int IL = 2>
 static void launch_prefill_shape(PrefillParams p, int M, hipStream_t stream) {
   p.n_mtiles = (M + BM - 1) / BM;
@@ -573,17 +569,7 @@ int launch_prefill(const GemmArgs& a, void* stream) {
   p.gshift = L->group == 512 ? 2 : L->group == 256 ? 1 : 0;
   p.bf16 = L->scale_format == SFMP_SCALE_BF16;
   p.n_mtiles = 0;
-#ifdef SFMP_EXPERIMENT
-  switch (g_sfmp_debug & 7) {
-    case 1: launch_prefill_shape<128, 1, 4>(p, a.M, (hipStream_t)stream); break;
-    case 2: launch_prefill_shape<256, 2, 2>(p, a.M, (hipStream_t)stream); break;
-    case 3: launch_prefill_shape<256, 1, 4>(p, a.M, (hipStream_t)stream); break;
-    case 4: launch_prefill_shape<256, 2, 4>(p, a.M, (hipStream_t)stream); break;
-    default: launch_prefill_shape<128, 2, 2>(p, a.M, (hipStream_t)stream); break;
-  }
-#else
   launch_prefill_shape<128, 1, 4>(p, a.M, (hipStream_t)stream);
-#endif
   if (int e = check_launch("sfmp_gemm prefill launch")) return e;
   if (a.row_perm) {
     hipLaunchKernelGGL(scatter_cols_kernel, dim3((unsigned)a.M), dim3(256), (size_t)L->N * 2, (hipStream_t)stream,
