@@ -144,14 +144,21 @@ class Layer:
         return out
 
 
-def build_problems(W, cid, Ms=None, fast=False, only=None, **fmt):
-    """fmt: group / scale_format / block passed on to the generator (default: group 128, fp16, 128x128 blocks)."""
+def build_problems(W, cid, Ms=None, fast=False, only=None, allocated_bits=None, **fmt):
+    """fmt: group / scale_format / block passed on to the generator (default: group 128, fp16, 128x128 blocks).
+    allocated_bits: take the bitmap from the sorting-based allocation on synthetic salience at this average width
+    (salient rows and columns first: wide tiles cluster in the top-left corner) instead of a shuffled one."""
     spec = W.CONFIGS[cid]
     out = []
     for si, (label, K, N) in enumerate(spec.shapes):
         if only is not None and label not in only:
             continue
         M = (Ms or spec.Ms)[0]
+        if allocated_bits is not None:
+            blk = fmt.get("block", (4, 1))
+            fmt = dict(fmt, bitmap=W.allocation.allocated_layout(N, K, allocated_bits, np.random.default_rng(
+                77000 + 1000 * cid + si), block=(blk[0], max(blk[1], fmt.get("group", 128) // 128)))["bitmap"])
+            fmt.pop("block", None)
         out.append(W.make_problem(label, K, N, M, 1000 * cid + si, w_std=spec.w_std[si], fractions=spec.fractions,
                                   outliers=spec.outliers, use_col_perm=spec.col_perm, use_row_perm=spec.row_perm[si],
                                   fast_codes=fast, **fmt))
@@ -374,6 +381,19 @@ def main():
                 us_per_layer=round(msf * 1e3, 2), MB=round(bf / 1e6, 1), GBps=round(bf / msf / 1e6, 1),
                 pct_hbm_peak=round(100 * bf / msf / 1e6 / HBM_PEAK_GBPS, 2))
             del lf, pf
+            torch.cuda.empty_cache()
+        if args.section in ("all", "decode"):
+            # bitmaps as the method produces them: Algorithm 1 on synthetic salience, (512, 128) blocks, average 3.0
+            # bits; rows and columns sorted by salience, so tile rows differ in bytes (4-bit rows first)
+            pa = build_problems(W, 2, fast=True, allocated_bits=3.0)
+            ba = sum(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, index_words=p.bitmap.size, group=p.group) for p in pa)
+            la = Layer(pa, int(np.ceil(2 ** 30 / ba)))
+            msa, _ = time_steps(torch, la, 120, 12, use_graph=not args.eager, groups=FUSED_GROUPS)
+            extra["layer_8b_M1_allocated_bitmaps"] = dict(
+                us_per_layer=round(msa * 1e3, 2), MB=round(ba / 1e6, 1), GBps=round(ba / msa / 1e6, 1),
+                pct_hbm_peak=round(100 * ba / msa / 1e6 / HBM_PEAK_GBPS, 2),
+                avg_bits=[round(p.avg_bits, 3) for p in pa])
+            del la, pa
             torch.cuda.empty_cache()
         if args.section in ("all", "batch"):
             # small batches (configs[2]: 50 % 2-bit / 50 % 3-bit) through the ring-skinny kernel: 4 batched calls

@@ -36,3 +36,4 @@ from .generators import (  # noqa: F401
     algorithmic_bytes,
     metadata_bits_per_weight,
 )
+from . import allocation  # noqa: E402,F401

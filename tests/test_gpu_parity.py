@@ -311,3 +311,14 @@ def test_batched_launch_with_mixed_parameter_formats(torch_cuda):
     torch.cuda.synchronize()
     for p, (_, _, _, _, Y) in zip(probs, batch):
         _check(p, Y.cpu().numpy())
+
+
+@pytest.mark.parametrize("M", [1, 8, 40])
+def test_allocated_bitmap_from_salience(torch_cuda, M):
+    # the bitmap the offline side produces (sorted salience, Algorithm 1, (512, 128) blocks): wide tiles clustered
+    from gpu_util import run_gemm
+    lay = W.allocation.allocated_layout(2048, 1536, 2.75, np.random.default_rng(12), block=(4, 1))
+    p = W.make_problem("alloc", 1536, 2048, M, 515, bitmap=lay["bitmap"], outliers=True)
+    assert set(np.unique(p.bitmap).tolist()) == {2, 3, 4}
+    _check(p, run_gemm(p))
+
