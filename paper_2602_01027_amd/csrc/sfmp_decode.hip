@@ -268,7 +268,6 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
     float sf, zf;
     params_to_float(scw, zrw, (misc >> 22) & 16u, p.bf16 != 0, sf, zf);  // bit 26 of misc: odd sigma -> high half
     acc += sf * t + zf * sx;
-  
     if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
       switch ((misc >> 17) & 0x7F) {
 #define SFMP_CASE(q) case q: accs[q] = acc; break;
