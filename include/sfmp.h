@@ -150,7 +150,7 @@ int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream);
  *             on entry are irrelevant, contents on return are unspecified.
  * M = 1 runs the bandwidth-bound GEMV kernel, 2 <= M <= 16 (and M = 1 with K above about 32k) the
  * same scheme with the activations staged per tile column, larger M the MFMA prefill kernels
- * (SFMP_ERR_SHAPE there if K > 57344, or with a permutation whose vector exceeds 160 KiB of fp16).
+ * (SFMP_ERR_SHAPE there if K > 57344, or with a row permutation and N > 81920).
  * Asynchronous on hip_stream; holds no global state.  The permutations are not checked for
  * being bijections (out-of-range entries are the caller's error; use sfmp_check_perm). */
 int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
