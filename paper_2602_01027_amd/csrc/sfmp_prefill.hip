@@ -193,12 +193,14 @@ __global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) 
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-  // blocks are dealt round-robin to the 8 XCDs: keep all tile rows of one M block on one XCD so
-  // that its activation rows stay in that XCD's L2.
+  // Blocks are dealt round-robin to the 8 XCDs.  XCD x owns the M blocks x, x+8, ... (their activation rows
+  // stay in that XCD's L2) and walks the tile rows with its M blocks innermost: the blocks that need the
+  // same weight tiles run at the same time, so a tile comes from HBM once per XCD, not once per M block.
   const int xcd = blockIdx.x % 8;
   const int within = blockIdx.x / 8;
-  const int mt = xcd + 8 * (within / p.ntr);
-  const int tr = within % p.ntr;
+  const int mper = (p.n_mtiles + 7) / 8;  // M blocks per XCD (upper bound)
+  const int mt = xcd + 8 * (within % mper);
+  const int tr = within / mper;
   if (mt >= p.n_mtiles) return;
   const int m0 = mt * BM;
 
