@@ -353,7 +353,9 @@ __global__ __launch_bounds__(NW * 64) void gemv_batched_kernel(const GemvBatch b
 // units of row m stored at position u ^ m (conflict-free MFMA operand reads).  These copies hit in L2.
 // The group sums of the activations come from one more MFMA against a vector of ones.
 struct RSkinnyParams {
-  const unsigned char* xblk;  // [ntc][MB][256 bytes], swizzled
+  const unsigned char* xblk;  // staged activations [ntc][MB][256 bytes], swizzled (not used by the resident variant)
+  const _Float16* X;          // resident variant: the caller's activations [M, K] ...
+  const int32_t* col_perm;    // ... and column permutation (or NULL); staged into LDS by every workgroup
   const uint8_t* s2;
   const uint8_t* s3;
   const uint8_t* s4;
@@ -404,14 +406,18 @@ __global__ __launch_bounds__(MB * 16) void stage_rows_kernel(const _Float16* __r
 template <int MB>
 constexpr int rskinny_slot_bytes() { return kSlotBytes + MB * 256; }
 
-template <int NW, int S, int MB>
+// RES (resident): when MB x K fp16 fit in LDS beside the rings, every workgroup stages the activations itself,
+// exactly as the GEMV kernel does (raw copy into the idle rings, permute inside LDS) into the same per-tile-column
+// swizzled layout; there is then no staging kernel and an item brings only its slab and parameters.
+template <int NW, int S, int MB, bool RES>
 __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int bid, const int G, unsigned char* lds_raw) {
   constexpr int NT = NW * 64;
-  constexpr int kSlot = rskinny_slot_bytes<MB>();
-  constexpr int kCopies = 2 + MB / 4;  // direct copies per item: slab, scales+zeros, MB/4 x 1 KiB of activations
-  // LDS: red [max_slabs][4][64] f32 | rings [NW][S][kSlot]
+  constexpr int kSlot = RES ? kSlotBytes : rskinny_slot_bytes<MB>();
+  constexpr int kCopies = RES ? 2 : 2 + MB / 4;  // direct copies per item: slab, scales+zeros, MB/4 x 1 KiB of activations
+  // LDS: red [max_slabs][4][64] f32 | (Xs [ntc][MB][256 B]) | rings [NW][S][kSlot]
   float* red = reinterpret_cast<float*>(lds_raw);
-  unsigned char* rings = lds_raw + (size_t)p.max_slabs * 1024;
+  unsigned char* Xs = lds_raw + (size_t)p.max_slabs * 1024;
+  unsigned char* rings = Xs + (RES ? (size_t)p.ntc * (MB * 256) : (size_t)0);
 
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
@@ -461,11 +467,52 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
     if (data_voff < slab_bytes)
       __builtin_amdgcn_global_load_lds((gptr_t)((const char*)a + data_voff), (lptr_t)slot, 16, 0, 0);
     if (lane < 32) __builtin_amdgcn_global_load_lds((gptr_t)((const char*)sa + sz_voff), (lptr_t)(slot + 1024), 4, 0, 0);
-    const unsigned char* xsrc = p.xblk + (int64_t)(misc & 0xFFFF) * (MB * 256) + data_voff;
+    if constexpr (!RES) {
+      const unsigned char* xsrc = p.xblk + (int64_t)(misc & 0xFFFF) * (MB * 256) + data_voff;
 #pragma unroll
-    for (int c = 0; c < MB / 4; ++c)
-      __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + c * 1024), (lptr_t)(slot + kSlotBytes + c * 1024), 16, 0, 0);
+      for (int c = 0; c < MB / 4; ++c)
+        __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + c * 1024), (lptr_t)(slot + kSlotBytes + c * 1024), 16, 0, 0);
+    }
   };
+
+  if constexpr (RES) {
+    // stage the activations: direct copies of the M rows into the (still idle) ring memory, 1 KiB per wavefront
+    // and copy, all in flight together; then permute inside LDS.  One thread serves one (tile column, unit of 8
+    // columns) for every row: the permutation entries are the same for all rows.
+    _Float16* Xraw = reinterpret_cast<_Float16*>(rings);
+    const int raw_bytes = p.M * p.K * 2;
+    for (int c = wave * 1024; c < raw_bytes; c += NW * 1024)
+      if (c + (int)data_voff < raw_bytes)
+        __builtin_amdgcn_global_load_lds((gptr_t)((const char*)p.X + c + data_voff), (lptr_t)(rings + c), 16, 0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    for (int u = tid; u < p.ntc * 16; u += NT) {
+      const int tc = u / 16, unit = u % 16;
+      const int k0 = tc * kTile + unit * 8;
+      int4 c0 = {k0, k0 + 1, k0 + 2, k0 + 3}, c1 = {k0 + 4, k0 + 5, k0 + 6, k0 + 7};
+      if (p.col_perm) {
+        c0 = reinterpret_cast<const int4*>(p.col_perm + k0)[0];
+        c1 = reinterpret_cast<const int4*>(p.col_perm + k0)[1];
+      }
+#pragma unroll
+      for (int m = 0; m < MB; ++m) {
+        half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (m < p.M) {
+          const _Float16* row = Xraw + (size_t)m * p.K;
+          v[0] = row[c0.x];
+          v[1] = row[c0.y];
+          v[2] = row[c0.z];
+          v[3] = row[c0.w];
+          v[4] = row[c1.x];
+          v[5] = row[c1.y];
+          v[6] = row[c1.z];
+          v[7] = row[c1.w];
+        }
+        *reinterpret_cast<half8*>(Xs + ((size_t)tc * MB + m) * 256 + ((unit ^ m) * 16)) = v;
+      }
+    }
+    __syncthreads();  // Xs is complete, the raw copy is dead: the rings may be filled
+  }
 
   half8 ones;
 #pragma unroll
@@ -476,7 +523,8 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   // operand addresses inside a slot: activation row i16, unit 4*kappa + kb at position unit ^ i16
   uint32_t a_off[4];
 #pragma unroll
-  for (int kappa = 0; kappa < 4; ++kappa) a_off[kappa] = kSlotBytes + i16 * 256 + (((4 * kappa + kb) ^ i16) * 16);
+  for (int kappa = 0; kappa < 4; ++kappa)
+    a_off[kappa] = (RES ? 0 : kSlotBytes) + i16 * 256 + (((4 * kappa + kb) ^ i16) * 16);
 
   floatx4 accs[kGemvMaxSlabs];
 #pragma unroll
@@ -487,8 +535,9 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
     const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
     const unsigned char* slot = ring + s * kSlot;
     if (MB == 16 || i16 < MB) {
+      const unsigned char* abase = RES ? Xs + (size_t)(misc & 0xFFFF) * (MB * 256) : slot;
 #pragma unroll
-      for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = *reinterpret_cast<const half8*>(slot + a_off[kappa]);
+      for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = *reinterpret_cast<const half8*>(abase + a_off[kappa]);
     }
     floatx4 sx = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -582,10 +631,10 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   }
 }
 
-template <int NW, int S, int MB>
+template <int NW, int S, int MB, bool RES>
 __global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  rskinny_body<NW, S, MB>(p, (int)blockIdx.x, (int)gridDim.x, lds_raw);
+  rskinny_body<NW, S, MB, RES>(p, (int)blockIdx.x, (int)gridDim.x, lds_raw);
 }
 
 // Several independent problems with the same M in one launch (q, k and v, or gate and up of a decoder
@@ -596,12 +645,12 @@ struct RSkinnyBatch {
   int32_t count;
 };
 
-template <int NW, int S, int MB>
+template <int NW, int S, int MB, bool RES>
 __global__ __launch_bounds__(NW * 64) void rskinny_batched_kernel(const RSkinnyBatch b) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   int i = 0;
   while (i + 1 < b.count && (int)blockIdx.x >= b.first[i + 1]) ++i;
-  rskinny_body<NW, S, MB>(b.p[i], (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
+  rskinny_body<NW, S, MB, RES>(b.p[i], (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
 }
 
 // Staging for a batch: job j (one per distinct activation matrix) owns workgroups [first[j], first[j+1]).
@@ -665,6 +714,18 @@ static RSkinnyShape rskinny_shape(int32_t M) {
   if (M <= 8) return {8, 8, 5};
   return {16, 8, 3};
 }
+// The resident variant (activations staged into LDS by every workgroup, no staging kernel) exists for blocks of
+// 4 rows.  It is used when the reduction buffer, the activation block and the rings stay within 160 KiB and the
+// M x K activations are at most 32 KiB: measured, the saved launch outweighs 256 workgroups each permuting the
+// activations up to that size (8 to 17 % on K = 4096 with M <= 4) and no longer beyond it.
+constexpr int32_t kResidentSlots = 8;
+constexpr int64_t kResidentMaxRawBytes = 32 * 1024;
+static bool rskinny_resident_fit(int32_t M, int32_t mb, int32_t nw, int32_t K, int32_t max_slabs) {
+  if (mb != 4) return false;
+  const int64_t xs = (int64_t)mb * K * 2, ring_bytes = (int64_t)nw * kResidentSlots * kSlotBytes;
+  return (int64_t)M * K * 2 <= kResidentMaxRawBytes && xs <= ring_bytes &&
+         (int64_t)max_slabs * 1024 + xs + ring_bytes <= 160 * 1024;
+}
 
 DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
   DecodePlan d;
@@ -680,6 +741,7 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
       d.slots = f.slots;
       d.max_slabs = f.max_slabs;
       d.mb = 1;
+      d.resident = false;
       d.workspace_bytes = 0;
       return d;
     }
@@ -692,9 +754,15 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
   d.gemv = false;
   d.grid = grid;
   d.max_slabs = (nslab + grid - 1) / grid;
-  d.slots = sh.slots;
   d.mb = sh.mb;
-  d.lds_bytes = d.max_slabs * 1024 + sh.nw * sh.slots * (kSlotBytes + sh.mb * 256);
+  d.resident = rskinny_resident_fit(M, sh.mb, sh.nw, K, d.max_slabs);
+  if (d.resident) {
+    d.slots = kResidentSlots;
+    d.lds_bytes = d.max_slabs * 1024 + sh.mb * K * 2 + sh.nw * d.slots * kSlotBytes;
+  } else {
+    d.slots = sh.slots;
+    d.lds_bytes = d.max_slabs * 1024 + sh.nw * sh.slots * (kSlotBytes + sh.mb * 256);
+  }
   d.workspace_bytes = round_up_256((int64_t)ntc * sh.mb * 256);
   return d;
 }
@@ -818,25 +886,12 @@ int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
   return launch_gemv_variant(slots, true, b, (unsigned)first, (size_t)lds, stream);
 }
 
-template <int NW, int S, int MB>
-static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* stream) {
+static RSkinnyParams rskinny_params(const GemmArgs& a, int32_t M, const void* xblk, int32_t max_slabs) {
   const sfmp_layout_t* L = a.L;
-  static bool attr_set = false;
-  const void* fn = reinterpret_cast<const void*>(&rskinny_kernel<NW, S, MB>);
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) {
-      note_hip_error("hipFuncSetAttribute(skinny)", hipGetErrorString(e));
-      return SFMP_ERR_HIP;
-    }
-    attr_set = true;
-  }
-  const int32_t ntc = L->K / kTile;
-  hipLaunchKernelGGL((stage_rows_kernel<MB>), dim3((unsigned)ntc), dim3(MB * 16), 0, (hipStream_t)stream,
-                     (const _Float16*)a.X, a.col_perm, (unsigned char*)a.workspace, (int)a.M, (int)L->K);
-  if (int e = after_launch("sfmp_gemm activation staging launch")) return e;
   RSkinnyParams p;
-  p.xblk = (const unsigned char*)a.workspace;
+  p.xblk = (const unsigned char*)xblk;
+  p.X = (const _Float16*)a.X;
+  p.col_perm = a.col_perm;
   p.s2 = a.s2;
   p.s3 = a.s3;
   p.s4 = a.s4;
@@ -845,15 +900,37 @@ static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* 
   p.zeros = (const _Float16*)a.zeros;
   p.row_perm = a.row_perm;
   p.Y = (_Float16*)a.Y;
-  p.M = a.M;
+  p.M = M;
   p.N = L->N;
   p.K = L->K;
   p.ntr = L->N / kTile;
-  p.ntc = ntc;
+  p.ntc = L->K / kTile;
   p.nslab = 8 * p.ntr;
-  p.max_slabs = d.max_slabs;
+  p.max_slabs = max_slabs;
   p.gshift = L->group == 512 ? 2 : L->group == 256 ? 1 : 0;
   p.bf16 = L->scale_format == SFMP_SCALE_BF16;
+  return p;
+}
+
+template <int NW, int S, int MB, bool RES>
+static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* stream) {
+  const sfmp_layout_t* L = a.L;
+  static bool attr_set = false;
+  const void* fn = reinterpret_cast<const void*>(&rskinny_kernel<NW, S, MB, RES>);
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) {
+      note_hip_error("hipFuncSetAttribute(skinny)", hipGetErrorString(e));
+      return SFMP_ERR_HIP;
+    }
+    attr_set = true;
+  }
+  if (!RES) {
+    hipLaunchKernelGGL((stage_rows_kernel<MB>), dim3((unsigned)(L->K / kTile)), dim3(MB * 16), 0, (hipStream_t)stream,
+                       (const _Float16*)a.X, a.col_perm, (unsigned char*)a.workspace, (int)a.M, (int)L->K);
+    if (int e = after_launch("sfmp_gemm activation staging launch")) return e;
+  }
+  RSkinnyParams p = rskinny_params(a, a.M, a.workspace, d.max_slabs);
   void* kargs[] = {&p};
   hipError_t e = hipLaunchKernel(fn, dim3((unsigned)d.grid), dim3(NW * 64), kargs, (size_t)d.lds_bytes, (hipStream_t)stream);
   if (e != hipSuccess) {
@@ -865,9 +942,11 @@ static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* 
 
 static int launch_rskinny(const GemmArgs& a, const DecodePlan& d, void* stream) {
   switch (d.mb) {
-    case 4: return launch_rskinny_variant<8, 8, 4>(a, d, stream);
-    case 8: return launch_rskinny_variant<8, 5, 8>(a, d, stream);
-    default: return launch_rskinny_variant<8, 3, 16>(a, d, stream);
+    case 4:
+      return d.resident ? launch_rskinny_variant<8, kResidentSlots, 4, true>(a, d, stream)
+                        : launch_rskinny_variant<8, 8, 4, false>(a, d, stream);
+    case 8: return launch_rskinny_variant<8, 5, 8, false>(a, d, stream);
+    default: return launch_rskinny_variant<8, 3, 16, false>(a, d, stream);
   }
 }
 
@@ -906,10 +985,9 @@ int64_t batched_workspace_bytes(const GemmArgs* probs, int count, int32_t M) {
   return plan_batch_staging(probs, count, rskinny_shape(M).mb).bytes;
 }
 
-template <int NW, int S, int MB>
-static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int32_t M, void* workspace, void* stream) {
-  int32_t g[kGemvMaxBatch];
-  if (int e = split_grid(probs, count, g)) return e;
+template <int NW, int S, int MB, bool RES>
+static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int32_t M, const int32_t* g,
+                                          void* workspace, void* stream) {
   const BatchStagePlan sp = plan_batch_staging(probs, count, MB);
   StageBatch sb;
   sb.count = sp.njobs;
@@ -940,26 +1018,9 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
     const int32_t nslab = 8 * (L->N / kTile);
     const int32_t max_slabs = (nslab + g[i] - 1) / g[i];
     if (max_slabs > kGemvMaxSlabs) return SFMP_ERR_SHAPE;
-    RSkinnyParams& p = b.p[i];
-    p.xblk = (const unsigned char*)workspace + sp.offset[sp.job_of[i]];
-    p.s2 = probs[i].s2;
-    p.s3 = probs[i].s3;
-    p.s4 = probs[i].s4;
-    p.tile_desc = probs[i].index + 3;
-    p.scales = (const _Float16*)probs[i].scales;
-    p.zeros = (const _Float16*)probs[i].zeros;
-    p.row_perm = probs[i].row_perm;
-    p.Y = (_Float16*)probs[i].Y;
-    p.M = M;
-    p.N = L->N;
-    p.K = L->K;
-    p.ntr = L->N / kTile;
-    p.ntc = L->K / kTile;
-    p.nslab = nslab;
-    p.max_slabs = max_slabs;
-    p.gshift = L->group == 512 ? 2 : L->group == 256 ? 1 : 0;
-    p.bf16 = L->scale_format == SFMP_SCALE_BF16;
-    const int64_t need = (int64_t)max_slabs * 1024 + (int64_t)NW * S * rskinny_slot_bytes<MB>();
+    b.p[i] = rskinny_params(probs[i], M, (const unsigned char*)workspace + sp.offset[sp.job_of[i]], max_slabs);
+    const int64_t need = RES ? (int64_t)max_slabs * 1024 + (int64_t)MB * L->K * 2 + (int64_t)NW * S * kSlotBytes
+                             : (int64_t)max_slabs * 1024 + (int64_t)NW * S * rskinny_slot_bytes<MB>();
     lds = need > lds ? need : lds;
     b.first[i] = first;
     first += g[i];
@@ -968,7 +1029,7 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
   for (int i = count; i < kGemvMaxBatch; ++i) b.p[i] = b.p[0];
   if (lds > 160 * 1024) return SFMP_ERR_SHAPE;
   static bool attr_set = false;
-  const void* fn = reinterpret_cast<const void*>(&rskinny_batched_kernel<NW, S, MB>);
+  const void* fn = reinterpret_cast<const void*>(&rskinny_batched_kernel<NW, S, MB, RES>);
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) {
@@ -977,8 +1038,10 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
     }
     attr_set = true;
   }
-  hipLaunchKernelGGL((stage_rows_batched_kernel<MB>), dim3((unsigned)sfirst), dim3(MB * 16), 0, (hipStream_t)stream, sb);
-  if (int e = after_launch("sfmp_gemm_batched activation staging launch")) return e;
+  if (!RES) {
+    hipLaunchKernelGGL((stage_rows_batched_kernel<MB>), dim3((unsigned)sfirst), dim3(MB * 16), 0, (hipStream_t)stream, sb);
+    if (int e = after_launch("sfmp_gemm_batched activation staging launch")) return e;
+  }
   void* kargs[] = {&b};
   hipError_t e = hipLaunchKernel(fn, dim3((unsigned)first), dim3(NW * 64), kargs, (size_t)lds, (hipStream_t)stream);
   if (e != hipSuccess) {
@@ -991,10 +1054,21 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
 int launch_decode_batched(const GemmArgs* probs, int count, int32_t M, void* workspace, void* stream) {
   if (count < 1 || count > kGemvMaxBatch || M < 1 || M > kDecodeMaxM) return SFMP_ERR_SHAPE;
   if (M == 1) return launch_gemv_batched(probs, count, stream);
-  switch (rskinny_shape(M).mb) {
-    case 4: return launch_rskinny_batched_variant<8, 8, 4>(probs, count, M, workspace, stream);
-    case 8: return launch_rskinny_batched_variant<8, 5, 8>(probs, count, M, workspace, stream);
-    default: return launch_rskinny_batched_variant<8, 3, 16>(probs, count, M, workspace, stream);
+  int32_t g[kGemvMaxBatch];
+  if (int e = split_grid(probs, count, g)) return e;
+  const RSkinnyShape sh = rskinny_shape(M);
+  // the resident variant only when every problem of the batch fits it
+  bool resident = true;
+  for (int i = 0; i < count; ++i) {
+    const int32_t nslab = 8 * (probs[i].L->N / kTile);
+    resident = resident && rskinny_resident_fit(M, sh.mb, sh.nw, probs[i].L->K, (nslab + g[i] - 1) / g[i]);
+  }
+  switch (sh.mb) {
+    case 4:
+      return resident ? launch_rskinny_batched_variant<8, kResidentSlots, 4, true>(probs, count, M, g, workspace, stream)
+                      : launch_rskinny_batched_variant<8, 8, 4, false>(probs, count, M, g, workspace, stream);
+    case 8: return launch_rskinny_batched_variant<8, 5, 8, false>(probs, count, M, g, workspace, stream);
+    default: return launch_rskinny_batched_variant<8, 3, 16, false>(probs, count, M, g, workspace, stream);
   }
 }
 

@@ -114,6 +114,41 @@ def test_decode_extreme_aspect(torch_cuda, K, N, M):
     _check(p, run_gemm(p))
 
 
+@pytest.mark.parametrize("K,M", [(8192, 2), (5504, 2), (8192, 3), (5632, 3), (8192, 4), (4096, 4), (4096, 5)])
+def test_small_batch_both_activation_stagings(torch_cuda, K, M):
+    # M <= 4: up to 32 KiB of activations (M x K fp16) are staged into LDS by the kernel itself, larger ones by a
+    # separate launch into the workspace; both sides of that limit, the limit itself ((8192, 2), (4096, 4)) and an
+    # odd number of tile columns
+    from gpu_util import run_gemm
+    p = W.make_problem("staging", K, 384, M, 5150 + K + M, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, outliers=True,
+                       fast_codes=True)
+    _check(p, run_gemm(p))
+
+
+def test_batched_small_batch_mixed_staging(torch_cuda):
+    # one problem whose activations would fit the in-kernel staging and one whose do not: the batch takes the
+    # staged path for both, and gives bit for bit what separate calls (which differ in path) give
+    import paper_2602_01027_amd as S
+    from gpu_util import device_problem, run_gemm
+    torch = torch_cuda
+    M = 2
+    probs = [W.make_problem("fits", 2048, 384, M, 61, fractions={2: 0.5, 4: 0.5}),
+             W.make_problem("too_long", 16384, 256, M, 62, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, fast_codes=True)]
+    batch, keep = [], []
+    for p in probs:
+        dp, cp, rp = device_problem(p)
+        Y = torch.full((M, p.N), float("nan"), dtype=torch.float16, device="cuda:0")
+        batch.append((torch.from_numpy(p.X).to("cuda:0"), cp, dp, rp, Y))
+        keep.append((dp, cp, rp))
+    ws = torch.empty(S.sfmp_gemm_batched_workspace(batch, M), dtype=torch.uint8, device="cuda:0")
+    S.sfmp_gemm_batched(batch, M, ws)
+    torch.cuda.synchronize()
+    for p, (_, _, _, _, Y), (dp, cp, rp) in zip(probs, batch, keep):
+        y = Y.cpu().numpy()
+        _check(p, y)
+        assert np.array_equal(run_gemm(p, dp, cp, rp).view(np.uint16), y.view(np.uint16))
+
+
 def test_workspace_is_reusable_and_result_deterministic(torch_cuda):
     from gpu_util import device_problem, make_workspace, run_gemm
     p = W.make_problem("reuse", 2048, 1024, 4, 31337, fractions={2: 0.5, 3: 0.5}, outliers=True)
