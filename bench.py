@@ -422,6 +422,19 @@ def main():
                      pct_mfma_peak=round(100 * 2.0 * d["p"].M * d["p"].N * d["p"].K / t / 1e6 / MFMA_F16_PEAK_TFLOPS,
                                          2))
                 for d, t in zip(lp.proj, perp)]
+            # the same 4096 -> 14336 matrix at shorter prompts (the workgroup-to-XCD mapping has to keep all 8 XCDs
+            # busy when there are fewer than 8 blocks of 128 rows)
+            sweep = []
+            pg = [q for q in pp if q.N == 14336][0]
+            for M in (128, 256, 512, 1024):
+                pm = [W.with_activations(pg, M, outliers=True)]
+                lm = Layer(pm, 2)
+                t = time_each_projection(torch, lm, launches=24)[0]
+                fl = 2.0 * M * pg.N * pg.K
+                sweep.append(dict(M=M, us=round(t, 1), TFLOPs=round(fl / t / 1e6, 1),
+                                  pct_mfma_peak=round(100 * fl / t / 1e6 / MFMA_F16_PEAK_TFLOPS, 2)))
+                del lm, pm
+            extra["prefill_4096x14336_M_sweep"] = sweep
             del lp, pp
         result["extra"] = extra
 

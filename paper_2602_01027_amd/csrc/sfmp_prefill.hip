@@ -193,15 +193,12 @@ __global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) 
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-  // Blocks are dealt round-robin to the 8 XCDs.  XCD x owns the M blocks x, x+8, ... (their activation rows
-  // stay in that XCD's L2) and walks the tile rows with its M blocks innermost: the blocks that need the
-  // same weight tiles run at the same time, so a tile comes from HBM once per XCD, not once per M block.
-  const int xcd = blockIdx.x % 8;
-  const int within = blockIdx.x / 8;
-  const int mper = (p.n_mtiles + 7) / 8;  // M blocks per XCD (upper bound)
-  const int mt = xcd + 8 * (within % mper);
-  const int tr = within / mper;
-  if (mt >= p.n_mtiles) return;
+  // Work items (tile row, M block) are numbered with the M blocks innermost, and block b (which runs on XCD
+  // b % 8) takes item b.  With a multiple of 8 M blocks an XCD always sees the same M blocks (their activation
+  // rows stay in its L2), and in any case the blocks that run at the same time need the same weight tiles, so
+  // a tile comes from HBM once per XCD, not once per M block.  (Every XCD works for any number of M blocks.)
+  const int mt = (int)blockIdx.x % p.n_mtiles;
+  const int tr = (int)blockIdx.x / p.n_mtiles;
   const int m0 = mt * BM;
 
   // The K reduction runs over the tiles of this tile row sorted by width (first all 2-bit tiles, then
@@ -520,7 +517,7 @@ __global__ __launch_bounds__(64 * WM * WN, (BM == 128 ? 2 : 1) * ((WM * WN + 3) 
 template <int BM, int WM, int WN, int IL = 2>
 static void launch_prefill_shape(PrefillParams p, int M, hipStream_t stream) {
   p.n_mtiles = (M + BM - 1) / BM;
-  const unsigned grid = 8u * (unsigned)((p.n_mtiles + 7) / 8) * (unsigned)p.ntr;
+  const unsigned grid = (unsigned)p.n_mtiles * (unsigned)p.ntr;
   hipLaunchKernelGGL((prefill_kernel<BM, WM, WN, IL>), dim3(grid), dim3(64 * WM * WN), 0, stream, p);
 }
 
