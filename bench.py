@@ -422,6 +422,14 @@ def main():
                      pct_mfma_peak=round(100 * 2.0 * d["p"].M * d["p"].N * d["p"].K / t / 1e6 / MFMA_F16_PEAK_TFLOPS,
                                          2))
                 for d, t in zip(lp.proj, perp)]
+            # the same call when the product may stay in reordered row order (the next matrix gathers from it
+            # through a folded permutation): no un-permute pass
+            pg_ = [q for q in pp if q.N == 14336][0]
+            import dataclasses as _dc
+            lf = Layer([_dc.replace(pg_, row_perm=None)], 2)
+            tf = time_each_projection(torch, lf, launches=24)[0]
+            extra["prefill_M2048_4096x14336_rows_left_reordered_us"] = round(tf, 1)
+            del lf
             # the same 4096 -> 14336 matrix at shorter prompts (the workgroup-to-XCD mapping has to keep all 8 XCDs
             # busy when there are fewer than 8 blocks of 128 rows)
             sweep = []

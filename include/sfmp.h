@@ -198,6 +198,19 @@ int sfmp_gemm_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, i
 /* Host only.  SFMP_OK if perm_host[0..n) is a permutation of 0..n-1, else SFMP_ERR_PERM. */
 int sfmp_check_perm(const int32_t* perm_host, int32_t n);
 
+/* Host only.  Folds the row permutation of one matrix into the column permutation of the next, so that the
+ * first product can stay in reordered row order (row_perm_dev = NULL: no un-permute pass) and the second
+ * gathers from it directly (Section 3.4: the reordering is applied to activations and undone on outputs; the
+ * overhead analysis of Appendix E counts exactly these two reorder operations per layer):
+ *   folded[j] = inverse(row_perm_prev)[col_perm_next[j]],   j in [0, n)
+ * so that  Xt[:, folded[j]] = X[:, col_perm_next[j]]  whenever  Xt[:, i] = X[:, row_perm_prev[i]],  which holds
+ * for Xt = f(Yt), X = f(Y) with any element-wise f between the two matrices (a per-feature weight, as in a norm,
+ * has to be reordered by the caller the same way).  col_perm_next_host = NULL stands for the identity.  n is
+ * the first matrix' N and the second one's K.  SFMP_ERR_PERM if either input is not a permutation.
+ * folded_host may not alias the inputs. */
+int sfmp_fold_perms(const int32_t* row_perm_prev_host, const int32_t* col_perm_next_host, int32_t n,
+                    int32_t* folded_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -133,6 +133,23 @@ def dequant_rows(codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray, rows:
     return s * q + z
 
 
+def fold_perms(row_perm_prev: np.ndarray, col_perm_next: Optional[np.ndarray]) -> np.ndarray:
+    """The column permutation that lets a matrix read the previous product while it is still in reordered row
+    order (Section 3.4; the two reorder operations per layer of Appendix E collapse into one gather).
+
+    Written from its defining property, by search: folded[j] is the position i at which the reordered product
+    holds the feature that the plain gather would fetch, i.e. the i with row_perm_prev[i] == col_perm_next[j]."""
+    r = np.asarray(row_perm_prev).astype(np.int64)
+    n = r.size
+    c = np.arange(n, dtype=np.int64) if col_perm_next is None else np.asarray(col_perm_next).astype(np.int64)
+    out = np.empty(n, dtype=np.int32)
+    for j in range(n):
+        (hits,) = np.nonzero(r == c[j])
+        assert hits.size == 1, "row_perm_prev is not a permutation"
+        out[j] = hits[0]
+    return out
+
+
 def rel_frobenius(Y: np.ndarray, Y_ref: np.ndarray) -> float:
     """||Y - Y_ref||_F / ||Y_ref||_F in float64 (the acceptance measure for fp16 outputs)."""
     Yd = np.asarray(Y, dtype=np.float64)

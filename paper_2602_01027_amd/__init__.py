@@ -22,5 +22,6 @@ from .binding import (  # noqa: F401
     sfmp_gemm_batched_workspace,
     make_gemv_batch,
     sfmp_check_perm,
+    sfmp_fold_perms,
     upload_packed,
 )

@@ -35,7 +35,7 @@ class SfmpGemvProblem(C.Structure):
 
 EXPORTS = ("sfmp_strerror", "sfmp_pack_query", "sfmp_layout_set_quant", "sfmp_pack", "sfmp_unpack", "sfmp_gemm_workspace",
            "sfmp_workspace_init", "sfmp_gemm", "sfmp_gemv_batched", "sfmp_gemm_batched_workspace",
-           "sfmp_gemm_batched", "sfmp_check_perm")
+           "sfmp_gemm_batched", "sfmp_check_perm", "sfmp_fold_perms")
 
 
 def lib_path() -> str:
@@ -64,6 +64,7 @@ def load_library():
     lib.sfmp_gemm.argtypes = [vp, i32, vp, LP, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.sfmp_gemv_batched.argtypes = [vp, i32, vp]
     lib.sfmp_check_perm.argtypes = [vp, i32]
+    lib.sfmp_fold_perms.argtypes = [vp, vp, i32, vp]
     for name in EXPORTS:
         if name != "sfmp_strerror":
             getattr(lib, name).restype = C.c_int
@@ -128,6 +129,16 @@ def sfmp_pack(codes: np.ndarray, bitmap: np.ndarray):
 def sfmp_check_perm(perm: np.ndarray) -> int:
     p = np.ascontiguousarray(perm, dtype=np.int32)
     return int(load_library().sfmp_check_perm(_host_ptr(p), int(p.size)))
+
+
+def sfmp_fold_perms(row_perm_prev: np.ndarray, col_perm_next: Optional[np.ndarray]) -> np.ndarray:
+    """folded[j] = inverse(row_perm_prev)[col_perm_next[j]] (col_perm_next None = identity), int32."""
+    r = np.ascontiguousarray(row_perm_prev, dtype=np.int32)
+    c = None if col_perm_next is None else np.ascontiguousarray(col_perm_next, dtype=np.int32)
+    out = np.empty(r.size, dtype=np.int32)
+    _check(load_library().sfmp_fold_perms(_host_ptr(r), None if c is None else _host_ptr(c), int(r.size),
+                                          _host_ptr(out)))
+    return out
 
 
 @dataclass

@@ -196,4 +196,16 @@ int sfmp_check_perm(const int32_t* perm_host, int32_t n) {
   return SFMP_OK;
 }
 
+int sfmp_fold_perms(const int32_t* row_perm_prev_host, const int32_t* col_perm_next_host, int32_t n,
+                    int32_t* folded_host) {
+  if (!row_perm_prev_host || !folded_host) return SFMP_ERR_NULL;
+  if (int e = sfmp_check_perm(row_perm_prev_host, n)) return e;
+  if (col_perm_next_host)
+    if (int e = sfmp_check_perm(col_perm_next_host, n)) return e;
+  std::vector<int32_t> inverse((size_t)n);
+  for (int32_t i = 0; i < n; ++i) inverse[(size_t)row_perm_prev_host[i]] = i;
+  for (int32_t j = 0; j < n; ++j) folded_host[j] = inverse[(size_t)(col_perm_next_host ? col_perm_next_host[j] : j)];
+  return SFMP_OK;
+}
+
 }  // extern "C"

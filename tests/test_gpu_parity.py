@@ -357,3 +357,32 @@ def test_allocated_bitmap_from_salience(torch_cuda, M):
     assert set(np.unique(p.bitmap).tolist()) == {2, 3, 4}
     _check(p, run_gemm(p))
 
+
+
+# ---------------------------------------------------------------------------------------------
+# permutation folding: the first product stays in reordered row order, the second gathers from it
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("M", [1, 4, 48])
+def test_folded_permutations_two_matrix_chain(torch_cuda, M):
+    import paper_2602_01027_amd as S
+    from gpu_util import device_problem, run_gemm
+    torch = torch_cuda
+    p1 = W.make_problem("up", 512, 1024, M, 9100, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, outliers=True)
+    p2 = W.make_problem("down", 1024, 384, M, 9200, fractions={2: 0.5, 3: 0.5})
+    assert p1.row_perm is not None and p2.col_perm is not None
+    dp1, cp1, rp1 = device_problem(p1)
+    dp2, cp2, rp2 = device_problem(p2)
+    relu = lambda y: np.maximum(y, np.float16(0))
+    # plain: un-permute the first product, gather for the second
+    Y1 = run_gemm(p1, dp1, cp1, rp1)
+    _check(p1, Y1)
+    X2 = relu(Y1)
+    Y2 = run_gemm(p2, dp2, cp2, rp2, X=X2)
+    _check(dataclasses.replace(p2, X=X2), Y2)
+    # folded: no un-permute, one folded gather
+    Y1t = run_gemm(p1, dp1, cp1, None)
+    assert np.array_equal(Y1t.view(np.uint16), Y1[:, p1.row_perm].view(np.uint16))
+    folded = S.sfmp_fold_perms(p1.row_perm, p2.col_perm)
+    assert np.array_equal(folded, O.fold_perms(p1.row_perm, p2.col_perm))
+    Y2f = run_gemm(p2, dp2, torch.from_numpy(folded).to("cuda:0"), rp2, X=relu(Y1t))
+    assert np.array_equal(Y2f.view(np.uint16), Y2.view(np.uint16))

@@ -121,3 +121,28 @@ def test_layout_set_quant_accepts_the_documented_formats_only():
     L3 = S.sfmp_pack_query(np.full((1, 3), 2, dtype=np.int8), 128, 384)
     assert lib.sfmp_layout_set_quant(C.byref(L3), 256, 0) == -8
     assert lib.sfmp_layout_set_quant(None, 128, 0) == -1
+
+
+def test_fold_perms_matches_oracle_and_its_defining_property():
+    # NEXT: permutation folding.  The C ABI result equals the oracle's (written as a search), and both satisfy
+    # the property that defines them: gathering from the reordered product with the folded permutation fetches
+    # what the plain gather fetches from the un-permuted one.
+    import paper_2602_01027_amd as S
+    from oracle import sfmp_oracle as O
+    rng = np.random.default_rng(5)
+    for n in (1, 7, 128, 1000):
+        r = rng.permutation(n).astype(np.int32)
+        c = rng.permutation(n).astype(np.int32)
+        f = S.sfmp_fold_perms(r, c)
+        assert np.array_equal(f, O.fold_perms(r, c))
+        Y = rng.standard_normal((3, n))
+        Yt = Y[:, r]                      # the product left in reordered row order
+        assert np.array_equal(Yt[:, f], Y[:, c])
+        f_id = S.sfmp_fold_perms(r, None)
+        assert np.array_equal(f_id, O.fold_perms(r, None))
+        assert np.array_equal(Yt[:, f_id], Y)  # identity next permutation: the fold is the inverse
+    assert S.sfmp_check_perm(f) == 0
+    with pytest.raises(S.SfmpError):
+        S.sfmp_fold_perms(np.array([0, 0, 1], dtype=np.int32), None)
+    with pytest.raises(S.SfmpError):
+        S.sfmp_fold_perms(np.array([0, 2, 1], dtype=np.int32), np.array([0, 3, 1], dtype=np.int32))
