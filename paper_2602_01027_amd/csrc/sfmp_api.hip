@@ -28,6 +28,11 @@ int sfmp_gemm_workspace(const sfmp_layout_t* layout, int32_t M, int64_t* bytes) 
   if (M <= kDecodeMaxM) {
     const DecodePlan d = make_decode_plan(layout->N, layout->K, M);
     *bytes = d.workspace_bytes;
+  } else if (use_chunked_decode(layout->N, layout->K, M)) {
+    GemmArgs a{};
+    a.L = layout;
+    a.M = M;
+    *bytes = chunked_decode_workspace_bytes(a);
   } else {
     const PrefillPlan d = make_prefill_plan(layout->N, layout->K, M);
     *bytes = d.xperm_bytes + d.ytmp_bytes;
@@ -141,7 +146,9 @@ int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const s
   a.Y = Y_dev;
   a.workspace = workspace_dev;
   a.workspace_bytes = workspace_bytes;
-  return M <= kDecodeMaxM ? launch_decode(a, hip_stream) : launch_prefill(a, hip_stream);
+  if (M <= kDecodeMaxM) return launch_decode(a, hip_stream);
+  if (use_chunked_decode(layout->N, layout->K, M)) return launch_decode_chunked(a, hip_stream);
+  return launch_prefill(a, hip_stream);
 }
 
 }  // extern "C"

@@ -20,6 +20,8 @@
 // Skinny GEMM (2..16), and any M = 1 problem whose activation vector does not fit in LDS beside the
 // rings: the same scheme with the activations of each tile column travelling through the ring slots
 // (see rskinny_kernel).
+#include <cstdlib>
+
 #include "sfmp_device.h"
 #include "sfmp_internal.h"
 
@@ -660,14 +662,15 @@ struct StageBatch {
   unsigned char* xblk[kGemvMaxBatch];
   int32_t K[kGemvMaxBatch];
   int32_t first[kGemvMaxBatch + 1];
-  int32_t count, M;
+  int32_t M[kGemvMaxBatch];  // rows of each job's activation matrix (at most MB)
+  int32_t count;
 };
 
 template <int MB>
 __global__ __launch_bounds__(MB * 16) void stage_rows_batched_kernel(const StageBatch b) {
   int j = 0;
   while (j + 1 < b.count && (int)blockIdx.x >= b.first[j + 1]) ++j;
-  stage_rows_tile<MB>(b.X[j], b.col_perm[j], b.xblk[j], b.M, b.K[j], (int)blockIdx.x - b.first[j]);
+  stage_rows_tile<MB>(b.X[j], b.col_perm[j], b.xblk[j], b.M[j], b.K[j], (int)blockIdx.x - b.first[j]);
 }
 
 // ============================================================================================
@@ -967,7 +970,7 @@ static BatchStagePlan plan_batch_staging(const GemmArgs* probs, int count, int32
     int j = 0;
     for (; j < sp.njobs; ++j) {
       const GemmArgs& r = probs[sp.rep[j]];
-      if (r.X == probs[i].X && r.col_perm == probs[i].col_perm && r.L->K == probs[i].L->K) break;
+      if (r.X == probs[i].X && r.col_perm == probs[i].col_perm && r.L->K == probs[i].L->K && r.M == probs[i].M) break;
     }
     if (j == sp.njobs) {
       sp.rep[j] = i;
@@ -991,7 +994,6 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
   const BatchStagePlan sp = plan_batch_staging(probs, count, MB);
   StageBatch sb;
   sb.count = sp.njobs;
-  sb.M = M;
   int32_t sfirst = 0;
   for (int j = 0; j < sp.njobs; ++j) {
     const GemmArgs& r = probs[sp.rep[j]];
@@ -999,6 +1001,7 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
     sb.col_perm[j] = r.col_perm;
     sb.xblk[j] = (unsigned char*)workspace + sp.offset[j];
     sb.K[j] = r.L->K;
+    sb.M[j] = r.M;
     sb.first[j] = sfirst;
     sfirst += r.L->K / kTile;
   }
@@ -1008,6 +1011,7 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
     sb.col_perm[j] = nullptr;
     sb.xblk[j] = nullptr;
     sb.K[j] = 0;
+    sb.M[j] = 0;
   }
   RSkinnyBatch b;
   b.count = count;
@@ -1018,7 +1022,7 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
     const int32_t nslab = 8 * (L->N / kTile);
     const int32_t max_slabs = (nslab + g[i] - 1) / g[i];
     if (max_slabs > kGemvMaxSlabs) return SFMP_ERR_SHAPE;
-    b.p[i] = rskinny_params(probs[i], M, (const unsigned char*)workspace + sp.offset[sp.job_of[i]], max_slabs);
+    b.p[i] = rskinny_params(probs[i], probs[i].M, (const unsigned char*)workspace + sp.offset[sp.job_of[i]], max_slabs);
     const int64_t need = RES ? (int64_t)max_slabs * 1024 + (int64_t)MB * L->K * 2 + (int64_t)NW * S * kSlotBytes
                              : (int64_t)max_slabs * 1024 + (int64_t)NW * S * rskinny_slot_bytes<MB>();
     lds = need > lds ? need : lds;
@@ -1070,6 +1074,48 @@ int launch_decode_batched(const GemmArgs* probs, int count, int32_t M, void* wor
     case 8: return launch_rskinny_batched_variant<8, 5, 8, false>(probs, count, M, g, workspace, stream);
     default: return launch_rskinny_batched_variant<8, 3, 16, false>(probs, count, M, g, workspace, stream);
   }
+}
+
+// 16 < M <= 128 on a matrix with few tile rows: the product is cut into chunks of 16 activation rows, one
+// problem of the batched ring kernel each (the same weights, its own rows of X and Y).  The chunks run side by
+// side on their shares of the CUs and read the same weights at about the same time, so the matrix comes from HBM
+// once and from the caches for the other chunks.  The MFMA prefill kernel with one workgroup per (128 rows, tile
+// row) leaves most CUs idle there and walks K serially (about 0.95 us per tile column whatever M is: 105 us for
+// 14336 -> 4096 against 31 us in two chunks, 52 in four, 91 in eight).  The cost of the chunked path grows with
+// the number of chunks and with N; measured break-even points on the 8B / 70B shapes:
+//   N <= 4096: up to 8 chunks;  N <= 8192: up to 4;  N <= 16384: 2;  wider: never;  K below 4096 not measured: never.
+bool use_chunked_decode(int32_t N, int32_t K, int32_t M) {
+  if (M <= kDecodeMaxM || M > kDecodeMaxM * kGemvMaxBatch) return false;
+#ifdef SFMP_EXPERIMENT
+  if (const char* v = getenv("SFMP_CHUNK")) return atoi(v) != 0 && (N / kTile <= 64 || M <= 64);
+#endif
+  const int32_t ntr = N / kTile, ntc = K / kTile, chunks = (M + kDecodeMaxM - 1) / kDecodeMaxM;
+  if (ntc < 32) return false;
+  return chunks <= (ntr <= 32 ? 8 : ntr <= 64 ? 4 : ntr <= 128 ? 2 : 0);
+}
+
+static int chunk_problems(const GemmArgs& a, GemmArgs* probs) {
+  const sfmp_layout_t* L = a.L;
+  const int count = (a.M + kDecodeMaxM - 1) / kDecodeMaxM;
+  for (int i = 0; i < count; ++i) {
+    probs[i] = a;
+    probs[i].X = (const char*)a.X + (int64_t)i * kDecodeMaxM * L->K * 2;
+    probs[i].Y = (char*)a.Y + (int64_t)i * kDecodeMaxM * L->N * 2;
+    probs[i].M = i + 1 < count ? kDecodeMaxM : a.M - i * kDecodeMaxM;
+  }
+  return count;
+}
+
+int64_t chunked_decode_workspace_bytes(const GemmArgs& a) {
+  GemmArgs probs[kGemvMaxBatch];
+  const int count = chunk_problems(a, probs);
+  return plan_batch_staging(probs, count, rskinny_shape(kDecodeMaxM).mb).bytes;
+}
+
+int launch_decode_chunked(const GemmArgs& a, void* stream) {
+  GemmArgs probs[kGemvMaxBatch];
+  const int count = chunk_problems(a, probs);
+  return launch_decode_batched(probs, count, kDecodeMaxM, a.workspace, stream);
 }
 
 int launch_decode(const GemmArgs& a, void* stream) {

@@ -64,5 +64,9 @@ int launch_decode(const GemmArgs& a, void* stream);
 int launch_gemv_batched(const GemmArgs* problems, int count, void* stream);
 int launch_decode_batched(const GemmArgs* problems, int count, int32_t M, void* workspace, void* stream);
 int64_t batched_workspace_bytes(const GemmArgs* problems, int count, int32_t M);
+// 16 < M <= 128 on matrices with few tile rows: chunks of 16 rows through the batched ring kernel
+bool use_chunked_decode(int32_t N, int32_t K, int32_t M);
+int64_t chunked_decode_workspace_bytes(const GemmArgs& a);
+int launch_decode_chunked(const GemmArgs& a, void* stream);
 int launch_prefill(const GemmArgs& a, void* stream);
 }  // namespace sfmp

@@ -149,6 +149,18 @@ def test_batched_small_batch_mixed_staging(torch_cuda):
         assert np.array_equal(run_gemm(p, dp, cp, rp).view(np.uint16), y.view(np.uint16))
 
 
+@pytest.mark.parametrize("K,N,M", [(4096, 512, 17), (4096, 512, 100), (4096, 512, 128), (4096, 8192, 64),
+                                   (4096, 8192, 65), (4096, 16384, 32), (4096, 16384, 33)])
+def test_medium_batch_chunked_and_prefill_sides(torch_cuda, K, N, M):
+    # 16 < M <= 128 with K >= 4096: chunks of 16 rows through the batched ring kernel while the matrix is narrow
+    # enough (last chunk of 1 and of 4 rows, the full 8 chunks), the MFMA kernel beyond; both sides of each limit
+    from gpu_util import run_gemm
+    p = W.make_problem("medium", K, N, M, 6200 + N + M, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, outliers=True,
+                       fast_codes=True)
+    rows = None if N <= 512 else np.random.default_rng(M).choice(N, 384, replace=False)
+    _check(p, run_gemm(p), rows)
+
+
 def test_workspace_is_reusable_and_result_deterministic(torch_cuda):
     from gpu_util import device_problem, make_workspace, run_gemm
     p = W.make_problem("reuse", 2048, 1024, 4, 31337, fractions={2: 0.5, 3: 0.5}, outliers=True)
