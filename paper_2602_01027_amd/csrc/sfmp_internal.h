@@ -25,8 +25,11 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M);
 
 // Prefill path (M > 16): workspace holds the column-gathered activation.
 struct PrefillPlan {
+  int32_t bm;           // rows of a workgroup's block: 128, or 64 on small grids
+  int32_t ksplit;       // > 1: K is cut into this many ranges, one workgroup each, fp32 partial products
   int64_t xperm_bytes;  // column-gathered activation copy
-  int64_t ytmp_bytes;   // product in reordered row order, before the row un-permute pass
+  int64_t ytmp_bytes;   // product in reordered row order before the row un-permute pass (ksplit == 1: fp16
+                        // [M, N] if a row permutation is given; ksplit > 1: fp32 [ksplit, M, N])
 };
 PrefillPlan make_prefill_plan(int32_t N, int32_t K, int32_t M);
 

@@ -103,6 +103,43 @@ __global__ __launch_bounds__(256) void scatter_cols_kernel(const _Float16* __res
   for (int i = threadIdx.x; i < N / 8; i += 256) dst[i] = reinterpret_cast<const uint4*>(row)[i];
 }
 
+// Y[m, row_perm[i]] (or Y[m, i]) = fp16( sum over the K ranges, in range order, of partial[ks][m][i] ): the second
+// half of a split-K product, one row through LDS per workgroup.
+__global__ __launch_bounds__(1024) void reduce_split_kernel(const float* __restrict__ partial, int ksplit, int M,
+                                                            const int32_t* __restrict__ row_perm,
+                                                            _Float16* __restrict__ Y, int N) {
+  // (1024 threads and all loads of a thread's column group issued before the sum: with few rows there are few
+  // workgroups, and a chain of dependent round trips per thread made this pass longer than the GEMM)
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  _Float16* row = reinterpret_cast<_Float16*>(lds_raw);
+  const int64_t m = blockIdx.x;
+  for (int i = threadIdx.x; i < N / 4; i += 1024) {
+    floatx4 v[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      v[ks] = ks < ksplit ? *reinterpret_cast<const floatx4*>(partial + ((int64_t)ks * M + m) * N + 4 * i)
+                          : floatx4{0.f, 0.f, 0.f, 0.f};
+    floatx4 s = v[0];
+#pragma unroll
+    for (int ks = 1; ks < 8; ++ks) s += v[ks];  // range order; the ranges past ksplit add zeros
+    if (row_perm) {
+      const int4 c = reinterpret_cast<const int4*>(row_perm)[i];
+      row[c.x] = (_Float16)s[0];
+      row[c.y] = (_Float16)s[1];
+      row[c.z] = (_Float16)s[2];
+      row[c.w] = (_Float16)s[3];
+    } else {
+      row[4 * i] = (_Float16)s[0];
+      row[4 * i + 1] = (_Float16)s[1];
+      row[4 * i + 2] = (_Float16)s[2];
+      row[4 * i + 3] = (_Float16)s[3];
+    }
+  }
+  __syncthreads();
+  uint4* dst = reinterpret_cast<uint4*>(Y + m * N);
+  for (int i = threadIdx.x; i < N / 8; i += 1024) dst[i] = reinterpret_cast<const uint4*>(row)[i];
+}
+
 // -------------------------------------------------------------------------------------------
 // dequant + MFMA GEMM
 // -------------------------------------------------------------------------------------------
@@ -118,6 +155,8 @@ struct PrefillParams {
   int32_t M, N, K, ntr, ntc, n_mtiles;
   int32_t gshift;  // log2(group / 128): tile column tc uses parameter row tc >> gshift
   int32_t bf16;    // scales and zeros are bfloat16 (else fp16)
+  int32_t ksplit;  // K ranges (1 = the whole K in one workgroup)
+  float* partial;  // ksplit > 1: fp32 partial products [ksplit][M][N], rows of Wt in reordered order
 };
 
 constexpr int kPrefillMaxTiles = 224 * 2;  // K <= 57344
@@ -198,9 +237,14 @@ __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) 
   // b % 8) takes item b.  With a multiple of 8 M blocks an XCD always sees the same M blocks (their activation
   // rows stay in its L2), and in any case the blocks that run at the same time need the same weight tiles, so
   // a tile comes from HBM once per XCD, not once per M block.  (Every XCD works for any number of M blocks.)
-  const int mt = (int)blockIdx.x % p.n_mtiles;
-  const int tr = (int)blockIdx.x / p.n_mtiles;
+  // With K split into ranges (few workgroups otherwise: short prompts), the ranges of an item are innermost.
+  const int ks = (int)blockIdx.x % p.ksplit;
+  const int mt = ((int)blockIdx.x / p.ksplit) % p.n_mtiles;
+  const int tr = ((int)blockIdx.x / p.ksplit) / p.n_mtiles;
   const int m0 = mt * BM;
+  // this workgroup's share of the width-sorted tile sequence: positions [e_first, e_end)
+  const int e_first = (int)((int64_t)ks * p.ntc / p.ksplit), e_end = (int)((int64_t)(ks + 1) * p.ntc / p.ksplit);
+  const int e_last = e_end - 1;
 
   // The K reduction runs over the tiles of this tile row sorted by width (first all 2-bit tiles, then
   // the 3-bit, then the 4-bit ones; the order of a sum is free): three loops, each with a straight-line
@@ -415,7 +459,7 @@ __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) 
     asm volatile("" ::: "memory");
     // past the end the last tile is loaded again, into the idle buffer and the landing registers: same
     // load count on every path
-    const int nn = min(e + 2, p.ntc - 1);
+    const int nn = min(e + 2, e_last);
     issue_x(nn, e);
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (decltype(in_run)::value)
@@ -456,18 +500,18 @@ __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) 
     } else {
       interleave();
       __builtin_amdgcn_sched_barrier(0);
-      make_b_any(min(e + 1, p.ntc - 1), k0, b0);
+      make_b_any(min(e + 1, e_last), k0, b0);
     }
   };
 
-  // prologue: tile 0 lands, then its k-step 0 is prepared while tile 1 is on its way
-  issue_x(0, 0);
+  // prologue: the first tile lands, then its k-step 0 is prepared while the second is on its way
+  issue_x(e_first, e_first);
   __builtin_amdgcn_sched_barrier(0);
-  issue_w_generic(0, fw, fsz);
+  issue_w_generic(e_first, fw, fsz);
   __builtin_amdgcn_sched_barrier(0);
-  sync_and_issue(-1, std::integral_constant<bool, false>{}, k0);
-  read_a(0, k0, a0);
-  make_b_any(0, k0, b0);
+  sync_and_issue(e_first - 1, std::integral_constant<bool, false>{}, k0);
+  read_a(e_first, k0, a0);
+  make_b_any(e_first, k0, b0);
   __builtin_amdgcn_sched_barrier(0);
 
   const std::integral_constant<bool, true> in_run;
@@ -475,13 +519,15 @@ __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) 
   const std::integral_constant<int, 2> b2;
   const std::integral_constant<int, 3> b3;
   const std::integral_constant<int, 4> b4;
-  int e = 0;
-  for (; e + 2 < end2; ++e) step(b2, in_run, e);
-  for (; e < end2; ++e) step(b2, run_ends, e);
-  for (; e + 2 < end3; ++e) step(b3, in_run, e);
-  for (; e < end3; ++e) step(b3, run_ends, e);
-  for (; e + 2 < p.ntc; ++e) step(b4, in_run, e);
-  for (; e < p.ntc; ++e) step(b4, run_ends, e);
+  // the runs of this workgroup's share: [e_first, r2) 2-bit, [r2, r3) 3-bit, [r3, e_end) 4-bit
+  const int r2 = min(max(end2, e_first), e_end), r3 = min(max(end3, e_first), e_end);
+  int e = e_first;
+  for (; e + 2 < r2; ++e) step(b2, in_run, e);
+  for (; e < r2; ++e) step(b2, run_ends, e);
+  for (; e + 2 < r3; ++e) step(b3, in_run, e);
+  for (; e < r3; ++e) step(b3, run_ends, e);
+  for (; e + 2 < e_end; ++e) step(b4, in_run, e);
+  for (; e < e_end; ++e) step(b4, run_ends, e);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the idle loads of the last two steps
 
   // epilogue: the block goes through LDS (the activation buffers are free now) so that it leaves in whole
@@ -490,6 +536,28 @@ __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) 
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();  // every wavefront's idle loads have landed and its operand reads returned
   asm volatile("" ::: "memory");
+  if (p.ksplit > 1) {
+    // partial product in fp32: rows of 512 bytes through LDS (BM x 512 bytes = the two activation buffers)
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int row = 16 * MI * wm + 16 * i + 4 * kb + r;
+        float* dst = reinterpret_cast<float*>(Xs + row * 512 + (8 * i16 + NS * wn) * 4);
+#pragma unroll
+        for (int j = 0; j < NS; ++j) dst[j] = acc[i][j][r];
+      }
+    __syncthreads();
+    float* pbase = p.partial + ((int64_t)ks * p.M + m0) * p.N + (int64_t)tr * 128;
+    const int prow = tid / 32, punit = tid % 32;
+#pragma unroll
+    for (int i = 0; i < BM / (S::kThreads / 32); ++i) {
+      const int row = prow + (S::kThreads / 32) * i;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(Xs + row * 512 + punit * 16);
+      if (m0 + row < p.M) *reinterpret_cast<u32x4*>(pbase + (int64_t)row * p.N + punit * 4) = v;
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -518,14 +586,34 @@ __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) 
 template <int BM, int WM, int WN, int IL = 2>
 static void launch_prefill_shape(PrefillParams p, int M, hipStream_t stream) {
   p.n_mtiles = (M + BM - 1) / BM;
-  const unsigned grid = (unsigned)p.n_mtiles * (unsigned)p.ntr;
+  const unsigned grid = (unsigned)p.n_mtiles * (unsigned)p.ntr * (unsigned)p.ksplit;
   hipLaunchKernelGGL((prefill_kernel<BM, WM, WN, IL>), dim3(grid), dim3(64 * WM * WN), 0, stream, p);
 }
 
 PrefillPlan make_prefill_plan(int32_t N, int32_t K, int32_t M) {
   PrefillPlan d;
+  const int64_t ntr = N / kTile, ntc = K / kTile;
+  // 64-row blocks when 128-row blocks would leave half of the CUs without a workgroup (short prompts on narrow
+  // matrices): twice the workgroups, each half as long; measured 8 to 13 % faster there, slower elsewhere
+  d.bm = (int64_t)((M + 127) / 128) * ntr <= 128 ? 64 : 128;
+  // Still at most one workgroup per CU: a workgroup walks its K/128 tiles one after the other (about 0.95 us
+  // each) while most of the machine idles, so K is cut into ranges of at least 8 tiles, one workgroup each
+  // (up to two workgroups per CU), fp32 partial products, and a reduction pass in a fixed order.
+  const int64_t blocks = (int64_t)((M + d.bm - 1) / d.bm) * ntr;
+  int64_t ks = 1;
+  if (blocks <= 256) {
+    ks = 512 / blocks;
+    if (ks > ntc / 8) ks = ntc / 8;
+    if (ks > 8) ks = 8;
+    if (ks < 3) ks = 1;  // two ranges measured between -5 and +6 %: not worth the reduction pass
+  }
+#ifdef SFMP_EXPERIMENT
+  if (const char* v = getenv("SFMP_BM")) d.bm = atoi(v);
+  if (const char* v = getenv("SFMP_KSPLIT")) ks = atoi(v);
+#endif
+  d.ksplit = (int32_t)ks;
   d.xperm_bytes = round_up_256((int64_t)((M + kTile - 1) / kTile) * kTile * K * 2);  // whole 128-row blocks
-  d.ytmp_bytes = round_up_256((int64_t)M * N * 2);
+  d.ytmp_bytes = round_up_256(ks > 1 ? ks * (int64_t)M * N * 4 : (int64_t)M * N * 2);
   return d;
 }
 
@@ -542,7 +630,7 @@ int launch_prefill(const GemmArgs& a, void* stream) {
   const sfmp_layout_t* L = a.L;
   const PrefillPlan plan = make_prefill_plan(L->N, L->K, a.M);
   // the staging / scatter passes hold one fp16 row in LDS (K <= 57344 fits)
-  if ((a.row_perm && (int64_t)L->N * 2 > 160 * 1024) ||
+  if (((a.row_perm || plan.ksplit > 1) && (int64_t)L->N * 2 > 160 * 1024) ||
       L->K / kTile > kPrefillMaxTiles)
     return SFMP_ERR_SHAPE;
   static bool attr_set = false;
@@ -551,6 +639,9 @@ int launch_prefill(const GemmArgs& a, void* stream) {
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&scatter_cols_kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e2 == hipSuccess)
+      e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&reduce_split_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e1 != hipSuccess || e2 != hipSuccess) {
       note_hip_error("hipFuncSetAttribute(gather/scatter)", hipGetErrorString(e1 != hipSuccess ? e1 : e2));
       return SFMP_ERR_HIP;
@@ -580,18 +671,18 @@ int launch_prefill(const GemmArgs& a, void* stream) {
   p.gshift = L->group == 512 ? 2 : L->group == 256 ? 1 : 0;
   p.bf16 = L->scale_format == SFMP_SCALE_BF16;
   p.n_mtiles = 0;
-  // 64-row blocks when 128-row blocks would leave half of the CUs without a workgroup (short prompts on narrow
-  // matrices): twice the workgroups, each half as long; measured 8 to 13 % faster there, slower elsewhere
-  int bm = (int64_t)((a.M + 127) / 128) * p.ntr <= 128 ? 64 : 128;
-#ifdef SFMP_EXPERIMENT
-  if (const char* v = getenv("SFMP_BM")) bm = atoi(v);
-#endif
-  if (bm == 64)
+  p.ksplit = plan.ksplit;
+  p.partial = plan.ksplit > 1 ? (float*)((char*)a.workspace + plan.xperm_bytes) : nullptr;
+  if (plan.bm == 64)
     launch_prefill_shape<64, 1, 4>(p, a.M, (hipStream_t)stream);
   else
     launch_prefill_shape<128, 1, 4>(p, a.M, (hipStream_t)stream);
   if (int e = check_launch("sfmp_gemm prefill launch")) return e;
-  if (a.row_perm) {
+  if (plan.ksplit > 1) {
+    hipLaunchKernelGGL(reduce_split_kernel, dim3((unsigned)a.M), dim3(1024), (size_t)L->N * 2, (hipStream_t)stream,
+                       (const float*)p.partial, (int)plan.ksplit, (int)a.M, a.row_perm, (_Float16*)a.Y, (int)L->N);
+    if (int e = check_launch("sfmp_gemm split-K reduction launch")) return e;
+  } else if (a.row_perm) {
     hipLaunchKernelGGL(scatter_cols_kernel, dim3((unsigned)a.M), dim3(256), (size_t)L->N * 2, (hipStream_t)stream,
                        (const _Float16*)Yt, a.row_perm, (_Float16*)a.Y, (int)L->N);
     if (int e = check_launch("sfmp_gemm row scatter launch")) return e;

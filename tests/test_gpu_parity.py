@@ -161,6 +161,20 @@ def test_medium_batch_chunked_and_prefill_sides(torch_cuda, K, N, M):
     _check(p, run_gemm(p), rows)
 
 
+@pytest.mark.parametrize("K,N,M,row_perm", [(4096, 16384, 40, False), (4096, 2048, 200, True), (3072, 1024, 300, False)])
+def test_short_prompt_split_k(torch_cuda, K, N, M, row_perm):
+    # few workgroups otherwise: K cut into 3 to 8 ranges with fp32 partial products and a reduction pass; with and
+    # without the row un-permute folded into that pass, ragged M, 64-row blocks
+    from gpu_util import run_gemm
+    p = W.make_problem("splitk", K, N, M, 7300 + N + M, fractions={2: 0.25, 3: 0.25, 4: 0.5}, outliers=True,
+                       fast_codes=True, use_row_perm=row_perm)
+    assert (p.row_perm is not None) == row_perm
+    rows = np.random.default_rng(M).choice(N, 384, replace=False)
+    y1 = run_gemm(p)
+    _check(p, y1, rows)
+    assert np.array_equal(y1.view(np.uint16), run_gemm(p).view(np.uint16))  # fixed reduction order
+
+
 def test_workspace_is_reusable_and_result_deterministic(torch_cuda):
     from gpu_util import device_problem, make_workspace, run_gemm
     p = W.make_problem("reuse", 2048, 1024, 4, 31337, fractions={2: 0.5, 3: 0.5}, outliers=True)
