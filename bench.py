@@ -43,7 +43,7 @@ def parse_args():
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of HIP-graph replays")
     ap.add_argument("--separate", action="store_true",
                     help="one launch per projection (7) instead of q|k|v, o, gate|up, down sharing launches (4)")
-    ap.add_argument("--section", choices=("all", "decode", "batch", "prefill"), default="all",
+    ap.add_argument("--section", choices=("all", "decode", "batch", "prefill", "sweep"), default="all",
                     help="which side reports to run after the headline measurement (for profiling one kernel "
                          "family at a time): decode = per-projection and 70B M=1, batch = M in {4, 16}, prefill = "
                          "M=2048; with batch or prefill the headline region runs 2 steps only")
@@ -296,7 +296,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     groups = None if args.separate else FUSED_GROUPS
-    if args.section in ("batch", "prefill"):
+    if args.section in ("batch", "prefill", "sweep"):
         args.steps, args.warmup = 2, 1
     ms_step, wall_ms = time_steps(torch, layer, args.steps, args.warmup, use_graph=not args.eager, groups=groups)
     us_layer = ms_step * 1e3
@@ -444,6 +444,22 @@ def main():
                 del lm, pm
             extra["prefill_4096x14336_M_sweep"] = sweep
             del lp, pp
+        if args.section in ("all", "sweep"):
+            # one call of sfmp_gemm at every batch size on two 8B matrices: which kernels a given M runs is the
+            # library's choice (GEMV, ring kernel, its chunked form, MFMA kernel with or without a split K)
+            ps = build_problems(W, 2, fast=True, only=("8b.q", "8b.down"))
+            sweep = {}
+            for q in ps:
+                rows = []
+                for M in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048):
+                    lm = Layer([W.with_activations(q, M, outliers=False)], 8 if M <= 128 else 2)
+                    t = time_each_projection(torch, lm, launches=32 if M <= 128 else 16)[0]
+                    rows.append(dict(M=M, us=round(t, 1), us_per_row=round(t / M, 2),
+                                     TFLOPs=round(2.0 * M * q.N * q.K / t / 1e6, 1)))
+                    del lm
+                sweep[f"{q.K}->{q.N}"] = rows
+            extra["single_call_M_sweep"] = sweep
+            del ps
         result["extra"] = extra
 
     if not args.no_cpu_baseline:

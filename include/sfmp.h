@@ -149,9 +149,9 @@ int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream);
  *   workspace device memory of at least sfmp_gemm_workspace() bytes, 256-byte aligned; contents
  *             on entry are irrelevant, contents on return are unspecified.
  * M = 1 runs the bandwidth-bound GEMV kernel, 2 <= M <= 16 (and M = 1 with K above about 32k) the
- * same scheme with the activations staged per tile column, 16 < M <= 128 on matrices with K >= 4096 and
- * few tile rows (N <= 4096: M <= 128; N <= 8192: M <= 64; N <= 16384: M <= 32) that kernel once more, on
- * chunks of 16 rows side by side in one launch, and everything else the MFMA prefill kernels (with K
+ * same scheme with the activations staged per tile column, 16 < M <= 128 on narrow matrices with
+ * K >= 4096 (N <= 1024: M <= 128; N <= 4096: M <= 32) that kernel once more, on chunks of 16 rows side
+ * by side in one launch, and everything else the MFMA prefill kernels (with K
  * cut into ranges and fp32 partial products in the workspace when there would be few workgroups;
  * SFMP_ERR_SHAPE there if K > 57344, or, with a row permutation or a split K, N > 81920).
  * Asynchronous on hip_stream; holds no global state.  The permutations are not checked for

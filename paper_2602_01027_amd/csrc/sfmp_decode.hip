@@ -1076,22 +1076,21 @@ int launch_decode_batched(const GemmArgs* probs, int count, int32_t M, void* wor
   }
 }
 
-// 16 < M <= 128 on a matrix with few tile rows: the product is cut into chunks of 16 activation rows, one
-// problem of the batched ring kernel each (the same weights, its own rows of X and Y).  The chunks run side by
-// side on their shares of the CUs and read the same weights at about the same time, so the matrix comes from HBM
-// once and from the caches for the other chunks.  The MFMA prefill kernel with one workgroup per (128 rows, tile
-// row) leaves most CUs idle there and walks K serially (about 0.95 us per tile column whatever M is: 105 us for
-// 14336 -> 4096 against 31 us in two chunks, 52 in four, 91 in eight).  The cost of the chunked path grows with
-// the number of chunks and with N; measured break-even points on the 8B / 70B shapes:
-//   N <= 4096: up to 8 chunks;  N <= 8192: up to 4;  N <= 16384: 2;  wider: never;  K below 4096 not measured: never.
+// 16 < M <= 128 on a narrow matrix: the product is cut into chunks of 16 activation rows, one problem of the
+// batched ring kernel each (the same weights, its own rows of X and Y).  The chunks run side by side on their
+// shares of the CUs and read the same weights at about the same time, so the matrix comes from HBM once and
+// from the caches for the other chunks.  Against the MFMA kernel with a split K the cost grows quickly with the
+// number of chunks and with N; measured on the 8B / 70B shapes the chunked form wins for
+//   N <= 1024: up to 8 chunks (4096 -> 1024: 13-17 us against 18-19);  N <= 4096: 2 chunks (4096 -> 4096: 16 us
+//   against 19);  wider, or K below 4096 (not measured): never.
 bool use_chunked_decode(int32_t N, int32_t K, int32_t M) {
   if (M <= kDecodeMaxM || M > kDecodeMaxM * kGemvMaxBatch) return false;
-#ifdef SFMP_EXPERIMENT
-  if (const char* v = getenv("SFMP_CHUNK")) return atoi(v) != 0 && (N / kTile <= 64 || M <= 64);
-#endif
   const int32_t ntr = N / kTile, ntc = K / kTile, chunks = (M + kDecodeMaxM - 1) / kDecodeMaxM;
+#ifdef SFMP_EXPERIMENT
+  if (const char* v = getenv("SFMP_CHUNK")) return atoi(v) != 0 && (ntr <= 64 || M <= 64);
+#endif
   if (ntc < 32) return false;
-  return chunks <= (ntr <= 32 ? 8 : ntr <= 64 ? 4 : ntr <= 128 ? 2 : 0);
+  return chunks <= (ntr <= 8 ? 8 : ntr <= 32 ? 2 : 0);
 }
 
 static int chunk_problems(const GemmArgs& a, GemmArgs* probs) {

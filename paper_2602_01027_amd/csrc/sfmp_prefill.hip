@@ -605,7 +605,7 @@ PrefillPlan make_prefill_plan(int32_t N, int32_t K, int32_t M) {
     ks = 512 / blocks;
     if (ks > ntc / 8) ks = ntc / 8;
     if (ks > 8) ks = 8;
-    if (ks < 3) ks = 1;  // two ranges measured between -5 and +6 %: not worth the reduction pass
+    if (ks < 3 && ntc < 64) ks = 1;  // two ranges of a short K measured between -5 and +6 %; of a long K +20 %
   }
 #ifdef SFMP_EXPERIMENT
   if (const char* v = getenv("SFMP_BM")) d.bm = atoi(v);

@@ -149,11 +149,12 @@ def test_batched_small_batch_mixed_staging(torch_cuda):
         assert np.array_equal(run_gemm(p, dp, cp, rp).view(np.uint16), y.view(np.uint16))
 
 
-@pytest.mark.parametrize("K,N,M", [(4096, 512, 17), (4096, 512, 100), (4096, 512, 128), (4096, 8192, 64),
-                                   (4096, 8192, 65), (4096, 16384, 32), (4096, 16384, 33)])
+@pytest.mark.parametrize("K,N,M", [(4096, 512, 17), (4096, 512, 100), (4096, 1024, 128), (4096, 1152, 128),
+                                   (4096, 4096, 32), (4096, 4096, 33), (4096, 8192, 64)])
 def test_medium_batch_chunked_and_prefill_sides(torch_cuda, K, N, M):
     # 16 < M <= 128 with K >= 4096: chunks of 16 rows through the batched ring kernel while the matrix is narrow
-    # enough (last chunk of 1 and of 4 rows, the full 8 chunks), the MFMA kernel beyond; both sides of each limit
+    # enough (last chunk of 1 and of 4 rows, the full 8 chunks), the MFMA kernel with a split K beyond; both sides
+    # of each limit
     from gpu_util import run_gemm
     p = W.make_problem("medium", K, N, M, 6200 + N + M, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, outliers=True,
                        fast_codes=True)
