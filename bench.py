@@ -341,6 +341,27 @@ def main():
         },
     }
 
+    # second denominator: what a plain streaming read reaches on this machine (1 GiB, cold), beside the data sheet
+    try:
+        import paper_2602_01027_amd as S_
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+        outp = torch.empty(2048, dtype=torch.uint8, device="cuda:0")
+        for _ in range(2):
+            S_.sfmp_stream_read_probe(src, outp)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            S_.sfmp_stream_read_probe(src, outp)
+        e1.record()
+        torch.cuda.synchronize()
+        stream_gbps = 5 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, outp
+        result["roofline"]["measured_stream_read_GBps"] = round(stream_gbps, 1)
+        result["roofline"]["frac_of_measured_stream_read"] = round(gbps / stream_gbps, 4)
+    except Exception as ex:  # the probe is an aid: never let it take the bench line down
+        result["roofline"]["measured_stream_read_GBps"] = None
+        result["roofline"]["measured_stream_read_error"] = str(ex)
+
     if not args.no_extra:
         extra = {}
         if args.section in ("all", "decode"):

@@ -198,6 +198,12 @@ int sfmp_gemm_batched_workspace(const sfmp_gemv_problem_t* problems_host, int32_
 int sfmp_gemm_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, int32_t M, void* workspace_dev,
                       int64_t workspace_bytes, void* hip_stream);
 
+/* Measurement aid, not part of the product path (Section 4.4 compares kernels by latency; a bandwidth-bound
+ * kernel is judged here against what the memory system delivers): reads bytes (a multiple of 16) from src_dev
+ * once with plain streaming loads and writes 2048 bytes of check words to out_dev, so that a bench can time it
+ * and report the streaming-read bandwidth of this machine beside the data-sheet figure.  Asynchronous. */
+int sfmp_stream_read_probe(const void* src_dev, int64_t bytes, void* out_dev, void* hip_stream);
+
 /* Host only.  SFMP_OK if perm_host[0..n) is a permutation of 0..n-1, else SFMP_ERR_PERM. */
 int sfmp_check_perm(const int32_t* perm_host, int32_t n);
 

@@ -41,6 +41,12 @@ int sfmp_gemm_workspace(const sfmp_layout_t* layout, int32_t M, int64_t* bytes) 
   return SFMP_OK;
 }
 
+int sfmp_stream_read_probe(const void* src_dev, int64_t bytes, void* out_dev, void* hip_stream) {
+  if (!src_dev || !out_dev) return SFMP_ERR_NULL;
+  if (bytes < 16 || (bytes % 16) != 0 || !aligned(src_dev, 16) || !aligned(out_dev, 4)) return SFMP_ERR_SHAPE;
+  return launch_stream_read(src_dev, bytes, out_dev, hip_stream);
+}
+
 int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream) {
   if (!workspace_dev) return SFMP_ERR_NULL;
   if (bytes < 0 || (bytes % 16) != 0 || !aligned(workspace_dev, 256)) return SFMP_ERR_WORKSPACE;

@@ -37,6 +37,10 @@ constexpr int32_t kDecodeMaxM = 16;
 
 inline int64_t round_up_256(int64_t v) { return (v + 255) / 256 * 256; }
 
+// measurement aid (streaming-read probe): grid of the probe kernel = words it writes to its output
+constexpr int32_t kStreamReadGrid = 512;
+int launch_stream_read(const void* src, int64_t bytes, void* out, void* stream);
+
 }  // namespace sfmp
 
 // Kernel launchers (defined in the .hip files).  All are asynchronous on `stream` and return
