@@ -146,3 +146,42 @@ def test_fold_perms_matches_oracle_and_its_defining_property():
         S.sfmp_fold_perms(np.array([0, 0, 1], dtype=np.int32), None)
     with pytest.raises(S.SfmpError):
         S.sfmp_fold_perms(np.array([0, 2, 1], dtype=np.int32), np.array([0, 3, 1], dtype=np.int32))
+
+
+def _plan_mirror(N, K, M):
+    """The documented path selection of sfmp_gemm, restated: which kernels a call takes and the workspace it needs."""
+    ntr, ntc = N // 128, K // 128
+    up256 = lambda v: (v + 255) // 256 * 256
+    if M <= 16:
+        if M == 1 and K <= 32768 - 1:  # the GEMV kernel holds the activation vector in LDS: no workspace
+            return "gemv", None
+        mb = 4 if M <= 4 else 8 if M <= 8 else 16
+        return "ring", up256(ntc * mb * 256)
+    chunks = (M + 15) // 16
+    if M <= 128 and ntc >= 32 and chunks <= (8 if ntr <= 8 else 2 if ntr <= 32 else 0):
+        return "chunked", chunks * up256(ntc * 16 * 256)
+    bm = 64 if ((M + 127) // 128) * ntr <= 128 else 128
+    blocks = ((M + bm - 1) // bm) * ntr
+    ks = 1
+    if blocks <= 256:
+        ks = max(1, min(512 // blocks, ntc // 8, 8))
+        if ks < 3 and ntc < 64:
+            ks = 1
+    xperm = up256(((M + 127) // 128) * 128 * K * 2)
+    ytmp = up256(ks * M * N * 4 if ks > 1 else M * N * 2)
+    return f"mfma bm={bm} ksplit={ks}", xperm + ytmp
+
+
+@pytest.mark.parametrize("N,K,M", [(4096, 4096, 4), (4096, 14336, 16), (1024, 4096, 128), (1152, 4096, 128),
+                                    (4096, 4096, 32), (4096, 4096, 33), (4096, 14336, 256), (14336, 4096, 48),
+                                    (14336, 4096, 256), (4096, 4096, 2048), (28672, 8192, 2048), (4096, 2048, 100),
+                                    (8192, 28672, 512)])
+def test_workspace_query_follows_the_documented_path_selection(N, K, M):
+    bitmap = np.full((N // 128, K // 128), 3, dtype=np.int8)
+    L = S.sfmp_pack_query(bitmap, N, K)
+    name, expected = _plan_mirror(N, K, M)
+    got = S.sfmp_gemm_workspace(L, M)
+    if expected is not None:
+        assert got == max(256, expected), (name, got, expected)
+    else:
+        assert got == 256, (name, got)
