@@ -74,6 +74,7 @@ constexpr int kGemvMaxSlabs = 16;    // slabs per workgroup kept in register acc
 constexpr int kGemvMaxItems = 64;    // items per wavefront: one lane of the item registers each
 constexpr int kSlotBytes = 1024 + 128;  // slab bytes (<= 1 KiB) + 16 scale dwords + 16 zero dwords
 
+typedef float floatx16v __attribute__((ext_vector_type(16)));
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -244,7 +245,10 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
   for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = half8{0, 0, 0, 0, 0, 0, 0, 0};
   // One fp32 sum per slab of this workgroup, kept in registers: an LDS store inside the loop would
   // make the compiler wait for every outstanding global->LDS copy (it cannot tell them apart).
-  float accs[kGemvMaxSlabs];
+  // (a vector type: the write of element j at the end of a slab becomes one indexed register move; a switch over
+  // 16 scalars became a ladder of some 40 branches and moves that ran after every second item when K = 4096)
+  static_assert(kGemvMaxSlabs == 16, "per-slab sums are held in a 16-element vector");
+  floatx16v accs;
 #pragma unroll
   for (int q = 0; q < kGemvMaxSlabs; ++q) accs[q] = 0.f;
   float acc = 0.f;
@@ -271,14 +275,8 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
     params_to_float(scw, zrw, (misc >> 22) & 16u, p.bf16 != 0, sf, zf);  // bit 26 of misc: odd sigma -> high half
     acc += sf * t + zf * sx;
     if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
-      switch ((misc >> 17) & 0x7F) {
-#define SFMP_CASE(q) case q: accs[q] = acc; break;
-        SFMP_CASE(0) SFMP_CASE(1) SFMP_CASE(2) SFMP_CASE(3) SFMP_CASE(4) SFMP_CASE(5) SFMP_CASE(6) SFMP_CASE(7)
-        SFMP_CASE(8) SFMP_CASE(9) SFMP_CASE(10) SFMP_CASE(11) SFMP_CASE(12) SFMP_CASE(13) SFMP_CASE(14)
-        SFMP_CASE(15)
-#undef SFMP_CASE
-        default: break;
-      }
+      asm volatile("" ::: "memory");  // keeps this a branch: as a select it copied all 16 sums after every item
+      accs[(misc >> 17) & 15] = acc;
       acc = 0.f;
     }
   };
@@ -528,9 +526,11 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   for (int kappa = 0; kappa < 4; ++kappa)
     a_off[kappa] = (RES ? 0 : kSlotBytes) + i16 * 256 + (((4 * kappa + kb) ^ i16) * 16);
 
-  floatx4 accs[kGemvMaxSlabs];
+  // finished sums: accs[r][q] = output element r of this lane for slab q (register-indexed writes, no switch)
+  static_assert(kGemvMaxSlabs == 16, "the finished sums live in 16-wide register vectors");
+  floatx16v accs0, accs1, accs2, accs3;  // four named vectors: an array of them went to scratch memory
 #pragma unroll
-  for (int q = 0; q < kGemvMaxSlabs; ++q) accs[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int q = 0; q < kGemvMaxSlabs; ++q) accs0[q] = 0.f, accs1[q] = 0.f, accs2[q] = 0.f, accs3[q] = 0.f;
   floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 
   auto consume = [&](int e, int s) {
@@ -572,14 +572,9 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
     params_to_float(scw, zrw, (misc >> 22) & 16u, p.bf16 != 0, sf, zf);  // bit 26 of misc: odd sigma -> high half
     acc += sf * t + zf * sx;
     if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
-      switch ((misc >> 17) & 0x7F) {
-#define SFMP_CASE(q) case q: accs[q] = acc; break;
-        SFMP_CASE(0) SFMP_CASE(1) SFMP_CASE(2) SFMP_CASE(3) SFMP_CASE(4) SFMP_CASE(5) SFMP_CASE(6) SFMP_CASE(7)
-        SFMP_CASE(8) SFMP_CASE(9) SFMP_CASE(10) SFMP_CASE(11) SFMP_CASE(12) SFMP_CASE(13) SFMP_CASE(14)
-        SFMP_CASE(15)
-#undef SFMP_CASE
-        default: break;
-      }
+      asm volatile("" ::: "memory");  // keeps this a branch rather than a select over all the sums
+      const int q = (misc >> 17) & 15;
+      accs0[q] = acc[0], accs1[q] = acc[1], accs2[q] = acc[2], accs3[q] = acc[3];
       acc = floatx4{0.f, 0.f, 0.f, 0.f};
     }
   };
@@ -610,10 +605,11 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
 #pragma unroll
       for (int q = 0; q < kGemvMaxSlabs; ++q)
         if (q < nj) {
+          const float fin[4] = {accs0[q], accs1[q], accs2[q], accs3[q]};
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             float* dst = red + (q * 4 + r) * 64 + lane;
-            *dst = (w == 0 ? 0.f : *dst) + accs[q][r];
+            *dst = (w == 0 ? 0.f : *dst) + fin[r];
           }
         }
     }
