@@ -75,6 +75,16 @@ constexpr int kGemvMaxItems = 64;    // items per wavefront: one lane of the ite
 constexpr int kSlotBytes = 1024 + 128;  // slab bytes (<= 1 KiB) + 16 scale dwords + 16 zero dwords
 
 typedef float floatx16v __attribute__((ext_vector_type(16)));
+#ifdef SFMP_EXPERIMENT
+__device__ unsigned long long g_stamps[256 * 8];
+__device__ unsigned long long g_wave_done[256 * 16];
+#define SFMP_STAMP(k)                                                        \
+  do {                                                                       \
+    if (threadIdx.x == 0) g_stamps[blockIdx.x * 8 + (k)] = wall_clock64();   \
+  } while (0)
+#else
+#define SFMP_STAMP(k)
+#endif
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -105,10 +115,11 @@ __device__ __forceinline__ float unit_group_sum(const half8& v) {
   float s = 0.f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) s += (float)v[e];
-  s += __shfl_xor(s, 8, 16);
-  s += __shfl_xor(s, 4, 16);
-  s += __shfl_xor(s, 2, 16);
-  s += __shfl_xor(s, 1, 16);
+  // rotations inside each row of 16 lanes (data-parallel primitives of the vector ALU, no trip through LDS)
+  s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0x128, 0xF, 0xF, false));  // row_ror:8
+  s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0x124, 0xF, 0xF, false));  // row_ror:4
+  s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0x122, 0xF, 0xF, false));  // row_ror:2
+  s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0x121, 0xF, 0xF, false));  // row_ror:1
   return s;
 }
 
@@ -127,97 +138,143 @@ __device__ __forceinline__ float gemv_item(const unsigned char* slot, int lane, 
 // an item needs (packed-slab address, scale address, tile column, flags) is computed once, by lane e
 // for item e, and later broadcast with v_readlane: the steady-state loop does no address arithmetic.
 // The ring is refilled item by item, so S-1 copies per wavefront are always in flight.
+// LDS stores the compiler does not see as LDS accesses.  After a direct global->LDS copy has been issued the
+// compiler puts a wait for ALL outstanding copies in front of every ordinary LDS store (it cannot tell the
+// destinations apart); these stores are used while ring copies are in flight, to regions no copy writes.
+// The caller waits with s_waitcnt lgkmcnt(0) before anyone reads what was stored.
+__device__ __forceinline__ void lds_store_b128_untracked(void* dst, const half8& v) {
+  const uint32_t off = (uint32_t)(uintptr_t)(lptr_t)dst;
+  asm volatile("ds_write_b128 %0, %1" ::"v"(off), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_store_b32_untracked(void* dst, float v) {
+  const uint32_t off = (uint32_t)(uintptr_t)(lptr_t)dst;
+  asm volatile("ds_write_b32 %0, %1" ::"v"(off), "v"(v) : "memory");
+}
+// workgroup barrier that waits for this wavefront's LDS traffic only, not for its outstanding global->LDS copies
+__device__ __forceinline__ void barrier_lds_only() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+constexpr int kGemvUnitIters = 4;  // 16-byte activation units per thread: K <= 8 * 4 * 1024 = 32768
+
+// bytes of the region shared by the raw activation copy (start of the kernel) and the reduction buffer (end)
+__host__ __device__ inline int64_t gemv_shared_region_bytes(int32_t K, int32_t max_slabs, int nw) {
+  const int64_t raw = (int64_t)K * 2, red = (int64_t)max_slabs * nw * 64;
+  return ((raw > red ? raw : red) + 15) & ~(int64_t)15;
+}
+
+// NW wavefronts per workgroup, S ring slots per wavefront.
+//
+// A wavefront's work is a list of at most 64 "items" (one 16-row slab of one tile each).  Everything
+// an item needs (packed-slab address, scale address, tile column, flags) is computed once, by lane e
+// for item e, and later broadcast with v_readlane: the steady-state loop does no address arithmetic.
+// The ring is refilled item by item, so S-1 copies per wavefront are always in flight.
+//
+// Order of the start: a launch of this size lasts about 10 us, of which each dependent trip to memory is most of
+// a microsecond, so everything that depends on the arguments alone (tile descriptors, raw activations, column
+// permutation, the output positions of the end) is requested at once; the ring is filled as soon as the
+// descriptors are there, and the activations are permuted inside LDS while the first slabs are on their way.
 template <int NW, int S>
 __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, const int G, unsigned char* lds_raw) {
   constexpr int NT = NW * 64;
-  // LDS: Xs [K] fp16 | Sx [ntc] f32 | red [max_slabs][NW][16] f32 | rings [NW][S][kSlotBytes]
-  // (the raw activation copy used while permuting aliases the rings: they are idle until then)
+  // LDS: Xs [K] fp16 | Sx [ntc] f32 | shared region: raw activations, later red [max_slabs][NW][16] f32 |
+  //      rings [NW][S][kSlotBytes]
   _Float16* Xs = reinterpret_cast<_Float16*>(lds_raw);
   float* Sx = reinterpret_cast<float*>(lds_raw + (size_t)p.K * 2);
-  float* red = Sx + p.ntc;
-  unsigned char* rings =
-      lds_raw + (((size_t)p.K * 2 + (size_t)p.ntc * 4 + (size_t)p.max_slabs * NW * 64 + 15) & ~(size_t)15);
-  _Float16* Xraw = reinterpret_cast<_Float16*>(rings);
+  unsigned char* shared_region = lds_raw + (((size_t)p.K * 2 + (size_t)p.ntc * 4 + 15) & ~(size_t)15);
+  _Float16* Xraw = reinterpret_cast<_Float16*>(shared_region);
+  float* red = reinterpret_cast<float*>(shared_region);
+  unsigned char* rings = shared_region + gemv_shared_region_bytes(p.K, p.max_slabs, NW);
 
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  SFMP_STAMP(0);
   // Virtual slab index v = bid + G*j (G is a multiple of 8, block b runs on XCD b%8): XCD x gets
   // the contiguous slab range [x*ntr, (x+1)*ntr), so the 8 slabs of a tile row run on one XCD.
   const int nj = (p.nslab - bid + G - 1) / G;                           // slabs of this workgroup
   const int my_cnt = p.ntc > wave ? (p.ntc - wave + NW - 1) / NW : 0;  // tiles per slab of this wavefront
   const int E = nj * my_cnt;                                           // items of this wavefront (<= 64)
 
-  // ---- per-item registers: lane e describes item e = j*my_cnt + i (tile column wave + NW*i of slab j)
-  uint32_t it_alo = 0, it_ahi = 0, it_slo = 0, it_shi = 0, it_misc = 0;
-  if (lane < E) {
-    const int j = lane / my_cnt, i = lane - j * my_cnt;
-    const int v = bid + G * j;
+  // ---- requests that depend on the arguments alone, all issued before the first wait
+  // (1) tile descriptor of item `lane`: item e = j*my_cnt + i is tile column wave + NW*i of slab j
+  const int it_j = lane / (my_cnt > 0 ? my_cnt : 1), it_i = lane - it_j * my_cnt;
+  const int it_v = bid + G * it_j;
+  const int it_slab = (it_v % 8) * p.ntr + it_v / 8;
+  const int it_tr = it_slab / 8, it_sigma = it_slab % 8;
+  const int it_tc = wave + NW * it_i;
+  // (every load below is unconditional, from a clamped and always valid address: a load under a condition makes
+  // the compiler wait for it at the end of the condition, and the requests would go out one after the other)
+  const int32_t d = p.tile_desc[lane < E ? (int64_t)it_tr * p.ntc + it_tc : (int64_t)0];
+  // (2) where the sum that thread tid adds up at the end goes: output row 8*r16 + sigma of slab tid/16
+  int64_t out_row = 0;
+  if (tid < nj * 16) {
+    const int v = bid + G * (tid / 16);
     const int slab = (v % 8) * p.ntr + v / 8;
-    const int tr = slab / 8, sigma = slab % 8;
-    const int tc = wave + NW * i;
-    const int32_t d = p.tile_desc[(int64_t)tr * p.ntc + tc];
-    const int bm2 = d & 3;  // bit-width - 2
-    const uint8_t* base = bm2 == 0 ? p.s2 : bm2 == 1 ? p.s3 : p.s4;
+    out_row = (int64_t)(slab / 8) * kTile + 8 * (tid % 16) + (slab % 8);
+  }
+  int32_t out_col = *(p.row_perm ? p.row_perm + out_row : p.tile_desc);
+  // (3) activations: raw copy straight into LDS (into their final place when there is no permutation);
+  //     column permutation into registers (entries of the last unit for threads beyond the end)
+  const int units = p.K / 8;
+  int4 c0[kGemvUnitIters], c1[kGemvUnitIters];
+  {
+    _Float16* xdst = p.col_perm ? Xraw : Xs;
+    const int4* cp = reinterpret_cast<const int4*>(p.col_perm ? (const void*)p.col_perm : (const void*)p.X);
+#pragma unroll
+    for (int u = 0; u < kGemvUnitIters; ++u) {
+      if (u * NT < units) {  // uniform
+        const int i = tid + u * NT;
+        if (i < units)
+          __builtin_amdgcn_global_load_lds((gptr_t)(p.X + 8 * (size_t)i),
+                                           (lptr_t)(xdst + 8 * (size_t)(wave * 64 + u * NT)), 16, 0, 0);
+        const int ic = p.col_perm ? min(i, units - 1) : 0;
+        c0[u] = cp[2 * ic];
+        c1[u] = cp[2 * ic + 1];
+      }
+    }
+  }
+  SFMP_STAMP(1);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // one trip to memory for all of the above
+  // (the loaded registers are "used" here so that the compiler places its own wait for them here as well: placed
+  // after the ring has been filled it would have to be a wait for every ring copy)
+#pragma unroll
+  for (int u = 0; u < kGemvUnitIters; ++u)
+    if (u * NT < units)
+      asm volatile("" : "+v"(c0[u].x), "+v"(c0[u].y), "+v"(c0[u].z), "+v"(c0[u].w), "+v"(c1[u].x), "+v"(c1[u].y),
+                   "+v"(c1[u].z), "+v"(c1[u].w));
+  asm volatile("" : "+v"(out_col));
+
+  // ---- per-item registers of lane e
+  uint32_t it_alo = 0, it_ahi = 0, it_slo = 0, it_shi = 0, it_misc = 0;
+  {
+    // the three stream bases as vector registers: selected per lane, not fetched from the argument block by index
+    uint32_t b2l = (uint32_t)(uint64_t)p.s2, b2h = (uint32_t)((uint64_t)p.s2 >> 32);
+    uint32_t b3l = (uint32_t)(uint64_t)p.s3, b3h = (uint32_t)((uint64_t)p.s3 >> 32);
+    uint32_t b4l = (uint32_t)(uint64_t)p.s4, b4h = (uint32_t)((uint64_t)p.s4 >> 32);
+    asm volatile("" : "+v"(b2l), "+v"(b2h), "+v"(b3l), "+v"(b3h), "+v"(b4l), "+v"(b4h));
+    const int bm2 = d & 3;  // bit-width - 2 (the use of d makes the compiler wait for the loads above, here)
+    const uint32_t bl = bm2 == 0 ? b2l : bm2 == 1 ? b3l : b4l;
+    const uint32_t bh = bm2 == 0 ? b2h : bm2 == 1 ? b3h : b4h;
     const int64_t slab_bytes = 256 * (bm2 + 2);
-    const uint64_t a = (uint64_t)(base + (int64_t)(d >> 2) * (8 * slab_bytes) + sigma * slab_bytes);
+    const uint64_t a = (((uint64_t)bh << 32) | bl) + (uint64_t)((int64_t)(d >> 2) * (8 * slab_bytes) + it_sigma * slab_bytes);
     // address of the aligned dword holding the fp16 scale of row 128*tr + sigma (rows 8*l + sigma are
     // 16 bytes apart); direct-to-LDS copies need dword-aligned addresses, the wanted fp16 is the
     // low half for even sigma and the high half for odd sigma
-    const uint64_t sa = (uint64_t)(p.scales + (int64_t)(tc >> p.gshift) * p.N + (int64_t)tr * kTile + (sigma & ~1));
-    it_alo = (uint32_t)a;
-    it_ahi = (uint32_t)(a >> 32);
-    it_slo = (uint32_t)sa;
-    it_shi = (uint32_t)(sa >> 32);
-    it_misc = (uint32_t)tc | ((i == my_cnt - 1) ? 0x10000u : 0u) | ((uint32_t)j << 17) | ((uint32_t)bm2 << 24) |
-              ((uint32_t)(sigma & 1) << 26);
+    const uint64_t sa =
+        (uint64_t)(p.scales + (int64_t)(it_tc >> p.gshift) * p.N + (int64_t)it_tr * kTile + (it_sigma & ~1));
+    if (lane < E) {
+      it_alo = (uint32_t)a;
+      it_ahi = (uint32_t)(a >> 32);
+      it_slo = (uint32_t)sa;
+      it_shi = (uint32_t)(sa >> 32);
+      it_misc = (uint32_t)it_tc | ((it_i == my_cnt - 1) ? 0x10000u : 0u) | ((uint32_t)it_j << 17) |
+                ((uint32_t)bm2 << 24) | ((uint32_t)(it_sigma & 1) << 26);
+    }
   }
   // per-lane parts of the two copies of an item
   const uint32_t data_voff = lane * 16;
   const int64_t sz_voff = (int64_t)(lane & 15) * 16 + (lane < 16 ? (int64_t)0 : (int64_t)((const char*)p.zeros - (const char*)p.scales));
-
-  // ---- stage the activation vector once per workgroup: raw copy, then permute inside LDS
-  const int units = p.K / 8;
-  if (p.col_perm) {
-    for (int i = tid; i < units; i += NT)
-      reinterpret_cast<uint4*>(Xraw)[i] = reinterpret_cast<const uint4*>(p.X)[i];
-    int4 c0 = make_int4(0, 0, 0, 0), c1 = c0;
-    if (tid < units) {
-      c0 = reinterpret_cast<const int4*>(p.col_perm)[2 * tid];
-      c1 = reinterpret_cast<const int4*>(p.col_perm)[2 * tid + 1];
-    }
-    __syncthreads();
-    for (int i = tid; i < units; i += NT) {
-      if (i != tid) {
-        c0 = reinterpret_cast<const int4*>(p.col_perm)[2 * i];
-        c1 = reinterpret_cast<const int4*>(p.col_perm)[2 * i + 1];
-      }
-      half8 v;
-      v[0] = Xraw[c0.x];
-      v[1] = Xraw[c0.y];
-      v[2] = Xraw[c0.z];
-      v[3] = Xraw[c0.w];
-      v[4] = Xraw[c1.x];
-      v[5] = Xraw[c1.y];
-      v[6] = Xraw[c1.z];
-      v[7] = Xraw[c1.w];
-      *reinterpret_cast<half8*>(Xs + 8 * i) = v;
-      const float s = unit_group_sum(v);
-      if ((lane & 15) == 0) Sx[i / 16] = s;
-    }
-  } else {
-    for (int i = tid; i < units; i += NT) {
-      union {
-        uint4 u;
-        half8 h;
-      } v;
-      v.u = reinterpret_cast<const uint4*>(p.X)[i];
-      *reinterpret_cast<half8*>(Xs + 8 * i) = v.h;
-      const float s = unit_group_sum(v.h);
-      if ((lane & 15) == 0) Sx[i / 16] = s;
-    }
-  }
-  __syncthreads();  // Xs and Sx are complete; the raw copy is dead and the rings may be filled
 
   // Issue item e into ring slot s: exactly two direct global->LDS copies, the slab (16 B per lane,
   // 32/48/64 lanes) and its 16 scale + 16 zero dwords (lanes 0-15 / 16-31).
@@ -236,9 +293,42 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
       __builtin_amdgcn_global_load_lds((gptr_t)((const char*)sa + sz_voff), (lptr_t)(slot + 1024), 4, 0, 0);
   };
 
-  // ---- prologue: fill the ring
+  // ---- prologue: fill the ring.  The first kEarly items of every wavefront go out now and start the stream;
+  // the rest of the ring follows after the activations are in place: filling a whole ring takes about a
+  // microsecond (the copies of 16 wavefronts queue up in one address unit), and the permutation would wait for it
+  constexpr int kEarly = 2;
   const int npro = min(S, E);
-  for (int e = 0; e < npro; ++e) issue_item(e, e);
+  for (int e = 0; e < min(kEarly, npro); ++e) issue_item(e, e);
+  SFMP_STAMP(2);
+
+  // ---- while those copies are on their way: permute the activations inside LDS and add up each tile column
+  barrier_lds_only();  // every wavefront's part of the raw copy has landed (each waited for its own above)
+#pragma unroll
+  for (int u = 0; u < kGemvUnitIters; ++u) {
+    const int i = tid + u * NT;
+    if (i < units) {
+      half8 v;
+      if (p.col_perm) {
+        v[0] = Xraw[c0[u].x];
+        v[1] = Xraw[c0[u].y];
+        v[2] = Xraw[c0[u].z];
+        v[3] = Xraw[c0[u].w];
+        v[4] = Xraw[c1[u].x];
+        v[5] = Xraw[c1[u].y];
+        v[6] = Xraw[c1[u].z];
+        v[7] = Xraw[c1[u].w];
+        lds_store_b128_untracked(Xs + 8 * i, v);
+      } else {
+        v = *reinterpret_cast<const half8*>(Xs + 8 * i);
+      }
+      const float s = unit_group_sum(v);
+      if ((lane & 15) == 0) lds_store_b32_untracked(Sx + i / 16, s);
+    }
+  }
+  barrier_lds_only();  // Xs and Sx are complete
+  SFMP_STAMP(3);
+  for (int e = kEarly; e < npro; ++e) issue_item(e, e);
+  SFMP_STAMP(4);
 
   half8 a[4];
 #pragma unroll
@@ -292,11 +382,16 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
     if (++s == S) s = 0;
   }
   // ---- tail: nothing left to issue
+  SFMP_STAMP(5);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   for (; e < E; ++e) {
     consume(e, s);
     if (++s == S) s = 0;
   }
+  SFMP_STAMP(6);
+#ifdef SFMP_EXPERIMENT
+  if (lane == 0) g_wave_done[blockIdx.x * 16 + wave] = wall_clock64();
+#endif
 
   if (lane < 16) {
 #pragma unroll
@@ -304,17 +399,13 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
       if (q < nj) red[(q * NW + wave) * 16 + lane] = accs[q];
   }
   __syncthreads();
-  for (int o = tid; o < nj * 16; o += NT) {
-    const int jj = o / 16, r16 = o % 16;
+  if (tid < nj * 16) {  // nj <= 16: one sum per thread at most
     float sum = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) sum += red[(jj * NW + w) * 16 + r16];
-    const int v = bid + G * jj;
-    const int slab = (v % 8) * p.ntr + v / 8;
-    const int64_t row = (int64_t)(slab / 8) * kTile + 8 * r16 + (slab % 8);
-    const int64_t col = p.row_perm ? p.row_perm[row] : row;
-    p.Y[col] = (_Float16)sum;
+    for (int w = 0; w < NW; ++w) sum += red[((tid / 16) * NW + w) * 16 + tid % 16];
+    p.Y[p.row_perm ? (int64_t)out_col : out_row] = (_Float16)sum;
   }
+  SFMP_STAMP(7);
 }
 
 template <int NW, int S>
@@ -688,17 +779,21 @@ struct GemvFit {
   bool ok;
   int32_t slots, max_slabs, lds_bytes;
 };
+// LDS of the GEMV kernel in front of the rings: activations, their tile-column sums, the shared region
+static int64_t gemv_fixed_lds_bytes(int32_t K, int32_t max_slabs) {
+  return ((int64_t)K * 2 + (int64_t)(K / kTile) * 4 + 15) / 16 * 16 + gemv_shared_region_bytes(K, max_slabs, kGemvWaves);
+}
 static GemvFit gemv_fit(int32_t N, int32_t K, int32_t grid) {
   GemvFit f;
   const int32_t ntr = N / kTile, ntc = K / kTile, nslab = 8 * ntr;
   f.max_slabs = (nslab + grid - 1) / grid;
-  const int64_t fixed = ((int64_t)K * 2 + (int64_t)ntc * 4 + (int64_t)f.max_slabs * kGemvWaves * 64 + 15) / 16 * 16;
+  const int64_t fixed = gemv_fixed_lds_bytes(K, f.max_slabs);
   int64_t slots = (160 * 1024 - fixed) / ((int64_t)kGemvWaves * kSlotBytes);
   if (slots > kGemvMaxSlots) slots = kGemvMaxSlots;
   const int64_t ring_bytes = slots * kGemvWaves * kSlotBytes;
   const int64_t items = (int64_t)f.max_slabs * ((ntc + kGemvWaves - 1) / kGemvWaves);
   f.ok = grid >= 8 && grid % 8 == 0 && grid <= nslab && slots >= kGemvMinSlots && f.max_slabs <= kGemvMaxSlabs &&
-         items <= kGemvMaxItems && (int64_t)K * 2 <= ring_bytes;
+         items <= kGemvMaxItems && K / 8 <= kGemvUnitIters * kGemvWaves * 64;
   f.slots = (int32_t)slots;
   f.lds_bytes = (int32_t)(fixed + ring_bytes);
   return f;
@@ -876,10 +971,7 @@ int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
   // with fewer slots than a problem could use alone its LDS footprint only shrinks: size for the largest
   for (int i = 0; i < count; ++i) {
     const sfmp_layout_t* L = probs[i].L;
-    const int64_t fixed =
-        ((int64_t)L->K * 2 + (int64_t)(L->K / kTile) * 4 + (int64_t)b.p[i].max_slabs * kGemvWaves * 64 + 15) / 16 * 16;
-    const int64_t need = fixed + (int64_t)slots * kGemvWaves * kSlotBytes;
-    if ((int64_t)L->K * 2 > (int64_t)slots * kGemvWaves * kSlotBytes) return SFMP_ERR_SHAPE;
+    const int64_t need = gemv_fixed_lds_bytes(L->K, b.p[i].max_slabs) + (int64_t)slots * kGemvWaves * kSlotBytes;
     lds = need > lds ? (int32_t)need : lds;
   }
   return launch_gemv_variant(slots, true, b, (unsigned)first, (size_t)lds, stream);
@@ -1124,3 +1216,12 @@ int launch_decode(const GemmArgs& a, void* stream) {
 }
 
 }  // namespace sfmp
+
+#ifdef SFMP_EXPERIMENT
+extern "C" int sfmp_debug_stamps(unsigned long long* host_out) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(sfmp::g_stamps), sizeof(unsigned long long) * 256 * 8);
+}
+extern "C" int sfmp_debug_wave_done(unsigned long long* host_out) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(sfmp::g_wave_done), sizeof(unsigned long long) * 256 * 16);
+}
+#endif
