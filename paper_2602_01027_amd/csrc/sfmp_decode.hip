@@ -46,6 +46,71 @@ __device__ __forceinline__ floatx4 slab_dot(const uint32_t* w, const half8 (&a)[
   return t;
 }
 
+// The same sum for activation row 0 only, in units of 2^-24: class 0 counts 1, class i counts 2^-pos(i); the
+// caller multiplies by 2^24 once per slab instead of once per item.
+template <int B>
+__device__ __forceinline__ float slab_dot_row0_units(const uint32_t* w, const half8 (&a)[4]) {
+  uint32_t op[4][4];
+  unpack_slab<B>(w, op);
+  floatx4 c[num_classes<B>()];
+#pragma unroll
+  for (int i = 0; i < num_classes<B>(); ++i) c[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kappa = 0; kappa < 4; ++kappa)
+    c[step_class<B>(kappa)] =
+        __builtin_amdgcn_mfma_f32_16x16x32_f16(a[kappa], as_half8(op[kappa]), c[step_class<B>(kappa)], 0, 0, 0);
+  float t = c[0][0];
+#pragma unroll
+  for (int i = 1; i < num_classes<B>(); ++i) t += c[i][0] * pow2f(-class_pos<B>(i));
+  return t;
+}
+
+// Direct global->LDS copies written out by hand: scalar base address + 32-bit lane offset (no 64-bit vector
+// address arithmetic per copy), lanes chosen by a mask in scalar registers.  Lane l writes 16 (4) bytes at LDS byte
+// lds_off + 16 l (4 l).  EXEC is restored inside the statement.  The compiler does not count these copies: the
+// caller waits for them with s_waitcnt vmcnt, and no compiler-placed wait stands in front of later LDS stores.
+__device__ __forceinline__ void lds_copy_b128(uint64_t sbase, uint32_t voff, uint32_t lds_off, uint64_t lanes) {
+  uint64_t saved;
+  asm volatile(
+      "s_mov_b64 %0, exec\n\t"
+      "s_mov_b64 exec, %4\n\t"
+      "s_mov_b32 m0, %3\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %2, %1\n\t"
+      "s_mov_b64 exec, %0"
+      : "=&s"(saved)
+      : "s"(sbase), "v"(voff), "s"(lds_off), "s"(lanes)
+      : "memory");
+}
+__device__ __forceinline__ void lds_copy_b32(uint64_t sbase, uint32_t voff, uint32_t lds_off, uint64_t lanes) {
+  uint64_t saved;
+  asm volatile(
+      "s_mov_b64 %0, exec\n\t"
+      "s_mov_b64 exec, %4\n\t"
+      "s_mov_b32 m0, %3\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dword %2, %1\n\t"
+      "s_mov_b64 exec, %0"
+      : "=&s"(saved)
+      : "s"(sbase), "v"(voff), "s"(lds_off), "s"(lanes)
+      : "memory");
+}
+
+// the same with a full 64-bit address per lane (lanes whose addresses have no common 32-bit range)
+__device__ __forceinline__ void lds_copy_b32_vaddr(uint64_t vaddr, uint32_t lds_off, uint64_t lanes) {
+  uint64_t saved;
+  asm volatile(
+      "s_mov_b64 %0, exec\n\t"
+      "s_mov_b64 exec, %3\n\t"
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dword %1, off\n\t"
+      "s_mov_b64 exec, %0"
+      : "=&s"(saved)
+      : "v"(vaddr), "s"(lds_off), "s"(lanes)
+      : "memory");
+}
+
 // ============================================================================================
 // GEMV, M = 1
 // ============================================================================================
@@ -73,11 +138,13 @@ constexpr int kGemvMinSlots = 4;
 constexpr int kGemvMaxSlabs = 16;    // slabs per workgroup kept in register accumulators
 constexpr int kGemvMaxItems = 64;    // items per wavefront: one lane of the item registers each
 constexpr int kSlotBytes = 1024 + 128;  // slab bytes (<= 1 KiB) + 16 scale dwords + 16 zero dwords
+constexpr int kGemvSlotParamBytes = 128;  // GEMV slots: [16 scale dwords | 16 zero dwords | slab]
 
 typedef float floatx16v __attribute__((ext_vector_type(16)));
 #ifdef SFMP_EXPERIMENT
 __device__ unsigned long long g_stamps[256 * 8];
 __device__ unsigned long long g_wave_done[256 * 16];
+__device__ int g_mode;
 #define SFMP_STAMP(k)                                                        \
   do {                                                                       \
     if (threadIdx.x == 0) g_stamps[blockIdx.x * 8 + (k)] = wall_clock64();   \
@@ -245,53 +312,48 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
                    "+v"(c1[u].z), "+v"(c1[u].w));
   asm volatile("" : "+v"(out_col));
 
-  // ---- per-item registers of lane e
-  uint32_t it_alo = 0, it_ahi = 0, it_slo = 0, it_shi = 0, it_misc = 0;
+  // ---- per-item registers of lane e: 32-bit offsets of the slab inside its stream and of the parameter dwords
+  // inside the scale / zero arrays (each stream and array is below 4 GiB), and the item's flags
+  uint32_t it_woff = 0, it_soff = 0, it_misc = 0;
   {
-    // the three stream bases as vector registers: selected per lane, not fetched from the argument block by index
-    uint32_t b2l = (uint32_t)(uint64_t)p.s2, b2h = (uint32_t)((uint64_t)p.s2 >> 32);
-    uint32_t b3l = (uint32_t)(uint64_t)p.s3, b3h = (uint32_t)((uint64_t)p.s3 >> 32);
-    uint32_t b4l = (uint32_t)(uint64_t)p.s4, b4h = (uint32_t)((uint64_t)p.s4 >> 32);
-    asm volatile("" : "+v"(b2l), "+v"(b2h), "+v"(b3l), "+v"(b3h), "+v"(b4l), "+v"(b4h));
-    const int bm2 = d & 3;  // bit-width - 2 (the use of d makes the compiler wait for the loads above, here)
-    const uint32_t bl = bm2 == 0 ? b2l : bm2 == 1 ? b3l : b4l;
-    const uint32_t bh = bm2 == 0 ? b2h : bm2 == 1 ? b3h : b4h;
-    const int64_t slab_bytes = 256 * (bm2 + 2);
-    const uint64_t a = (((uint64_t)bh << 32) | bl) + (uint64_t)((int64_t)(d >> 2) * (8 * slab_bytes) + it_sigma * slab_bytes);
-    // address of the aligned dword holding the fp16 scale of row 128*tr + sigma (rows 8*l + sigma are
-    // 16 bytes apart); direct-to-LDS copies need dword-aligned addresses, the wanted fp16 is the
-    // low half for even sigma and the high half for odd sigma
-    const uint64_t sa =
-        (uint64_t)(p.scales + (int64_t)(it_tc >> p.gshift) * p.N + (int64_t)it_tr * kTile + (it_sigma & ~1));
+    const uint32_t bm2 = (uint32_t)d & 3u;  // bit-width - 2 (the use of d makes the compiler wait for the loads above, here)
+    const uint32_t slab_bytes = 256u * (bm2 + 2u);
     if (lane < E) {
-      it_alo = (uint32_t)a;
-      it_ahi = (uint32_t)(a >> 32);
-      it_slo = (uint32_t)sa;
-      it_shi = (uint32_t)(sa >> 32);
-      it_misc = (uint32_t)it_tc | ((it_i == my_cnt - 1) ? 0x10000u : 0u) | ((uint32_t)it_j << 17) |
-                ((uint32_t)bm2 << 24) | ((uint32_t)(it_sigma & 1) << 26);
+      it_woff = ((uint32_t)d >> 2) * (8u * slab_bytes) + (uint32_t)it_sigma * slab_bytes;
+      // the aligned dword holding the fp16 scale of row 128*tr + sigma (rows 8*l + sigma are 16 bytes apart);
+      // direct-to-LDS copies need dword-aligned addresses, the wanted fp16 is the low half for even sigma and
+      // the high half for odd sigma
+      it_soff = 2u * (uint32_t)((it_tc >> p.gshift) * p.N + it_tr * kTile + (it_sigma & ~1));
+      it_misc = (uint32_t)it_tc | ((it_i == my_cnt - 1) ? 0x10000u : 0u) | ((uint32_t)it_j << 17) | (bm2 << 24) |
+                ((uint32_t)(it_sigma & 1) << 26);
     }
   }
-  // per-lane parts of the two copies of an item
+  // per-lane offsets of the copies of an item (bytes from the item's scalar base address)
   const uint32_t data_voff = lane * 16;
-  const int64_t sz_voff = (int64_t)(lane & 15) * 16 + (lane < 16 ? (int64_t)0 : (int64_t)((const char*)p.zeros - (const char*)p.scales));
+  // parameters: lanes 0-15 read the scale dwords, lanes 16-31 the zero dwords, in one copy (the two arrays may lie
+  // anywhere, hence a 64-bit lane part: array base + 16 bytes per row pair, to which the item's offset is added)
+  const uint64_t par_vbase = (lane < 16 ? (uint64_t)p.scales : (uint64_t)p.zeros) + (uint64_t)((lane & 15) * 16);
 
-  // Issue item e into ring slot s: exactly two direct global->LDS copies, the slab (16 B per lane,
-  // 32/48/64 lanes) and its 16 scale + 16 zero dwords (lanes 0-15 / 16-31).
-  unsigned char* ring = rings + (size_t)wave * S * kSlotBytes;
-  auto issue_item = [&](int e, int s) {
-    // (v_readlane returns a signed int: go through uint32_t, or the low word would be sign-extended)
-    const uint64_t a = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_ahi, e) << 32) |
-                       (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_alo, e);
-    const uint64_t sa = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_shi, e) << 32) |
-                        (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_slo, e);
-    const uint32_t slab_bytes = 256u * ((((uint32_t)__builtin_amdgcn_readlane((int)it_misc, e) >> 24) & 3u) + 2u);
-    unsigned char* slot = ring + s * kSlotBytes;
-    if (data_voff < slab_bytes)
-      __builtin_amdgcn_global_load_lds((gptr_t)((const char*)a + data_voff), (lptr_t)slot, 16, 0, 0);
-    if (lane < 32)
-      __builtin_amdgcn_global_load_lds((gptr_t)((const char*)sa + sz_voff), (lptr_t)(slot + 1024), 4, 0, 0);
+  // Issue item e into ring slot s: two direct global->LDS copies, the 16 scale dwords + 16 zero dwords (lanes
+  // 0-15 / 16-31) and the slab (16 B per lane, 32/48/64 lanes, scalar address).
+  const uint32_t ring_off = (uint32_t)(uintptr_t)(lptr_t)(rings + (size_t)wave * S * kSlotBytes);
+  const uint64_t s2b = (uint64_t)p.s2, s3b = (uint64_t)p.s3, s4b = (uint64_t)p.s4;
+  auto issue_item = [&](int e, int s) __attribute__((always_inline)) {
+    const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
+    const uint32_t woff = (uint32_t)__builtin_amdgcn_readlane((int)it_woff, e);
+    const uint32_t soff = (uint32_t)__builtin_amdgcn_readlane((int)it_soff, e);
+    const uint32_t bm2 = (misc >> 24) & 3u;
+    // (the three bases pass through an empty statement right before the choice: as plain captured variables they
+    // sit next to each other in the closure, and the choice by width becomes an indexed load from it in scratch)
+    uint64_t b2 = s2b, b3 = s3b, b4 = s4b;
+    asm volatile("" : "+s"(b2), "+s"(b3), "+s"(b4));
+    const uint64_t wbase = (bm2 == 0 ? b2 : bm2 == 1 ? b3 : b4) + woff;
+    const uint64_t wlanes = bm2 == 0 ? 0xFFFFFFFFull : bm2 == 1 ? 0xFFFFFFFFFFFFull : ~0ull;
+    const uint32_t slot = ring_off + (uint32_t)s * kSlotBytes;
+    lds_copy_b32_vaddr(par_vbase + soff, slot, 0xFFFFFFFFull);
+    lds_copy_b128(wbase, data_voff, slot + kGemvSlotParamBytes, wlanes);
   };
+  constexpr int kCopiesPerItem = 2;
 
   // ---- prologue: fill the ring.  The first kEarly items of every wavefront go out now and start the stream;
   // the rest of the ring follows after the activations are in place: filling a whole ring takes about a
@@ -333,61 +395,146 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
   half8 a[4];
 #pragma unroll
   for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = half8{0, 0, 0, 0, 0, 0, 0, 0};
-  // One fp32 sum per slab of this workgroup, kept in registers: an LDS store inside the loop would
-  // make the compiler wait for every outstanding global->LDS copy (it cannot tell them apart).
+  // One fp32 sum per slab of this workgroup, kept in registers.
   // (a vector type: the write of element j at the end of a slab becomes one indexed register move; a switch over
   // 16 scalars became a ladder of some 40 branches and moves that ran after every second item when K = 4096)
   static_assert(kGemvMaxSlabs == 16, "per-slab sums are held in a 16-element vector");
   floatx16v accs;
 #pragma unroll
   for (int q = 0; q < kGemvMaxSlabs; ++q) accs[q] = 0.f;
-  float acc = 0.f;
+  // running sums of the current slab: scale * (code sum, in units of 2^-24) and zero * (activation sum)
+  float acc_q = 0.f, acc_z = 0.f;
 
-  auto consume = [&](int e, int s) {
+  // The loop is bound by the number of vector instructions per item (measured: the vector ALU is busy for most
+  // of it and the time follows the instruction count), so everything that can be is kept off the vector ALU:
+  // addresses are scalar plus a loop-invariant lane offset, the tile-column sums sit in one register (lane i:
+  // this wavefront's i-th tile column) and reach a scalar register by v_readlane, the two parameters are
+  // brought together by one byte permute and widened inside the fused multiply-adds.
+  float sx_lane = 0.f;
+  if (lane < my_cnt) sx_lane = Sx[wave + NW * lane];
+  uint32_t lane_w2 = kGemvSlotParamBytes + lane * 8, lane_w3 = kGemvSlotParamBytes + lane * 12,
+           lane_w4 = kGemvSlotParamBytes + lane * 16, lane_p = (lane & 15) * 4;
+  asm volatile("" : "+v"(lane_w2), "+v"(lane_w3), "+v"(lane_w4), "+v"(lane_p), "+v"(sx_lane));
+  const unsigned char* lds0 = lds_raw - (uint32_t)(uintptr_t)(lptr_t)lds_raw;  // LDS byte 0
+
+#ifdef SFMP_XMODE
+  const int xmode = __builtin_amdgcn_readfirstlane(g_mode);
+#endif
+  auto consume = [&](int e, int s) __attribute__((always_inline)) {
     const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
     const int tc = misc & 0xFFFF;
-    const unsigned char* slot = ring + s * kSlotBytes;
+    const uint32_t slot = ring_off + (uint32_t)s * kSlotBytes;
+#ifdef SFMP_XMODE
+    if (xmode == 1) return;
+    if (xmode == 2) {
+      const uint32_t* src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w4));
+      acc_q += __uint_as_float(src[0] ^ src[1] ^ src[2] ^ src[3]);
+      return;
+    }
+#endif
     if ((lane & 15) == 0) {  // only activation row 0 exists: lanes 0,16,32,48 feed it
 #pragma unroll
       for (int kappa = 0; kappa < 4; ++kappa)
         a[kappa] = *reinterpret_cast<const half8*>(Xs + tc * kTile + 32 * kappa + 8 * (lane / 16));
     }
-    const float sx = Sx[tc];
+    const float sx = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sx_lane), tc / NW));
+    const uint32_t scw = *reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_p));
+    const uint32_t zrw = *reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_p) + 64);
     float t;
+    uint32_t w[4];
+    const uint32_t* src;
     switch ((misc >> 24) & 3) {
-      case 0: t = gemv_item<2>(slot, lane, a); break;
-      case 1: t = gemv_item<3>(slot, lane, a); break;
-      default: t = gemv_item<4>(slot, lane, a); break;
+      case 0:
+        src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w2));
+        w[0] = src[0], w[1] = src[1];
+        t = slab_dot_row0_units<2>(w, a);
+        break;
+      case 1:
+        src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w3));
+        w[0] = src[0], w[1] = src[1], w[2] = src[2];
+        t = slab_dot_row0_units<3>(w, a);
+        break;
+      default:
+        src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w4));
+        w[0] = src[0], w[1] = src[1], w[2] = src[2], w[3] = src[3];
+        t = slab_dot_row0_units<4>(w, a);
+        break;
     }
-    const uint32_t scw = *reinterpret_cast<const uint32_t*>(slot + 1024 + (lane & 15) * 4);
-    const uint32_t zrw = *reinterpret_cast<const uint32_t*>(slot + 1088 + (lane & 15) * 4);
-    float sf, zf;
-    params_to_float(scw, zrw, (misc >> 22) & 16u, p.bf16 != 0, sf, zf);  // bit 26 of misc: odd sigma -> high half
-    acc += sf * t + zf * sx;
+    // low half: scale, high half: zero (bit 26 of misc: odd sigma -> the high halves of the two dwords)
+    const uint32_t sel = (misc & (1u << 26)) ? 0x07060302u : 0x05040100u;
+    const uint32_t sz = __builtin_amdgcn_perm(zrw, scw, sel);
+    if (p.bf16) {
+      asm volatile("; bfloat16 parameters");
+      acc_q += __uint_as_float(sz << 16) * t;
+      acc_z += __uint_as_float(sz & 0xFFFF0000u) * sx;
+    } else {
+      // fp32 multiply-adds that read their first factor as fp16 from the low / high half of sz
+      asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "+v"(acc_q) : "v"(sz), "v"(t));
+      asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(acc_z) : "v"(sz), "s"(sx));
+    }
     if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
       asm volatile("" ::: "memory");  // keeps this a branch: as a select it copied all 16 sums after every item
-      accs[(misc >> 17) & 15] = acc;
-      acc = 0.f;
+      accs[(misc >> 17) & 15] = acc_q * 16777216.f + acc_z;
+      acc_q = 0.f, acc_z = 0.f;
     }
   };
 
+#ifdef SFMP_XMODE
+  if (xmode == 3) {  // streaming experiment: weights only, one copy per item, nothing consumed
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    auto issue_w = [&](int e, int s) __attribute__((always_inline)) {
+      const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
+      const uint32_t woff = (uint32_t)__builtin_amdgcn_readlane((int)it_woff, e);
+      const uint32_t bm2 = (misc >> 24) & 3u;
+      uint64_t b2 = s2b, b3 = s3b, b4 = s4b;
+      asm volatile("" : "+s"(b2), "+s"(b3), "+s"(b4));
+      const uint64_t wbase = (bm2 == 0 ? b2 : bm2 == 1 ? b3 : b4) + woff;
+      const uint64_t wlanes = bm2 == 0 ? 0xFFFFFFFFull : bm2 == 1 ? 0xFFFFFFFFFFFFull : ~0ull;
+      lds_copy_b128(wbase, data_voff, ring_off + (uint32_t)s * kSlotBytes + kGemvSlotParamBytes, wlanes);
+    };
+    for (int e = 0; e < npro; ++e) issue_w(e, e);
+    int s = 0;
+    for (int e = 0; e + S < E; ++e) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(S - 1) : "memory");
+      issue_w(e + S, s);
+      if (++s == S) s = 0;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    return;
+  }
+#endif
   // ---- steady state: item e has landed once at most the S-1 younger items (2 copies each) are
   // outstanding; consume it and refill its slot with item e + S
   int s = 0;
   int e = 0;
   for (; e + S < E; ++e) {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (S - 1)) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * (S - 1)) : "memory");
     consume(e, s);
     issue_item(e + S, s);
     if (++s == S) s = 0;
   }
-  // ---- tail: nothing left to issue
+  // ---- tail: nothing left to issue; item e has landed once at most the E-1-e younger items are outstanding
+  // (most launches of a decoder layer have no more than S items per wavefront and are all tail: waiting for
+  // everything first would put the whole arithmetic behind the whole transfer)
   SFMP_STAMP(5);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   for (; e < E; ++e) {
+#ifdef SFMP_VB
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+    switch (E - 1 - e) {
+      case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+      case 1: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * 1) : "memory"); break;
+      case 2: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * 2) : "memory"); break;
+      case 3: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * 3) : "memory"); break;
+      case 4: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * 4) : "memory"); break;
+      case 5: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * 5) : "memory"); break;
+      case 6: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * 6) : "memory"); break;
+      default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * 7) : "memory"); break;
+    }
     consume(e, s);
     if (++s == S) s = 0;
   }
+  static_assert(S <= 8 && kCopiesPerItem * 7 < 64, "the tail's waits cover up to 7 younger items");
   SFMP_STAMP(6);
 #ifdef SFMP_EXPERIMENT
   if (lane == 0) g_wave_done[blockIdx.x * 16 + wave] = wall_clock64();
@@ -547,7 +694,7 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
       (int64_t)(lane & 15) * 16 + (lane < 16 ? (int64_t)0 : (int64_t)((const char*)p.zeros - (const char*)p.scales));
 
   unsigned char* ring = rings + (size_t)wave * S * kSlot;
-  auto issue_item = [&](int e, int s) {
+  auto issue_item = [&](int e, int s) __attribute__((always_inline)) {
     const uint64_t a = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_ahi, e) << 32) |
                        (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_alo, e);
     const uint64_t sa = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_shi, e) << 32) |
@@ -624,7 +771,7 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   for (int q = 0; q < kGemvMaxSlabs; ++q) accs0[q] = 0.f, accs1[q] = 0.f, accs2[q] = 0.f, accs3[q] = 0.f;
   floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 
-  auto consume = [&](int e, int s) {
+  auto consume = [&](int e, int s) __attribute__((always_inline)) {
     const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
     const unsigned char* slot = ring + s * kSlot;
     if (MB == 16 || i16 < MB) {
@@ -1221,6 +1368,7 @@ int launch_decode(const GemmArgs& a, void* stream) {
 extern "C" int sfmp_debug_stamps(unsigned long long* host_out) {
   return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(sfmp::g_stamps), sizeof(unsigned long long) * 256 * 8);
 }
+extern "C" int sfmp_debug_mode(int m) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(sfmp::g_mode), &m, sizeof(int)); }
 extern "C" int sfmp_debug_wave_done(unsigned long long* host_out) {
   return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(sfmp::g_wave_done), sizeof(unsigned long long) * 256 * 16);
 }
