@@ -133,8 +133,12 @@ struct GemvParams {
 
 constexpr int kGemvWaves = 16;       // wavefronts per workgroup; one workgroup per CU
 constexpr int kGemvMaxGrid = 256;    // persistent grid: at most one workgroup per CU
-constexpr int kGemvMaxSlots = 8;     // ring slots per wavefront (compile-time variants 4..8)
-constexpr int kGemvMinSlots = 4;
+// Ring slots per wavefront.  Two: one item being consumed, one on its way.  The 4096 wavefronts of a launch are
+// what keeps the memory system busy; deeper rings (up to 8 were tried, all that LDS allows) were measured slower by
+// up to 14 %: every wavefront then requests its whole share at once, the data comes back wavefront by wavefront,
+// and the arithmetic of the wavefronts served last starts when the transfer is nearly over.
+constexpr int kGemvMaxSlots = 2;
+constexpr int kGemvMinSlots = 2;
 constexpr int kGemvMaxSlabs = 16;    // slabs per workgroup kept in register accumulators
 constexpr int kGemvMaxItems = 64;    // items per wavefront: one lane of the item registers each
 constexpr int kSlotBytes = 1024 + 128;  // slab bytes (<= 1 KiB) + 16 scale dwords + 16 zero dwords
@@ -443,6 +447,29 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
     float t;
     uint32_t w[4];
     const uint32_t* src;
+#ifdef SFMP_XMODE
+    if (xmode == 5 || xmode == 6) {
+      src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w4));
+      w[0] = src[0], w[1] = src[1], w[2] = src[2], w[3] = src[3];
+      if (xmode == 5) {  // unpack, no matrix instructions
+        uint32_t op[4][4];
+        unpack_slab<4>(w, op);
+        uint32_t x = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) x ^= op[i][j];
+        t = __uint_as_float(x) + (float)a[0][0] + (float)a[1][0] + (float)a[2][0] + (float)a[3][0];
+      } else {  // matrix instructions, no unpack
+        floatx4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = c0;
+        c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[0], as_half8(w), c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[1], as_half8(w), c1, 0, 0, 0);
+        c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[2], as_half8(w), c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[3], as_half8(w), c1, 0, 0, 0);
+        t = c0[0] + c1[0] * 0.0625f;
+      }
+    } else
+#endif
     switch ((misc >> 24) & 3) {
       case 0:
         src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w2));
@@ -937,6 +964,9 @@ static GemvFit gemv_fit(int32_t N, int32_t K, int32_t grid) {
   const int64_t fixed = gemv_fixed_lds_bytes(K, f.max_slabs);
   int64_t slots = (160 * 1024 - fixed) / ((int64_t)kGemvWaves * kSlotBytes);
   if (slots > kGemvMaxSlots) slots = kGemvMaxSlots;
+#ifdef SFMP_EXPERIMENT
+  if (const char* v = getenv("SFMP_SLOTS")) { if (atoi(v) < slots) slots = atoi(v); }
+#endif
   const int64_t ring_bytes = slots * kGemvWaves * kSlotBytes;
   const int64_t items = (int64_t)f.max_slabs * ((ntc + kGemvWaves - 1) / kGemvWaves);
   f.ok = grid >= 8 && grid % 8 == 0 && grid <= nslab && slots >= kGemvMinSlots && f.max_slabs <= kGemvMaxSlabs &&
@@ -1057,11 +1087,9 @@ static int launch_gemv_variant(int slots, bool batched, const KernelArg& arg, un
       return SFMP_ERR_HIP;                                                                                     \
     }                                                                                                          \
   } break;
+    SFMP_GEMV_CASE(2)
+    SFMP_GEMV_CASE(3)
     SFMP_GEMV_CASE(4)
-    SFMP_GEMV_CASE(5)
-    SFMP_GEMV_CASE(6)
-    SFMP_GEMV_CASE(7)
-    SFMP_GEMV_CASE(8)
 #undef SFMP_GEMV_CASE
     default: return SFMP_ERR_SHAPE;
   }
