@@ -20,6 +20,7 @@
 // Skinny GEMM (2..16), and any M = 1 problem whose activation vector does not fit in LDS beside the
 // rings: the same scheme with the activations of each tile column travelling through the ring slots
 // (see rskinny_kernel).
+#include <algorithm>
 #include <cstdlib>
 
 #include "sfmp_device.h"
@@ -43,6 +44,25 @@ __device__ __forceinline__ floatx4 slab_dot(const uint32_t* w, const half8 (&a)[
   floatx4 t = c[0] * pow2f(24 - class_pos<B>(0));
 #pragma unroll
   for (int i = 1; i < num_classes<B>(); ++i) t += c[i] * pow2f(24 - class_pos<B>(i));
+  return t;
+}
+
+// The same sums in units of 2^-24 (class 0 counts 1, class i counts 2^-pos(i)): the caller multiplies by 2^24
+// once per slab instead of once per item.
+template <int B>
+__device__ __forceinline__ floatx4 slab_dot_units(const uint32_t* w, const half8 (&a)[4]) {
+  uint32_t op[4][4];
+  unpack_slab<B>(w, op);
+  floatx4 c[num_classes<B>()];
+#pragma unroll
+  for (int i = 0; i < num_classes<B>(); ++i) c[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kappa = 0; kappa < 4; ++kappa)
+    c[step_class<B>(kappa)] =
+        __builtin_amdgcn_mfma_f32_16x16x32_f16(a[kappa], as_half8(op[kappa]), c[step_class<B>(kappa)], 0, 0, 0);
+  floatx4 t = c[0];
+#pragma unroll
+  for (int i = 1; i < num_classes<B>(); ++i) t += c[i] * pow2f(-class_pos<B>(i));
   return t;
 }
 
@@ -146,12 +166,12 @@ constexpr int kGemvSlotParamBytes = 128;  // GEMV slots: [16 scale dwords | 16 z
 
 typedef float floatx16v __attribute__((ext_vector_type(16)));
 #ifdef SFMP_EXPERIMENT
-__device__ unsigned long long g_stamps[256 * 8];
-__device__ unsigned long long g_wave_done[256 * 16];
+__device__ unsigned long long g_stamps[1024 * 8];
+__device__ unsigned long long g_wave_done[1024 * 16];
 __device__ int g_mode;
 #define SFMP_STAMP(k)                                                        \
   do {                                                                       \
-    if (threadIdx.x == 0) g_stamps[blockIdx.x * 8 + (k)] = wall_clock64();   \
+    if (threadIdx.x == 0 && blockIdx.x < 1024) g_stamps[blockIdx.x * 8 + (k)] = wall_clock64(); \
   } while (0)
 #else
 #define SFMP_STAMP(k)
@@ -545,9 +565,6 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
   // everything first would put the whole arithmetic behind the whole transfer)
   SFMP_STAMP(5);
   for (; e < E; ++e) {
-#ifdef SFMP_VB
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
     switch (E - 1 - e) {
       case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
       case 1: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * 1) : "memory"); break;
@@ -564,7 +581,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
   static_assert(S <= 8 && kCopiesPerItem * 7 < 64, "the tail's waits cover up to 7 younger items");
   SFMP_STAMP(6);
 #ifdef SFMP_EXPERIMENT
-  if (lane == 0) g_wave_done[blockIdx.x * 16 + wave] = wall_clock64();
+  if (lane == 0 && blockIdx.x < 1024) g_wave_done[blockIdx.x * 16 + wave] = wall_clock64();
 #endif
 
   if (lane < 16) {
@@ -670,19 +687,29 @@ __global__ __launch_bounds__(MB * 16) void stage_rows_kernel(const _Float16* __r
 
 template <int MB>
 constexpr int rskinny_slot_bytes() { return kSlotBytes + MB * 256; }
+// resident variant: bytes of the raw copy of the activations in LDS
+__host__ __device__ inline size_t rskinny_raw_bytes(int32_t M, int32_t K) { return ((size_t)M * K * 2 + 15) & ~(size_t)15; }
 
 // RES (resident): when MB x K fp16 fit in LDS beside the rings, every workgroup stages the activations itself,
 // exactly as the GEMV kernel does (raw copy into the idle rings, permute inside LDS) into the same per-tile-column
 // swizzled layout; there is then no staging kernel and an item brings only its slab and parameters.
-template <int NW, int S, int MB, bool RES>
+// ACC: slabs per workgroup whose finished sums are held in registers (4, 8 or 16; 4 x ACC registers).  With 16
+// the kernel needs about 130 vector registers and runs 8 wavefronts per CU; with 4 or 8 it stays below 128 and runs
+// 16, which is what covers the latencies of its loop.
+template <int NW, int S, int MB, bool RES, int ACC>
 __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int bid, const int G, unsigned char* lds_raw) {
   constexpr int NT = NW * 64;
   constexpr int kSlot = RES ? kSlotBytes : rskinny_slot_bytes<MB>();
   constexpr int kCopies = RES ? 2 : 2 + MB / 4;  // direct copies per item: slab, scales+zeros, MB/4 x 1 KiB of activations
-  // LDS: red [max_slabs][4][64] f32 | (Xs [ntc][MB][256 B]) | rings [NW][S][kSlot]
+  constexpr int kRedGroups = NW / 4;  // the final sum over the wavefronts is taken in groups of four
+  // LDS: red [NW/4][max_slabs][4][64] f32 | (Xs [ntc][MB][256 B] | SxL | raw activations [M][K] fp16) |
+  //      rings [NW][S][kSlot]
   float* red = reinterpret_cast<float*>(lds_raw);
-  unsigned char* Xs = lds_raw + (size_t)p.max_slabs * 1024;
-  unsigned char* rings = Xs + (RES ? (size_t)p.ntc * (MB * 256) : (size_t)0);
+  unsigned char* Xs = lds_raw + (size_t)p.max_slabs * 1024 * kRedGroups;
+  // (resident) SxL [ntc][4 lane groups][4] f32: the sums of the activations of rows 4g..4g+3 over a tile column
+  float* SxL = reinterpret_cast<float*>(Xs + (RES ? (size_t)p.ntc * (MB * 256) : (size_t)0));
+  unsigned char* raw_region = reinterpret_cast<unsigned char*>(SxL) + (RES ? (size_t)p.ntc * 64 : (size_t)0);
+  unsigned char* rings = raw_region + (RES ? rskinny_raw_bytes(p.M, p.K) : (size_t)0);
 
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
@@ -693,7 +720,9 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   const int my_cnt = p.ntc > wave ? (p.ntc - wave + NW - 1) / NW : 0;
   const int E = nj * my_cnt;  // items of this wavefront, handled in batches of 64 (one lane describes one item)
 
-  uint32_t it_alo = 0, it_ahi = 0, it_slo = 0, it_shi = 0, it_misc = 0;
+  // per-item registers of lane e: 32-bit offsets of the slab inside its stream and of the parameter dwords inside
+  // the scale / zero arrays, and the item's flags (as in the GEMV kernel)
+  uint32_t it_woff = 0, it_soff = 0, it_misc = 0;
   auto describe = [&](int e0, int Eb) {
     if (lane < Eb) {
       const int ge = e0 + lane;
@@ -702,53 +731,51 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
       const int slab = (v % 8) * p.ntr + v / 8;
       const int tr = slab / 8, sigma = slab % 8;
       const int tc = wave + NW * i;
-      const int32_t d = p.tile_desc[(int64_t)tr * p.ntc + tc];
-      const int bm2 = d & 3;
-      const uint8_t* base = bm2 == 0 ? p.s2 : bm2 == 1 ? p.s3 : p.s4;
-      const int64_t slab_bytes = 256 * (bm2 + 2);
-      const uint64_t a = (uint64_t)(base + (int64_t)(d >> 2) * (8 * slab_bytes) + sigma * slab_bytes);
-      const uint64_t sa = (uint64_t)(p.scales + (int64_t)(tc >> p.gshift) * p.N + (int64_t)tr * kTile + (sigma & ~1));
-      it_alo = (uint32_t)a;
-      it_ahi = (uint32_t)(a >> 32);
-      it_slo = (uint32_t)sa;
-      it_shi = (uint32_t)(sa >> 32);
-      it_misc = (uint32_t)tc | ((i == my_cnt - 1) ? 0x10000u : 0u) | ((uint32_t)j << 17) | ((uint32_t)bm2 << 24) |
+      const uint32_t d = (uint32_t)p.tile_desc[(int64_t)tr * p.ntc + tc];
+      const uint32_t bm2 = d & 3u;
+      const uint32_t slab_bytes = 256u * (bm2 + 2u);
+      it_woff = (d >> 2) * (8u * slab_bytes) + (uint32_t)sigma * slab_bytes;
+      it_soff = 2u * (uint32_t)((tc >> p.gshift) * p.N + tr * kTile + (sigma & ~1));
+      it_misc = (uint32_t)tc | ((i == my_cnt - 1) ? 0x10000u : 0u) | ((uint32_t)j << 17) | (bm2 << 24) |
                 ((uint32_t)(sigma & 1) << 26);
     }
   };
   const uint32_t data_voff = lane * 16;
-  const int64_t sz_voff =
-      (int64_t)(lane & 15) * 16 + (lane < 16 ? (int64_t)0 : (int64_t)((const char*)p.zeros - (const char*)p.scales));
+  const uint64_t par_vbase = (lane < 16 ? (uint64_t)p.scales : (uint64_t)p.zeros) + (uint64_t)((lane & 15) * 16);
 
-  unsigned char* ring = rings + (size_t)wave * S * kSlot;
+  // Issue item e into ring slot s: the slab (scalar address, 32/48/64 lanes), the 16 scale + 16 zero dwords, and
+  // without resident activations MB/4 KiB of staged activations of the item's tile column (scalar address)
+  const uint32_t ring_off = (uint32_t)(uintptr_t)(lptr_t)(rings + (size_t)wave * S * kSlot);
+  const unsigned char* ring = rings + (size_t)wave * S * kSlot;
+  const uint64_t s2b = (uint64_t)p.s2, s3b = (uint64_t)p.s3, s4b = (uint64_t)p.s4, xb = (uint64_t)p.xblk;
   auto issue_item = [&](int e, int s) __attribute__((always_inline)) {
-    const uint64_t a = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_ahi, e) << 32) |
-                       (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_alo, e);
-    const uint64_t sa = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_shi, e) << 32) |
-                        (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)it_slo, e);
     const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
-    const uint32_t slab_bytes = 256u * (((misc >> 24) & 3u) + 2u);
-    unsigned char* slot = ring + s * kSlot;
-    if (data_voff < slab_bytes)
-      __builtin_amdgcn_global_load_lds((gptr_t)((const char*)a + data_voff), (lptr_t)slot, 16, 0, 0);
-    if (lane < 32) __builtin_amdgcn_global_load_lds((gptr_t)((const char*)sa + sz_voff), (lptr_t)(slot + 1024), 4, 0, 0);
+    const uint32_t woff = (uint32_t)__builtin_amdgcn_readlane((int)it_woff, e);
+    const uint32_t soff = (uint32_t)__builtin_amdgcn_readlane((int)it_soff, e);
+    const uint32_t bm2 = (misc >> 24) & 3u;
+    uint64_t b2 = s2b, b3 = s3b, b4 = s4b;  // (see the GEMV kernel: keeps the choice out of scratch memory)
+    asm volatile("" : "+s"(b2), "+s"(b3), "+s"(b4));
+    const uint64_t wbase = (bm2 == 0 ? b2 : bm2 == 1 ? b3 : b4) + woff;
+    const uint64_t wlanes = bm2 == 0 ? 0xFFFFFFFFull : bm2 == 1 ? 0xFFFFFFFFFFFFull : ~0ull;
+    const uint32_t slot = ring_off + (uint32_t)s * kSlot;
+    lds_copy_b128(wbase, data_voff, slot, wlanes);
+    lds_copy_b32_vaddr(par_vbase + soff, slot + 1024, 0xFFFFFFFFull);
     if constexpr (!RES) {
-      const unsigned char* xsrc = p.xblk + (int64_t)(misc & 0xFFFF) * (MB * 256) + data_voff;
+      const uint64_t xsrc = xb + (uint64_t)(misc & 0xFFFF) * (MB * 256);
 #pragma unroll
-      for (int c = 0; c < MB / 4; ++c)
-        __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + c * 1024), (lptr_t)(slot + kSlotBytes + c * 1024), 16, 0, 0);
+      for (int c = 0; c < MB / 4; ++c) lds_copy_b128(xsrc + c * 1024, data_voff, slot + kSlotBytes + c * 1024, ~0ull);
     }
   };
 
   if constexpr (RES) {
-    // stage the activations: direct copies of the M rows into the (still idle) ring memory, 1 KiB per wavefront
+    // stage the activations: direct copies of the M rows into their own LDS region, 1 KiB per wavefront
     // and copy, all in flight together; then permute inside LDS.  One thread serves one (tile column, unit of 8
     // columns) for every row: the permutation entries are the same for all rows.
-    _Float16* Xraw = reinterpret_cast<_Float16*>(rings);
+    _Float16* Xraw = reinterpret_cast<_Float16*>(raw_region);
     const int raw_bytes = p.M * p.K * 2;
     for (int c = wave * 1024; c < raw_bytes; c += NW * 1024)
       if (c + (int)data_voff < raw_bytes)
-        __builtin_amdgcn_global_load_lds((gptr_t)((const char*)p.X + c + data_voff), (lptr_t)(rings + c), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)((const char*)p.X + c + data_voff), (lptr_t)(raw_region + c), 16, 0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     for (int u = tid; u < p.ntc * 16; u += NT) {
@@ -759,6 +786,8 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
         c0 = reinterpret_cast<const int4*>(p.col_perm + k0)[0];
         c1 = reinterpret_cast<const int4*>(p.col_perm + k0)[1];
       }
+      static_assert(MB == 4, "the resident variant keeps one group of four activation rows");
+      floatx4 sums;
 #pragma unroll
       for (int m = 0; m < MB; ++m) {
         half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -774,9 +803,12 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
           v[7] = row[c1.w];
         }
         *reinterpret_cast<half8*>(Xs + ((size_t)tc * MB + m) * 256 + ((unit ^ m) * 16)) = v;
+        sums[m] = unit_group_sum(v);  // over the 16 units of the tile column (16 consecutive lanes)
       }
+      // rows 0-3 belong to lane group 0 of the product; the groups of rows 4-15 (not present) read zeros
+      if (unit < 4) *reinterpret_cast<floatx4*>(SxL + tc * 16 + unit * 4) = unit == 0 ? sums : floatx4{0.f, 0.f, 0.f, 0.f};
     }
-    __syncthreads();  // Xs is complete, the raw copy is dead: the rings may be filled
+    __syncthreads();  // Xs is complete
   }
 
   half8 ones;
@@ -792,11 +824,13 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
     a_off[kappa] = (RES ? 0 : kSlotBytes) + i16 * 256 + (((4 * kappa + kb) ^ i16) * 16);
 
   // finished sums: accs[r][q] = output element r of this lane for slab q (register-indexed writes, no switch)
-  static_assert(kGemvMaxSlabs == 16, "the finished sums live in 16-wide register vectors");
-  floatx16v accs0, accs1, accs2, accs3;  // four named vectors: an array of them went to scratch memory
+  static_assert(ACC == 4 || ACC == 8 || ACC == 16, "the finished sums live in 4-, 8- or 16-wide register vectors");
+  typedef float accv __attribute__((ext_vector_type(ACC)));
+  accv accs0, accs1, accs2, accs3;  // four named vectors: an array of them went to scratch memory
 #pragma unroll
-  for (int q = 0; q < kGemvMaxSlabs; ++q) accs0[q] = 0.f, accs1[q] = 0.f, accs2[q] = 0.f, accs3[q] = 0.f;
-  floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int q = 0; q < ACC; ++q) accs0[q] = 0.f, accs1[q] = 0.f, accs2[q] = 0.f, accs3[q] = 0.f;
+  // running sums of the current slab: scale * (code sums, in units of 2^-24) and zero * (activation sums)
+  floatx4 acc_q = {0.f, 0.f, 0.f, 0.f}, acc_z = {0.f, 0.f, 0.f, 0.f};
 
   auto consume = [&](int e, int s) __attribute__((always_inline)) {
     const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
@@ -806,9 +840,14 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
 #pragma unroll
       for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = *reinterpret_cast<const half8*>(abase + a_off[kappa]);
     }
-    floatx4 sx = {0.f, 0.f, 0.f, 0.f};
+    floatx4 sx;
+    if constexpr (RES) {
+      sx = *reinterpret_cast<const floatx4*>(SxL + (misc & 0xFFFF) * 16 + kb * 4);
+    } else {
+      sx = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kappa = 0; kappa < 4; ++kappa) sx = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[kappa], ones, sx, 0, 0, 0);
+      for (int kappa = 0; kappa < 4; ++kappa) sx = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[kappa], ones, sx, 0, 0, 0);
+    }
     floatx4 t;
     {
       uint32_t w[4];
@@ -817,17 +856,17 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
         case 0:
           src = reinterpret_cast<const uint32_t*>(slot + lane * 8);
           w[0] = src[0], w[1] = src[1];
-          t = slab_dot<2>(w, a);
+          t = slab_dot_units<2>(w, a);
           break;
         case 1:
           src = reinterpret_cast<const uint32_t*>(slot + lane * 12);
           w[0] = src[0], w[1] = src[1], w[2] = src[2];
-          t = slab_dot<3>(w, a);
+          t = slab_dot_units<3>(w, a);
           break;
         default:
           src = reinterpret_cast<const uint32_t*>(slot + lane * 16);
           w[0] = src[0], w[1] = src[1], w[2] = src[2], w[3] = src[3];
-          t = slab_dot<4>(w, a);
+          t = slab_dot_units<4>(w, a);
           break;
       }
     }
@@ -835,12 +874,14 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
     const uint32_t zrw = *reinterpret_cast<const uint32_t*>(slot + 1088 + (lane & 15) * 4);
     float sf, zf;
     params_to_float(scw, zrw, (misc >> 22) & 16u, p.bf16 != 0, sf, zf);  // bit 26 of misc: odd sigma -> high half
-    acc += sf * t + zf * sx;
+    acc_q += sf * t;
+    acc_z += zf * sx;
     if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
       asm volatile("" ::: "memory");  // keeps this a branch rather than a select over all the sums
-      const int q = (misc >> 17) & 15;
+      const int q = (misc >> 17) & (ACC - 1);
+      const floatx4 acc = acc_q * 16777216.f + acc_z;
       accs0[q] = acc[0], accs1[q] = acc[1], accs2[q] = acc[2], accs3[q] = acc[3];
-      acc = floatx4{0.f, 0.f, 0.f, 0.f};
+      acc_q = floatx4{0.f, 0.f, 0.f, 0.f}, acc_z = floatx4{0.f, 0.f, 0.f, 0.f};
     }
   };
 
@@ -857,47 +898,65 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
       issue_item(e + S, s);
       if (++s == S) s = 0;
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // tail: item e has landed once at most the Eb-1-e younger items are outstanding
     for (; e < Eb; ++e) {
+      switch (Eb - 1 - e) {
+        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+        case 1: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies * 1) : "memory"); break;
+        case 2: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies * 2) : "memory"); break;
+        case 3: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies * 3) : "memory"); break;
+        case 4: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies * 4) : "memory"); break;
+        case 5: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies * 5) : "memory"); break;
+        case 6: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies * 6) : "memory"); break;
+        default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies * 7) : "memory"); break;
+      }
       consume(e, s);
       if (++s == S) s = 0;
     }
   }
+  static_assert(S <= 8 && kCopies * 7 < 64, "the tail's waits cover up to 7 younger items");
 
-  // the wavefronts add their sums one after the other: a fixed order, so results repeat bit for bit
-  for (int w = 0; w < NW; ++w) {
-    if (wave == w) {
+  // The wavefronts add their sums in a fixed order, so results repeat bit for bit: inside each group of four
+  // (wavefronts 4g..4g+3) one after the other into the group's buffer, then the groups in turn at the output.
+  {
+    float* mine = red + (size_t)(wave / 4) * p.max_slabs * 256;
+    for (int w = 0; w < 4; ++w) {
+      if (wave % 4 == w) {
 #pragma unroll
-      for (int q = 0; q < kGemvMaxSlabs; ++q)
-        if (q < nj) {
-          const float fin[4] = {accs0[q], accs1[q], accs2[q], accs3[q]};
+        for (int q = 0; q < ACC; ++q)
+          if (q < nj) {
+            const float fin[4] = {accs0[q], accs1[q], accs2[q], accs3[q]};
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            float* dst = red + (q * 4 + r) * 64 + lane;
-            *dst = (w == 0 ? 0.f : *dst) + fin[r];
+            for (int r = 0; r < 4; ++r) {
+              float* dst = mine + (q * 4 + r) * 64 + lane;
+              *dst = (w == 0 ? 0.f : *dst) + fin[r];
+            }
           }
-        }
+      }
+      __syncthreads();
     }
-    __syncthreads();
   }
   for (int o = tid; o < nj * 256; o += NT) {
     const int jj = o / 256, rem = o % 256;
     const int r = rem / 64, l = rem % 64;
     const int m = 4 * (l / 16) + r;
     if (m < p.M) {
+      float sum = red[o];
+#pragma unroll
+      for (int g = 1; g < kRedGroups; ++g) sum += red[(size_t)g * p.max_slabs * 256 + o];
       const int v = bid + G * jj;
       const int slab = (v % 8) * p.ntr + v / 8;
       const int64_t row = (int64_t)(slab / 8) * kTile + 8 * (l % 16) + (slab % 8);
       const int64_t col = p.row_perm ? p.row_perm[row] : row;
-      p.Y[(int64_t)m * p.N + col] = (_Float16)red[o];
+      p.Y[(int64_t)m * p.N + col] = (_Float16)sum;
     }
   }
 }
 
-template <int NW, int S, int MB, bool RES>
+template <int NW, int S, int MB, bool RES, int ACC>
 __global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  rskinny_body<NW, S, MB, RES>(p, (int)blockIdx.x, (int)gridDim.x, lds_raw);
+  rskinny_body<NW, S, MB, RES, ACC>(p, (int)blockIdx.x, (int)gridDim.x, lds_raw);
 }
 
 // Several independent problems with the same M in one launch (q, k and v, or gate and up of a decoder
@@ -908,12 +967,12 @@ struct RSkinnyBatch {
   int32_t count;
 };
 
-template <int NW, int S, int MB, bool RES>
+template <int NW, int S, int MB, bool RES, int ACC>
 __global__ __launch_bounds__(NW * 64) void rskinny_batched_kernel(const RSkinnyBatch b) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   int i = 0;
   while (i + 1 < b.count && (int)blockIdx.x >= b.first[i + 1]) ++i;
-  rskinny_body<NW, S, MB, RES>(b.p[i], (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
+  rskinny_body<NW, S, MB, RES, ACC>(b.p[i], (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
 }
 
 // Staging for a batch: job j (one per distinct activation matrix) owns workgroups [first[j], first[j+1]).
@@ -976,26 +1035,47 @@ static GemvFit gemv_fit(int32_t N, int32_t K, int32_t grid) {
   return f;
 }
 
-// ring-skinny variants: activation rows padded to MB, NW wavefronts, S ring slots
-struct RSkinnyShape {
-  int32_t mb, nw, slots;
+// ring-skinny variants: activation rows padded to MB, NW wavefronts, S ring slots, ACC slabs per workgroup in
+// registers, activations resident in LDS or travelling through the rings
+struct RSkinnyConfig {
+  int32_t mb, nw, slots, acc;
+  bool resident;
 };
-static RSkinnyShape rskinny_shape(int32_t M) {
-  if (M <= 4) return {4, 8, 8};
-  if (M <= 8) return {8, 8, 5};
-  return {16, 8, 3};
+static int32_t rskinny_mb(int32_t M) { return M <= 4 ? 4 : M <= 8 ? 8 : 16; }
+// LDS of the ring-skinny kernel: reduction buffers, (resident: activations in operand layout, their tile-column sums,
+// their raw copy), rings
+static int64_t rskinny_lds_bytes(const RSkinnyConfig& c, int32_t max_slabs, int32_t M, int32_t K) {
+  const int64_t red = (int64_t)max_slabs * 1024 * (c.nw / 4);
+  return c.resident ? red + (int64_t)c.mb * K * 2 + (int64_t)(K / kTile) * 64 + (int64_t)rskinny_raw_bytes(M, K) +
+                          (int64_t)c.nw * c.slots * kSlotBytes
+                    : red + (int64_t)c.nw * c.slots * (kSlotBytes + c.mb * 256);
 }
 // The resident variant (activations staged into LDS by every workgroup, no staging kernel) exists for blocks of
-// 4 rows.  It is used when the reduction buffer, the activation block and the rings stay within 160 KiB and the
-// M x K activations are at most 32 KiB: measured, the saved launch outweighs 256 workgroups each permuting the
-// activations up to that size (8 to 17 % on K = 4096 with M <= 4) and no longer beyond it.
-constexpr int32_t kResidentSlots = 8;
+// 4 rows and M x K activations of at most 32 KiB: measured, the saved launch outweighs 256 workgroups each permuting
+// the activations up to that size (8 to 17 % on K = 4096 with M <= 4) and no longer beyond it.
 constexpr int64_t kResidentMaxRawBytes = 32 * 1024;
-static bool rskinny_resident_fit(int32_t M, int32_t mb, int32_t nw, int32_t K, int32_t max_slabs) {
-  if (mb != 4) return false;
-  const int64_t xs = (int64_t)mb * K * 2, ring_bytes = (int64_t)nw * kResidentSlots * kSlotBytes;
-  return (int64_t)M * K * 2 <= kResidentMaxRawBytes && xs <= ring_bytes &&
-         (int64_t)max_slabs * 1024 + xs + ring_bytes <= 160 * 1024;
+#ifndef SFMP_RS_RES
+#define SFMP_RS_RES 3
+#define SFMP_RS_MB4 3
+#define SFMP_RS_MB8 2
+#define SFMP_RS_MB16 3
+#endif
+// max_slabs: the largest number of slabs of a workgroup over the problems of the launch; K: the largest K
+static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs) {
+  RSkinnyConfig c;
+  c.mb = rskinny_mb(M);
+  // 16 wavefronts where the finished sums fit beside the rest in 128 registers and the rings in LDS
+  const bool wide = c.mb <= 8 && max_slabs <= 8;
+  c.nw = wide ? 16 : 8;
+  c.acc = !wide ? 16 : max_slabs <= 4 ? 4 : 8;
+  c.resident = false;
+  if (c.mb == 4 && (int64_t)M * K * 2 <= kResidentMaxRawBytes) {
+    c.resident = true;
+    c.slots = SFMP_RS_RES;
+    if (rskinny_lds_bytes(c, max_slabs, M, K) > 160 * 1024) c.resident = false;
+  }
+  if (!c.resident) c.slots = c.mb == 4 ? SFMP_RS_MB4 : c.mb == 8 ? SFMP_RS_MB8 : SFMP_RS_MB16;
+  return c;
 }
 
 DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
@@ -1019,22 +1099,19 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
   }
   // Everything else goes through the ring-skinny kernel: one workgroup per CU while a workgroup's share
   // stays within 16 slabs (N <= 65536), more workgroups beyond that.
-  const RSkinnyShape sh = rskinny_shape(M);
   int32_t grid = nslab < kGemvMaxGrid ? nslab : kGemvMaxGrid;
   if ((nslab + grid - 1) / grid > kGemvMaxSlabs) grid = ((nslab + kGemvMaxSlabs - 1) / kGemvMaxSlabs + 7) / 8 * 8;
   d.gemv = false;
   d.grid = grid;
   d.max_slabs = (nslab + grid - 1) / grid;
-  d.mb = sh.mb;
-  d.resident = rskinny_resident_fit(M, sh.mb, sh.nw, K, d.max_slabs);
-  if (d.resident) {
-    d.slots = kResidentSlots;
-    d.lds_bytes = d.max_slabs * 1024 + sh.mb * K * 2 + sh.nw * d.slots * kSlotBytes;
-  } else {
-    d.slots = sh.slots;
-    d.lds_bytes = d.max_slabs * 1024 + sh.nw * sh.slots * (kSlotBytes + sh.mb * 256);
-  }
-  d.workspace_bytes = round_up_256((int64_t)ntc * sh.mb * 256);
+  const RSkinnyConfig c = rskinny_config(M, K, d.max_slabs);
+  d.mb = c.mb;
+  d.nw = c.nw;
+  d.acc = c.acc;
+  d.resident = c.resident;
+  d.slots = c.slots;
+  d.lds_bytes = (int32_t)rskinny_lds_bytes(c, d.max_slabs, M, K);
+  d.workspace_bytes = round_up_256((int64_t)ntc * c.mb * 256);
   return d;
 }
 
@@ -1178,11 +1255,11 @@ static RSkinnyParams rskinny_params(const GemmArgs& a, int32_t M, const void* xb
   return p;
 }
 
-template <int NW, int S, int MB, bool RES>
+template <int NW, int S, int MB, bool RES, int ACC>
 static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* stream) {
   const sfmp_layout_t* L = a.L;
   static bool attr_set = false;
-  const void* fn = reinterpret_cast<const void*>(&rskinny_kernel<NW, S, MB, RES>);
+  const void* fn = reinterpret_cast<const void*>(&rskinny_kernel<NW, S, MB, RES, ACC>);
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) {
@@ -1206,14 +1283,20 @@ static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* 
   return after_launch("sfmp_gemm skinny launch");
 }
 
+// The compiled configurations (see rskinny_config): X(NW, S, MB, RES, ACC)
+#define SFMP_RSKINNY_CONFIGS(X)                                                                                   \
+  X(16, SFMP_RS_RES, 4, true, 4) X(16, SFMP_RS_RES, 4, true, 8) X(8, SFMP_RS_RES, 4, true, 16)                    \
+  X(16, SFMP_RS_MB4, 4, false, 4) X(16, SFMP_RS_MB4, 4, false, 8) X(8, SFMP_RS_MB4, 4, false, 16)                 \
+  X(16, SFMP_RS_MB8, 8, false, 4) X(16, SFMP_RS_MB8, 8, false, 8) X(8, SFMP_RS_MB8, 8, false, 16)                 \
+  X(8, SFMP_RS_MB16, 16, false, 16)
+
 static int launch_rskinny(const GemmArgs& a, const DecodePlan& d, void* stream) {
-  switch (d.mb) {
-    case 4:
-      return d.resident ? launch_rskinny_variant<8, kResidentSlots, 4, true>(a, d, stream)
-                        : launch_rskinny_variant<8, 8, 4, false>(a, d, stream);
-    case 8: return launch_rskinny_variant<8, 5, 8, false>(a, d, stream);
-    default: return launch_rskinny_variant<8, 3, 16, false>(a, d, stream);
-  }
+#define SFMP_X(NW_, S_, MB_, RES_, ACC_)                                                      \
+  if (d.nw == NW_ && d.mb == MB_ && d.resident == RES_ && d.acc == ACC_ && d.slots == S_)     \
+    return launch_rskinny_variant<NW_, S_, MB_, RES_, ACC_>(a, d, stream);
+  SFMP_RSKINNY_CONFIGS(SFMP_X)
+#undef SFMP_X
+  return SFMP_ERR_SHAPE;
 }
 
 // ---- batched launch for 2 <= M <= 16 ---------------------------------------------------------------
@@ -1248,10 +1331,10 @@ static BatchStagePlan plan_batch_staging(const GemmArgs* probs, int count, int32
 
 int64_t batched_workspace_bytes(const GemmArgs* probs, int count, int32_t M) {
   if (M < 2) return 0;
-  return plan_batch_staging(probs, count, rskinny_shape(M).mb).bytes;
+  return plan_batch_staging(probs, count, rskinny_mb(M)).bytes;
 }
 
-template <int NW, int S, int MB, bool RES>
+template <int NW, int S, int MB, bool RES, int ACC>
 static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int32_t M, const int32_t* g,
                                           void* workspace, void* stream) {
   const BatchStagePlan sp = plan_batch_staging(probs, count, MB);
@@ -1286,8 +1369,9 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
     const int32_t max_slabs = (nslab + g[i] - 1) / g[i];
     if (max_slabs > kGemvMaxSlabs) return SFMP_ERR_SHAPE;
     b.p[i] = rskinny_params(probs[i], probs[i].M, (const unsigned char*)workspace + sp.offset[sp.job_of[i]], max_slabs);
-    const int64_t need = RES ? (int64_t)max_slabs * 1024 + (int64_t)MB * L->K * 2 + (int64_t)NW * S * kSlotBytes
-                             : (int64_t)max_slabs * 1024 + (int64_t)NW * S * rskinny_slot_bytes<MB>();
+    const RSkinnyConfig cfg = {MB, NW, S, ACC, RES};
+    if (max_slabs > ACC) return SFMP_ERR_SHAPE;
+    const int64_t need = rskinny_lds_bytes(cfg, max_slabs, probs[i].M, L->K);
     lds = need > lds ? need : lds;
     b.first[i] = first;
     first += g[i];
@@ -1296,7 +1380,7 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
   for (int i = count; i < kGemvMaxBatch; ++i) b.p[i] = b.p[0];
   if (lds > 160 * 1024) return SFMP_ERR_SHAPE;
   static bool attr_set = false;
-  const void* fn = reinterpret_cast<const void*>(&rskinny_batched_kernel<NW, S, MB, RES>);
+  const void* fn = reinterpret_cast<const void*>(&rskinny_batched_kernel<NW, S, MB, RES, ACC>);
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) {
@@ -1323,20 +1407,21 @@ int launch_decode_batched(const GemmArgs* probs, int count, int32_t M, void* wor
   if (M == 1) return launch_gemv_batched(probs, count, stream);
   int32_t g[kGemvMaxBatch];
   if (int e = split_grid(probs, count, g)) return e;
-  const RSkinnyShape sh = rskinny_shape(M);
-  // the resident variant only when every problem of the batch fits it
-  bool resident = true;
+  // one configuration for the whole launch: the one that fits the problem with the most slabs per workgroup and
+  // the largest K (resident activations only when every problem of the batch fits them)
+  int32_t max_slabs = 0, max_k = 0;
   for (int i = 0; i < count; ++i) {
     const int32_t nslab = 8 * (probs[i].L->N / kTile);
-    resident = resident && rskinny_resident_fit(M, sh.mb, sh.nw, probs[i].L->K, (nslab + g[i] - 1) / g[i]);
+    max_slabs = std::max(max_slabs, (nslab + g[i] - 1) / g[i]);
+    max_k = std::max(max_k, probs[i].L->K);
   }
-  switch (sh.mb) {
-    case 4:
-      return resident ? launch_rskinny_batched_variant<8, kResidentSlots, 4, true>(probs, count, M, g, workspace, stream)
-                      : launch_rskinny_batched_variant<8, 8, 4, false>(probs, count, M, g, workspace, stream);
-    case 8: return launch_rskinny_batched_variant<8, 5, 8, false>(probs, count, M, g, workspace, stream);
-    default: return launch_rskinny_batched_variant<8, 3, 16, false>(probs, count, M, g, workspace, stream);
-  }
+  const RSkinnyConfig c = rskinny_config(M, max_k, max_slabs);
+#define SFMP_X(NW_, S_, MB_, RES_, ACC_)                                                    \
+  if (c.nw == NW_ && c.mb == MB_ && c.resident == RES_ && c.acc == ACC_ && c.slots == S_)   \
+    return launch_rskinny_batched_variant<NW_, S_, MB_, RES_, ACC_>(probs, count, M, g, workspace, stream);
+  SFMP_RSKINNY_CONFIGS(SFMP_X)
+#undef SFMP_X
+  return SFMP_ERR_SHAPE;
 }
 
 // 16 < M <= 128 on a narrow matrix: the product is cut into chunks of 16 activation rows, one problem of the
@@ -1371,7 +1456,7 @@ static int chunk_problems(const GemmArgs& a, GemmArgs* probs) {
 int64_t chunked_decode_workspace_bytes(const GemmArgs& a) {
   GemmArgs probs[kGemvMaxBatch];
   const int count = chunk_problems(a, probs);
-  return plan_batch_staging(probs, count, rskinny_shape(kDecodeMaxM).mb).bytes;
+  return plan_batch_staging(probs, count, rskinny_mb(kDecodeMaxM)).bytes;
 }
 
 int launch_decode_chunked(const GemmArgs& a, void* stream) {

@@ -18,6 +18,8 @@ struct DecodePlan {
   int32_t slots;     // ring slots per wavefront
   int32_t max_slabs; // 16-row slabs per workgroup (upper bound)
   int32_t mb;        // activation rows padded to this (ring-skinny: 4, 8 or 16)
+  int32_t nw;        // ring-skinny: wavefronts per workgroup (8 or 16)
+  int32_t acc;       // ring-skinny: slabs per workgroup held in registers (4, 8 or 16)
   bool resident;     // ring-skinny: activations staged into LDS by the kernel itself, no staging launch
   int64_t workspace_bytes;  // staged activations of the ring-skinny kernel
 };
