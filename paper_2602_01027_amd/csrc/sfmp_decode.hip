@@ -767,48 +767,79 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
     }
   };
 
+  int issued_early = 0;  // items of the first batch that are already on their way when the loop below starts
   if constexpr (RES) {
-    // stage the activations: direct copies of the M rows into their own LDS region, 1 KiB per wavefront
-    // and copy, all in flight together; then permute inside LDS.  One thread serves one (tile column, unit of 8
-    // columns) for every row: the permutation entries are the same for all rows.
+    // Start of the resident form, ordered as in the GEMV kernel: everything that depends on the arguments alone is
+    // requested at once (raw copies of the M rows into their own LDS region, 1 KiB per wavefront and copy; the
+    // column permutation into registers; the tile descriptors of the first batch of items), the first items of
+    // every ring go out as soon as the descriptors are there, and the activations are permuted inside LDS while
+    // those are on their way.  One thread serves one (tile column, unit of 8 columns) for every row: the
+    // permutation entries are the same for all rows.
     _Float16* Xraw = reinterpret_cast<_Float16*>(raw_region);
-    const int raw_bytes = p.M * p.K * 2;
-    for (int c = wave * 1024; c < raw_bytes; c += NW * 1024)
-      if (c + (int)data_voff < raw_bytes)
-        __builtin_amdgcn_global_load_lds((gptr_t)((const char*)p.X + c + data_voff), (lptr_t)(raw_region + c), 16, 0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    for (int u = tid; u < p.ntc * 16; u += NT) {
-      const int tc = u / 16, unit = u % 16;
-      const int k0 = tc * kTile + unit * 8;
-      int4 c0 = {k0, k0 + 1, k0 + 2, k0 + 3}, c1 = {k0 + 4, k0 + 5, k0 + 6, k0 + 7};
-      if (p.col_perm) {
-        c0 = reinterpret_cast<const int4*>(p.col_perm + k0)[0];
-        c1 = reinterpret_cast<const int4*>(p.col_perm + k0)[1];
-      }
-      static_assert(MB == 4, "the resident variant keeps one group of four activation rows");
-      floatx4 sums;
-#pragma unroll
-      for (int m = 0; m < MB; ++m) {
-        half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (m < p.M) {
-          const _Float16* row = Xraw + (size_t)m * p.K;
-          v[0] = row[c0.x];
-          v[1] = row[c0.y];
-          v[2] = row[c0.z];
-          v[3] = row[c0.w];
-          v[4] = row[c1.x];
-          v[5] = row[c1.y];
-          v[6] = row[c1.z];
-          v[7] = row[c1.w];
-        }
-        *reinterpret_cast<half8*>(Xs + ((size_t)tc * MB + m) * 256 + ((unit ^ m) * 16)) = v;
-        sums[m] = unit_group_sum(v);  // over the 16 units of the tile column (16 consecutive lanes)
-      }
-      // rows 0-3 belong to lane group 0 of the product; the groups of rows 4-15 (not present) read zeros
-      if (unit < 4) *reinterpret_cast<floatx4*>(SxL + tc * 16 + unit * 4) = unit == 0 ? sums : floatx4{0.f, 0.f, 0.f, 0.f};
+    const uint32_t raw_off = (uint32_t)(uintptr_t)(lptr_t)raw_region;
+    const int raw_bytes = p.M * p.K * 2;  // a multiple of 256
+    for (int c = wave * 1024; c < raw_bytes; c += NW * 1024) {
+      const int nl = min(64, (raw_bytes - c) / 16);
+      lds_copy_b128((uint64_t)p.X + (uint64_t)c, data_voff, raw_off + (uint32_t)c, nl == 64 ? ~0ull : (1ull << nl) - 1);
     }
-    __syncthreads();  // Xs is complete
+    const int units = p.ntc * 16;
+    int4 c0[kGemvUnitIters], c1[kGemvUnitIters];
+#pragma unroll
+    for (int ui = 0; ui < kGemvUnitIters; ++ui) {
+      if (ui * NT < units) {  // uniform
+        const int u = min(tid + ui * NT, units - 1);
+        const int k0 = u * 8;  // = 128 * (tile column) + 8 * (unit)
+        if (p.col_perm) {
+          c0[ui] = reinterpret_cast<const int4*>(p.col_perm + k0)[0];
+          c1[ui] = reinterpret_cast<const int4*>(p.col_perm + k0)[1];
+        } else {
+          c0[ui] = int4{k0, k0 + 1, k0 + 2, k0 + 3};
+          c1[ui] = int4{k0 + 4, k0 + 5, k0 + 6, k0 + 7};
+        }
+      }
+    }
+    const int Eb0 = min(64, E);
+    describe(0, Eb0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // one trip to memory for all of the above
+#pragma unroll
+    for (int ui = 0; ui < kGemvUnitIters; ++ui)
+      if (ui * NT < units)
+        asm volatile("" : "+v"(c0[ui].x), "+v"(c0[ui].y), "+v"(c0[ui].z), "+v"(c0[ui].w), "+v"(c1[ui].x),
+                     "+v"(c1[ui].y), "+v"(c1[ui].z), "+v"(c1[ui].w));
+    asm volatile("" : "+v"(it_woff), "+v"(it_soff), "+v"(it_misc));
+    issued_early = min(2, min(S, Eb0));
+    for (int e = 0; e < issued_early; ++e) issue_item(e, e);
+    barrier_lds_only();  // every wavefront's part of the raw copy has landed (each waited for its own above)
+#pragma unroll
+    for (int ui = 0; ui < kGemvUnitIters; ++ui) {
+      const int u = tid + ui * NT;
+      if (u < units) {
+        const int tc = u / 16, unit = u % 16;
+        static_assert(MB == 4, "the resident variant keeps one group of four activation rows");
+        floatx4 sums;
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+          half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+          if (m < p.M) {
+            const _Float16* row = Xraw + (size_t)m * p.K;
+            v[0] = row[c0[ui].x];
+            v[1] = row[c0[ui].y];
+            v[2] = row[c0[ui].z];
+            v[3] = row[c0[ui].w];
+            v[4] = row[c1[ui].x];
+            v[5] = row[c1[ui].y];
+            v[6] = row[c1[ui].z];
+            v[7] = row[c1[ui].w];
+          }
+          *reinterpret_cast<half8*>(Xs + ((size_t)tc * MB + m) * 256 + ((unit ^ m) * 16)) = v;
+          sums[m] = unit_group_sum(v);  // over the 16 units of the tile column (16 consecutive lanes)
+        }
+        // rows 0-3 belong to lane group 0 of the product; the groups of rows 4-15 (not present) read zeros
+        if (unit < 4)
+          *reinterpret_cast<floatx4*>(SxL + tc * 16 + unit * 4) = unit == 0 ? sums : floatx4{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+    barrier_lds_only();  // Xs and SxL are complete
   }
 
   half8 ones;
@@ -887,9 +918,9 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
 
   for (int e0 = 0; e0 < E; e0 += 64) {
     const int Eb = min(64, E - e0);
-    describe(e0, Eb);
+    if (!RES || e0 > 0) describe(e0, Eb);
     const int npro = min(S, Eb);
-    for (int e = 0; e < npro; ++e) issue_item(e, e);
+    for (int e = (e0 == 0 ? issued_early : 0); e < npro; ++e) issue_item(e, e);
     int s = 0;
     int e = 0;
     for (; e + S < Eb; ++e) {
@@ -1056,9 +1087,9 @@ static int64_t rskinny_lds_bytes(const RSkinnyConfig& c, int32_t max_slabs, int3
 constexpr int64_t kResidentMaxRawBytes = 32 * 1024;
 #ifndef SFMP_RS_RES
 #define SFMP_RS_RES 3
-#define SFMP_RS_MB4 3
+#define SFMP_RS_MB4 2
 #define SFMP_RS_MB8 2
-#define SFMP_RS_MB16 3
+#define SFMP_RS_MB16 2
 #endif
 // max_slabs: the largest number of slabs of a workgroup over the problems of the launch; K: the largest K
 static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs) {
@@ -1069,7 +1100,7 @@ static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs) {
   c.nw = wide ? 16 : 8;
   c.acc = !wide ? 16 : max_slabs <= 4 ? 4 : 8;
   c.resident = false;
-  if (c.mb == 4 && (int64_t)M * K * 2 <= kResidentMaxRawBytes) {
+  if (c.mb == 4 && (int64_t)M * K * 2 <= kResidentMaxRawBytes && K / 8 <= kGemvUnitIters * c.nw * 64) {
     c.resident = true;
     c.slots = SFMP_RS_RES;
     if (rskinny_lds_bytes(c, max_slabs, M, K) > 160 * 1024) c.resident = false;
