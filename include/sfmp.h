@@ -153,7 +153,8 @@ int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream);
  * K >= 4096 (N <= 1024: M <= 128; N <= 4096: M <= 32) that kernel once more, on chunks of 16 rows side
  * by side in one launch, and everything else the MFMA prefill kernels (with K
  * cut into ranges and fp32 partial products in the workspace when there would be few workgroups;
- * SFMP_ERR_SHAPE there if K > 57344, or, with a row permutation or a split K, N > 81920).
+ * SFMP_ERR_SHAPE there if K > 57344, or, with a row permutation or a split K, N > 81920; the kernels for
+ * M <= 16 and for the chunked form return SFMP_ERR_SHAPE if N * K >= 2^33).
  * Asynchronous on hip_stream; holds no global state.  The permutations are not checked for
  * being bijections (out-of-range entries are the caller's error; use sfmp_check_perm). */
 int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,

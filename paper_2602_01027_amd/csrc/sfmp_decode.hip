@@ -1234,8 +1234,11 @@ static int split_grid(const GemmArgs* probs, int count, int32_t* g) {
   return SFMP_OK;
 }
 
+static bool decode_offsets_fit(const sfmp_layout_t* L);
 int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
   if (count < 1 || count > kGemvMaxBatch) return SFMP_ERR_SHAPE;
+  for (int i = 0; i < count; ++i)
+    if (!decode_offsets_fit(probs[i].L)) return SFMP_ERR_SHAPE;
   int32_t g[kGemvMaxBatch];
   if (int e = split_grid(probs, count, g)) return e;
   GemvBatch b;
@@ -1436,6 +1439,8 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
 int launch_decode_batched(const GemmArgs* probs, int count, int32_t M, void* workspace, void* stream) {
   if (count < 1 || count > kGemvMaxBatch || M < 1 || M > kDecodeMaxM) return SFMP_ERR_SHAPE;
   if (M == 1) return launch_gemv_batched(probs, count, stream);
+  for (int i = 0; i < count; ++i)
+    if (!decode_offsets_fit(probs[i].L)) return SFMP_ERR_SHAPE;
   int32_t g[kGemvMaxBatch];
   if (int e = split_grid(probs, count, g)) return e;
   // one configuration for the whole launch: the one that fits the problem with the most slabs per workgroup and
@@ -1496,8 +1501,13 @@ int launch_decode_chunked(const GemmArgs& a, void* stream) {
   return launch_decode_batched(probs, count, kDecodeMaxM, a.workspace, stream);
 }
 
+// The decode kernels address a slab by a 32-bit offset into its stream and the parameters by a 32-bit offset into
+// their arrays: every stream must stay below 4 GiB, which N * K < 2^33 guarantees at any mix of widths.
+static bool decode_offsets_fit(const sfmp_layout_t* L) { return (int64_t)L->N * L->K < ((int64_t)1 << 33); }
+
 int launch_decode(const GemmArgs& a, void* stream) {
   const sfmp_layout_t* L = a.L;
+  if (!decode_offsets_fit(L)) return SFMP_ERR_SHAPE;
   const DecodePlan d = make_decode_plan(L->N, L->K, a.M);
   if (d.gemv) {
     const GemvParams p = gemv_params(a, d.max_slabs);
