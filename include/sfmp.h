@@ -221,6 +221,39 @@ int sfmp_check_perm(const int32_t* perm_host, int32_t n);
 int sfmp_fold_perms(const int32_t* row_perm_prev_host, const int32_t* col_perm_next_host, int32_t n,
                     int32_t* folded_host);
 
+/* ---- One-bit lookup-table GEMV on a bit-plane format (the paper's own kernel scheme) ----------------------
+ * Section 3.5 and Appendix F describe the unified kernel as a one-bit lookup-table GEMM: every block is
+ * decomposed into one-bit matrices (Appendix B, Eq. 10), put into +-1 form (s^ = s/2, W^_i = 2 W_i - 1,
+ * z^ = z + (2^b - 1) s / 2), packed 8 input features to a byte, and multiplied through tables of the signed
+ * sums of 8 activations held in on-chip memory, of which half is stored (mirror storage).  The three calls
+ * below are that scheme for M = 1, as a measured alternative to sfmp_gemm (which contracts on the matrix cores):
+ * the same operation Y = X[col_perm] . (s q + z)^T with the same bitmap, scale / zero arrays (fp16, group
+ * length 128 only) and permutations, on its own weight format.
+ *
+ * Bit-plane format B1: tiles of 128 x 128 codes in row-major order of (tile row, tile column); a tile of width b
+ * holds b planes, lowest bit first; a plane is 128 rows x 16 bytes (2048 bytes); bit t of byte (r, g) is bit i of
+ * the code at row 128 tr + r, column 128 tc + 8 g + t.  tile_off[t], t = tr * (K/128) + tc, is the start of tile
+ * t in planes (units of 2048 bytes); tile_off[ntiles] is the total, so a tile's width is tile_off[t+1] - tile_off[t].
+ *
+ * sfmp_lut_pack_query: sizes of the two arrays for a bitmap [N/128, K/128] (host).  SFMP_ERR_SHAPE,
+ * SFMP_ERR_BITWIDTH as for sfmp_pack_query.
+ * sfmp_lut_pack: codes [N, K] uint8 (host, row-major, reordered coordinates) -> planes_host (plane_bytes bytes),
+ * tile_off_host (table_words uint32), both caller-allocated; SFMP_ERR_CODE_RANGE if a code does not fit its tile.
+ * sfmp_lut_gemv_workspace / sfmp_lut_gemv: device pointers throughout; X fp16 [K], col_perm int32 [K] or NULL,
+ * planes and tile_off as packed (uploaded unchanged), scales / zeros fp16 [K/128, N], row_perm int32 [N] or NULL,
+ * Y fp16 [N] fully overwritten; workspace of at least the queried bytes, 256-byte aligned, contents irrelevant
+ * on entry and unspecified on return (fp32 partial sums of the K ranges).  fp32 tables and accumulation, one
+ * round-to-nearest-even conversion at the end; results repeat bit for bit.  Asynchronous on hip_stream; two
+ * launches; no global state.  Errors as for sfmp_gemm. */
+int sfmp_lut_pack_query(const int8_t* bitmap_host, int32_t N, int32_t K, int64_t* plane_bytes, int64_t* table_words);
+int sfmp_lut_pack(const uint8_t* codes_host, const int8_t* bitmap_host, int32_t N, int32_t K, uint8_t* planes_host,
+                  uint32_t* tile_off_host);
+int sfmp_lut_gemv_workspace(int32_t N, int32_t K, int64_t* bytes);
+int sfmp_lut_gemv(const void* X_dev, const int32_t* col_perm_dev, int32_t N, int32_t K, const void* planes_dev,
+                  const uint32_t* tile_off_dev, const void* scales_dev, const void* zeros_dev,
+                  const int32_t* row_perm_dev, void* Y_dev, void* workspace_dev, int64_t workspace_bytes,
+                  void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

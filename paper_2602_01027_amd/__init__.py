@@ -24,5 +24,8 @@ from .binding import (  # noqa: F401
     sfmp_check_perm,
     sfmp_fold_perms,
     sfmp_stream_read_probe,
+    sfmp_lut_pack,
+    sfmp_lut_gemv_workspace,
+    sfmp_lut_gemv,
     upload_packed,
 )

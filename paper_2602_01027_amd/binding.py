@@ -35,7 +35,8 @@ class SfmpGemvProblem(C.Structure):
 
 EXPORTS = ("sfmp_strerror", "sfmp_pack_query", "sfmp_layout_set_quant", "sfmp_pack", "sfmp_unpack", "sfmp_gemm_workspace",
            "sfmp_workspace_init", "sfmp_gemm", "sfmp_gemv_batched", "sfmp_gemm_batched_workspace",
-           "sfmp_gemm_batched", "sfmp_check_perm", "sfmp_fold_perms", "sfmp_stream_read_probe")
+           "sfmp_gemm_batched", "sfmp_check_perm", "sfmp_fold_perms", "sfmp_stream_read_probe", "sfmp_lut_pack_query",
+           "sfmp_lut_pack", "sfmp_lut_gemv_workspace", "sfmp_lut_gemv")
 
 
 def lib_path() -> str:
@@ -64,6 +65,10 @@ def load_library():
     lib.sfmp_gemm.argtypes = [vp, i32, vp, LP, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.sfmp_gemv_batched.argtypes = [vp, i32, vp]
     lib.sfmp_check_perm.argtypes = [vp, i32]
+    lib.sfmp_lut_pack_query.argtypes = [vp, i32, i32, C.POINTER(i64), C.POINTER(i64)]
+    lib.sfmp_lut_pack.argtypes = [vp, vp, i32, i32, vp, vp]
+    lib.sfmp_lut_gemv_workspace.argtypes = [i32, i32, C.POINTER(i64)]
+    lib.sfmp_lut_gemv.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.sfmp_fold_perms.argtypes = [vp, vp, i32, vp]
     lib.sfmp_stream_read_probe.argtypes = [vp, i64, vp, vp]
     for name in EXPORTS:
@@ -251,3 +256,32 @@ def sfmp_gemm_batched(problems, M: int, workspace, stream=None) -> None:
     _check(load_library().sfmp_gemm_batched(C.cast(arr, C.c_void_p), len(problems), C.c_int32(M),
                                             C.c_void_p(workspace.data_ptr()), C.c_int64(workspace.numel()),
                                             _stream_ptr(stream)))
+
+
+def sfmp_lut_pack(codes: np.ndarray, bitmap: np.ndarray):
+    """codes [N, K] uint8, bitmap [N/128, K/128] int8 (host) -> (planes uint8 [bytes], tile_off uint32 [ntiles + 1])."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    bitmap = np.ascontiguousarray(bitmap, dtype=np.int8)
+    N, K = codes.shape
+    nbytes, words = C.c_int64(0), C.c_int64(0)
+    lib = load_library()
+    _check(lib.sfmp_lut_pack_query(_host_ptr(bitmap), N, K, C.byref(nbytes), C.byref(words)))
+    planes = np.zeros(int(nbytes.value), dtype=np.uint8)
+    tile_off = np.zeros(int(words.value), dtype=np.uint32)
+    _check(lib.sfmp_lut_pack(_host_ptr(codes), _host_ptr(bitmap), N, K, _host_ptr(planes), _host_ptr(tile_off)))
+    return planes, tile_off
+
+
+def sfmp_lut_gemv_workspace(N: int, K: int) -> int:
+    out = C.c_int64(0)
+    _check(load_library().sfmp_lut_gemv_workspace(int(N), int(K), C.byref(out)))
+    return int(out.value)
+
+
+def sfmp_lut_gemv(X, col_perm, N: int, K: int, planes, tile_off, scales, zeros, row_perm, Y, workspace,
+                  stream=None) -> None:
+    """Device tensors throughout (see include/sfmp.h): X fp16 [K], Y fp16 [N]."""
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load_library().sfmp_lut_gemv(_dev_ptr(X), _dev_ptr(col_perm), int(N), int(K), _dev_ptr(planes),
+                                        _dev_ptr(tile_off), _dev_ptr(scales), _dev_ptr(zeros), _dev_ptr(row_perm),
+                                        _dev_ptr(Y), _dev_ptr(workspace), nbytes, _stream_ptr(stream)))

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsfmp.so")
-SOURCES = ["sfmp_host.cpp", "sfmp_unpack.hip", "sfmp_decode.hip", "sfmp_prefill.hip", "sfmp_api.hip"]
+SOURCES = ["sfmp_host.cpp", "sfmp_unpack.hip", "sfmp_decode.hip", "sfmp_prefill.hip", "sfmp_lut.hip", "sfmp_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off for all device code of this library
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",

@@ -208,4 +208,53 @@ int sfmp_fold_perms(const int32_t* row_perm_prev_host, const int32_t* col_perm_n
   return SFMP_OK;
 }
 
+// ---- bit-plane format of the lookup-table GEMV ---------------------------------------------------------------
+int sfmp_lut_pack_query(const int8_t* bitmap_host, int32_t N, int32_t K, int64_t* plane_bytes, int64_t* table_words) {
+  if (!bitmap_host || !plane_bytes || !table_words) return SFMP_ERR_NULL;
+  if (int e = sfmp::check_shape(N, K)) return e;
+  const int64_t ntiles = (int64_t)(N / 128) * (K / 128);
+  int64_t planes = 0;
+  for (int64_t t = 0; t < ntiles; ++t) {
+    const int b = bitmap_host[t];
+    if (b < 2 || b > 4) return SFMP_ERR_BITWIDTH;
+    planes += b;
+  }
+  if (planes >= ((int64_t)1 << 32)) return SFMP_ERR_SHAPE;
+  *plane_bytes = planes * 2048;
+  *table_words = ntiles + 1;
+  return SFMP_OK;
+}
+
+int sfmp_lut_pack(const uint8_t* codes_host, const int8_t* bitmap_host, int32_t N, int32_t K, uint8_t* planes_host,
+                  uint32_t* tile_off_host) {
+  if (!codes_host || !bitmap_host || !planes_host || !tile_off_host) return SFMP_ERR_NULL;
+  int64_t plane_bytes = 0, words = 0;
+  if (int e = sfmp_lut_pack_query(bitmap_host, N, K, &plane_bytes, &words)) return e;
+  const int32_t ntr = N / 128, ntc = K / 128;
+  uint32_t off = 0;
+  for (int32_t tr = 0; tr < ntr; ++tr)
+    for (int32_t tc = 0; tc < ntc; ++tc) {
+      const int b = bitmap_host[(int64_t)tr * ntc + tc];
+      tile_off_host[(int64_t)tr * ntc + tc] = off;
+      for (int i = 0; i < b; ++i) {
+        uint8_t* plane = planes_host + ((int64_t)off + i) * 2048;
+        for (int r = 0; r < 128; ++r) {
+          const uint8_t* row = codes_host + ((int64_t)tr * 128 + r) * K + (int64_t)tc * 128;
+          for (int g = 0; g < 16; ++g) {
+            unsigned byte = 0;
+            for (int t = 0; t < 8; ++t) {
+              const unsigned q = row[8 * g + t];
+              if (i == 0 && (q >> b) != 0) return SFMP_ERR_CODE_RANGE;
+              byte |= ((q >> i) & 1u) << t;
+            }
+            plane[r * 16 + g] = (uint8_t)byte;
+          }
+        }
+      }
+      off += (uint32_t)b;
+    }
+  tile_off_host[(int64_t)ntr * ntc] = off;
+  return SFMP_OK;
+}
+
 }  // extern "C"

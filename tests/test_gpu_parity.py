@@ -413,3 +413,60 @@ def test_folded_permutations_two_matrix_chain(torch_cuda, M):
     assert np.array_equal(folded, O.fold_perms(p1.row_perm, p2.col_perm))
     Y2f = run_gemm(p2, dp2, torch.from_numpy(folded).to("cuda:0"), rp2, X=relu(Y1t))
     assert np.array_equal(Y2f.view(np.uint16), Y2.view(np.uint16))
+
+
+# ---------------------------------------------------------------------------------------------
+# one-bit lookup-table GEMV on the bit-plane format (the paper's own kernel scheme), M = 1
+# ---------------------------------------------------------------------------------------------
+def _run_lut(torch, p):
+    import paper_2602_01027_amd as S
+    dev = "cuda:0"
+    planes, tile_off = S.sfmp_lut_pack(p.codes, p.bitmap)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    ws = torch.empty(S.sfmp_lut_gemv_workspace(p.N, p.K), dtype=torch.uint8, device=dev)
+    Y = torch.full((p.N,), float("nan"), dtype=torch.float16, device=dev)
+    cp = d(p.col_perm) if p.col_perm is not None else None
+    rp = d(p.row_perm) if p.row_perm is not None else None
+    S.sfmp_lut_gemv(d(p.X[0]), cp, p.N, p.K, d(planes), d(tile_off.view(np.int32)), d(p.scales), d(p.zeros), rp, Y, ws)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy()[None, :]
+
+
+@pytest.mark.parametrize("K,N,fractions,perms", [
+    (128, 128, {2: 1.0}, True), (512, 384, None, True), (1152, 640, None, False), (4096, 1024, {2: 0.5, 4: 0.5}, True),
+    (1024, 4096, {3: 1.0}, True)])
+def test_lut_gemv_against_oracles(torch_cuda, K, N, fractions, perms):
+    from oracle import sfmp_lut_oracle as LO
+    p = W.make_problem("lut", K, N, 1, 4100 + K + N, fractions=fractions, use_col_perm=perms, use_row_perm=perms)
+    Y = _run_lut(torch_cuda, p)
+    _check(p, Y)  # against the plain definition
+    if K * N <= 512 * 384:  # and against the table algorithm itself, where that finishes in seconds
+        planes, tile_off = LO.lut_pack(p.codes, p.bitmap)
+        ref = LO.lut_gemv(p.X[0], p.col_perm, N, K, planes, tile_off, p.scales, p.zeros, p.row_perm)
+        assert O.rel_frobenius(Y, ref[None, :]) <= TOL
+
+
+def test_lut_gemv_full_size_sampled_and_repeatable(torch_cuda):
+    # the gate projection of the 8B layer at full size: sampled rows against the oracle, two runs bit-identical,
+    # and agreement with the MFMA path of the library on the same matrix
+    from gpu_util import run_gemm
+    p = W.make_problem("lut.gate", 4096, 14336, 1, 4242)
+    Y1 = _run_lut(torch_cuda, p)
+    Y2 = _run_lut(torch_cuda, p)
+    assert np.array_equal(Y1.view(np.uint16), Y2.view(np.uint16))
+    rows = np.random.default_rng(5).choice(p.N, size=96, replace=False)
+    _check(p, Y1, rows=np.sort(rows))
+    assert O.rel_frobenius(Y1, run_gemm(p).astype(np.float64)) <= 2 * TOL
+
+
+def test_lut_gemv_argument_errors(torch_cuda):
+    import paper_2602_01027_amd as S
+    torch = torch_cuda
+    p = W.make_problem("lut.err", 256, 256, 1, 77)
+    planes, tile_off = S.sfmp_lut_pack(p.codes, p.bitmap)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    Y = torch.zeros(p.N, dtype=torch.float16, device="cuda:0")
+    small = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(S.SfmpError) as e:
+        S.sfmp_lut_gemv(d(p.X[0]), None, p.N, p.K, d(planes), d(tile_off.view(np.int32)), d(p.scales), d(p.zeros), None, Y, small)
+    assert e.value.code == -5

@@ -185,3 +185,30 @@ def test_workspace_query_follows_the_documented_path_selection(N, K, M):
         assert got == max(256, expected), (name, got, expected)
     else:
         assert got == 256, (name, got)
+
+
+# ---- bit-plane format of the lookup-table GEMV: the library's packer against the oracle's, byte for byte ----------
+@pytest.mark.parametrize("seed,N,K,fractions", [(21, 128, 128, {4: 1.0}), (22, 256, 384, None), (23, 384, 256, {2: 0.6, 3: 0.4})])
+def test_lut_pack_bytes_match_oracle(seed, N, K, fractions):
+    from oracle import sfmp_lut_oracle as LO
+    p = W.make_problem("lutpack", K, N, 1, seed, fractions=fractions)
+    planes, tile_off = S.sfmp_lut_pack(p.codes, p.bitmap)
+    ref_planes, ref_off = LO.lut_pack(p.codes, p.bitmap)
+    assert np.array_equal(tile_off, ref_off)
+    assert np.array_equal(planes, ref_planes)
+    assert np.array_equal(LO.lut_unpack(N, K, planes, tile_off), p.codes)
+
+
+def test_lut_pack_errors():
+    codes = np.zeros((128, 128), dtype=np.uint8)
+    with pytest.raises(S.SfmpError) as e:
+        S.sfmp_lut_pack(codes, np.array([[5]], dtype=np.int8))
+    assert e.value.code == -3
+    codes[3, 7] = 4
+    with pytest.raises(S.SfmpError) as e:
+        S.sfmp_lut_pack(codes, np.array([[2]], dtype=np.int8))
+    assert e.value.code == -4
+    with pytest.raises(S.SfmpError) as e:
+        S.sfmp_lut_pack(np.zeros((100, 128), dtype=np.uint8), np.array([[2]], dtype=np.int8))
+    assert e.value.code == -2
+    assert S.sfmp_lut_gemv_workspace(4096, 4096) % 256 == 0
