@@ -43,7 +43,7 @@ def parse_args():
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of HIP-graph replays")
     ap.add_argument("--separate", action="store_true",
                     help="one launch per projection (7) instead of q|k|v, o, gate|up, down sharing launches (4)")
-    ap.add_argument("--section", choices=("all", "decode", "batch", "prefill", "sweep"), default="all",
+    ap.add_argument("--section", choices=("all", "decode", "batch", "prefill", "sweep", "lut"), default="all",
                     help="which side reports to run after the headline measurement (for profiling one kernel "
                          "family at a time): decode = per-projection and 70B M=1, batch = M in {4, 16}, prefill = "
                          "M=2048; with batch or prefill the headline region runs 2 steps only")
@@ -241,6 +241,41 @@ def time_each_projection(torch, layer, launches=60):
         torch.cuda.synchronize()
         out.append(e0.elapsed_time(e1) * 1e3 / launches)
     return out
+
+
+def time_lut(torch, S, p, replicas, launches):
+    """Average microseconds per call of sfmp_lut_gemv on problem p (graph replay, weights rotated over replicas)."""
+    dev = "cuda:0"
+    planes, tile_off = S.sfmp_lut_pack(p.codes, p.bitmap)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    reps = [(d(planes), d(tile_off.view(np.int32)), d(p.scales), d(p.zeros)) for _ in range(replicas)]
+    X, Y = d(p.X[0]), torch.zeros(p.N, dtype=torch.float16, device=dev)
+    cp = d(p.col_perm) if p.col_perm is not None else None
+    rp = d(p.row_perm) if p.row_perm is not None else None
+    ws = torch.empty(S.sfmp_lut_gemv_workspace(p.N, p.K), dtype=torch.uint8, device=dev)
+
+    def call(j, stream):
+        pl, to, sc, zr = reps[j % replicas]
+        S.sfmp_lut_gemv(X, cp, p.N, p.K, pl, to, sc, zr, rp, Y, ws, stream=stream)
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        call(0, side)
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        for j in range(launches):
+            call(j, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    g.replay()
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    g.replay()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / launches
 
 
 def cpu_baseline(problems):
@@ -481,6 +516,21 @@ def main():
                 sweep[f"{q.K}->{q.N}"] = rows
             extra["single_call_M_sweep"] = sweep
             del ps
+        if args.section in ("all", "lut"):
+            # the paper's own kernel scheme (one-bit lookup tables on a bit-plane format) beside the MFMA path, M = 1,
+            # same matrices, cold cache: uniform widths (its latency should follow the width) and the 1/3-each mix
+            rows = []
+            for (K, N) in ((4096, 4096), (4096, 14336)):
+                for label, fr in (("2-bit", {2: 1.0}), ("3-bit", {3: 1.0}), ("4-bit", {4: 1.0}), ("mixed 2/3/4", None)):
+                    q = W.make_problem(f"lut.{K}x{N}.{label}", K, N, 1, 9100 + N + len(label), fractions=fr, fast_codes=True)
+                    lm = Layer([q], 13)
+                    t_mfma = time_each_projection(torch, lm, launches=52)[0]
+                    del lm
+                    t_lut = time_lut(torch, S, q, 13, 52)
+                    wbytes = float(q.bitmap.astype(np.float64).sum()) * 2048.0
+                    rows.append(dict(shape=f"{K}->{N}", widths=label, lut_us=round(t_lut, 2), mfma_us=round(t_mfma, 2),
+                                     lut_GBps=round(wbytes / t_lut / 1e3, 1)))
+            extra["lut_gemv_vs_mfma_gemv_M1"] = rows
         result["extra"] = extra
 
     if not args.no_cpu_baseline:

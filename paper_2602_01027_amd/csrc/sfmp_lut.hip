@@ -18,7 +18,10 @@ namespace sfmp {
 
 constexpr int kLutThreads = 256;      // = output features per workgroup
 constexpr int kLutPlaneBytes = 2048;  // one bit plane of a 128 x 128 tile
-constexpr int kLutTargetGroups = 1024;  // workgroups aimed at: K is cut into ranges until there are about this many
+#ifndef SFMP_LUT_GROUPS
+#define SFMP_LUT_GROUPS 2048
+#endif
+constexpr int kLutTargetGroups = SFMP_LUT_GROUPS;  // workgroups aimed at: K is cut into ranges until there are about this many
 
 struct LutParams {
   const _Float16* X;
@@ -41,31 +44,43 @@ __global__ __launch_bounds__(kLutThreads) void lut_gemv_kernel(const LutParams p
   const int r = n % kTile;
   const int tc_begin = (int)((int64_t)ks * p.ntc / p.ksplit), tc_end = (int)((int64_t)(ks + 1) * p.ntc / p.ksplit);
 
-  float y = 0.f;
-  for (int tc = tc_begin; tc < tc_end; ++tc) {
-    const int buf = (tc - tc_begin) & 1;
-    // ---- this thread's bytes of the tile's planes: requested first, used after the tables are built
-    const uint32_t t0 = p.tile_off[tr * p.ntc + tc], t1 = p.tile_off[tr * p.ntc + tc + 1];
-    const int b = (int)(t1 - t0);
+  // Everything a tile column needs from memory is requested one column ahead (this thread's 16 bytes of each bit
+  // plane, its scale and zero, and the 8 activations of the table entries it builds), so that the lookups of a
+  // column run while the next column's data is on its way.
+  struct Column {
     u32x4 w[4];
+    float s, z, x[8];
+    int b;
+  };
+  const int g_build = tid / 16, sub = tid % 16;  // this thread builds entries 8 sub .. 8 sub + 7 of group g_build
+  auto request = [&](int tc, Column& c) {
+    const uint32_t t0 = p.tile_off[tr * p.ntc + tc], t1 = p.tile_off[tr * p.ntc + tc + 1];
+    c.b = (int)(t1 - t0);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      if (active && i < b)
-        w[i] = *reinterpret_cast<const u32x4*>(p.planes + ((size_t)t0 + i) * kLutPlaneBytes + (size_t)r * 16);
-    float s = 0.f, z = 0.f;
+      if (active && i < c.b)
+        c.w[i] = *reinterpret_cast<const u32x4*>(p.planes + ((size_t)t0 + i) * kLutPlaneBytes + (size_t)r * 16);
+    c.s = 0.f, c.z = 0.f;
     if (active) {
-      s = (float)p.scales[(size_t)tc * p.N + n];
-      z = (float)p.zeros[(size_t)tc * p.N + n];
+      c.s = (float)p.scales[(size_t)tc * p.N + n];
+      c.z = (float)p.zeros[(size_t)tc * p.N + n];
     }
-    // ---- tables of this tile column: thread (g, sub) builds entries 8 sub .. 8 sub + 7 of group g
-    {
-      const int g = tid / 16, sub = tid % 16;
-      float x[8];
 #pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const int k = tc * kTile + 8 * g + t;
-        x[t] = (float)p.X[p.col_perm ? p.col_perm[k] : k];
-      }
+    for (int t = 0; t < 8; ++t) {
+      const int k = tc * kTile + 8 * g_build + t;
+      c.x[t] = (float)p.X[p.col_perm ? p.col_perm[k] : k];
+    }
+  };
+
+  float y = 0.f;
+  Column cur, nxt;
+  if (tc_begin < tc_end) request(tc_begin, cur);
+  for (int tc = tc_begin; tc < tc_end; ++tc) {
+    const int buf = (tc - tc_begin) & 1;
+    if (tc + 1 < tc_end) request(tc + 1, nxt);
+    // ---- tables of this tile column
+    {
+      const float* x = cur.x;
       // bits 3..6 of the index come from sub, bit 7 is 0, bits 0..2 are filled in below
       float base = -x[0] - x[1] - x[2] - x[7];
 #pragma unroll
@@ -74,7 +89,7 @@ __global__ __launch_bounds__(kLutThreads) void lut_gemv_kernel(const LutParams p
 #pragma unroll
       for (int j = 0; j < 8; ++j)
         e[j] = base + 2.f * (((j & 1) ? x[0] : 0.f) + ((j & 2) ? x[1] : 0.f) + ((j & 4) ? x[2] : 0.f));
-      float* dst = &lut[buf][g][sub * 8];
+      float* dst = &lut[buf][g_build][sub * 8];
       *reinterpret_cast<floatx4*>(dst) = floatx4{e[0], e[1], e[2], e[3]};
       *reinterpret_cast<floatx4*>(dst + 4) = floatx4{e[4], e[5], e[6], e[7]};
     }
@@ -85,37 +100,50 @@ __global__ __launch_bounds__(kLutThreads) void lut_gemv_kernel(const LutParams p
 #pragma unroll
       for (int g = 0; g < 16; ++g) sum_x -= lut[buf][g][0];
       float total = 0.f;
-      for (int i = 0; i < b; ++i) {
-        float plane_sum = 0.f;
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          const uint32_t word = w[i][d];
+      for (int i = 0; i < 4; ++i) {
+        if (i < cur.b) {
+          float plane_sum = 0.f;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int g = 4 * d + q;
-            const int32_t top = (int32_t)(word << (24 - 8 * q)) >> 31;  // all ones if the byte's top bit is set
-            const uint32_t idx = ((word >> (8 * q)) ^ (uint32_t)top) & 0x7Fu;
-            const float v = lut[buf][g][idx];
-            plane_sum += __uint_as_float(__float_as_uint(v) ^ ((uint32_t)top & 0x80000000u));
+          for (int d = 0; d < 4; ++d) {
+            const uint32_t word = cur.w[i][d];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int g = 4 * d + q;
+              const int32_t top = (int32_t)(word << (24 - 8 * q)) >> 31;  // all ones if the byte's top bit is set
+              const uint32_t idx = ((word >> (8 * q)) ^ (uint32_t)top) & 0x7Fu;
+              const float v = lut[buf][g][idx];
+              plane_sum += __uint_as_float(__float_as_uint(v) ^ ((uint32_t)top & 0x80000000u));
+            }
           }
+          total += (float)(1 << i) * plane_sum;
         }
-        total += (float)(1 << i) * plane_sum;
       }
-      const float s_hat = 0.5f * s;
-      const float z_hat = z + 0.5f * (float)((1 << b) - 1) * s;
+      const float s_hat = 0.5f * cur.s;
+      const float z_hat = cur.z + 0.5f * (float)((1 << cur.b) - 1) * cur.s;
       y += s_hat * total + z_hat * sum_x;
     }
+    cur = nxt;
   }
   if (active) p.partial[(size_t)ks * p.N + n] = y;
 }
 
-__global__ __launch_bounds__(256) void lut_reduce_kernel(const float* __restrict__ partial, const int32_t* __restrict__ row_perm,
-                                                        _Float16* __restrict__ Y, int N, int ksplit) {
-  const int n = (int)blockIdx.x * 256 + (int)threadIdx.x;
+// fixed-order sum of the K ranges; the loads of 8 ranges are in flight together (one thread per output feature
+// would otherwise wait for up to ksplit dependent trips to memory)
+__global__ __launch_bounds__(64) void lut_reduce_kernel(const float* __restrict__ partial, const int32_t* __restrict__ row_perm,
+                                                       _Float16* __restrict__ Y, int N, int ksplit) {
+  const int n = (int)blockIdx.x * 64 + (int)threadIdx.x;
   if (n >= N) return;
+  const int32_t col = row_perm ? row_perm[n] : n;
   float sum = 0.f;
-  for (int ks = 0; ks < ksplit; ++ks) sum += partial[(size_t)ks * N + n];
-  Y[row_perm ? row_perm[n] : n] = (_Float16)sum;
+  for (int k0 = 0; k0 < ksplit; k0 += 8) {
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = k0 + j < ksplit ? partial[(size_t)(k0 + j) * N + n] : 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sum += v[j];
+  }
+  Y[col] = (_Float16)sum;
 }
 
 static int lut_ksplit(int32_t N, int32_t K) {
@@ -164,7 +192,7 @@ int sfmp_lut_gemv(const void* X_dev, const int32_t* col_perm_dev, int32_t N, int
     note_hip_error("sfmp_lut_gemv launch", hipGetErrorString(e));
     return SFMP_ERR_HIP;
   }
-  hipLaunchKernelGGL(lut_reduce_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, (hipStream_t)hip_stream,
+  hipLaunchKernelGGL(lut_reduce_kernel, dim3((unsigned)((N + 63) / 64)), dim3(64), 0, (hipStream_t)hip_stream,
                      (const float*)workspace_dev, row_perm_dev, (_Float16*)Y_dev, (int)N, ks);
   e = hipGetLastError();
   if (e != hipSuccess) {
