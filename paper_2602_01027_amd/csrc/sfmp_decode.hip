@@ -165,17 +165,6 @@ constexpr int kSlotBytes = 1024 + 128;  // slab bytes (<= 1 KiB) + 16 scale dwor
 constexpr int kGemvSlotParamBytes = 128;  // GEMV slots: [16 scale dwords | 16 zero dwords | slab]
 
 typedef float floatx16v __attribute__((ext_vector_type(16)));
-#ifdef SFMP_EXPERIMENT
-__device__ unsigned long long g_stamps[1024 * 8];
-__device__ unsigned long long g_wave_done[1024 * 16];
-__device__ int g_mode;
-#define SFMP_STAMP(k)                                                        \
-  do {                                                                       \
-    if (threadIdx.x == 0 && blockIdx.x < 1024) g_stamps[blockIdx.x * 8 + (k)] = wall_clock64(); \
-  } while (0)
-#else
-#define SFMP_STAMP(k)
-#endif
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -280,7 +269,6 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-  SFMP_STAMP(0);
   // Virtual slab index v = bid + G*j (G is a multiple of 8, block b runs on XCD b%8): XCD x gets
   // the contiguous slab range [x*ntr, (x+1)*ntr), so the 8 slabs of a tile row run on one XCD.
   const int nj = (p.nslab - bid + G - 1) / G;                           // slabs of this workgroup
@@ -325,7 +313,6 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
       }
     }
   }
-  SFMP_STAMP(1);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // one trip to memory for all of the above
   // (the loaded registers are "used" here so that the compiler places its own wait for them here as well: placed
   // after the ring has been filled it would have to be a wait for every ring copy)
@@ -385,7 +372,6 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
   constexpr int kEarly = 2;
   const int npro = min(S, E);
   for (int e = 0; e < min(kEarly, npro); ++e) issue_item(e, e);
-  SFMP_STAMP(2);
 
   // ---- while those copies are on their way: permute the activations inside LDS and add up each tile column
   barrier_lds_only();  // every wavefront's part of the raw copy has landed (each waited for its own above)
@@ -412,9 +398,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
     }
   }
   barrier_lds_only();  // Xs and Sx are complete
-  SFMP_STAMP(3);
   for (int e = kEarly; e < npro; ++e) issue_item(e, e);
-  SFMP_STAMP(4);
 
   half8 a[4];
 #pragma unroll
@@ -441,21 +425,10 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
   asm volatile("" : "+v"(lane_w2), "+v"(lane_w3), "+v"(lane_w4), "+v"(lane_p), "+v"(sx_lane));
   const unsigned char* lds0 = lds_raw - (uint32_t)(uintptr_t)(lptr_t)lds_raw;  // LDS byte 0
 
-#ifdef SFMP_XMODE
-  const int xmode = __builtin_amdgcn_readfirstlane(g_mode);
-#endif
   auto consume = [&](int e, int s) __attribute__((always_inline)) {
     const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
     const int tc = misc & 0xFFFF;
     const uint32_t slot = ring_off + (uint32_t)s * kSlotBytes;
-#ifdef SFMP_XMODE
-    if (xmode == 1) return;
-    if (xmode == 2) {
-      const uint32_t* src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w4));
-      acc_q += __uint_as_float(src[0] ^ src[1] ^ src[2] ^ src[3]);
-      return;
-    }
-#endif
     if ((lane & 15) == 0) {  // only activation row 0 exists: lanes 0,16,32,48 feed it
 #pragma unroll
       for (int kappa = 0; kappa < 4; ++kappa)
@@ -467,29 +440,6 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
     float t;
     uint32_t w[4];
     const uint32_t* src;
-#ifdef SFMP_XMODE
-    if (xmode == 5 || xmode == 6) {
-      src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w4));
-      w[0] = src[0], w[1] = src[1], w[2] = src[2], w[3] = src[3];
-      if (xmode == 5) {  // unpack, no matrix instructions
-        uint32_t op[4][4];
-        unpack_slab<4>(w, op);
-        uint32_t x = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) x ^= op[i][j];
-        t = __uint_as_float(x) + (float)a[0][0] + (float)a[1][0] + (float)a[2][0] + (float)a[3][0];
-      } else {  // matrix instructions, no unpack
-        floatx4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = c0;
-        c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[0], as_half8(w), c0, 0, 0, 0);
-        c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[1], as_half8(w), c1, 0, 0, 0);
-        c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[2], as_half8(w), c0, 0, 0, 0);
-        c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[3], as_half8(w), c1, 0, 0, 0);
-        t = c0[0] + c1[0] * 0.0625f;
-      }
-    } else
-#endif
     switch ((misc >> 24) & 3) {
       case 0:
         src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w2));
@@ -526,30 +476,6 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
     }
   };
 
-#ifdef SFMP_XMODE
-  if (xmode == 3) {  // streaming experiment: weights only, one copy per item, nothing consumed
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    auto issue_w = [&](int e, int s) __attribute__((always_inline)) {
-      const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
-      const uint32_t woff = (uint32_t)__builtin_amdgcn_readlane((int)it_woff, e);
-      const uint32_t bm2 = (misc >> 24) & 3u;
-      uint64_t b2 = s2b, b3 = s3b, b4 = s4b;
-      asm volatile("" : "+s"(b2), "+s"(b3), "+s"(b4));
-      const uint64_t wbase = (bm2 == 0 ? b2 : bm2 == 1 ? b3 : b4) + woff;
-      const uint64_t wlanes = bm2 == 0 ? 0xFFFFFFFFull : bm2 == 1 ? 0xFFFFFFFFFFFFull : ~0ull;
-      lds_copy_b128(wbase, data_voff, ring_off + (uint32_t)s * kSlotBytes + kGemvSlotParamBytes, wlanes);
-    };
-    for (int e = 0; e < npro; ++e) issue_w(e, e);
-    int s = 0;
-    for (int e = 0; e + S < E; ++e) {
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(S - 1) : "memory");
-      issue_w(e + S, s);
-      if (++s == S) s = 0;
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    return;
-  }
-#endif
   // ---- steady state: item e has landed once at most the S-1 younger items (2 copies each) are
   // outstanding; consume it and refill its slot with item e + S
   int s = 0;
@@ -563,7 +489,6 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
   // ---- tail: nothing left to issue; item e has landed once at most the E-1-e younger items are outstanding
   // (most launches of a decoder layer have no more than S items per wavefront and are all tail: waiting for
   // everything first would put the whole arithmetic behind the whole transfer)
-  SFMP_STAMP(5);
   for (; e < E; ++e) {
     switch (E - 1 - e) {
       case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
@@ -579,10 +504,6 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
     if (++s == S) s = 0;
   }
   static_assert(S <= 8 && kCopiesPerItem * 7 < 64, "the tail's waits cover up to 7 younger items");
-  SFMP_STAMP(6);
-#ifdef SFMP_EXPERIMENT
-  if (lane == 0 && blockIdx.x < 1024) g_wave_done[blockIdx.x * 16 + wave] = wall_clock64();
-#endif
 
   if (lane < 16) {
 #pragma unroll
@@ -596,7 +517,6 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
     for (int w = 0; w < NW; ++w) sum += red[((tid / 16) * NW + w) * 16 + tid % 16];
     p.Y[p.row_perm ? (int64_t)out_col : out_row] = (_Float16)sum;
   }
-  SFMP_STAMP(7);
 }
 
 template <int NW, int S>
@@ -1054,9 +974,6 @@ static GemvFit gemv_fit(int32_t N, int32_t K, int32_t grid) {
   const int64_t fixed = gemv_fixed_lds_bytes(K, f.max_slabs);
   int64_t slots = (160 * 1024 - fixed) / ((int64_t)kGemvWaves * kSlotBytes);
   if (slots > kGemvMaxSlots) slots = kGemvMaxSlots;
-#ifdef SFMP_EXPERIMENT
-  if (const char* v = getenv("SFMP_SLOTS")) { if (atoi(v) < slots) slots = atoi(v); }
-#endif
   const int64_t ring_bytes = slots * kGemvWaves * kSlotBytes;
   const int64_t items = (int64_t)f.max_slabs * ((ntc + kGemvWaves - 1) / kGemvWaves);
   f.ok = grid >= 8 && grid % 8 == 0 && grid <= nslab && slots >= kGemvMinSlots && f.max_slabs <= kGemvMaxSlabs &&
@@ -1085,12 +1002,8 @@ static int64_t rskinny_lds_bytes(const RSkinnyConfig& c, int32_t max_slabs, int3
 // 4 rows and M x K activations of at most 32 KiB: measured, the saved launch outweighs 256 workgroups each permuting
 // the activations up to that size (8 to 17 % on K = 4096 with M <= 4) and no longer beyond it.
 constexpr int64_t kResidentMaxRawBytes = 32 * 1024;
-#ifndef SFMP_RS_RES
-#define SFMP_RS_RES 3
-#define SFMP_RS_MB4 2
-#define SFMP_RS_MB8 2
-#define SFMP_RS_MB16 2
-#endif
+// ring slots per wavefront of the four forms (shallow, as in the GEMV kernel; 3 measured best for the resident form)
+constexpr int kSlotsResident = 3, kSlotsMb4 = 2, kSlotsMb8 = 2, kSlotsMb16 = 2;
 // max_slabs: the largest number of slabs of a workgroup over the problems of the launch; K: the largest K
 static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs) {
   RSkinnyConfig c;
@@ -1102,10 +1015,10 @@ static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs) {
   c.resident = false;
   if (c.mb == 4 && (int64_t)M * K * 2 <= kResidentMaxRawBytes && K / 8 <= kGemvUnitIters * c.nw * 64) {
     c.resident = true;
-    c.slots = SFMP_RS_RES;
+    c.slots = kSlotsResident;
     if (rskinny_lds_bytes(c, max_slabs, M, K) > 160 * 1024) c.resident = false;
   }
-  if (!c.resident) c.slots = c.mb == 4 ? SFMP_RS_MB4 : c.mb == 8 ? SFMP_RS_MB8 : SFMP_RS_MB16;
+  if (!c.resident) c.slots = c.mb == 4 ? kSlotsMb4 : c.mb == 8 ? kSlotsMb8 : kSlotsMb16;
   return c;
 }
 
@@ -1319,10 +1232,10 @@ static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* 
 
 // The compiled configurations (see rskinny_config): X(NW, S, MB, RES, ACC)
 #define SFMP_RSKINNY_CONFIGS(X)                                                                                   \
-  X(16, SFMP_RS_RES, 4, true, 4) X(16, SFMP_RS_RES, 4, true, 8) X(8, SFMP_RS_RES, 4, true, 16)                    \
-  X(16, SFMP_RS_MB4, 4, false, 4) X(16, SFMP_RS_MB4, 4, false, 8) X(8, SFMP_RS_MB4, 4, false, 16)                 \
-  X(16, SFMP_RS_MB8, 8, false, 4) X(16, SFMP_RS_MB8, 8, false, 8) X(8, SFMP_RS_MB8, 8, false, 16)                 \
-  X(8, SFMP_RS_MB16, 16, false, 16)
+  X(16, kSlotsResident, 4, true, 4) X(16, kSlotsResident, 4, true, 8) X(8, kSlotsResident, 4, true, 16)                    \
+  X(16, kSlotsMb4, 4, false, 4) X(16, kSlotsMb4, 4, false, 8) X(8, kSlotsMb4, 4, false, 16)                 \
+  X(16, kSlotsMb8, 8, false, 4) X(16, kSlotsMb8, 8, false, 8) X(8, kSlotsMb8, 8, false, 16)                 \
+  X(8, kSlotsMb16, 16, false, 16)
 
 static int launch_rskinny(const GemmArgs& a, const DecodePlan& d, void* stream) {
 #define SFMP_X(NW_, S_, MB_, RES_, ACC_)                                                      \
@@ -1470,9 +1383,6 @@ int launch_decode_batched(const GemmArgs* probs, int count, int32_t M, void* wor
 bool use_chunked_decode(int32_t N, int32_t K, int32_t M) {
   if (M <= kDecodeMaxM || M > kDecodeMaxM * kGemvMaxBatch) return false;
   const int32_t ntr = N / kTile, ntc = K / kTile, chunks = (M + kDecodeMaxM - 1) / kDecodeMaxM;
-#ifdef SFMP_EXPERIMENT
-  if (const char* v = getenv("SFMP_CHUNK")) return atoi(v) != 0 && (ntr <= 64 || M <= 64);
-#endif
   if (ntc < 32) return false;
   return chunks <= (ntr <= 8 ? 8 : ntr <= 32 ? 2 : 0);
 }
@@ -1518,12 +1428,3 @@ int launch_decode(const GemmArgs& a, void* stream) {
 
 }  // namespace sfmp
 
-#ifdef SFMP_EXPERIMENT
-extern "C" int sfmp_debug_stamps(unsigned long long* host_out) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(sfmp::g_stamps), sizeof(unsigned long long) * 256 * 8);
-}
-extern "C" int sfmp_debug_mode(int m) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(sfmp::g_mode), &m, sizeof(int)); }
-extern "C" int sfmp_debug_wave_done(unsigned long long* host_out) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(sfmp::g_wave_done), sizeof(unsigned long long) * 256 * 16);
-}
-#endif

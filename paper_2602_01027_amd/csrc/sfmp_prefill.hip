@@ -607,10 +607,6 @@ PrefillPlan make_prefill_plan(int32_t N, int32_t K, int32_t M) {
     if (ks > 8) ks = 8;
     if (ks < 3 && ntc < 64) ks = 1;  // two ranges of a short K measured between -5 and +6 %; of a long K +20 %
   }
-#ifdef SFMP_EXPERIMENT
-  if (const char* v = getenv("SFMP_BM")) d.bm = atoi(v);
-  if (const char* v = getenv("SFMP_KSPLIT")) ks = atoi(v);
-#endif
   d.ksplit = (int32_t)ks;
   d.xperm_bytes = round_up_256((int64_t)((M + kTile - 1) / kTile) * kTile * K * 2);  // whole 128-row blocks
   d.ytmp_bytes = round_up_256(ks > 1 ? ks * (int64_t)M * N * 4 : (int64_t)M * N * 2);
