@@ -9,17 +9,17 @@
 // independent of M.  One accumulator per field position p; per 128-column group the result is
 // scaled in fp32:  y += s * sum_p 2^(24-p) C_p + z * sum(x)      (Appendix B Eq. 11, re-associated).
 //
-// GEMV (M = 1): one workgroup owns one 16-row slab of a tile row over the WHOLE K range, so a
+// GEMV (M = 1): a workgroup owns whole 16-row slabs of tile rows over the WHOLE K range, so a
 // result never leaves the workgroup: no global partial sums, no atomics, no fences.  The
-// activation vector is copied to LDS with coalesced loads and permuted there (the column
-// permutation is fused into this load); wavefront w walks the tiles w, w+NW, ... of the tile
-// row, 4 slab loads in flight per lane; per-wavefront sums are combined through LDS and the 16
+// activation vector is copied to LDS and permuted there (the column permutation is fused into
+// this load); wavefront w walks the tiles w, w+NW, ... of its slabs, each slab arriving in a
+// two-slot ring by direct global->LDS copies; per-wavefront sums are combined through LDS and the
 // outputs are scattered through row_perm.  Workgroups are numbered so that the 8 slabs of a
 // tile row run on the same XCD (they share scale/zero cache lines and the index table).
 //
 // Skinny GEMM (2..16), and any M = 1 problem whose activation vector does not fit in LDS beside the
-// rings: the same scheme with the activations of each tile column travelling through the ring slots
-// (see rskinny_kernel).
+// rings: the same scheme with the activations of each tile column travelling through the ring slots,
+// or resident in LDS when there are few of them (see rskinny_kernel).
 #include <algorithm>
 #include <cstdlib>
 
@@ -212,12 +212,6 @@ __device__ __forceinline__ float gemv_item(const unsigned char* slot, int lane, 
   return slab_dot<B>(w, a)[0];
 }
 
-// NW wavefronts per workgroup, S ring slots per wavefront.
-//
-// A wavefront's work is a list of at most 64 "items" (one 16-row slab of one tile each).  Everything
-// an item needs (packed-slab address, scale address, tile column, flags) is computed once, by lane e
-// for item e, and later broadcast with v_readlane: the steady-state loop does no address arithmetic.
-// The ring is refilled item by item, so S-1 copies per wavefront are always in flight.
 // LDS stores the compiler does not see as LDS accesses.  After a direct global->LDS copy has been issued the
 // compiler puts a wait for ALL outstanding copies in front of every ordinary LDS store (it cannot tell the
 // destinations apart); these stores are used while ring copies are in flight, to regions no copy writes.
@@ -246,9 +240,9 @@ __host__ __device__ inline int64_t gemv_shared_region_bytes(int32_t K, int32_t m
 // NW wavefronts per workgroup, S ring slots per wavefront.
 //
 // A wavefront's work is a list of at most 64 "items" (one 16-row slab of one tile each).  Everything
-// an item needs (packed-slab address, scale address, tile column, flags) is computed once, by lane e
-// for item e, and later broadcast with v_readlane: the steady-state loop does no address arithmetic.
-// The ring is refilled item by item, so S-1 copies per wavefront are always in flight.
+// an item needs (offset of its slab in its stream, offset of its parameters, tile column, flags) is computed
+// once, by lane e for item e, and later broadcast with v_readlane; the addresses of the copies are scalar.
+// The ring is refilled item by item, so S-1 items per wavefront are always in flight.
 //
 // Order of the start: a launch of this size lasts about 10 us, of which each dependent trip to memory is most of
 // a microsecond, so everything that depends on the arguments alone (tile descriptors, raw activations, column
@@ -957,8 +951,8 @@ static int after_launch(const char* what) {
 }
 
 // Does an M = 1 problem fit the GEMV kernel when `grid` workgroups (a multiple of 8) work on it?  LDS holds
-// the permuted activation vector, the group sums, the reduction buffer and the per-wavefront rings; the
-// raw activation copy used while permuting aliases the rings (they are idle until then).
+// the permuted activation vector, the group sums, a region shared by the raw activation copy (start of the kernel)
+// and the reduction buffer (end), and the per-wavefront rings.
 struct GemvFit {
   bool ok;
   int32_t slots, max_slabs, lds_bytes;

@@ -125,6 +125,26 @@ def test_small_batch_both_activation_stagings(torch_cuda, K, M):
     _check(p, run_gemm(p))
 
 
+@pytest.mark.parametrize("K,N,M", [
+    (1024, 28672, 2),   # resident activations, 16 wavefronts, 7 slabs per workgroup in registers (8-wide vectors)
+    (4352, 28672, 4),   # 4 rows, activations too large to be resident (34 KiB): staged, 16 wavefronts
+    (1024, 28672, 8),   # 8 rows through the rings, 16 wavefronts
+    (512, 40960, 3),    # 10 slabs per workgroup: 8 wavefronts, 16-wide vectors, resident
+    (4352, 40960, 4),   # the same, staged
+    (1024, 40960, 7),   # the same, 8 rows
+    (1024, 40960, 12),  # 16 rows (always 8 wavefronts)
+])
+def test_ring_kernel_configurations(torch_cuda, K, N, M):
+    # the compiled forms of the small-batch kernel that the layer shapes above do not reach: wide matrices put more
+    # than 4 (more than 8) slabs on a workgroup.  Sampled output features, every tile row hit.
+    from gpu_util import run_gemm
+    p = W.make_problem("ringcfg", K, N, M, 6200 + N // 128 + M, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, fast_codes=True)
+    rng = np.random.default_rng(M)
+    rows = np.unique(np.concatenate([np.arange(N // 128) * 128 + rng.integers(0, 128, N // 128),
+                                     rng.choice(N, size=128, replace=False)]))
+    _check(p, run_gemm(p), rows=rows)
+
+
 def test_batched_small_batch_mixed_staging(torch_cuda):
     # one problem whose activations would fit the in-kernel staging and one whose do not: the batch takes the
     # staged path for both, and gives bit for bit what separate calls (which differ in path) give
