@@ -252,7 +252,7 @@ def time_lut(torch, S, p, replicas, launches):
     X, Y = d(p.X[0]), torch.zeros(p.N, dtype=torch.float16, device=dev)
     cp = d(p.col_perm) if p.col_perm is not None else None
     rp = d(p.row_perm) if p.row_perm is not None else None
-    ws = torch.empty(S.sfmp_lut_gemv_workspace(p.N, p.K), dtype=torch.uint8, device=dev)
+    ws = torch.zeros(S.sfmp_lut_gemv_workspace(p.N, p.K), dtype=torch.uint8, device=dev)
 
     def call(j, stream):
         pl, to, sc, zr = reps[j % replicas]

@@ -443,7 +443,7 @@ def _run_lut(torch, p):
     dev = "cuda:0"
     planes, tile_off = S.sfmp_lut_pack(p.codes, p.bitmap)
     d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-    ws = torch.empty(S.sfmp_lut_gemv_workspace(p.N, p.K), dtype=torch.uint8, device=dev)
+    ws = torch.zeros(S.sfmp_lut_gemv_workspace(p.N, p.K), dtype=torch.uint8, device=dev)
     Y = torch.full((p.N,), float("nan"), dtype=torch.float16, device=dev)
     cp = d(p.col_perm) if p.col_perm is not None else None
     rp = d(p.row_perm) if p.row_perm is not None else None
@@ -477,6 +477,29 @@ def test_lut_gemv_full_size_sampled_and_repeatable(torch_cuda):
     rows = np.random.default_rng(5).choice(p.N, size=96, replace=False)
     _check(p, Y1, rows=np.sort(rows))
     assert O.rel_frobenius(Y1, run_gemm(p).astype(np.float64)) <= 2 * TOL
+
+
+def test_lut_gemv_workspace_reuse(torch_cuda):
+    # one workspace, with arbitrary contents, used by several products of different shapes one after the other
+    import paper_2602_01027_amd as S
+    torch = torch_cuda
+    probs = [W.make_problem("lut.ws", K, N, 1, 4300 + i) for i, (K, N) in enumerate([(512, 640), (256, 1024), (512, 640)])]
+    nbytes = max(S.sfmp_lut_gemv_workspace(p.N, p.K) for p in probs)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    ws.fill_(0xAB)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    outs = []
+    for rep in range(2):
+        for p in probs:
+            planes, tile_off = S.sfmp_lut_pack(p.codes, p.bitmap)
+            Y = torch.full((p.N,), float("nan"), dtype=torch.float16, device="cuda:0")
+            S.sfmp_lut_gemv(d(p.X[0]), d(p.col_perm), p.N, p.K, d(planes), d(tile_off.view(np.int32)), d(p.scales),
+                            d(p.zeros), d(p.row_perm), Y, ws)
+            torch.cuda.synchronize()
+            outs.append(Y.cpu().numpy()[None, :])
+            _check(p, outs[-1])
+    for i in range(3):
+        assert np.array_equal(outs[i].view(np.uint16), outs[i + 3].view(np.uint16))
 
 
 def test_lut_gemv_argument_errors(torch_cuda):
