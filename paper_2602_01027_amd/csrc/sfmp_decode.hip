@@ -998,12 +998,15 @@ static int64_t rskinny_lds_bytes(const RSkinnyConfig& c, int32_t max_slabs, int3
 constexpr int64_t kResidentMaxRawBytes = 32 * 1024;
 // ring slots per wavefront of the four forms (shallow, as in the GEMV kernel; 3 measured best for the resident form)
 constexpr int kSlotsResident = 3, kSlotsMb4 = 2, kSlotsMb8 = 2, kSlotsMb16 = 2;
+// 16 rows with 16 wavefronts: a slot carries 4 KiB of activations, and only one per wavefront fits in LDS (the other
+// wavefronts of the SIMD cover the wait)
+constexpr int kSlotsMb16Wide = 1;
 // max_slabs: the largest number of slabs of a workgroup over the problems of the launch; K: the largest K
 static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs) {
   RSkinnyConfig c;
   c.mb = rskinny_mb(M);
   // 16 wavefronts where the finished sums fit beside the rest in 128 registers and the rings in LDS
-  const bool wide = c.mb <= 8 && max_slabs <= 8;
+  const bool wide = max_slabs <= 8;
   c.nw = wide ? 16 : 8;
   c.acc = !wide ? 16 : max_slabs <= 4 ? 4 : 8;
   c.resident = false;
@@ -1012,7 +1015,7 @@ static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs) {
     c.slots = kSlotsResident;
     if (rskinny_lds_bytes(c, max_slabs, M, K) > 160 * 1024) c.resident = false;
   }
-  if (!c.resident) c.slots = c.mb == 4 ? kSlotsMb4 : c.mb == 8 ? kSlotsMb8 : kSlotsMb16;
+  if (!c.resident) c.slots = c.mb == 4 ? kSlotsMb4 : c.mb == 8 ? kSlotsMb8 : wide ? kSlotsMb16Wide : kSlotsMb16;
   return c;
 }
 
@@ -1229,7 +1232,7 @@ static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* 
   X(16, kSlotsResident, 4, true, 4) X(16, kSlotsResident, 4, true, 8) X(8, kSlotsResident, 4, true, 16)                    \
   X(16, kSlotsMb4, 4, false, 4) X(16, kSlotsMb4, 4, false, 8) X(8, kSlotsMb4, 4, false, 16)                 \
   X(16, kSlotsMb8, 8, false, 4) X(16, kSlotsMb8, 8, false, 8) X(8, kSlotsMb8, 8, false, 16)                 \
-  X(8, kSlotsMb16, 16, false, 16)
+  X(16, kSlotsMb16Wide, 16, false, 4) X(16, kSlotsMb16Wide, 16, false, 8) X(8, kSlotsMb16, 16, false, 16)
 
 static int launch_rskinny(const GemmArgs& a, const DecodePlan& d, void* stream) {
 #define SFMP_X(NW_, S_, MB_, RES_, ACC_)                                                      \
