@@ -475,6 +475,10 @@ __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) 
 
   // in_run: tiles e+1 and e+2 have the same width B as tile e
   auto step = [&](auto btag, auto in_run, int e) __attribute__((always_inline)) {
+    // Two workgroups share a CU.  A wavefront inside the three groups that only compute is served before one that is
+    // at the synchronisation point or in the group right after it (whose loads have just been issued): the matrix
+    // pipe waits less on the other workgroup's bookkeeping (2-4 % measured, same box).
+    __builtin_amdgcn_s_setprio(1);
     mfmas(a0, b0);
     read_a(e, k1, a1);
     make_b(btag, k1, b1);
@@ -490,6 +494,7 @@ __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) 
     make_b(btag, k3, b1);
     interleave();
     __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(0);
     sync_and_issue(e, in_run, btag);
     mfmas(a1, b1);
     read_a(e + 1, k0, a0);
