@@ -476,7 +476,10 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
   int e = 0;
   for (; e + S < E; ++e) {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * (S - 1)) : "memory");
+    // a wavefront whose item has landed is served before one that is issuing copies or about to wait (2-3 %)
+    __builtin_amdgcn_s_setprio(1);
     consume(e, s);
+    __builtin_amdgcn_s_setprio(0);
     issue_item(e + S, s);
     if (++s == S) s = 0;
   }
@@ -494,7 +497,9 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, co
       case 6: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * 6) : "memory"); break;
       default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * 7) : "memory"); break;
     }
+    __builtin_amdgcn_s_setprio(1);
     consume(e, s);
+    __builtin_amdgcn_s_setprio(0);
     if (++s == S) s = 0;
   }
   static_assert(S <= 8 && kCopiesPerItem * 7 < 64, "the tail's waits cover up to 7 younger items");
@@ -839,7 +844,9 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
     int e = 0;
     for (; e + S < Eb; ++e) {
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies * (S - 1)) : "memory");
+      __builtin_amdgcn_s_setprio(1);
       consume(e, s);
+      __builtin_amdgcn_s_setprio(0);
       issue_item(e + S, s);
       if (++s == S) s = 0;
     }
@@ -855,7 +862,9 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
         case 6: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies * 6) : "memory"); break;
         default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies * 7) : "memory"); break;
       }
+      __builtin_amdgcn_s_setprio(1);
       consume(e, s);
+      __builtin_amdgcn_s_setprio(0);
       if (++s == S) s = 0;
     }
   }
