@@ -21,6 +21,7 @@
 // rings: the same scheme with the activations of each tile column travelling through the ring slots,
 // or resident in LDS when there are few of them (see rskinny_kernel).
 #include <algorithm>
+#include <cstddef>
 #include <cstdlib>
 
 #include "sfmp_device.h"
@@ -249,8 +250,18 @@ __host__ __device__ inline int64_t gemv_shared_region_bytes(int32_t K, int32_t m
 // permutation, the output positions of the end) is requested at once; the ring is filled as soon as the
 // descriptors are there, and the activations are permuted inside LDS while the first slabs are on their way.
 template <int NW, int S>
-__device__ __forceinline__ void gemv_body(const GemvParams& p, const int bid, const int G, unsigned char* lds_raw) {
+__device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid, const int G, unsigned char* lds_raw) {
   constexpr int NT = NW * 64;
+  // All arguments are fetched now, by scalar loads issued together: fetched where they are first used they arrive in
+  // two to four dependent trips to memory (the block spans two cache lines), of which a launch this short has no
+  // microsecond to spare.  The integers pass through the statement as outputs, so nothing computed from them can be
+  // placed in front of it.
+  GemvParams p = p_in;
+  asm volatile(""
+               : "+s"(p.N), "+s"(p.K), "+s"(p.ntr), "+s"(p.ntc), "+s"(p.nslab), "+s"(p.max_slabs), "+s"(p.gshift),
+                 "+s"(p.bf16)
+               : "s"(p.X), "s"(p.col_perm), "s"(p.s2), "s"(p.s3), "s"(p.s4), "s"(p.tile_desc), "s"(p.scales),
+                 "s"(p.zeros), "s"(p.row_perm), "s"(p.Y));
   // LDS: Xs [K] fp16 | Sx [ntc] f32 | shared region: raw activations, later red [max_slabs][NW][16] f32 |
   //      rings [NW][S][kSlotBytes]
   _Float16* Xs = reinterpret_cast<_Float16*>(lds_raw);
@@ -528,18 +539,31 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const GemvParams p) {
 // decoder layer): the persistent grid is split between the problems in proportion to their bytes;
 // workgroups [first[i], first[i+1]) run problem i exactly as a launch of that size would.
 constexpr int kGemvMaxBatch = 8;
+// (the table of first workgroups leads the struct and fills one 64-byte line: a workgroup finds its problem from one
+// scalar load without a loop of dependent ones, then fetches that problem's arguments in one go; entries from `count`
+// on hold the total, so the search needs no count)
 struct GemvBatch {
-  GemvParams p[kGemvMaxBatch];
   int32_t first[kGemvMaxBatch + 1];
   int32_t count;
+  int32_t pad[6];
+  GemvParams p[kGemvMaxBatch];
 };
+static_assert(offsetof(GemvBatch, p) == 64, "the header of a batch is one 64-byte line");
+
+// index of the problem that workgroup `bid` belongs to: the number of problems whose first workgroup is <= bid, minus one
+__device__ __forceinline__ int batch_problem_of(const int32_t (&first)[kGemvMaxBatch + 1], int bid) {
+  int i = 0;
+#pragma unroll
+  for (int k = 1; k < kGemvMaxBatch; ++k) i += bid >= first[k] ? 1 : 0;
+  return i;
+}
 
 template <int NW, int S>
 __global__ __launch_bounds__(NW * 64) void gemv_batched_kernel(const GemvBatch b) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  int i = 0;
-  while (i + 1 < b.count && (int)blockIdx.x >= b.first[i + 1]) ++i;
-  gemv_body<NW, S>(b.p[i], (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
+  const int i = batch_problem_of(b.first, (int)blockIdx.x);
+  const GemvParams p = b.p[i];
+  gemv_body<NW, S>(p, (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
 }
 
 // ============================================================================================
@@ -915,18 +939,20 @@ __global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p)
 
 // Several independent problems with the same M in one launch (q, k and v, or gate and up of a decoder
 // layer): the grid is split between the problems as in gemv_batched_kernel.
-struct RSkinnyBatch {
-  RSkinnyParams p[kGemvMaxBatch];
+struct RSkinnyBatch {  // laid out as GemvBatch
   int32_t first[kGemvMaxBatch + 1];
   int32_t count;
+  int32_t pad[6];
+  RSkinnyParams p[kGemvMaxBatch];
 };
+static_assert(offsetof(RSkinnyBatch, p) == 64, "the header of a batch is one 64-byte line");
 
 template <int NW, int S, int MB, bool RES, int ACC>
 __global__ __launch_bounds__(NW * 64) void rskinny_batched_kernel(const RSkinnyBatch b) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  int i = 0;
-  while (i + 1 < b.count && (int)blockIdx.x >= b.first[i + 1]) ++i;
-  rskinny_body<NW, S, MB, RES, ACC>(b.p[i], (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
+  const int i = batch_problem_of(b.first, (int)blockIdx.x);
+  const RSkinnyParams p = b.p[i];
+  rskinny_body<NW, S, MB, RES, ACC>(p, (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
 }
 
 // Staging for a batch: job j (one per distinct activation matrix) owns workgroups [first[j], first[j+1]).
@@ -1158,9 +1184,12 @@ int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
   if (count < 1 || count > kGemvMaxBatch) return SFMP_ERR_SHAPE;
   for (int i = 0; i < count; ++i)
     if (!decode_offsets_fit(probs[i].L)) return SFMP_ERR_SHAPE;
+  // a single problem takes the plain kernel: its arguments are the kernel's own, one line fetched once
+  if (count == 1 && probs[0].M == 1 && make_decode_plan(probs[0].L->N, probs[0].L->K, 1).gemv)
+    return launch_decode(probs[0], stream);
   int32_t g[kGemvMaxBatch];
   if (int e = split_grid(probs, count, g)) return e;
-  GemvBatch b;
+  GemvBatch b = {};
   b.count = count;
   int32_t slots = kGemvMaxSlots, lds = 0, first = 0;
   for (int i = 0; i < count; ++i) {
@@ -1312,7 +1341,7 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
     sb.K[j] = 0;
     sb.M[j] = 0;
   }
-  RSkinnyBatch b;
+  RSkinnyBatch b = {};
   b.count = count;
   int32_t first = 0;
   int64_t lds = 0;
