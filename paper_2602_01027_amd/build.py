@@ -13,7 +13,9 @@ SOURCES = ["sfmp_host.cpp", "sfmp_unpack.hip", "sfmp_decode.hip", "sfmp_prefill.
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off for all device code of this library
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
-         "-packed-fp32-ops", "-munsafe-fp-atomics", "-Wno-unused-command-line-argument"]
+         "-packed-fp32-ops", "-munsafe-fp-atomics", "-Wno-unused-command-line-argument",
+         # the first scalar kernel arguments arrive in scalar registers (the GEMV kernels are written for it)
+         "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 
 def _compile(src: str, objdir: str, extra) -> str:

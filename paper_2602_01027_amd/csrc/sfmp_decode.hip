@@ -249,19 +249,22 @@ __host__ __device__ inline int64_t gemv_shared_region_bytes(int32_t K, int32_t m
 // a microsecond, so everything that depends on the arguments alone (tile descriptors, raw activations, column
 // permutation, the output positions of the end) is requested at once; the ring is filled as soon as the
 // descriptors are there, and the activations are permuted inside LDS while the first slabs are on their way.
-template <int NW, int S>
+template <int NW, int S, bool PRELOADED = false>
 __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid, const int G, unsigned char* lds_raw) {
   constexpr int NT = NW * 64;
-  // All arguments are fetched now, by scalar loads issued together: fetched where they are first used they arrive in
-  // two to four dependent trips to memory (the block spans two cache lines), of which a launch this short has no
-  // microsecond to spare.  The integers pass through the statement as outputs, so nothing computed from them can be
-  // placed in front of it.
+  // PRELOADED (the plain kernel): the integers and the four pointers of the first requests are in scalar registers
+  // when the kernel starts; the other pointers are fetched behind those requests, see below.
+  // Otherwise (a problem of a batch, whose arguments lie in the argument block): all arguments are fetched now, by
+  // scalar loads issued together: fetched where they are first used they arrive in two to four dependent trips to
+  // memory (the block spans two cache lines), of which a launch this short has no microsecond to spare.  The integers
+  // pass through the statement as outputs, so nothing computed from them can be placed in front of it.
   GemvParams p = p_in;
-  asm volatile(""
-               : "+s"(p.N), "+s"(p.K), "+s"(p.ntr), "+s"(p.ntc), "+s"(p.nslab), "+s"(p.max_slabs), "+s"(p.gshift),
-                 "+s"(p.bf16)
-               : "s"(p.X), "s"(p.col_perm), "s"(p.s2), "s"(p.s3), "s"(p.s4), "s"(p.tile_desc), "s"(p.scales),
-                 "s"(p.zeros), "s"(p.row_perm), "s"(p.Y));
+  if constexpr (!PRELOADED)
+    asm volatile(""
+                 : "+s"(p.N), "+s"(p.K), "+s"(p.ntr), "+s"(p.ntc), "+s"(p.nslab), "+s"(p.max_slabs), "+s"(p.gshift),
+                   "+s"(p.bf16)
+                 : "s"(p.X), "s"(p.col_perm), "s"(p.s2), "s"(p.s3), "s"(p.s4), "s"(p.tile_desc), "s"(p.scales),
+                   "s"(p.zeros), "s"(p.row_perm), "s"(p.Y));
   // LDS: Xs [K] fp16 | Sx [ntc] f32 | shared region: raw activations, later red [max_slabs][NW][16] f32 |
   //      rings [NW][S][kSlotBytes]
   _Float16* Xs = reinterpret_cast<_Float16*>(lds_raw);
@@ -318,6 +321,8 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
       }
     }
   }
+  if constexpr (PRELOADED)  // the remaining arguments travel together with the requests above
+    asm volatile("" ::"s"(p.s2), "s"(p.s3), "s"(p.s4), "s"(p.scales), "s"(p.zeros), "s"(p.Y));
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // one trip to memory for all of the above
   // (the loaded registers are "used" here so that the compiler places its own wait for them here as well: placed
   // after the ring has been filled it would have to be a wait for every ring copy)
@@ -529,26 +534,36 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   }
 }
 
+// The arguments are scalars rather than one struct: built with -mllvm -amdgpu-kernarg-preload-count=16, the first
+// 14 dwords of scalar arguments (the four pointers of the first requests and the integers that address them) are
+// placed in scalar registers by the command processor before the first wavefront starts, so the kernel's first global
+// requests wait for no argument load; the rest of the arguments travel while those requests are in flight.
 template <int NW, int S>
-__global__ __launch_bounds__(NW * 64) void gemv_kernel(const GemvParams p) {
+__global__ __launch_bounds__(NW * 64) void gemv_kernel(
+    const int32_t* tile_desc, const _Float16* X, const int32_t* col_perm, const int32_t* row_perm, int32_t nslab,
+    int32_t ntr, int32_t ntc, int32_t K, int32_t N, int32_t grid, int32_t max_slabs, int32_t gshift, int32_t bf16,
+    const uint8_t* s2, const uint8_t* s3, const uint8_t* s4, const _Float16* scales, const _Float16* zeros, _Float16* Y) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  gemv_body<NW, S>(p, (int)blockIdx.x, (int)gridDim.x, lds_raw);
+  GemvParams p;
+  p.X = X, p.col_perm = col_perm, p.s2 = s2, p.s3 = s3, p.s4 = s4, p.tile_desc = tile_desc, p.scales = scales;
+  p.zeros = zeros, p.row_perm = row_perm, p.Y = Y, p.N = N, p.K = K, p.ntr = ntr, p.ntc = ntc, p.nslab = nslab;
+  p.max_slabs = max_slabs, p.gshift = gshift, p.bf16 = bf16;
+  gemv_body<NW, S, true>(p, (int)blockIdx.x, grid, lds_raw);  // (gridDim.x would be one more load at entry)
 }
 
 // Several independent M = 1 problems in one launch (for example q, k and v, or gate and up of a
 // decoder layer): the persistent grid is split between the problems in proportion to their bytes;
 // workgroups [first[i], first[i+1]) run problem i exactly as a launch of that size would.
 constexpr int kGemvMaxBatch = 8;
-// (the table of first workgroups leads the struct and fills one 64-byte line: a workgroup finds its problem from one
-// scalar load without a loop of dependent ones, then fetches that problem's arguments in one go; entries from `count`
-// on hold the total, so the search needs no count)
+struct GemvBatchProblems {
+  GemvParams p[kGemvMaxBatch];
+};
+// host-side description of a batch: first[i] = first workgroup of problem i; entries from `count` on hold the total
 struct GemvBatch {
   int32_t first[kGemvMaxBatch + 1];
   int32_t count;
-  int32_t pad[6];
-  GemvParams p[kGemvMaxBatch];
+  GemvBatchProblems probs;
 };
-static_assert(offsetof(GemvBatch, p) == 64, "the header of a batch is one 64-byte line");
 
 // index of the problem that workgroup `bid` belongs to: the number of problems whose first workgroup is <= bid, minus one
 __device__ __forceinline__ int batch_problem_of(const int32_t (&first)[kGemvMaxBatch + 1], int bid) {
@@ -558,12 +573,26 @@ __device__ __forceinline__ int batch_problem_of(const int32_t (&first)[kGemvMaxB
   return i;
 }
 
+// (first[1..8] arrive as scalar arguments, hence in preloaded scalar registers: a workgroup finds its problem, and
+// its range of workgroups, without a load and without a loop of dependent ones, then fetches that problem's arguments
+// in one go)
 template <int NW, int S>
-__global__ __launch_bounds__(NW * 64) void gemv_batched_kernel(const GemvBatch b) {
+__global__ __launch_bounds__(NW * 64) void gemv_batched_kernel(int32_t f1, int32_t f2, int32_t f3, int32_t f4,
+                                                               int32_t f5, int32_t f6, int32_t f7, int32_t f8,
+                                                               const GemvBatchProblems b) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  const int i = batch_problem_of(b.first, (int)blockIdx.x);
+  const int bid = (int)blockIdx.x;
+  const int32_t f[kGemvMaxBatch + 1] = {0, f1, f2, f3, f4, f5, f6, f7, f8};
+  int i = 0, lo = 0, hi = f8;
+#pragma unroll
+  for (int k = kGemvMaxBatch - 1; k >= 1; --k) {
+    const bool at_or_after = bid >= f[k];
+    i += at_or_after ? 1 : 0;
+    lo = at_or_after && f[k] > lo ? f[k] : lo;
+    hi = at_or_after ? hi : f[k];
+  }
   const GemvParams p = b.p[i];
-  gemv_body<NW, S>(p, (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
+  gemv_body<NW, S>(p, bid - lo, hi - lo, lds_raw);
 }
 
 // ============================================================================================
@@ -1115,38 +1144,41 @@ static GemvParams gemv_params(const GemmArgs& a, int32_t max_slabs) {
   return p;
 }
 
-// Launches gemv_kernel / gemv_batched_kernel instantiated for S ring slots.
-template <typename KernelArg>
-static int launch_gemv_variant(int slots, bool batched, const KernelArg& arg, unsigned grid, size_t lds_bytes,
-                               void* stream) {
-  switch (slots) {
-#define SFMP_GEMV_CASE(S_)                                                                                     \
-  case S_: {                                                                                                   \
-    static bool attr_set[2] = {false, false};                                                                  \
-    const void* fn = batched ? reinterpret_cast<const void*>(&gemv_batched_kernel<kGemvWaves, S_>)             \
-                             : reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, S_>);                    \
-    if (!attr_set[batched]) {                                                                                  \
-      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);          \
-      if (e != hipSuccess) {                                                                                   \
-        note_hip_error("hipFuncSetAttribute(gemv)", hipGetErrorString(e));                                     \
-        return SFMP_ERR_HIP;                                                                                   \
-      }                                                                                                        \
-      attr_set[batched] = true;                                                                                \
-    }                                                                                                          \
-    void* kargs[] = {const_cast<KernelArg*>(&arg)};                                                            \
-    hipError_t e = hipLaunchKernel(fn, dim3(grid), dim3(kGemvWaves * 64), kargs, lds_bytes, (hipStream_t)stream); \
-    if (e != hipSuccess) {                                                                                     \
-      note_hip_error("sfmp gemv launch", hipGetErrorString(e));                                                \
-      return SFMP_ERR_HIP;                                                                                     \
-    }                                                                                                          \
-  } break;
-    SFMP_GEMV_CASE(2)
-    SFMP_GEMV_CASE(3)
-    SFMP_GEMV_CASE(4)
-#undef SFMP_GEMV_CASE
-    default: return SFMP_ERR_SHAPE;
+static_assert(kGemvMinSlots == 2 && kGemvMaxSlots == 2, "the GEMV kernels are instantiated for two ring slots");
+
+static int launch_gemv_function(const void* fn, bool* attr_set, void** kargs, unsigned grid, size_t lds_bytes,
+                                void* stream) {
+  if (!*attr_set) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) {
+      note_hip_error("hipFuncSetAttribute(gemv)", hipGetErrorString(e));
+      return SFMP_ERR_HIP;
+    }
+    *attr_set = true;
+  }
+  hipError_t e = hipLaunchKernel(fn, dim3(grid), dim3(kGemvWaves * 64), kargs, lds_bytes, (hipStream_t)stream);
+  if (e != hipSuccess) {
+    note_hip_error("sfmp gemv launch", hipGetErrorString(e));
+    return SFMP_ERR_HIP;
   }
   return after_launch("sfmp gemv launch");
+}
+
+// gemv_kernel over `grid` workgroups (the order of kargs is the kernel's parameter list)
+static int launch_gemv_plain(GemvParams q, int32_t grid, size_t lds_bytes, void* stream) {
+  static bool attr_set = false;
+  void* kargs[] = {&q.tile_desc, &q.X, &q.col_perm, &q.row_perm, &q.nslab, &q.ntr, &q.ntc, &q.K, &q.N, &grid,
+                   &q.max_slabs, &q.gshift, &q.bf16, &q.s2, &q.s3, &q.s4, &q.scales, &q.zeros, &q.Y};
+  return launch_gemv_function(reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, 2>), &attr_set, kargs,
+                              (unsigned)grid, lds_bytes, stream);
+}
+
+static int launch_gemv_batch(GemvBatch b, size_t lds_bytes, void* stream) {
+  static bool attr_set = false;
+  void* kargs[] = {&b.first[1], &b.first[2], &b.first[3], &b.first[4], &b.first[5],
+                   &b.first[6], &b.first[7], &b.first[8], &b.probs};
+  return launch_gemv_function(reinterpret_cast<const void*>(&gemv_batched_kernel<kGemvWaves, 2>), &attr_set, kargs,
+                              (unsigned)b.first[kGemvMaxBatch], lds_bytes, stream);
 }
 
 // Splits the 256 workgroups of a persistent launch between `count` problems in units of 8 (one per XCD), greedily to
@@ -1196,7 +1228,7 @@ int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
     const GemvFit f = gemv_fit(probs[i].L->N, probs[i].L->K, g[i]);
     if (!f.ok) return SFMP_ERR_SHAPE;
     slots = f.slots < slots ? f.slots : slots;
-    b.p[i] = gemv_params(probs[i], f.max_slabs);
+    b.probs.p[i] = gemv_params(probs[i], f.max_slabs);
     b.first[i] = first;
     first += g[i];
   }
@@ -1205,10 +1237,10 @@ int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
   // with fewer slots than a problem could use alone its LDS footprint only shrinks: size for the largest
   for (int i = 0; i < count; ++i) {
     const sfmp_layout_t* L = probs[i].L;
-    const int64_t need = gemv_fixed_lds_bytes(L->K, b.p[i].max_slabs) + (int64_t)slots * kGemvWaves * kSlotBytes;
+    const int64_t need = gemv_fixed_lds_bytes(L->K, b.probs.p[i].max_slabs) + (int64_t)slots * kGemvWaves * kSlotBytes;
     lds = need > lds ? (int32_t)need : lds;
   }
-  return launch_gemv_variant(slots, true, b, (unsigned)first, (size_t)lds, stream);
+  return launch_gemv_batch(b, (size_t)lds, stream);
 }
 
 static RSkinnyParams rskinny_params(const GemmArgs& a, int32_t M, const void* xblk, int32_t max_slabs) {
@@ -1456,7 +1488,7 @@ int launch_decode(const GemmArgs& a, void* stream) {
   const DecodePlan d = make_decode_plan(L->N, L->K, a.M);
   if (d.gemv) {
     const GemvParams p = gemv_params(a, d.max_slabs);
-    return launch_gemv_variant(d.slots, false, p, (unsigned)d.grid, (size_t)d.lds_bytes, stream);
+    return launch_gemv_plain(p, d.grid, (size_t)d.lds_bytes, stream);
   }
   return launch_rskinny(a, d, stream);
 }
