@@ -249,7 +249,7 @@ __host__ __device__ inline int64_t gemv_shared_region_bytes(int32_t K, int32_t m
 // a microsecond, so everything that depends on the arguments alone (tile descriptors, raw activations, column
 // permutation, the output positions of the end) is requested at once; the ring is filled as soon as the
 // descriptors are there, and the activations are permuted inside LDS while the first slabs are on their way.
-template <int NW, int S, bool PRELOADED = false>
+template <int NW, int S, bool PRELOADED, bool ANYFMT>
 __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid, const int G, unsigned char* lds_raw) {
   constexpr int NT = NW * 64;
   // PRELOADED (the plain kernel): the integers and the four pointers of the first requests are in scalar registers
@@ -470,7 +470,9 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
     // low half: scale, high half: zero (bit 26 of misc: odd sigma -> the high halves of the two dwords)
     const uint32_t sel = (misc & (1u << 26)) ? 0x07060302u : 0x05040100u;
     const uint32_t sz = __builtin_amdgcn_perm(zrw, scw, sel);
-    if (p.bf16) {
+    // (ANYFMT: the storage type of the parameters is looked up per item; the kernels for fp16 alone have no such
+    // branch in the loop, which also spares the register copies where its two sides meet)
+    if (ANYFMT && p.bf16) {
       asm volatile("; bfloat16 parameters");
       acc_q += __uint_as_float(sz << 16) * t;
       acc_z += __uint_as_float(sz & 0xFFFF0000u) * sx;
@@ -538,7 +540,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
 // 14 dwords of scalar arguments (the four pointers of the first requests and the integers that address them) are
 // placed in scalar registers by the command processor before the first wavefront starts, so the kernel's first global
 // requests wait for no argument load; the rest of the arguments travel while those requests are in flight.
-template <int NW, int S>
+template <int NW, int S, bool ANYFMT>
 __global__ __launch_bounds__(NW * 64) void gemv_kernel(
     const int32_t* tile_desc, const _Float16* X, const int32_t* col_perm, const int32_t* row_perm, int32_t nslab,
     int32_t ntr, int32_t ntc, int32_t K, int32_t N, int32_t grid, int32_t max_slabs, int32_t gshift, int32_t bf16,
@@ -548,7 +550,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(
   p.X = X, p.col_perm = col_perm, p.s2 = s2, p.s3 = s3, p.s4 = s4, p.tile_desc = tile_desc, p.scales = scales;
   p.zeros = zeros, p.row_perm = row_perm, p.Y = Y, p.N = N, p.K = K, p.ntr = ntr, p.ntc = ntc, p.nslab = nslab;
   p.max_slabs = max_slabs, p.gshift = gshift, p.bf16 = bf16;
-  gemv_body<NW, S, true>(p, (int)blockIdx.x, grid, lds_raw);  // (gridDim.x would be one more load at entry)
+  gemv_body<NW, S, true, ANYFMT>(p, (int)blockIdx.x, grid, lds_raw);  // (gridDim.x would be one more load at entry)
 }
 
 // Several independent M = 1 problems in one launch (for example q, k and v, or gate and up of a
@@ -576,7 +578,7 @@ __device__ __forceinline__ int batch_problem_of(const int32_t (&first)[kGemvMaxB
 // (first[1..8] arrive as scalar arguments, hence in preloaded scalar registers: a workgroup finds its problem, and
 // its range of workgroups, without a load and without a loop of dependent ones, then fetches that problem's arguments
 // in one go)
-template <int NW, int S>
+template <int NW, int S, bool ANYFMT>
 __global__ __launch_bounds__(NW * 64) void gemv_batched_kernel(int32_t f1, int32_t f2, int32_t f3, int32_t f4,
                                                                int32_t f5, int32_t f6, int32_t f7, int32_t f8,
                                                                const GemvBatchProblems b) {
@@ -592,7 +594,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_batched_kernel(int32_t f1, int32
     hi = at_or_after ? hi : f[k];
   }
   const GemvParams p = b.p[i];
-  gemv_body<NW, S>(p, bid - lo, hi - lo, lds_raw);
+  gemv_body<NW, S, false, ANYFMT>(p, bid - lo, hi - lo, lds_raw);
 }
 
 // ============================================================================================
@@ -1165,20 +1167,26 @@ static int launch_gemv_function(const void* fn, bool* attr_set, void** kargs, un
 }
 
 // gemv_kernel over `grid` workgroups (the order of kargs is the kernel's parameter list)
+// (two instantiations of each kernel: parameters in fp16 throughout, or a storage type looked up per problem)
 static int launch_gemv_plain(GemvParams q, int32_t grid, size_t lds_bytes, void* stream) {
-  static bool attr_set = false;
+  static bool attr_set[2] = {false, false};
   void* kargs[] = {&q.tile_desc, &q.X, &q.col_perm, &q.row_perm, &q.nslab, &q.ntr, &q.ntc, &q.K, &q.N, &grid,
                    &q.max_slabs, &q.gshift, &q.bf16, &q.s2, &q.s3, &q.s4, &q.scales, &q.zeros, &q.Y};
-  return launch_gemv_function(reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, 2>), &attr_set, kargs,
-                              (unsigned)grid, lds_bytes, stream);
+  const bool any = q.bf16 != 0;
+  const void* fn = any ? reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, 2, true>)
+                       : reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, 2, false>);
+  return launch_gemv_function(fn, &attr_set[any], kargs, (unsigned)grid, lds_bytes, stream);
 }
 
 static int launch_gemv_batch(GemvBatch b, size_t lds_bytes, void* stream) {
-  static bool attr_set = false;
+  static bool attr_set[2] = {false, false};
   void* kargs[] = {&b.first[1], &b.first[2], &b.first[3], &b.first[4], &b.first[5],
                    &b.first[6], &b.first[7], &b.first[8], &b.probs};
-  return launch_gemv_function(reinterpret_cast<const void*>(&gemv_batched_kernel<kGemvWaves, 2>), &attr_set, kargs,
-                              (unsigned)b.first[kGemvMaxBatch], lds_bytes, stream);
+  bool any = false;
+  for (int i = 0; i < b.count; ++i) any = any || b.probs.p[i].bf16 != 0;
+  const void* fn = any ? reinterpret_cast<const void*>(&gemv_batched_kernel<kGemvWaves, 2, true>)
+                       : reinterpret_cast<const void*>(&gemv_batched_kernel<kGemvWaves, 2, false>);
+  return launch_gemv_function(fn, &attr_set[any], kargs, (unsigned)b.first[kGemvMaxBatch], lds_bytes, stream);
 }
 
 // Splits the 256 workgroups of a persistent launch between `count` problems in units of 8 (one per XCD), greedily to
