@@ -340,7 +340,8 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
     const uint32_t bm2 = (uint32_t)d & 3u;  // bit-width - 2 (the use of d makes the compiler wait for the loads above, here)
     const uint32_t slab_bytes = 256u * (bm2 + 2u);
     if (lane < E) {
-      it_woff = ((uint32_t)d >> 2) * (8u * slab_bytes) + (uint32_t)it_sigma * slab_bytes;
+      // (a multiple of 256: the two low bits carry the width for issue_item, which then needs no other register)
+      it_woff = (((uint32_t)d >> 2) * (8u * slab_bytes) + (uint32_t)it_sigma * slab_bytes) | bm2;
       // the aligned dword holding the fp16 scale of row 128*tr + sigma (rows 8*l + sigma are 16 bytes apart);
       // direct-to-LDS copies need dword-aligned addresses, the wanted fp16 is the low half for even sigma and
       // the high half for odd sigma
@@ -360,10 +361,9 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   const uint32_t ring_off = (uint32_t)(uintptr_t)(lptr_t)(rings + (size_t)wave * S * kSlotBytes);
   const uint64_t s2b = (uint64_t)p.s2, s3b = (uint64_t)p.s3, s4b = (uint64_t)p.s4;
   auto issue_item = [&](int e, int s) __attribute__((always_inline)) {
-    const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
-    const uint32_t woff = (uint32_t)__builtin_amdgcn_readlane((int)it_woff, e);
+    const uint32_t woff_w = (uint32_t)__builtin_amdgcn_readlane((int)it_woff, e);
     const uint32_t soff = (uint32_t)__builtin_amdgcn_readlane((int)it_soff, e);
-    const uint32_t bm2 = (misc >> 24) & 3u;
+    const uint32_t bm2 = woff_w & 3u, woff = woff_w & ~3u;
     // (the three bases pass through an empty statement right before the choice: as plain captured variables they
     // sit next to each other in the closure, and the choice by width becomes an indexed load from it in scratch)
     uint64_t b2 = s2b, b3 = s3b, b4 = s4b;
