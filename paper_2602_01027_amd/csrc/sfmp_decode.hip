@@ -132,6 +132,27 @@ __device__ __forceinline__ void lds_copy_b32_vaddr(uint64_t vaddr, uint32_t lds_
       : "memory");
 }
 
+// The two copies of a GEMV item in one statement: 32 parameter dwords (lanes 0-31, a full 64-bit address per lane) to
+// LDS byte lds_off, then 16 bytes per lane of the slab (scalar base + lane offset; lanes 0-31 always, of lanes 32-63
+// those whose bit is set in hi_lanes) to lds_off + slab_off.  Only the upper half of EXEC changes, and it is put back;
+// the writes to EXEC sit between each write of M0 and the copy that uses it (the wait state M0 needs).
+__device__ __forceinline__ void lds_copy_item(uint64_t par_vaddr, uint64_t slab_sbase, uint32_t slab_voff,
+                                              uint32_t lds_off, uint32_t lds_off_slab, uint32_t hi_lanes) {
+  uint32_t saved;
+  asm volatile(
+      "s_mov_b32 m0, %3\n\t"
+      "s_mov_b32 %0, exec_hi\n\t"
+      "s_mov_b32 exec_hi, 0\n\t"
+      "global_load_lds_dword %1, off\n\t"
+      "s_mov_b32 m0, %4\n\t"
+      "s_mov_b32 exec_hi, %5\n\t"
+      "global_load_lds_dwordx4 %6, %2\n\t"
+      "s_mov_b32 exec_hi, %0"
+      : "=&s"(saved)
+      : "v"(par_vaddr), "s"(slab_sbase), "s"(lds_off), "s"(lds_off_slab), "s"(hi_lanes), "v"(slab_voff)
+      : "memory");
+}
+
 // ============================================================================================
 // GEMV, M = 1
 // ============================================================================================
@@ -335,13 +356,17 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
 
   // ---- per-item registers of lane e: 32-bit offsets of the slab inside its stream and of the parameter dwords
   // inside the scale / zero arrays (each stream and array is below 4 GiB), and the item's flags
-  uint32_t it_woff = 0, it_soff = 0, it_misc = 0;
+  uint32_t it_wlo = 0, it_whi = 0, it_xhi = 0, it_soff = 0, it_misc = 0;
   {
     const uint32_t bm2 = (uint32_t)d & 3u;  // bit-width - 2 (the use of d makes the compiler wait for the loads above, here)
     const uint32_t slab_bytes = 256u * (bm2 + 2u);
     if (lane < E) {
-      // (a multiple of 256: the two low bits carry the width for issue_item, which then needs no other register)
-      it_woff = (((uint32_t)d >> 2) * (8u * slab_bytes) + (uint32_t)it_sigma * slab_bytes) | bm2;
+      // address of the slab (the choice of the stream is made here, once, by the lane that describes the item) and
+      // the upper half of the lane mask of its copy: 32, 48 or 64 lanes of 16 bytes
+      const uint64_t waddr = (uint64_t)(bm2 == 0 ? p.s2 : bm2 == 1 ? p.s3 : p.s4) +
+                             (((uint32_t)d >> 2) * (8u * slab_bytes) + (uint32_t)it_sigma * slab_bytes);
+      it_wlo = (uint32_t)waddr, it_whi = (uint32_t)(waddr >> 32);
+      it_xhi = bm2 == 0 ? 0u : bm2 == 1 ? 0xFFFFu : 0xFFFFFFFFu;
       // the aligned dword holding the fp16 scale of row 128*tr + sigma (rows 8*l + sigma are 16 bytes apart);
       // direct-to-LDS copies need dword-aligned addresses, the wanted fp16 is the low half for even sigma and
       // the high half for odd sigma
@@ -359,20 +384,13 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   // Issue item e into ring slot s: two direct global->LDS copies, the 16 scale dwords + 16 zero dwords (lanes
   // 0-15 / 16-31) and the slab (16 B per lane, 32/48/64 lanes, scalar address).
   const uint32_t ring_off = (uint32_t)(uintptr_t)(lptr_t)(rings + (size_t)wave * S * kSlotBytes);
-  const uint64_t s2b = (uint64_t)p.s2, s3b = (uint64_t)p.s3, s4b = (uint64_t)p.s4;
   auto issue_item = [&](int e, int s) __attribute__((always_inline)) {
-    const uint32_t woff_w = (uint32_t)__builtin_amdgcn_readlane((int)it_woff, e);
+    const uint32_t wlo = (uint32_t)__builtin_amdgcn_readlane((int)it_wlo, e);
+    const uint32_t whi = (uint32_t)__builtin_amdgcn_readlane((int)it_whi, e);
+    const uint32_t xhi = (uint32_t)__builtin_amdgcn_readlane((int)it_xhi, e);
     const uint32_t soff = (uint32_t)__builtin_amdgcn_readlane((int)it_soff, e);
-    const uint32_t bm2 = woff_w & 3u, woff = woff_w & ~3u;
-    // (the three bases pass through an empty statement right before the choice: as plain captured variables they
-    // sit next to each other in the closure, and the choice by width becomes an indexed load from it in scratch)
-    uint64_t b2 = s2b, b3 = s3b, b4 = s4b;
-    asm volatile("" : "+s"(b2), "+s"(b3), "+s"(b4));
-    const uint64_t wbase = (bm2 == 0 ? b2 : bm2 == 1 ? b3 : b4) + woff;
-    const uint64_t wlanes = bm2 == 0 ? 0xFFFFFFFFull : bm2 == 1 ? 0xFFFFFFFFFFFFull : ~0ull;
     const uint32_t slot = ring_off + (uint32_t)s * kSlotBytes;
-    lds_copy_b32_vaddr(par_vbase + soff, slot, 0xFFFFFFFFull);
-    lds_copy_b128(wbase, data_voff, slot + kGemvSlotParamBytes, wlanes);
+    lds_copy_item(par_vbase + soff, ((uint64_t)whi << 32) | wlo, data_voff, slot, slot + kGemvSlotParamBytes, xhi);
   };
   constexpr int kCopiesPerItem = 2;
 
@@ -450,22 +468,18 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
     float t;
     uint32_t w[4];
     const uint32_t* src;
-    switch ((misc >> 24) & 3) {
-      case 0:
-        src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w2));
-        w[0] = src[0], w[1] = src[1];
-        t = slab_dot_row0_units<2>(w, a);
-        break;
-      case 1:
-        src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w3));
-        w[0] = src[0], w[1] = src[1], w[2] = src[2];
-        t = slab_dot_row0_units<3>(w, a);
-        break;
-      default:
-        src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w4));
-        w[0] = src[0], w[1] = src[1], w[2] = src[2], w[3] = src[3];
-        t = slab_dot_row0_units<4>(w, a);
-        break;
+    if (misc & (2u << 24)) {
+      src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w4));
+      w[0] = src[0], w[1] = src[1], w[2] = src[2], w[3] = src[3];
+      t = slab_dot_row0_units<4>(w, a);
+    } else if (misc & (1u << 24)) {
+      src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w3));
+      w[0] = src[0], w[1] = src[1], w[2] = src[2];
+      t = slab_dot_row0_units<3>(w, a);
+    } else {
+      src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w2));
+      w[0] = src[0], w[1] = src[1];
+      t = slab_dot_row0_units<2>(w, a);
     }
     // low half: scale, high half: zero (bit 26 of misc: odd sigma -> the high halves of the two dwords)
     const uint32_t sel = (misc & (1u << 26)) ? 0x07060302u : 0x05040100u;
