@@ -384,12 +384,11 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   // Issue item e into ring slot s: two direct global->LDS copies, the 16 scale dwords + 16 zero dwords (lanes
   // 0-15 / 16-31) and the slab (16 B per lane, 32/48/64 lanes, scalar address).
   const uint32_t ring_off = (uint32_t)(uintptr_t)(lptr_t)(rings + (size_t)wave * S * kSlotBytes);
-  auto issue_item = [&](int e, int s) __attribute__((always_inline)) {
+  auto issue_item = [&](int e, uint32_t slot) __attribute__((always_inline)) {
     const uint32_t wlo = (uint32_t)__builtin_amdgcn_readlane((int)it_wlo, e);
     const uint32_t whi = (uint32_t)__builtin_amdgcn_readlane((int)it_whi, e);
     const uint32_t xhi = (uint32_t)__builtin_amdgcn_readlane((int)it_xhi, e);
     const uint32_t soff = (uint32_t)__builtin_amdgcn_readlane((int)it_soff, e);
-    const uint32_t slot = ring_off + (uint32_t)s * kSlotBytes;
     lds_copy_item(par_vbase + soff, ((uint64_t)whi << 32) | wlo, data_voff, slot, slot + kGemvSlotParamBytes, xhi);
   };
   constexpr int kCopiesPerItem = 2;
@@ -399,7 +398,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   // microsecond (the copies of 16 wavefronts queue up in one address unit), and the permutation would wait for it
   constexpr int kEarly = 2;
   const int npro = min(S, E);
-  for (int e = 0; e < min(kEarly, npro); ++e) issue_item(e, e);
+  for (int e = 0; e < min(kEarly, npro); ++e) issue_item(e, ring_off + (uint32_t)e * kSlotBytes);
 
   // ---- while those copies are on their way: permute the activations inside LDS and add up each tile column
   barrier_lds_only();  // every wavefront's part of the raw copy has landed (each waited for its own above)
@@ -426,7 +425,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
     }
   }
   barrier_lds_only();  // Xs and Sx are complete
-  for (int e = kEarly; e < npro; ++e) issue_item(e, e);
+  for (int e = kEarly; e < npro; ++e) issue_item(e, ring_off + (uint32_t)e * kSlotBytes);
 
   half8 a[4];
 #pragma unroll
@@ -453,10 +452,9 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   asm volatile("" : "+v"(lane_w2), "+v"(lane_w3), "+v"(lane_w4), "+v"(lane_p), "+v"(sx_lane));
   const unsigned char* lds0 = lds_raw - (uint32_t)(uintptr_t)(lptr_t)lds_raw;  // LDS byte 0
 
-  auto consume = [&](int e, int s) __attribute__((always_inline)) {
+  auto consume = [&](int e, uint32_t slot) __attribute__((always_inline)) {
     const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
     const int tc = misc & 0xFFFF;
-    const uint32_t slot = ring_off + (uint32_t)s * kSlotBytes;
     if ((lane & 15) == 0) {  // only activation row 0 exists: lanes 0,16,32,48 feed it
 #pragma unroll
       for (int kappa = 0; kappa < 4; ++kappa)
@@ -504,16 +502,25 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
 
   // ---- steady state: item e has landed once at most the S-1 younger items (2 copies each) are
   // outstanding; consume it and refill its slot with item e + S
-  int s = 0;
+  // (the LDS address of the current slot is carried along: with two slots the next one is a subtraction away)
+  uint32_t slot = ring_off;
+  auto next_slot = [&]() __attribute__((always_inline)) {
+    if constexpr (S == 2) {
+      slot = (2u * ring_off + kSlotBytes) - slot;
+    } else {
+      slot += kSlotBytes;
+      if (slot == ring_off + S * kSlotBytes) slot = ring_off;
+    }
+  };
   int e = 0;
   for (; e + S < E; ++e) {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * (S - 1)) : "memory");
     // a wavefront whose item has landed is served before one that is issuing copies or about to wait (2-3 %)
     __builtin_amdgcn_s_setprio(1);
-    consume(e, s);
+    consume(e, slot);
     __builtin_amdgcn_s_setprio(0);
-    issue_item(e + S, s);
-    if (++s == S) s = 0;
+    issue_item(e + S, slot);
+    next_slot();
   }
   // ---- tail: nothing left to issue; item e has landed once at most the E-1-e younger items are outstanding
   // (most launches of a decoder layer have no more than S items per wavefront and are all tail: waiting for
@@ -530,9 +537,9 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
       default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopiesPerItem * 7) : "memory"); break;
     }
     __builtin_amdgcn_s_setprio(1);
-    consume(e, s);
+    consume(e, slot);
     __builtin_amdgcn_s_setprio(0);
-    if (++s == S) s = 0;
+    next_slot();
   }
   static_assert(S <= 8 && kCopiesPerItem * 7 < 64, "the tail's waits cover up to 7 younger items");
 
