@@ -717,7 +717,7 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
 
   // per-item registers of lane e: 32-bit offsets of the slab inside its stream and of the parameter dwords inside
   // the scale / zero arrays, and the item's flags (as in the GEMV kernel)
-  uint32_t it_woff = 0, it_soff = 0, it_misc = 0;
+  uint32_t it_wlo = 0, it_whi = 0, it_xhi = 0, it_soff = 0, it_misc = 0;
   auto describe = [&](int e0, int Eb) {
     if (lane < Eb) {
       const int ge = e0 + lane;
@@ -729,7 +729,15 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
       const uint32_t d = (uint32_t)p.tile_desc[(int64_t)tr * p.ntc + tc];
       const uint32_t bm2 = d & 3u;
       const uint32_t slab_bytes = 256u * (bm2 + 2u);
-      it_woff = (d >> 2) * (8u * slab_bytes) + (uint32_t)sigma * slab_bytes;
+      // (address of the slab and upper half of the lane mask of its copy, as in the GEMV kernel; the three bases
+      // pass through an empty statement: chosen straight from the argument struct, the choice became an indexed load
+      // from a copy of the struct in scratch memory)
+      uint64_t b2 = (uint64_t)p.s2, b3 = (uint64_t)p.s3, b4 = (uint64_t)p.s4;
+      asm volatile("" : "+s"(b2), "+s"(b3), "+s"(b4));
+      const uint64_t waddr = (bm2 == 0 ? b2 : bm2 == 1 ? b3 : b4) +
+                             ((d >> 2) * (8u * slab_bytes) + (uint32_t)sigma * slab_bytes);
+      it_wlo = (uint32_t)waddr, it_whi = (uint32_t)(waddr >> 32);
+      it_xhi = bm2 == 0 ? 0u : bm2 == 1 ? 0xFFFFu : 0xFFFFFFFFu;
       it_soff = 2u * (uint32_t)((tc >> p.gshift) * p.N + tr * kTile + (sigma & ~1));
       it_misc = (uint32_t)tc | ((i == my_cnt - 1) ? 0x10000u : 0u) | ((uint32_t)j << 17) | (bm2 << 24) |
                 ((uint32_t)(sigma & 1) << 26);
@@ -742,20 +750,16 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   // without resident activations MB/4 KiB of staged activations of the item's tile column (scalar address)
   const uint32_t ring_off = (uint32_t)(uintptr_t)(lptr_t)(rings + (size_t)wave * S * kSlot);
   const unsigned char* ring = rings + (size_t)wave * S * kSlot;
-  const uint64_t s2b = (uint64_t)p.s2, s3b = (uint64_t)p.s3, s4b = (uint64_t)p.s4, xb = (uint64_t)p.xblk;
+  const uint64_t xb = (uint64_t)p.xblk;
   auto issue_item = [&](int e, int s) __attribute__((always_inline)) {
-    const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
-    const uint32_t woff = (uint32_t)__builtin_amdgcn_readlane((int)it_woff, e);
+    const uint32_t wlo = (uint32_t)__builtin_amdgcn_readlane((int)it_wlo, e);
+    const uint32_t whi = (uint32_t)__builtin_amdgcn_readlane((int)it_whi, e);
+    const uint32_t xhi = (uint32_t)__builtin_amdgcn_readlane((int)it_xhi, e);
     const uint32_t soff = (uint32_t)__builtin_amdgcn_readlane((int)it_soff, e);
-    const uint32_t bm2 = (misc >> 24) & 3u;
-    uint64_t b2 = s2b, b3 = s3b, b4 = s4b;  // (see the GEMV kernel: keeps the choice out of scratch memory)
-    asm volatile("" : "+s"(b2), "+s"(b3), "+s"(b4));
-    const uint64_t wbase = (bm2 == 0 ? b2 : bm2 == 1 ? b3 : b4) + woff;
-    const uint64_t wlanes = bm2 == 0 ? 0xFFFFFFFFull : bm2 == 1 ? 0xFFFFFFFFFFFFull : ~0ull;
     const uint32_t slot = ring_off + (uint32_t)s * kSlot;
-    lds_copy_b128(wbase, data_voff, slot, wlanes);
-    lds_copy_b32_vaddr(par_vbase + soff, slot + 1024, 0xFFFFFFFFull);
+    lds_copy_item(par_vbase + soff, ((uint64_t)whi << 32) | wlo, data_voff, slot + 1024, slot, xhi);
     if constexpr (!RES) {
+      const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
       const uint64_t xsrc = xb + (uint64_t)(misc & 0xFFFF) * (MB * 256);
 #pragma unroll
       for (int c = 0; c < MB / 4; ++c) lds_copy_b128(xsrc + c * 1024, data_voff, slot + kSlotBytes + c * 1024, ~0ull);
@@ -801,7 +805,7 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
       if (ui * NT < units)
         asm volatile("" : "+v"(c0[ui].x), "+v"(c0[ui].y), "+v"(c0[ui].z), "+v"(c0[ui].w), "+v"(c1[ui].x),
                      "+v"(c1[ui].y), "+v"(c1[ui].z), "+v"(c1[ui].w));
-    asm volatile("" : "+v"(it_woff), "+v"(it_soff), "+v"(it_misc));
+    asm volatile("" : "+v"(it_wlo), "+v"(it_whi), "+v"(it_xhi), "+v"(it_soff), "+v"(it_misc));
     issued_early = min(2, min(S, Eb0));
     for (int e = 0; e < issued_early; ++e) issue_item(e, e);
     barrier_lds_only();  // every wavefront's part of the raw copy has landed (each waited for its own above)
