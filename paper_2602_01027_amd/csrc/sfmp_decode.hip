@@ -167,7 +167,9 @@ struct GemvParams {
   const _Float16* zeros;
   const int32_t* row_perm;
   _Float16* Y;
-  int32_t N, K, ntr, ntc, nslab;
+  int32_t N, K, ntr, ntc;
+  // slabs of workgroup b of the problem's G workgroups: nj_q + (b < nj_r), with 8 ntr = nj_q G + nj_r (divided on the host)
+  int32_t nj_q, nj_r;
   int32_t max_slabs;  // slabs per workgroup (upper bound), sizes the reduction buffer
   int32_t gshift;     // log2(group / 128): tile column tc uses parameter row tc >> gshift
   int32_t bf16;       // scales and zeros are bfloat16 (else fp16)
@@ -282,7 +284,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   GemvParams p = p_in;
   if constexpr (!PRELOADED)
     asm volatile(""
-                 : "+s"(p.N), "+s"(p.K), "+s"(p.ntr), "+s"(p.ntc), "+s"(p.nslab), "+s"(p.max_slabs), "+s"(p.gshift),
+                 : "+s"(p.N), "+s"(p.K), "+s"(p.ntr), "+s"(p.ntc), "+s"(p.nj_q), "+s"(p.nj_r), "+s"(p.max_slabs), "+s"(p.gshift),
                    "+s"(p.bf16)
                  : "s"(p.X), "s"(p.col_perm), "s"(p.s2), "s"(p.s3), "s"(p.s4), "s"(p.tile_desc), "s"(p.scales),
                    "s"(p.zeros), "s"(p.row_perm), "s"(p.Y));
@@ -295,31 +297,37 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   float* red = reinterpret_cast<float*>(shared_region);
   unsigned char* rings = shared_region + gemv_shared_region_bytes(p.K, p.max_slabs, NW);
 
-  const int tid = threadIdx.x;
-  const int lane = tid % kWave;
-  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  // (index arithmetic below is unsigned and free of integer division: these instructions stand between the start of
+  // a wavefront and its first load, four wavefronts deep on every SIMD)
+  const uint32_t tid = threadIdx.x;
+  const uint32_t lane = tid % kWave;
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
+  const uint32_t ubid = (uint32_t)bid, uG = (uint32_t)G, untr = (uint32_t)p.ntr, untc = (uint32_t)p.ntc;
   // Virtual slab index v = bid + G*j (G is a multiple of 8, block b runs on XCD b%8): XCD x gets
   // the contiguous slab range [x*ntr, (x+1)*ntr), so the 8 slabs of a tile row run on one XCD.
-  const int nj = (p.nslab - bid + G - 1) / G;                           // slabs of this workgroup
-  const int my_cnt = p.ntc > wave ? (p.ntc - wave + NW - 1) / NW : 0;  // tiles per slab of this wavefront
-  const int E = nj * my_cnt;                                           // items of this wavefront (<= 64)
+  const int nj = p.nj_q + (bid < p.nj_r ? 1 : 0);                        // slabs of this workgroup
+  const int my_cnt = untc > wave ? (int)((untc - wave + NW - 1) / NW) : 0;  // tiles per slab of this wavefront
+  const int E = nj * my_cnt;                                             // items of this wavefront (<= 64)
 
   // ---- requests that depend on the arguments alone, all issued before the first wait
   // (1) tile descriptor of item `lane`: item e = j*my_cnt + i is tile column wave + NW*i of slab j
-  const int it_j = lane / (my_cnt > 0 ? my_cnt : 1), it_i = lane - it_j * my_cnt;
-  const int it_v = bid + G * it_j;
-  const int it_slab = (it_v % 8) * p.ntr + it_v / 8;
-  const int it_tr = it_slab / 8, it_sigma = it_slab % 8;
-  const int it_tc = wave + NW * it_i;
+  // (j = lane / my_cnt through a float reciprocal: exact, since lane + 0.5 is at least 0.5 / 64 away from a multiple
+  // of my_cnt <= 64 and the reciprocal is good to 2^-22)
+  const uint32_t it_j = (uint32_t)(((float)lane + 0.5f) * __builtin_amdgcn_rcpf((float)(my_cnt > 0 ? my_cnt : 1)));
+  const uint32_t it_i = lane - it_j * (uint32_t)my_cnt;
+  const uint32_t it_v = ubid + uG * it_j;
+  const uint32_t it_slab = (it_v % 8) * untr + it_v / 8;
+  const uint32_t it_tr = it_slab / 8, it_sigma = it_slab % 8;
+  const uint32_t it_tc = wave + NW * it_i;
   // (every load below is unconditional, from a clamped and always valid address: a load under a condition makes
   // the compiler wait for it at the end of the condition, and the requests would go out one after the other)
-  const int32_t d = p.tile_desc[lane < E ? (int64_t)it_tr * p.ntc + it_tc : (int64_t)0];
+  const int32_t d = p.tile_desc[(int)lane < E ? it_tr * untc + it_tc : 0u];
   // (2) where the sum that thread tid adds up at the end goes: output row 8*r16 + sigma of slab tid/16
-  int64_t out_row = 0;
-  if (tid < nj * 16) {
-    const int v = bid + G * (tid / 16);
-    const int slab = (v % 8) * p.ntr + v / 8;
-    out_row = (int64_t)(slab / 8) * kTile + 8 * (tid % 16) + (slab % 8);
+  uint32_t out_row = 0;
+  if (tid < (uint32_t)nj * 16) {
+    const uint32_t v = ubid + uG * (tid / 16);
+    const uint32_t slab = (v % 8) * untr + v / 8;
+    out_row = (slab / 8) * kTile + 8 * (tid % 16) + (slab % 8);
   }
   int32_t out_col = *(p.row_perm ? p.row_perm + out_row : p.tile_desc);
   // (3) activations: raw copy straight into LDS (into their final place when there is no permutation);
@@ -343,7 +351,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
     }
   }
   if constexpr (PRELOADED)  // the remaining arguments travel together with the requests above
-    asm volatile("" ::"s"(p.s2), "s"(p.s3), "s"(p.s4), "s"(p.scales), "s"(p.zeros), "s"(p.Y));
+    asm volatile("" : "+s"(p.N) : "s"(p.s2), "s"(p.s3), "s"(p.s4), "s"(p.scales), "s"(p.zeros), "s"(p.Y));
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // one trip to memory for all of the above
   // (the loaded registers are "used" here so that the compiler places its own wait for them here as well: placed
   // after the ring has been filled it would have to be a wait for every ring copy)
@@ -563,13 +571,14 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
 // requests wait for no argument load; the rest of the arguments travel while those requests are in flight.
 template <int NW, int S, bool ANYFMT>
 __global__ __launch_bounds__(NW * 64) void gemv_kernel(
-    const int32_t* tile_desc, const _Float16* X, const int32_t* col_perm, const int32_t* row_perm, int32_t nslab,
-    int32_t ntr, int32_t ntc, int32_t K, int32_t N, int32_t grid, int32_t max_slabs, int32_t gshift, int32_t bf16,
-    const uint8_t* s2, const uint8_t* s3, const uint8_t* s4, const _Float16* scales, const _Float16* zeros, _Float16* Y) {
+    const int32_t* tile_desc, const _Float16* X, const int32_t* col_perm, const int32_t* row_perm, int32_t nj_q,
+    int32_t nj_r, int32_t ntr, int32_t ntc, int32_t K, int32_t grid, int32_t N, int32_t max_slabs, int32_t gshift,
+    int32_t bf16, const uint8_t* s2, const uint8_t* s3, const uint8_t* s4, const _Float16* scales, const _Float16* zeros,
+    _Float16* Y) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   GemvParams p;
   p.X = X, p.col_perm = col_perm, p.s2 = s2, p.s3 = s3, p.s4 = s4, p.tile_desc = tile_desc, p.scales = scales;
-  p.zeros = zeros, p.row_perm = row_perm, p.Y = Y, p.N = N, p.K = K, p.ntr = ntr, p.ntc = ntc, p.nslab = nslab;
+  p.zeros = zeros, p.row_perm = row_perm, p.Y = Y, p.N = N, p.K = K, p.ntr = ntr, p.ntc = ntc, p.nj_q = nj_q, p.nj_r = nj_r;
   p.max_slabs = max_slabs, p.gshift = gshift, p.bf16 = bf16;
   gemv_body<NW, S, true, ANYFMT>(p, (int)blockIdx.x, grid, lds_raw);  // (gridDim.x would be one more load at entry)
 }
@@ -1147,7 +1156,7 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
   return d;
 }
 
-static GemvParams gemv_params(const GemmArgs& a, int32_t max_slabs) {
+static GemvParams gemv_params(const GemmArgs& a, int32_t max_slabs, int32_t grid) {
   const sfmp_layout_t* L = a.L;
   GemvParams p;
   p.X = (const _Float16*)a.X;
@@ -1164,7 +1173,8 @@ static GemvParams gemv_params(const GemmArgs& a, int32_t max_slabs) {
   p.K = L->K;
   p.ntr = L->N / kTile;
   p.ntc = L->K / kTile;
-  p.nslab = 8 * p.ntr;
+  p.nj_q = 8 * p.ntr / grid;
+  p.nj_r = 8 * p.ntr % grid;
   p.max_slabs = max_slabs;
   p.gshift = L->group == 512 ? 2 : L->group == 256 ? 1 : 0;
   p.bf16 = L->scale_format == SFMP_SCALE_BF16;
@@ -1195,8 +1205,8 @@ static int launch_gemv_function(const void* fn, bool* attr_set, void** kargs, un
 // (two instantiations of each kernel: parameters in fp16 throughout, or a storage type looked up per problem)
 static int launch_gemv_plain(GemvParams q, int32_t grid, size_t lds_bytes, void* stream) {
   static bool attr_set[2] = {false, false};
-  void* kargs[] = {&q.tile_desc, &q.X, &q.col_perm, &q.row_perm, &q.nslab, &q.ntr, &q.ntc, &q.K, &q.N, &grid,
-                   &q.max_slabs, &q.gshift, &q.bf16, &q.s2, &q.s3, &q.s4, &q.scales, &q.zeros, &q.Y};
+  void* kargs[] = {&q.tile_desc, &q.X, &q.col_perm, &q.row_perm, &q.nj_q, &q.nj_r, &q.ntr, &q.ntc, &q.K, &grid,
+                   &q.N, &q.max_slabs, &q.gshift, &q.bf16, &q.s2, &q.s3, &q.s4, &q.scales, &q.zeros, &q.Y};
   const bool any = q.bf16 != 0;
   const void* fn = any ? reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, 2, true>)
                        : reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, 2, false>);
@@ -1261,7 +1271,7 @@ int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
     const GemvFit f = gemv_fit(probs[i].L->N, probs[i].L->K, g[i]);
     if (!f.ok) return SFMP_ERR_SHAPE;
     slots = f.slots < slots ? f.slots : slots;
-    b.probs.p[i] = gemv_params(probs[i], f.max_slabs);
+    b.probs.p[i] = gemv_params(probs[i], f.max_slabs, g[i]);
     b.first[i] = first;
     first += g[i];
   }
@@ -1520,7 +1530,7 @@ int launch_decode(const GemmArgs& a, void* stream) {
   if (!decode_offsets_fit(L)) return SFMP_ERR_SHAPE;
   const DecodePlan d = make_decode_plan(L->N, L->K, a.M);
   if (d.gemv) {
-    const GemvParams p = gemv_params(a, d.max_slabs);
+    const GemvParams p = gemv_params(a, d.max_slabs, d.grid);
     return launch_gemv_plain(p, d.grid, (size_t)d.lds_bytes, stream);
   }
   return launch_rskinny(a, d, stream);
