@@ -729,13 +729,16 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   uint32_t it_wlo = 0, it_whi = 0, it_xhi = 0, it_soff = 0, it_misc = 0;
   auto describe = [&](int e0, int Eb) {
     if (lane < Eb) {
-      const int ge = e0 + lane;
-      const int j = ge / my_cnt, i = ge - j * my_cnt;
-      const int v = bid + G * j;
-      const int slab = (v % 8) * p.ntr + v / 8;
-      const int tr = slab / 8, sigma = slab % 8;
-      const int tc = wave + NW * i;
-      const uint32_t d = (uint32_t)p.tile_desc[(int64_t)tr * p.ntc + tc];
+      // (unsigned arithmetic, and ge / my_cnt through a float reciprocal: exact for ge < 2^10 and my_cnt <= 64, since
+      // ge + 0.5 is at least 0.5 / 64 away from a multiple of my_cnt; as in the GEMV kernel)
+      const uint32_t ge = (uint32_t)(e0 + lane);
+      const uint32_t j = (uint32_t)(((float)ge + 0.5f) * __builtin_amdgcn_rcpf((float)my_cnt));
+      const uint32_t i = ge - j * (uint32_t)my_cnt;
+      const uint32_t v = (uint32_t)bid + (uint32_t)G * j;
+      const uint32_t slab = (v % 8) * (uint32_t)p.ntr + v / 8;
+      const uint32_t tr = slab / 8, sigma = slab % 8;
+      const uint32_t tc = (uint32_t)wave + NW * i;
+      const uint32_t d = (uint32_t)p.tile_desc[tr * (uint32_t)p.ntc + tc];
       const uint32_t bm2 = d & 3u;
       const uint32_t slab_bytes = 256u * (bm2 + 2u);
       // (address of the slab and upper half of the lane mask of its copy, as in the GEMV kernel; the three bases
@@ -748,7 +751,7 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
       it_wlo = (uint32_t)waddr, it_whi = (uint32_t)(waddr >> 32);
       it_xhi = bm2 == 0 ? 0u : bm2 == 1 ? 0xFFFFu : 0xFFFFFFFFu;
       it_soff = 2u * (uint32_t)((tc >> p.gshift) * p.N + tr * kTile + (sigma & ~1));
-      it_misc = (uint32_t)tc | ((i == my_cnt - 1) ? 0x10000u : 0u) | ((uint32_t)j << 17) | (bm2 << 24) |
+      it_misc = (uint32_t)tc | ((i == (uint32_t)(my_cnt - 1)) ? 0x10000u : 0u) | ((uint32_t)j << 17) | (bm2 << 24) |
                 ((uint32_t)(sigma & 1) << 26);
     }
   };
