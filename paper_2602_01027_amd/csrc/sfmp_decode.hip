@@ -650,7 +650,8 @@ struct RSkinnyParams {
   const _Float16* zeros;
   const int32_t* row_perm;
   _Float16* Y;
-  int32_t M, N, K, ntr, ntc, nslab, max_slabs;
+  int32_t M, N, K, ntr, ntc, max_slabs;
+  int32_t nj_q, nj_r;  // as in GemvParams: slabs of workgroup b = nj_q + (b < nj_r)
   int32_t gshift, bf16;  // as in GemvParams
 };
 
@@ -720,7 +721,7 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int i16 = lane % 16, kb = lane / 16;
   // same slab numbering as the GEMV kernel: the 8 slabs of a tile row run on one XCD
-  const int nj = (p.nslab - bid + G - 1) / G;
+  const int nj = p.nj_q + (bid < p.nj_r ? 1 : 0);
   const int my_cnt = p.ntc > wave ? (p.ntc - wave + NW - 1) / NW : 0;
   const int E = nj * my_cnt;  // items of this wavefront, handled in batches of 64 (one lane describes one item)
 
@@ -1289,7 +1290,7 @@ int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
   return launch_gemv_batch(b, (size_t)lds, stream);
 }
 
-static RSkinnyParams rskinny_params(const GemmArgs& a, int32_t M, const void* xblk, int32_t max_slabs) {
+static RSkinnyParams rskinny_params(const GemmArgs& a, int32_t M, const void* xblk, int32_t max_slabs, int32_t grid) {
   const sfmp_layout_t* L = a.L;
   RSkinnyParams p;
   p.xblk = (const unsigned char*)xblk;
@@ -1308,7 +1309,8 @@ static RSkinnyParams rskinny_params(const GemmArgs& a, int32_t M, const void* xb
   p.K = L->K;
   p.ntr = L->N / kTile;
   p.ntc = L->K / kTile;
-  p.nslab = 8 * p.ntr;
+  p.nj_q = 8 * p.ntr / grid;
+  p.nj_r = 8 * p.ntr % grid;
   p.max_slabs = max_slabs;
   p.gshift = L->group == 512 ? 2 : L->group == 256 ? 1 : 0;
   p.bf16 = L->scale_format == SFMP_SCALE_BF16;
@@ -1333,7 +1335,7 @@ static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* 
                        (const _Float16*)a.X, a.col_perm, (unsigned char*)a.workspace, (int)a.M, (int)L->K);
     if (int e = after_launch("sfmp_gemm activation staging launch")) return e;
   }
-  RSkinnyParams p = rskinny_params(a, a.M, a.workspace, d.max_slabs);
+  RSkinnyParams p = rskinny_params(a, a.M, a.workspace, d.max_slabs, d.grid);
   void* kargs[] = {&p};
   hipError_t e = hipLaunchKernel(fn, dim3((unsigned)d.grid), dim3(NW * 64), kargs, (size_t)d.lds_bytes, (hipStream_t)stream);
   if (e != hipSuccess) {
@@ -1428,7 +1430,8 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
     const int32_t nslab = 8 * (L->N / kTile);
     const int32_t max_slabs = (nslab + g[i] - 1) / g[i];
     if (max_slabs > kGemvMaxSlabs) return SFMP_ERR_SHAPE;
-    b.p[i] = rskinny_params(probs[i], probs[i].M, (const unsigned char*)workspace + sp.offset[sp.job_of[i]], max_slabs);
+    b.p[i] = rskinny_params(probs[i], probs[i].M, (const unsigned char*)workspace + sp.offset[sp.job_of[i]], max_slabs,
+                            g[i]);
     const RSkinnyConfig cfg = {MB, NW, S, ACC, RES};
     if (max_slabs > ACC) return SFMP_ERR_SHAPE;
     const int64_t need = rskinny_lds_bytes(cfg, max_slabs, probs[i].M, L->K);
