@@ -212,3 +212,18 @@ def test_lut_pack_errors():
         S.sfmp_lut_pack(np.zeros((100, 128), dtype=np.uint8), np.array([[2]], dtype=np.int8))
     assert e.value.code == -2
     assert S.sfmp_lut_gemv_workspace(4096, 4096) % 256 == 0
+
+
+def test_float_reciprocal_item_index_is_exact():
+    """The decode kernels find the slab index of an item as floor((e + 0.5) * rcp(c)) in fp32 instead of an integer
+    division (e < 1024 items, c <= 64 tile columns per wavefront).  Exact even if the hardware reciprocal is off by
+    two units in the last place in either direction."""
+    e = np.arange(1024)
+    g = e.astype(np.float32) + np.float32(0.5)
+    for c in range(1, 65):
+        r = np.float32(1) / np.float32(c)
+        lo = np.nextafter(np.nextafter(r, np.float32(0)), np.float32(0))
+        hi = np.nextafter(np.nextafter(r, np.float32(2)), np.float32(2))
+        for rr in (lo, r, hi):
+            j = (g * np.float32(rr)).astype(np.uint32)
+            assert np.array_equal(j, e // c), c
