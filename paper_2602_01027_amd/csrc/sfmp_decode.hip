@@ -362,8 +362,8 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
                    "+v"(c1[u].z), "+v"(c1[u].w));
   asm volatile("" : "+v"(out_col));
 
-  // ---- per-item registers of lane e: 32-bit offsets of the slab inside its stream and of the parameter dwords
-  // inside the scale / zero arrays (each stream and array is below 4 GiB), and the item's flags
+  // ---- per-item registers of lane e: address of the slab, upper half of the lane mask of its copy, 32-bit offset of
+  // the parameter dwords inside the scale / zero arrays (each stream and array is below 4 GiB), and the item's flags
   uint32_t it_wlo = 0, it_whi = 0, it_xhi = 0, it_soff = 0, it_misc = 0;
   {
     const uint32_t bm2 = (uint32_t)d & 3u;  // bit-width - 2 (the use of d makes the compiler wait for the loads above, here)
@@ -725,8 +725,8 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   const int my_cnt = p.ntc > wave ? (p.ntc - wave + NW - 1) / NW : 0;
   const int E = nj * my_cnt;  // items of this wavefront, handled in batches of 64 (one lane describes one item)
 
-  // per-item registers of lane e: 32-bit offsets of the slab inside its stream and of the parameter dwords inside
-  // the scale / zero arrays, and the item's flags (as in the GEMV kernel)
+  // per-item registers of lane e: address of the slab, upper half of the lane mask of its copy, 32-bit offset of the
+  // parameter dwords inside the scale / zero arrays, and the item's flags (as in the GEMV kernel)
   uint32_t it_wlo = 0, it_whi = 0, it_xhi = 0, it_soff = 0, it_misc = 0;
   auto describe = [&](int e0, int Eb) {
     if (lane < Eb) {
