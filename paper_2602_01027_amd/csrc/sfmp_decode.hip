@@ -29,26 +29,9 @@
 
 namespace sfmp {
 
-// sum over the slab's 128 columns of q * x for the 16 rows of the slab (lane%16) and the 16
-// activation rows (4*(lane/16) + r), scaled to plain integers-times-x.
-template <int B>
-__device__ __forceinline__ floatx4 slab_dot(const uint32_t* w, const half8 (&a)[4]) {
-  uint32_t op[4][4];
-  unpack_slab<B>(w, op);
-  floatx4 c[num_classes<B>()];
-#pragma unroll
-  for (int i = 0; i < num_classes<B>(); ++i) c[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int kappa = 0; kappa < 4; ++kappa)
-    c[step_class<B>(kappa)] =
-        __builtin_amdgcn_mfma_f32_16x16x32_f16(a[kappa], as_half8(op[kappa]), c[step_class<B>(kappa)], 0, 0, 0);
-  floatx4 t = c[0] * pow2f(24 - class_pos<B>(0));
-#pragma unroll
-  for (int i = 1; i < num_classes<B>(); ++i) t += c[i] * pow2f(24 - class_pos<B>(i));
-  return t;
-}
 
-// The same sums in units of 2^-24 (class 0 counts 1, class i counts 2^-pos(i)): the caller multiplies by 2^24
+// Sum over the slab's 128 columns of q * x for the 16 rows of the slab (lane%16) and the 16 activation rows
+// (4*(lane/16) + r), in units of 2^-24 (class 0 counts 1, class i counts 2^-pos(i)): the caller multiplies by 2^24
 // once per slab instead of once per item.
 template <int B>
 __device__ __forceinline__ floatx4 slab_dot_units(const uint32_t* w, const half8 (&a)[4]) {
@@ -87,8 +70,8 @@ __device__ __forceinline__ float slab_dot_row0_units(const uint32_t* w, const ha
 }
 
 // Direct global->LDS copies written out by hand: scalar base address + 32-bit lane offset (no 64-bit vector
-// address arithmetic per copy), lanes chosen by a mask in scalar registers.  Lane l writes 16 (4) bytes at LDS byte
-// lds_off + 16 l (4 l).  EXEC is restored inside the statement.  The compiler does not count these copies: the
+// address arithmetic per copy), lanes chosen by a mask in scalar registers.  Lane l writes 16 bytes at LDS byte
+// lds_off + 16 l.  EXEC is restored inside the statement.  The compiler does not count these copies: the
 // caller waits for them with s_waitcnt vmcnt, and no compiler-placed wait stands in front of later LDS stores.
 __device__ __forceinline__ void lds_copy_b128(uint64_t sbase, uint32_t voff, uint32_t lds_off, uint64_t lanes) {
   uint64_t saved;
@@ -101,34 +84,6 @@ __device__ __forceinline__ void lds_copy_b128(uint64_t sbase, uint32_t voff, uin
       "s_mov_b64 exec, %0"
       : "=&s"(saved)
       : "s"(sbase), "v"(voff), "s"(lds_off), "s"(lanes)
-      : "memory");
-}
-__device__ __forceinline__ void lds_copy_b32(uint64_t sbase, uint32_t voff, uint32_t lds_off, uint64_t lanes) {
-  uint64_t saved;
-  asm volatile(
-      "s_mov_b64 %0, exec\n\t"
-      "s_mov_b64 exec, %4\n\t"
-      "s_mov_b32 m0, %3\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dword %2, %1\n\t"
-      "s_mov_b64 exec, %0"
-      : "=&s"(saved)
-      : "s"(sbase), "v"(voff), "s"(lds_off), "s"(lanes)
-      : "memory");
-}
-
-// the same with a full 64-bit address per lane (lanes whose addresses have no common 32-bit range)
-__device__ __forceinline__ void lds_copy_b32_vaddr(uint64_t vaddr, uint32_t lds_off, uint64_t lanes) {
-  uint64_t saved;
-  asm volatile(
-      "s_mov_b64 %0, exec\n\t"
-      "s_mov_b64 exec, %3\n\t"
-      "s_mov_b32 m0, %2\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dword %1, off\n\t"
-      "s_mov_b64 exec, %0"
-      : "=&s"(saved)
-      : "v"(vaddr), "s"(lds_off), "s"(lanes)
       : "memory");
 }
 
@@ -227,14 +182,6 @@ __device__ __forceinline__ float unit_group_sum(const half8& v) {
   return s;
 }
 
-template <int B>
-__device__ __forceinline__ float gemv_item(const unsigned char* slot, int lane, const half8 (&a)[4]) {
-  uint32_t w[B];
-  const uint32_t* src = reinterpret_cast<const uint32_t*>(slot + lane * (4 * B));
-#pragma unroll
-  for (int i = 0; i < B; ++i) w[i] = src[i];
-  return slab_dot<B>(w, a)[0];
-}
 
 // LDS stores the compiler does not see as LDS accesses.  After a direct global->LDS copy has been issued the
 // compiler puts a wait for ALL outstanding copies in front of every ordinary LDS store (it cannot tell the
