@@ -18,9 +18,15 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-tar
          "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 
+# Per-file flags.  The decode kernels' loops branch on scalar values (the width of an item, the end of a slab); left to
+# its default the compiler rewrites these branches into its structured form for divergent control flow, some eight
+# scalar instructions per item of a loop whose time is its instruction count.
+FILE_FLAGS = {"sfmp_decode.hip": ["-mllvm", "-structurizecfg-skip-uniform-regions"]}
+
+
 def _compile(src: str, objdir: str, extra) -> str:
     obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     if src.endswith(".cpp"):
         cmd.insert(1, "-x")
         cmd.insert(2, "hip")
