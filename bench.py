@@ -43,10 +43,15 @@ def parse_args():
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of HIP-graph replays")
     ap.add_argument("--separate", action="store_true",
                     help="one launch per projection (7) instead of q|k|v, o, gate|up, down sharing launches (4)")
-    ap.add_argument("--section", choices=("all", "decode", "batch", "prefill", "sweep", "lut"), default="all",
-                    help="which side reports to run after the headline measurement (for profiling one kernel "
-                         "family at a time): decode = per-projection and 70B M=1, batch = M in {4, 16}, prefill = "
-                         "M=2048; with batch or prefill the headline region runs 2 steps only")
+    ap.add_argument("--section", choices=("all", "decode", "layers", "batch", "prefill", "prefill_sweep", "sweep", "lut"),
+                    default="all",
+                    help="which reports to run after the headline measurement (for profiling one kernel family at a "
+                         "time): decode = per-projection and 70B M=1, layers = one layer of configs[2] and [3] at every "
+                         "M, batch = M in {4, 16} both ways, prefill = M=2048 on the six shapes of configs[4] "
+                         "(roofline_prefill), prefill_sweep = shorter prompts; with anything but all / decode / lut the "
+                         "headline region runs 2 steps only")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the M=2048 matrix-core measurement")
+    ap.add_argument("--prefill-launches", type=int, default=12, help="sfmp_gemm calls timed per prefill shape")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (known size) so that rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE readings can be scaled")
@@ -73,8 +78,7 @@ class Layer:
             rp = [torch.from_numpy(p.row_perm).to(device) for _ in range(replicas)] if p.row_perm is not None else None
             X = torch.from_numpy(p.X).to(device)
             Y = torch.empty((p.M, p.N), dtype=torch.float16, device=device)
-            ws = torch.empty(S.sfmp_gemm_workspace(L, p.M), dtype=torch.uint8, device=device)
-            S.sfmp_workspace_init(ws)
+            ws = torch.empty(S.sfmp_gemm_workspace(L, p.M), dtype=torch.uint8, device=device)  # contents irrelevant
             self.proj.append(dict(p=p, layout=L, reps=reps, cp=cp, rp=rp, X=X, Y=Y, ws=ws))
         torch.cuda.synchronize()
         self._args = {}
@@ -144,6 +148,16 @@ class Layer:
         return out
 
 
+def build_problems_iter(W, cid):
+    """The problems of a configuration one at a time (codes drawn directly), so that only one 70B matrix is in host
+    memory at once."""
+    spec = W.CONFIGS[cid]
+    for si, (label, K, N) in enumerate(spec.shapes):
+        yield W.make_problem(label, K, N, spec.Ms[0], 1000 * cid + si, w_std=spec.w_std[si], fractions=spec.fractions,
+                             outliers=spec.outliers, use_col_perm=spec.col_perm, use_row_perm=spec.row_perm[si],
+                             fast_codes=True)
+
+
 def build_problems(W, cid, Ms=None, fast=False, only=None, allocated_bits=None, **fmt):
     """fmt: group / scale_format / block passed on to the generator (default: group 128, fp16, 128x128 blocks).
     allocated_bits: take the bitmap from the sorting-based allocation on synthetic salience at this average width
@@ -168,40 +182,47 @@ def build_problems(W, cid, Ms=None, fast=False, only=None, allocated_bits=None, 
 FUSED_GROUPS = [[0, 1, 2], [3], [4, 5], [6]]  # q|k|v, o, gate|up, down: what a decoder layer can run together
 
 
+def do_step(layer, r, stream_ptr, groups):
+    """One step on replica r: one launch per projection (groups None), or independent projections sharing launches."""
+    if groups is None:
+        layer.step(r, stream_ptr)
+    else:
+        layer.step_fused(r, stream_ptr, groups)
+
+
+def capture_step_graphs(torch, layer, groups):
+    """One HIP graph per weight replica, each holding the launches of one step (after an eager warm-up on the capture
+    stream: module load, first touch).  The timed region replays them in rotation."""
+    stream = torch.cuda.current_stream()
+    graphs = []
+    side = torch.cuda.Stream()
+    side.wait_stream(stream)
+    with torch.cuda.stream(side):
+        for r in range(layer.replicas):
+            do_step(layer, r, side.cuda_stream, groups)
+    side.synchronize()
+    for r in range(layer.replicas):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            do_step(layer, r, torch.cuda.current_stream().cuda_stream, groups)
+        graphs.append(g)
+    torch.cuda.synchronize()
+    return graphs
+
+
 def time_steps(torch, layer, steps, warmup, use_graph, groups=None):
     """Times `steps` steps after `warmup`; returns (ms_per_step from HIP events, wall ms_per_step).
 
     groups None: one launch per projection; else independent projections share a launch."""
     R = layer.replicas
-
-    def do_step(r, sp):
-        if groups is None:
-            layer.step(r, sp)
-        else:
-            layer.step_fused(r, sp, groups)
-
     stream = torch.cuda.current_stream()
-    graphs = None
-    if use_graph:
-        graphs = []
-        side = torch.cuda.Stream()
-        side.wait_stream(stream)
-        with torch.cuda.stream(side):
-            for r in range(R):  # eager warm-up on the capture stream (module load, first-touch)
-                do_step(r, side.cuda_stream)
-        side.synchronize()
-        for r in range(R):
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=side):
-                do_step(r, torch.cuda.current_stream().cuda_stream)
-            graphs.append(g)
-        torch.cuda.synchronize()
+    graphs = capture_step_graphs(torch, layer, groups) if use_graph else None
 
     def run(i):
         if graphs is not None:
             graphs[i % R].replay()
         else:
-            do_step(i % R, stream.cuda_stream)
+            do_step(layer, i % R, stream.cuda_stream, groups)
 
     for i in range(warmup):
         run(i)
@@ -295,14 +316,31 @@ def cpu_baseline(problems):
                        f"host has {NCPU} usable cores")
 
 
-def load_traffic():
-    path = os.path.join(ROOT, "profiles", "decode_traffic.json")
-    if os.path.exists(path):
-        try:
-            return json.load(open(path)).get("bytes_per_launch")
-        except Exception:
-            return None
-    return None
+def profile_figures():
+    """Figures taken from the rocprofv3 summaries under profiles/ (kernel-trace means, counter traffic); the file names
+    its sources.  They are constants of the tracked profiles, not measured in this run."""
+    path = os.path.join(ROOT, "profiles", "bench_profile_figures.json")
+    try:
+        return json.load(open(path))
+    except Exception:
+        return {}
+
+
+def layer_line(torch, W, cid, M, steps, eager, groups):
+    """One transformer layer of configuration cid at batch M: microseconds per layer and its share of the bounds."""
+    fused = groups is not None and M <= 16
+    pb = build_problems(W, cid, Ms=(M,), fast=True)
+    bb = sum(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, index_words=p.bitmap.size) for p in pb)
+    fl = sum(2.0 * p.M * p.N * p.K for p in pb)
+    lb = Layer(pb, int(np.ceil(2 ** 30 / bb)))
+    ms, _ = time_steps(torch, lb, steps, max(2, steps // 10), use_graph=not eager, groups=groups if fused else None)
+    row = dict(M=M, us_per_layer=round(ms * 1e3, 2), launches="4 batched calls" if fused else "7 calls",
+               MB=round(bb / 1e6, 1), GBps=round(bb / ms / 1e6, 1),
+               frac_hbm_peak=round(bb / ms / 1e6 / HBM_PEAK_GBPS, 4),
+               TFLOPs=round(fl / ms / 1e9, 2), frac_mfma_peak=round(fl / ms / 1e9 / MFMA_F16_PEAK_TFLOPS, 4))
+    del lb, pb
+    torch.cuda.empty_cache()
+    return row
 
 
 def main():
@@ -316,6 +354,7 @@ def main():
     S.load_library()  # fails loudly if the HIP library is not built
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    figs = profile_figures()
 
     problems = build_problems(W, 2)
     layer_bytes = sum(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, index_words=p.bitmap.size) for p in problems)
@@ -331,12 +370,15 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     groups = None if args.separate else FUSED_GROUPS
-    if args.section in ("batch", "prefill", "sweep"):
+    if args.section in ("batch", "prefill", "sweep", "layers"):
         args.steps, args.warmup = 2, 1
     ms_step, wall_ms = time_steps(torch, layer, args.steps, args.warmup, use_graph=not args.eager, groups=groups)
     us_layer = ms_step * 1e3
     gbps = layer_bytes / (ms_step * 1e-3) / 1e9
     n_launch = len(problems) if groups is None else len(groups)
+    dec = figs.get("gemv_8b_decode", {})
+    k_us = dec.get("kernel_avg_us")
+    bytes_per_launch = layer_bytes / n_launch
 
     result = {
         "metric": "us_per_layer_M1 (Llama-3-8B-shaped decoder layer, 7 mixed 2/3/4-bit projections, avg 3.0 bits)",
@@ -368,25 +410,31 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(gbps / HBM_PEAK_GBPS, 4),
-            "traffic": load_traffic(),
-            "bytes_per_launch_avg": int(layer_bytes / n_launch),
+            "traffic": dec.get("traffic_bytes_per_launch"),
+            "bytes_per_launch_avg": int(bytes_per_launch),
             "avg_launch_us": round(us_layer / n_launch, 3),
-            "note": "achieved = algorithmic bytes of all launches of a step / HIP-event time of the step "
-                    "(launch gaps included), averaged over the timed region",
+            "kernel_avg_us": k_us,
+            "kernel_frac": round(bytes_per_launch / (k_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if k_us else None,
+            "note": "achieved / frac = algorithmic bytes of all launches of a step / HIP-event time of the step "
+                    "(launch gaps of the graph replay included), measured in this run; kernel_frac = the same bytes per "
+                    "launch / kernel_avg_us, the mean duration of the GEMV kernels in the tracked rocprofv3 kernel trace "
+                    f"({dec.get('kernel_trace_source')}; kernel time only, a constant of that profile, not measured in "
+                    f"this run); traffic = FETCH_SIZE + WRITE_SIZE per launch from {dec.get('traffic_source')} (counter "
+                    "run, also a constant of that profile)",
         },
     }
 
     # second denominator: what a plain streaming read reaches on this machine (1 GiB, cold), beside the data sheet
     try:
-        import paper_2602_01027_amd as S_
+        from paper_2602_01027_amd import probe
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
         outp = torch.empty(2048, dtype=torch.uint8, device="cuda:0")
         for _ in range(2):
-            S_.sfmp_stream_read_probe(src, outp)
+            probe.stream_read(src, outp)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(5):
-            S_.sfmp_stream_read_probe(src, outp)
+            probe.stream_read(src, outp)
         e1.record()
         torch.cuda.synchronize()
         stream_gbps = 5 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
@@ -397,33 +445,75 @@ def main():
         result["roofline"]["measured_stream_read_GBps"] = None
         result["roofline"]["measured_stream_read_error"] = str(ex)
 
+    extra = {}
+    if not args.no_extra and args.section in ("all", "decode"):
+        if groups is not None:
+            ms7, _ = time_steps(torch, layer, args.steps, args.warmup, use_graph=not args.eager, groups=None)
+            extra["seven_separate_launches_us_per_layer"] = round(ms7 * 1e3, 3)
+        per = time_each_projection(torch, layer)
+        extra["per_projection_8b_M1"] = [
+            dict(shape=f"{d['p'].K}->{d['p'].N}", label=d["p"].label, us=round(t, 3), MB=round(b / 1e6, 3),
+                 GBps=round(b / t / 1e3, 1), pct_hbm_peak=round(100 * b / t / 1e3 / HBM_PEAK_GBPS, 2))
+            for d, t, b in zip(layer.proj, per, per_proj_bytes)]
+    del layer
+    torch.cuda.empty_cache()
+
+    if not args.no_prefill and args.section in ("all", "prefill"):
+        # The matrix-core half of the metric: configs[4], M = 2048, all six shapes, one sfmp_gemm call each (staging +
+        # GEMM + row un-permute where the configuration has a row permutation), codes drawn directly (timing only).
+        rows, tot_fl, tot_t = [], 0.0, 0.0
+        kfig = figs.get("prefill_M2048", {})
+        for pp in build_problems_iter(W, 5):
+            lp = Layer([pp], 1)
+            t = time_each_projection(torch, lp, launches=args.prefill_launches)[0]
+            fl = 2.0 * pp.M * pp.N * pp.K
+            kus = kfig.get("kernel_us", {}).get(f"{pp.K}->{pp.N}")
+            rows.append(dict(shape=f"{pp.K}->{pp.N}", us=round(t, 1), GFLOP=round(fl / 1e9, 1),
+                             TFLOPs=round(fl / t / 1e6, 1), frac=round(fl / t / 1e6 / MFMA_F16_PEAK_TFLOPS, 4),
+                             kernel_us=kus,
+                             kernel_frac=round(fl / kus / 1e6 / MFMA_F16_PEAK_TFLOPS, 4) if kus else None))
+            tot_fl += fl
+            tot_t += t
+            del lp, pp
+            torch.cuda.empty_cache()
+        result["roofline_prefill"] = {
+            "bound": "mfma",
+            "kernel": "sfmp::prefill_kernel (fp16 MFMA, weights dequantised in registers) + activation staging and "
+                      "row un-permute passes",
+            "achieved": round(tot_fl / tot_t / 1e6, 1),
+            "peak": MFMA_F16_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(tot_fl / tot_t / 1e6 / MFMA_F16_PEAK_TFLOPS, 4),
+            "traffic": None,
+            "workload": "configs[4]: M=2048 on 4096->4096, 4096->1024, 4096->14336, 14336->4096, 8192->28672, "
+                        "28672->8192; 50 % 3-bit / 50 % 4-bit tiles, outlier columns",
+            "per_shape": rows,
+            "note": "achieved / frac = FLOP-weighted aggregate: total 2*M*N*K of the six shapes / total HIP-event time of "
+                    "one whole sfmp_gemm call each (graph of back-to-back calls), measured in this run; per-shape "
+                    f"kernel_us / kernel_frac = GEMM kernel alone from the tracked kernel trace ({kfig.get('source')}), "
+                    "constants of that profile",
+        }
+
     if not args.no_extra:
-        extra = {}
+        if args.section in ("all", "layers"):
+            # the pass / fail lines of the other decode configurations: one transformer layer each
+            extra["layer_8b_config3_2p5bit"] = [layer_line(torch, W, 3, M, 60 if M <= 16 else 30, args.eager, FUSED_GROUPS)
+                                                for M in (1, 4, 16, 64)]
+            extra["layer_70b_config4_3p25bit"] = [layer_line(torch, W, 4, M, 40, args.eager, FUSED_GROUPS) for M in (1, 8)]
         if args.section in ("all", "decode"):
-            if groups is not None:
-                ms7, _ = time_steps(torch, layer, args.steps, args.warmup, use_graph=not args.eager, groups=None)
-                extra["seven_separate_launches_us_per_layer"] = round(ms7 * 1e3, 3)
-            per = time_each_projection(torch, layer)
-            extra["per_projection_8b_M1"] = [
-                dict(shape=f"{d['p'].K}->{d['p'].N}", label=d["p"].label, us=round(t, 3), MB=round(b / 1e6, 3),
-                     GBps=round(b / t / 1e3, 1), pct_hbm_peak=round(100 * b / t / 1e3 / HBM_PEAK_GBPS, 2))
-                for d, t, b in zip(layer.proj, per, per_proj_bytes)]
-        del layer
-        torch.cuda.empty_cache()
-        if args.section in ("all", "decode"):
-            # 70B-shaped decode layer (configs[3]) at M = 1, codes drawn directly (timing only)
+            # 70B-shaped decode layer (configs[3]) at M = 1, one launch per projection, and every projection alone
             p70 = build_problems(W, 4, Ms=(1,), fast=True)
             b70 = sum(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, index_words=p.bitmap.size) for p in p70)
             l70 = Layer(p70, int(np.ceil(2 ** 30 / b70)))
             ms70, _ = time_steps(torch, l70, 60, 6, use_graph=not args.eager)
             per70 = time_each_projection(torch, l70, launches=24)
             b70p = l70.bytes_per_proj(W)
-            extra["layer_70b_M1"] = dict(us_per_layer=round(ms70 * 1e3, 2), MB=round(b70 / 1e6, 1),
-                                         GBps=round(b70 / ms70 / 1e6, 1),
-                                         pct_hbm_peak=round(100 * b70 / ms70 / 1e6 / HBM_PEAK_GBPS, 2),
-                                         per_projection=[dict(shape=f"{d['p'].K}->{d['p'].N}", us=round(t, 2),
-                                                              GBps=round(b / t / 1e3, 1))
-                                                         for d, t, b in zip(l70.proj, per70, b70p)])
+            extra["layer_70b_M1_seven_launches"] = dict(
+                us_per_layer=round(ms70 * 1e3, 2), MB=round(b70 / 1e6, 1), GBps=round(b70 / ms70 / 1e6, 1),
+                pct_hbm_peak=round(100 * b70 / ms70 / 1e6 / HBM_PEAK_GBPS, 2),
+                per_projection=[dict(shape=f"{d['p'].K}->{d['p'].N}", us=round(t, 2), GBps=round(b / t / 1e3, 1),
+                                     pct_hbm_peak=round(100 * b / t / 1e3 / HBM_PEAK_GBPS, 2))
+                                for d, t, b in zip(l70.proj, per70, b70p)])
             del l70, p70
             torch.cuda.empty_cache()
         if args.section in ("all", "decode"):
@@ -451,9 +541,8 @@ def main():
                 avg_bits=[round(p.avg_bits, 3) for p in pa])
             del la, pa
             torch.cuda.empty_cache()
-        if args.section in ("all", "batch"):
-            # small batches (configs[2]: 50 % 2-bit / 50 % 3-bit) through the ring-skinny kernel: 4 batched calls
-            # (q|k|v, o, gate|up, down: 8 kernels) and, for comparison, 7 separate calls (14 kernels)
+        if args.section in ("batch",):
+            # small batches (configs[2]) both ways: 4 batched calls and 7 separate calls
             rows = []
             for M in (4, 16):
                 pb = build_problems(W, 3, Ms=(M,), fast=True)
@@ -467,29 +556,15 @@ def main():
                 del lb, pb
                 torch.cuda.empty_cache()
             extra["layer_8b_small_batch"] = rows
-        if args.section in ("all", "prefill"):
-            # prefill (configs[4]) at M = 2048 on two 8B shapes, codes drawn directly (timing only)
-            pp = build_problems(W, 5, fast=True, only=("8b.gate", "8b.q"))
-            lp = Layer(pp, 2)
-            perp = time_each_projection(torch, lp, launches=24)
-            extra["prefill_M2048"] = [
-                dict(shape=f"{d['p'].K}->{d['p'].N}", us=round(t, 1),
-                     TFLOPs=round(2.0 * d["p"].M * d["p"].N * d["p"].K / t / 1e6, 1),
-                     pct_mfma_peak=round(100 * 2.0 * d["p"].M * d["p"].N * d["p"].K / t / 1e6 / MFMA_F16_PEAK_TFLOPS,
-                                         2))
-                for d, t in zip(lp.proj, perp)]
-            # the same call when the product may stay in reordered row order (the next matrix gathers from it
-            # through a folded permutation): no un-permute pass
-            pg_ = [q for q in pp if q.N == 14336][0]
+        if args.section in ("prefill_sweep",):
+            # the 4096 -> 14336 matrix at shorter prompts, and with the rows left in reordered order
+            pp = build_problems(W, 5, fast=True, only=("8b.gate",))
+            pg = pp[0]
             import dataclasses as _dc
-            lf = Layer([_dc.replace(pg_, row_perm=None)], 2)
-            tf = time_each_projection(torch, lf, launches=24)[0]
-            extra["prefill_M2048_4096x14336_rows_left_reordered_us"] = round(tf, 1)
+            lf = Layer([_dc.replace(pg, row_perm=None)], 2)
+            extra["prefill_M2048_4096x14336_rows_left_reordered_us"] = round(time_each_projection(torch, lf, launches=24)[0], 1)
             del lf
-            # the same 4096 -> 14336 matrix at shorter prompts (the workgroup-to-XCD mapping has to keep all 8 XCDs
-            # busy when there are fewer than 8 blocks of 128 rows)
             sweep = []
-            pg = [q for q in pp if q.N == 14336][0]
             for M in (128, 256, 512, 1024):
                 pm = [W.with_activations(pg, M, outliers=True)]
                 lm = Layer(pm, 2)
@@ -499,7 +574,7 @@ def main():
                                   pct_mfma_peak=round(100 * fl / t / 1e6 / MFMA_F16_PEAK_TFLOPS, 2)))
                 del lm, pm
             extra["prefill_4096x14336_M_sweep"] = sweep
-            del lp, pp
+            del pp
         if args.section in ("all", "sweep"):
             # one call of sfmp_gemm at every batch size on two 8B matrices: which kernels a given M runs is the
             # library's choice (GEMV, ring kernel, its chunked form, MFMA kernel with or without a split K)
@@ -531,6 +606,7 @@ def main():
                     rows.append(dict(shape=f"{K}->{N}", widths=label, lut_us=round(t_lut, 2), mfma_us=round(t_mfma, 2),
                                      lut_GBps=round(wbytes / t_lut / 1e3, 1)))
             extra["lut_gemv_vs_mfma_gemv_M1"] = rows
+    if extra:
         result["extra"] = extra
 
     if not args.no_cpu_baseline:

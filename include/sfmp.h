@@ -48,7 +48,8 @@
  *   lane feeds to a 16x16x32 fp16 matrix instruction.
  *
  *   Block-index table (int32 words), replacing any run-time offset computation
- *   (Appendix H attributes a <=3 % cost to computing block offsets at run time):
+ *   (Appendix G, "Comparison with LUT-based GEMM Family", attributes a <=3 % cost to computing block offsets at
+ *   run time):
  *       [0,3)                 number of tiles of width 2, 3, 4
  *       [3, 3+nt)             tile_desc[tr*(K/128)+tc] = (slot << 2) | (b-2); slot = index of
  *                             the tile inside stream S_b
@@ -78,6 +79,7 @@ extern "C" {
 #define SFMP_ERR_HIP (-6)         /* a HIP call or kernel launch failed */
 #define SFMP_ERR_PERM (-7)        /* sfmp_check_perm: not a permutation of 0..n-1 */
 #define SFMP_ERR_LAYOUT (-8)      /* layout struct inconsistent with itself */
+#define SFMP_ERR_ALIGN (-9)       /* a device pointer is not aligned as required (see sfmp_gemm) */
 
 /* Sizes of a packed matrix.  Filled by sfmp_pack_query / sfmp_pack; passed by the caller,
  * unchanged, to the device entry points. */
@@ -96,7 +98,7 @@ typedef struct sfmp_layout {
 const char* sfmp_strerror(int code);
 
 /* Host only.  Sizes of the three streams and of the index table for a bitmap
- * (int8 [N/128, K/128], row-major, host).  Section 4.3 "Extra Metadata": one int8 per block. */
+ * (int8 [N/128, K/128], row-major, host).  Section 4.2, paragraph "Extra Metadata": one int8 per block. */
 int sfmp_pack_query(const int8_t* bitmap_host, int32_t N, int32_t K, sfmp_layout_t* out);
 
 /* Host only.  Chooses the quantisation-parameter format of a layout filled by sfmp_pack_query / sfmp_pack
@@ -141,13 +143,24 @@ int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream);
  *   layout, s2, s3, s4, index   a matrix packed by sfmp_pack, uploaded unchanged.
  *   scales, zeros  16-bit [K/group, N] (group-major; group and storage type from the layout, fp16 and 128
  *             unless sfmp_layout_set_quant said otherwise): w_hat = s*q + z (Appendix B Eq. 11).
- *   bitmap    int8 [N/128, K/128] (device); must be the bitmap the matrix was packed with.
+ *   bitmap    int8 [N/128, K/128] (device), the bitmap the matrix was packed with, or NULL.  It is part of the
+ *             operation's statement (Section 4.2 "Extra Metadata": one int8 per block) but no kernel reads it: the
+ *             block-index table that sfmp_pack derived from it carries every tile's width and position, and is
+ *             the authority.  A bitmap that disagrees with the index table is not detected.
  *   row_perm  int32 [N]; output feature i of the reordered product is stored at column
  *             row_perm[i] of Y (undoing P_row of Eq. 9); NULL = leave the rows reordered.
  *   Y         fp16 [M, N] row-major; fully overwritten.  fp32 accumulation, one
  *             round-to-nearest-even conversion at the end.
  *   workspace device memory of at least sfmp_gemm_workspace() bytes, 256-byte aligned; contents
  *             on entry are irrelevant, contents on return are unspecified.
+ * Alignment (SFMP_ERR_ALIGN otherwise): X, col_perm, row_perm, s2, s3, s4, scales and zeros 16 bytes (the kernels
+ * read them with 16-byte vector loads and direct global-to-LDS copies); index 4 bytes; Y 2 bytes for M <= 16 and
+ * 16 bytes for M > 16 (whole 16-byte row segments are stored there).
+ * Number range: for M <= 16 scales and zeros are widened to fp32 and never rounded.  For M > 16 on the matrix-core
+ * path the dequantised weight s*q + z is formed and rounded ONCE in fp16 (bf16 parameters are converted to fp16 first,
+ * which is exact inside fp16's normal range): scales, zeros and weights must lie within fp16's normal range,
+ * 2^-14 <= |v| <= 65504 (or be 0), to keep full precision; below it a weight carries an absolute error of up to 2^-25,
+ * above it it overflows.
  * M = 1 runs the bandwidth-bound GEMV kernel, 2 <= M <= 16 (and M = 1 with K above about 32k) the
  * same scheme with the activations staged per tile column, 16 < M <= 128 on narrow matrices with
  * K >= 4096 (N <= 1024: M <= 128; N <= 4096: M <= 32) that kernel once more, on chunks of 16 rows side
@@ -155,7 +168,8 @@ int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream);
  * cut into ranges and fp32 partial products in the workspace when there would be few workgroups;
  * SFMP_ERR_SHAPE there if K > 57344, or, with a row permutation or a split K, N > 81920; the kernels for
  * M <= 16 and for the chunked form return SFMP_ERR_SHAPE if N * K >= 2^33).
- * Asynchronous on hip_stream; holds no global state.  The permutations are not checked for
+ * Asynchronous on hip_stream; re-entrant and thread-safe.  The only state kept between calls is a mutex-guarded
+ * record, per device, of the kernels whose LDS limit has been raised.  The permutations are not checked for
  * being bijections (out-of-range entries are the caller's error; use sfmp_check_perm). */
 int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
               const void* s2_dev, const void* s3_dev, const void* s4_dev, const int32_t* index_dev,
@@ -199,19 +213,13 @@ int sfmp_gemm_batched_workspace(const sfmp_gemv_problem_t* problems_host, int32_
 int sfmp_gemm_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, int32_t M, void* workspace_dev,
                       int64_t workspace_bytes, void* hip_stream);
 
-/* Measurement aid, not part of the product path (Section 4.4 compares kernels by latency; a bandwidth-bound
- * kernel is judged here against what the memory system delivers): reads bytes (a multiple of 16) from src_dev
- * once with plain streaming loads and writes 2048 bytes of check words to out_dev, so that a bench can time it
- * and report the streaming-read bandwidth of this machine beside the data-sheet figure.  Asynchronous. */
-int sfmp_stream_read_probe(const void* src_dev, int64_t bytes, void* out_dev, void* hip_stream);
-
 /* Host only.  SFMP_OK if perm_host[0..n) is a permutation of 0..n-1, else SFMP_ERR_PERM. */
 int sfmp_check_perm(const int32_t* perm_host, int32_t n);
 
 /* Host only.  Folds the row permutation of one matrix into the column permutation of the next, so that the
  * first product can stay in reordered row order (row_perm_dev = NULL: no un-permute pass) and the second
  * gathers from it directly (Section 3.4: the reordering is applied to activations and undone on outputs; the
- * overhead analysis of Appendix E counts exactly these two reorder operations per layer):
+ * reorder-overhead measurement of Section 4.2 counts exactly these two reorder operations per layer):
  *   folded[j] = inverse(row_perm_prev)[col_perm_next[j]],   j in [0, n)
  * so that  Xt[:, folded[j]] = X[:, col_perm_next[j]]  whenever  Xt[:, i] = X[:, row_perm_prev[i]],  which holds
  * for Xt = f(Yt), X = f(Y) with any element-wise f between the two matrices (a per-feature weight, as in a norm,

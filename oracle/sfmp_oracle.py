@@ -135,7 +135,7 @@ def dequant_rows(codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray, rows:
 
 def fold_perms(row_perm_prev: np.ndarray, col_perm_next: Optional[np.ndarray]) -> np.ndarray:
     """The column permutation that lets a matrix read the previous product while it is still in reordered row
-    order (Section 3.4; the two reorder operations per layer of Appendix E collapse into one gather).
+    order (Section 3.4; the two reorder operations per layer whose overhead Section 4.2 measures collapse into one gather).
 
     Written from its defining property, by search: folded[j] is the position i at which the reordered product
     holds the feature that the plain gather would fetch, i.e. the i with row_perm_prev[i] == col_perm_next[j]."""

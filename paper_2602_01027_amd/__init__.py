@@ -23,7 +23,6 @@ from .binding import (  # noqa: F401
     make_gemv_batch,
     sfmp_check_perm,
     sfmp_fold_perms,
-    sfmp_stream_read_probe,
     sfmp_lut_pack,
     sfmp_lut_gemv_workspace,
     sfmp_lut_gemv,

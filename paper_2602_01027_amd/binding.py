@@ -35,7 +35,7 @@ class SfmpGemvProblem(C.Structure):
 
 EXPORTS = ("sfmp_strerror", "sfmp_pack_query", "sfmp_layout_set_quant", "sfmp_pack", "sfmp_unpack", "sfmp_gemm_workspace",
            "sfmp_workspace_init", "sfmp_gemm", "sfmp_gemv_batched", "sfmp_gemm_batched_workspace",
-           "sfmp_gemm_batched", "sfmp_check_perm", "sfmp_fold_perms", "sfmp_stream_read_probe", "sfmp_lut_pack_query",
+           "sfmp_gemm_batched", "sfmp_check_perm", "sfmp_fold_perms", "sfmp_lut_pack_query",
            "sfmp_lut_pack", "sfmp_lut_gemv_workspace", "sfmp_lut_gemv")
 
 
@@ -70,7 +70,6 @@ def load_library():
     lib.sfmp_lut_gemv_workspace.argtypes = [i32, i32, C.POINTER(i64)]
     lib.sfmp_lut_gemv.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.sfmp_fold_perms.argtypes = [vp, vp, i32, vp]
-    lib.sfmp_stream_read_probe.argtypes = [vp, i64, vp, vp]
     for name in EXPORTS:
         if name != "sfmp_strerror":
             getattr(lib, name).restype = C.c_int
@@ -198,13 +197,6 @@ def sfmp_gemm_workspace(layout: SfmpLayout, M: int) -> int:
 def sfmp_workspace_init(workspace, stream=None) -> None:
     nbytes = workspace.numel() * workspace.element_size()
     _check(load_library().sfmp_workspace_init(_dev_ptr(workspace), nbytes, _stream_ptr(stream)))
-
-
-def sfmp_stream_read_probe(src, out, stream=None) -> None:
-    """Measurement aid: reads `src` (device tensor, a multiple of 16 bytes) once; `out` = at least 2048 bytes."""
-    nbytes = src.numel() * src.element_size()
-    assert out.numel() * out.element_size() >= 2048
-    _check(load_library().sfmp_stream_read_probe(_dev_ptr(src), nbytes, _dev_ptr(out), _stream_ptr(stream)))
 
 
 def sfmp_gemm(X, col_perm, layout: SfmpLayout, s2, s3, s4, index, scales, zeros, bitmap, row_perm, Y, workspace,

@@ -9,6 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsfmp.so")
+PROBE_LIB = os.path.join(HERE, "libsfmp_probe.so")  # the benchmark's streaming-read probe, not part of the product
 SOURCES = ["sfmp_host.cpp", "sfmp_unpack.hip", "sfmp_decode.hip", "sfmp_prefill.hip", "sfmp_lut.hip", "sfmp_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off for all device code of this library
@@ -53,6 +54,14 @@ def build(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError("link failed")
     if verbose:
         print("built", LIB)
+    probe_obj = _compile("sfmp_probe.hip", objdir, list(extra_flags))
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", probe_obj, "-o", PROBE_LIB],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        sys.stderr.write(r.stdout + r.stderr)
+        raise RuntimeError("link of the probe library failed")
+    if verbose:
+        print("built", PROBE_LIB)
     return LIB
 
 

@@ -1,11 +1,37 @@
 // extern "C" device entry points: argument checks, workspace sizing, path selection.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+#include <utility>
+#include <vector>
+
 #include "sfmp_internal.h"
 
 using namespace sfmp;
 
 static bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+namespace sfmp {
+int allow_full_lds(const void* fn, const char* what) {
+  static std::mutex mu;
+  static std::vector<std::pair<int, const void*>> done;  // (device, kernel) pairs whose limit has been raised
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    note_hip_error(what, "hipGetDevice failed");
+    return SFMP_ERR_HIP;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  for (const auto& d : done)
+    if (d.first == dev && d.second == fn) return SFMP_OK;
+  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e != hipSuccess) {
+    note_hip_error(what, hipGetErrorString(e));
+    return SFMP_ERR_HIP;
+  }
+  done.emplace_back(dev, fn);
+  return SFMP_OK;
+}
+}  // namespace sfmp
 
 extern "C" {
 
@@ -16,7 +42,7 @@ int sfmp_unpack(const sfmp_layout_t* layout, const void* s2_dev, const void* s3_
   if ((layout->count2 && !s2_dev) || (layout->count3 && !s3_dev) || (layout->count4 && !s4_dev)) return SFMP_ERR_NULL;
   if (!aligned(s2_dev, 16) || !aligned(s3_dev, 16) || !aligned(s4_dev, 16) || !aligned(codes_dev, 8) ||
       !aligned(index_dev, 4))
-    return SFMP_ERR_SHAPE;
+    return SFMP_ERR_ALIGN;
   return launch_unpack(layout, (const uint8_t*)s2_dev, (const uint8_t*)s3_dev, (const uint8_t*)s4_dev, index_dev,
                        codes_dev, hip_stream);
 }
@@ -41,12 +67,6 @@ int sfmp_gemm_workspace(const sfmp_layout_t* layout, int32_t M, int64_t* bytes) 
   return SFMP_OK;
 }
 
-int sfmp_stream_read_probe(const void* src_dev, int64_t bytes, void* out_dev, void* hip_stream) {
-  if (!src_dev || !out_dev) return SFMP_ERR_NULL;
-  if (bytes < 16 || (bytes % 16) != 0 || !aligned(src_dev, 16) || !aligned(out_dev, 4)) return SFMP_ERR_SHAPE;
-  return launch_stream_read(src_dev, bytes, out_dev, hip_stream);
-}
-
 int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream) {
   if (!workspace_dev) return SFMP_ERR_NULL;
   if (bytes < 0 || (bytes % 16) != 0 || !aligned(workspace_dev, 256)) return SFMP_ERR_WORKSPACE;
@@ -56,14 +76,16 @@ int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream) {
 static int check_gemm_pointers(const void* X_dev, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
                                const void* s2_dev, const void* s3_dev, const void* s4_dev, const int32_t* index_dev,
                                const void* scales_dev, const void* zeros_dev, const int8_t* bitmap_dev,
-                               const int32_t* row_perm_dev, const void* Y_dev) {
+                               const int32_t* row_perm_dev, const void* Y_dev, int32_t M) {
   if (int e = check_layout(layout)) return e;
-  if (!X_dev || !index_dev || !scales_dev || !zeros_dev || !bitmap_dev || !Y_dev) return SFMP_ERR_NULL;
+  (void)bitmap_dev;  // not read: the block-index table carries every tile's width
+  if (!X_dev || !index_dev || !scales_dev || !zeros_dev || !Y_dev) return SFMP_ERR_NULL;
   if ((layout->count2 && !s2_dev) || (layout->count3 && !s3_dev) || (layout->count4 && !s4_dev)) return SFMP_ERR_NULL;
+  // 16-byte vector loads / stores on everything but Y at M <= 16 (2-byte stores there)
   if (!aligned(s2_dev, 16) || !aligned(s3_dev, 16) || !aligned(s4_dev, 16) || !aligned(scales_dev, 16) ||
-      !aligned(zeros_dev, 16) || !aligned(X_dev, 16) || !aligned(Y_dev, 2) || !aligned(col_perm_dev, 16) ||
-      !aligned(row_perm_dev, 16) || !aligned(index_dev, 4))
-    return SFMP_ERR_SHAPE;
+      !aligned(zeros_dev, 16) || !aligned(X_dev, 16) || !aligned(Y_dev, M > kDecodeMaxM ? 16 : 2) ||
+      !aligned(col_perm_dev, 16) || !aligned(row_perm_dev, 16) || !aligned(index_dev, 4))
+    return SFMP_ERR_ALIGN;
   return SFMP_OK;
 }
 
@@ -73,7 +95,7 @@ static int marshal_batch(const sfmp_gemv_problem_t* problems_host, int32_t count
   for (int i = 0; i < count; ++i) {
     const sfmp_gemv_problem_t& q = problems_host[i];
     if (int e = check_gemm_pointers(q.X_dev, q.col_perm_dev, q.layout, q.s2_dev, q.s3_dev, q.s4_dev, q.index_dev,
-                                    q.scales_dev, q.zeros_dev, q.bitmap_dev, q.row_perm_dev, q.Y_dev))
+                                    q.scales_dev, q.zeros_dev, q.bitmap_dev, q.row_perm_dev, q.Y_dev, 1))
       return e;
     GemmArgs& a = args[i];
     a.X = q.X_dev;
@@ -124,18 +146,11 @@ int sfmp_gemm_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, i
   return launch_decode_batched(args, count, M, workspace_dev, hip_stream);
 }
 
-int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
-              const void* s2_dev, const void* s3_dev, const void* s4_dev, const int32_t* index_dev,
-              const void* scales_dev, const void* zeros_dev, const int8_t* bitmap_dev, const int32_t* row_perm_dev,
-              void* Y_dev, void* workspace_dev, int64_t workspace_bytes, void* hip_stream) {
-  if (int e = check_layout(layout)) return e;
-  if (M < 1) return SFMP_ERR_SHAPE;
-  if (int e = check_gemm_pointers(X_dev, col_perm_dev, layout, s2_dev, s3_dev, s4_dev, index_dev, scales_dev,
-                                  zeros_dev, bitmap_dev, row_perm_dev, Y_dev))
-    return e;
-  int64_t need = 0;
-  if (int e = sfmp_gemm_workspace(layout, M, &need)) return e;
-  if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < need) return SFMP_ERR_WORKSPACE;
+static int gemm_with_workspace(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
+                               const void* s2_dev, const void* s3_dev, const void* s4_dev, const int32_t* index_dev,
+                               const void* scales_dev, const void* zeros_dev, const int8_t* bitmap_dev,
+                               const int32_t* row_perm_dev, void* Y_dev, void* workspace_dev, int64_t workspace_bytes,
+                               void* hip_stream) {
   GemmArgs a;
   a.X = X_dev;
   a.M = M;
@@ -155,6 +170,22 @@ int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const s
   if (M <= kDecodeMaxM) return launch_decode(a, hip_stream);
   if (use_chunked_decode(layout->N, layout->K, M)) return launch_decode_chunked(a, hip_stream);
   return launch_prefill(a, hip_stream);
+}
+
+int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
+              const void* s2_dev, const void* s3_dev, const void* s4_dev, const int32_t* index_dev,
+              const void* scales_dev, const void* zeros_dev, const int8_t* bitmap_dev, const int32_t* row_perm_dev,
+              void* Y_dev, void* workspace_dev, int64_t workspace_bytes, void* hip_stream) {
+  if (int e = check_layout(layout)) return e;
+  if (M < 1) return SFMP_ERR_SHAPE;
+  if (int e = check_gemm_pointers(X_dev, col_perm_dev, layout, s2_dev, s3_dev, s4_dev, index_dev, scales_dev,
+                                  zeros_dev, bitmap_dev, row_perm_dev, Y_dev, M))
+    return e;
+  int64_t need = 0;
+  if (int e = sfmp_gemm_workspace(layout, M, &need)) return e;
+  if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < need) return SFMP_ERR_WORKSPACE;
+  return gemm_with_workspace(X_dev, M, col_perm_dev, layout, s2_dev, s3_dev, s4_dev, index_dev, scales_dev, zeros_dev,
+                             bitmap_dev, row_perm_dev, Y_dev, workspace_dev, workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

@@ -69,6 +69,8 @@ __device__ __forceinline__ float slab_dot_row0_units(const uint32_t* w, const ha
   return t;
 }
 
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"  // m0 is named as clobbered on purpose
 // Direct global->LDS copies written out by hand: scalar base address + 32-bit lane offset (no 64-bit vector
 // address arithmetic per copy), lanes chosen by a mask in scalar registers.  Lane l writes 16 bytes at LDS byte
 // lds_off + 16 l.  EXEC is restored inside the statement.  The compiler does not count these copies: the
@@ -84,7 +86,7 @@ __device__ __forceinline__ void lds_copy_b128(uint64_t sbase, uint32_t voff, uin
       "s_mov_b64 exec, %0"
       : "=&s"(saved)
       : "s"(sbase), "v"(voff), "s"(lds_off), "s"(lanes)
-      : "memory");
+      : "memory", "m0");
 }
 
 // The two copies of a GEMV item in one statement: 32 parameter dwords (lanes 0-31, a full 64-bit address per lane) to
@@ -105,8 +107,9 @@ __device__ __forceinline__ void lds_copy_item(uint64_t par_vaddr, uint64_t slab_
       "s_mov_b32 exec_hi, %0"
       : "=&s"(saved)
       : "v"(par_vaddr), "s"(slab_sbase), "s"(lds_off), "s"(lds_off_slab), "s"(hi_lanes), "v"(slab_voff)
-      : "memory");
+      : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // ============================================================================================
 // GEMV, M = 1
@@ -1134,16 +1137,8 @@ static GemvParams gemv_params(const GemmArgs& a, int32_t max_slabs, int32_t grid
 
 static_assert(kGemvMinSlots == 2 && kGemvMaxSlots == 2, "the GEMV kernels are instantiated for two ring slots");
 
-static int launch_gemv_function(const void* fn, bool* attr_set, void** kargs, unsigned grid, size_t lds_bytes,
-                                void* stream) {
-  if (!*attr_set) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) {
-      note_hip_error("hipFuncSetAttribute(gemv)", hipGetErrorString(e));
-      return SFMP_ERR_HIP;
-    }
-    *attr_set = true;
-  }
+static int launch_gemv_function(const void* fn, void** kargs, unsigned grid, size_t lds_bytes, void* stream) {
+  if (int e = allow_full_lds(fn, "hipFuncSetAttribute(gemv)")) return e;
   hipError_t e = hipLaunchKernel(fn, dim3(grid), dim3(kGemvWaves * 64), kargs, lds_bytes, (hipStream_t)stream);
   if (e != hipSuccess) {
     note_hip_error("sfmp gemv launch", hipGetErrorString(e));
@@ -1155,24 +1150,22 @@ static int launch_gemv_function(const void* fn, bool* attr_set, void** kargs, un
 // gemv_kernel over `grid` workgroups (the order of kargs is the kernel's parameter list)
 // (two instantiations of each kernel: parameters in fp16 throughout, or a storage type looked up per problem)
 static int launch_gemv_plain(GemvParams q, int32_t grid, size_t lds_bytes, void* stream) {
-  static bool attr_set[2] = {false, false};
   void* kargs[] = {&q.tile_desc, &q.X, &q.col_perm, &q.row_perm, &q.nj_q, &q.nj_r, &q.ntr, &q.ntc, &q.K, &grid,
                    &q.N, &q.max_slabs, &q.gshift, &q.bf16, &q.s2, &q.s3, &q.s4, &q.scales, &q.zeros, &q.Y};
   const bool any = q.bf16 != 0;
   const void* fn = any ? reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, 2, true>)
                        : reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, 2, false>);
-  return launch_gemv_function(fn, &attr_set[any], kargs, (unsigned)grid, lds_bytes, stream);
+  return launch_gemv_function(fn, kargs, (unsigned)grid, lds_bytes, stream);
 }
 
 static int launch_gemv_batch(GemvBatch b, size_t lds_bytes, void* stream) {
-  static bool attr_set[2] = {false, false};
   void* kargs[] = {&b.first[1], &b.first[2], &b.first[3], &b.first[4], &b.first[5],
                    &b.first[6], &b.first[7], &b.first[8], &b.probs};
   bool any = false;
   for (int i = 0; i < b.count; ++i) any = any || b.probs.p[i].bf16 != 0;
   const void* fn = any ? reinterpret_cast<const void*>(&gemv_batched_kernel<kGemvWaves, 2, true>)
                        : reinterpret_cast<const void*>(&gemv_batched_kernel<kGemvWaves, 2, false>);
-  return launch_gemv_function(fn, &attr_set[any], kargs, (unsigned)b.first[kGemvMaxBatch], lds_bytes, stream);
+  return launch_gemv_function(fn, kargs, (unsigned)b.first[kGemvMaxBatch], lds_bytes, stream);
 }
 
 // Splits the 256 workgroups of a persistent launch between `count` problems in units of 8 (one per XCD), greedily to
@@ -1267,16 +1260,8 @@ static RSkinnyParams rskinny_params(const GemmArgs& a, int32_t M, const void* xb
 template <int NW, int S, int MB, bool RES, int ACC>
 static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* stream) {
   const sfmp_layout_t* L = a.L;
-  static bool attr_set = false;
   const void* fn = reinterpret_cast<const void*>(&rskinny_kernel<NW, S, MB, RES, ACC>);
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) {
-      note_hip_error("hipFuncSetAttribute(skinny)", hipGetErrorString(e));
-      return SFMP_ERR_HIP;
-    }
-    attr_set = true;
-  }
+  if (int e = allow_full_lds(fn, "hipFuncSetAttribute(skinny)")) return e;
   if (!RES) {
     hipLaunchKernelGGL((stage_rows_kernel<MB>), dim3((unsigned)(L->K / kTile)), dim3(MB * 16), 0, (hipStream_t)stream,
                        (const _Float16*)a.X, a.col_perm, (unsigned char*)a.workspace, (int)a.M, (int)L->K);
@@ -1389,16 +1374,8 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
   for (int i = count; i <= kGemvMaxBatch; ++i) b.first[i] = first;
   for (int i = count; i < kGemvMaxBatch; ++i) b.p[i] = b.p[0];
   if (lds > 160 * 1024) return SFMP_ERR_SHAPE;
-  static bool attr_set = false;
   const void* fn = reinterpret_cast<const void*>(&rskinny_batched_kernel<NW, S, MB, RES, ACC>);
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) {
-      note_hip_error("hipFuncSetAttribute(skinny batched)", hipGetErrorString(e));
-      return SFMP_ERR_HIP;
-    }
-    attr_set = true;
-  }
+  if (int e = allow_full_lds(fn, "hipFuncSetAttribute(skinny batched)")) return e;
   if (!RES) {
     hipLaunchKernelGGL((stage_rows_batched_kernel<MB>), dim3((unsigned)sfirst), dim3(MB * 16), 0, (hipStream_t)stream, sb);
     if (int e = after_launch("sfmp_gemm_batched activation staging launch")) return e;

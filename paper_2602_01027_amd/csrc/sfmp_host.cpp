@@ -95,6 +95,7 @@ const char* sfmp_strerror(int code) {
       return buf;
     case SFMP_ERR_PERM: return "not a permutation of 0..n-1";
     case SFMP_ERR_LAYOUT: return "layout struct is inconsistent";
+    case SFMP_ERR_ALIGN: return "a device pointer is not aligned as the header requires (16 bytes for most)";
     default: return "unknown sfmp error code";
   }
 }

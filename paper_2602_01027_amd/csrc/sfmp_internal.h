@@ -37,11 +37,12 @@ PrefillPlan make_prefill_plan(int32_t N, int32_t K, int32_t M);
 
 constexpr int32_t kDecodeMaxM = 16;
 
-inline int64_t round_up_256(int64_t v) { return (v + 255) / 256 * 256; }
+// Raises the dynamic-LDS limit of kernel `fn` to the 160 KiB of a gfx950 compute unit.  Done once per (device,
+// kernel): the record of what has been done is the only state the library keeps between calls; it is guarded by a
+// mutex, so calls from several threads and on several devices are safe.  SFMP_OK or SFMP_ERR_HIP.
+int allow_full_lds(const void* fn, const char* what);
 
-// measurement aid (streaming-read probe): grid of the probe kernel = words it writes to its output
-constexpr int32_t kStreamReadGrid = 512;
-int launch_stream_read(const void* src, int64_t bytes, void* out, void* stream);
+inline int64_t round_up_256(int64_t v) { return (v + 255) / 256 * 256; }
 
 }  // namespace sfmp
 

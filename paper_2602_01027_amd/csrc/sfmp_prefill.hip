@@ -634,20 +634,11 @@ int launch_prefill(const GemmArgs& a, void* stream) {
   if (((a.row_perm || plan.ksplit > 1) && (int64_t)L->N * 2 > 160 * 1024) ||
       L->K / kTile > kPrefillMaxTiles)
     return SFMP_ERR_SHAPE;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_cols_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&scatter_cols_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e2 == hipSuccess)
-      e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&reduce_split_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e1 != hipSuccess || e2 != hipSuccess) {
-      note_hip_error("hipFuncSetAttribute(gather/scatter)", hipGetErrorString(e1 != hipSuccess ? e1 : e2));
-      return SFMP_ERR_HIP;
-    }
-    attr_set = true;
+  if (int e = allow_full_lds(reinterpret_cast<const void*>(&gather_cols_kernel), "hipFuncSetAttribute(gather)")) return e;
+  if (plan.ksplit > 1) {
+    if (int e = allow_full_lds(reinterpret_cast<const void*>(&reduce_split_kernel), "hipFuncSetAttribute(reduce)")) return e;
+  } else if (a.row_perm) {
+    if (int e = allow_full_lds(reinterpret_cast<const void*>(&scatter_cols_kernel), "hipFuncSetAttribute(scatter)")) return e;
   }
   // activations -> workspace: column permutation applied (if any), 128x128 blocks each contiguous
   _Float16* Xp = (_Float16*)a.workspace;

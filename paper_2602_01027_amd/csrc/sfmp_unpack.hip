@@ -78,39 +78,6 @@ int launch_unpack(const sfmp_layout_t* L, const uint8_t* s2, const uint8_t* s3, 
   return check_launch("sfmp_unpack launch");
 }
 
-// Measurement aid: reads `n16` 16-byte words once (persistent grid, 4 independent loads in flight per thread) and
-// writes one word per workgroup, so that a bench can print the streaming-read bandwidth this machine really
-// reaches beside the 8 TB/s of the data sheet.
-__global__ __launch_bounds__(1024) void stream_read_kernel(const u32x4* __restrict__ src, int64_t n16, uint32_t* out) {
-  const int64_t stride = (int64_t)gridDim.x * 1024;
-  uint32_t acc = 0;
-  int64_t i = (int64_t)blockIdx.x * 1024 + threadIdx.x;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride),
-                c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
-    const u32x4 x = a ^ b ^ c ^ d;
-    acc ^= x[0] ^ x[1] ^ x[2] ^ x[3];
-  }
-  for (; i < n16; i += stride) {
-    const u32x4 a = __builtin_nontemporal_load(src + i);
-    acc ^= a[0] ^ a[1] ^ a[2] ^ a[3];
-  }
-  __shared__ uint32_t red[1024];
-  red[threadIdx.x] = acc;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t r = 0;
-    for (int t = 0; t < 1024; ++t) r ^= red[t];
-    out[blockIdx.x] = r;
-  }
-}
-
-int launch_stream_read(const void* src, int64_t bytes, void* out, void* stream) {
-  hipLaunchKernelGGL(stream_read_kernel, dim3(kStreamReadGrid), dim3(1024), 0, (hipStream_t)stream, (const u32x4*)src,
-                     bytes / 16, (uint32_t*)out);
-  return check_launch("sfmp_stream_read_probe launch");
-}
-
 int launch_fill_zero(void* ptr, int64_t bytes, void* stream) {
   const int64_t n16 = bytes / 16;
   if (n16 == 0) return SFMP_OK;

@@ -8,7 +8,7 @@ that a weight matrix is stored [N, K] = [output features, input features]):
   ``Wt[i, j] = W[row_perm[i], col_perm[j]]``.
 * ``bitmap``   int8 ``[N/128, K/128]`` holding the literal bit-width 2, 3 or 4 of
   every 128x128 tile of ``Wt`` (Section 3.3 block-wise allocation; one int8
-  per block as in the metadata paragraph of Section 4.3).
+  per block as in the "Extra Metadata" paragraph of Section 4.2).
 * ``codes``    uint8 ``[N, K]`` integer codes of ``Wt``; ``scales`` / ``zeros``
   ``[K/G, N]``: one (s, z) pair per row per group of G reordered columns (G = 128 by
   default; 256 and 512 as in the paper's ablation of the block width n_b, which is also its
@@ -374,7 +374,7 @@ def algorithmic_bytes(N: int, K: int, M: int, bitmap: np.ndarray, *, col_perm: b
 
 
 def metadata_bits_per_weight(shapes: Sequence[Tuple[int, int]], block_rows: int = 512, block_cols: int = 128) -> float:
-    """Bit-width map + reorder vectors, in bits per weight (Section 4.3 metadata paragraph).
+    """Bit-width map + reorder vectors, in bits per weight (Section 4.2, paragraph "Extra Metadata").
 
     One int8 per (block_rows x block_cols) block and two 16-bit reorder vectors per matrix.
     """

@@ -1,5 +1,11 @@
-"""Helpers for the GPU parity tests: upload a problem, call the C ABI through the binding."""
+"""Helpers for the GPU parity tests: upload a problem, call the C ABI through the binding, and compare an
+output with the CPU oracle (whole-output and per-tile-row Frobenius error, and a derived per-element bound)."""
 import numpy as np
+
+TOL = 2e-3          # stated acceptance bound: relative Frobenius error against the float64 oracle
+U16 = 2.0 ** -11    # unit roundoff of fp16 (round to nearest)
+U32 = 2.0 ** -24    # unit roundoff of fp32
+FLOOR16 = 2.0 ** -25  # half the spacing of fp16 denormals: absolute rounding error below 2^-14
 
 
 def device_problem(p, device="cuda:0"):
@@ -14,13 +20,15 @@ def device_problem(p, device="cuda:0"):
     return dp, cp, rp
 
 
-def make_workspace(layout, M, device="cuda:0"):
+def make_workspace(layout, M, device="cuda:0", fill=0xFF):
+    """A workspace of the size the library asks for, filled with 0xFF bytes (fp16 / fp32 NaN patterns): the
+    library promises that the contents on entry are irrelevant, so the tests hand it the worst contents."""
     import torch
     import paper_2602_01027_amd as S
 
     nbytes = S.sfmp_gemm_workspace(layout, M)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
-    S.sfmp_workspace_init(ws)
+    ws.fill_(fill)
     return ws
 
 
@@ -40,3 +48,92 @@ def run_gemm(p, dp=None, cp=None, rp=None, ws=None, X=None, device="cuda:0"):
     S.sfmp_gemm(Xd, cp, dp.layout, dp.s2, dp.s3, dp.s4, dp.index, dp.scales, dp.zeros, dp.bitmap, rp, Y, ws)
     torch.cuda.synchronize()
     return Y.cpu().numpy()
+
+
+# ---------------------------------------------------------------------------------------------
+# comparison with the oracle
+# ---------------------------------------------------------------------------------------------
+def elementwise_tolerance(M, K, ref, A, B, X1):
+    """Bound on |y_gpu - ref| for one output, from the arithmetic of the kernels (first-order rounding analysis
+    with the standard gamma_n = n u / (1 - n u); nothing here is fitted to observed errors).
+
+    ref = sum_j x_j w_j (float64), A = sum_j |x_j| |w_j|, B = sum_j |x_j| (|s| q_j + |z|) >= A, X1 = sum_j |x_j|.
+
+    Every path ends in one fp32 -> fp16 rounding of its fp32 sum: u16 |sum| + 2^-25.
+
+    Decode kernels (M <= 16, and chunks of 16 rows of a medium batch): products x * q are exact (11-bit by 4-bit
+    significands); per 128-column group they form t = sum x q and sum x in fp32, then acc_q += s t, acc_z += z sum x,
+    y = 2^24 acc_q + acc_z, summed over the wavefronts.  The longest chain of fp32 roundings a term passes through:
+    at most 4 matrix instructions of 32 products into one accumulator (128), the combination of the field
+    positions (3), one fused multiply-add per item of a wavefront and slab (at most ceil(K / 1024)), the final
+    combination (1), the sum over 16 wavefronts (16): D = 148 + ceil(K / 1024) roundings, each relative to a
+    partial sum bounded by B.  Hence |err| <= u16 |ref| + 2^-25 + (1 + u16) gamma_D B.
+
+    MFMA prefill kernel (M > 16): w_j is rounded to fp16 once (|delta_j| <= u16 |w_j| + 2^-25; with bf16
+    parameters s q + z is formed in fp32 first: one more u32), products are exact in fp32, and all K products of
+    an output go through one accumulator chain (K / 32 matrix instructions of 32 products; a split K only shortens
+    it): |err| <= u16 |ref| + 2^-25 + (1 + u16) ((u16 + u32 + gamma_{K+8}) A + 2^-25 X1).
+    For M > 16 the library chooses between the two paths, so the larger bound applies.
+    """
+    D = 148 + -(-K // 1024)
+    g_d = D * U32 / (1.0 - D * U32)
+    tol = U16 * np.abs(ref) + FLOOR16 + (1.0 + U16) * g_d * B
+    if M > 16:
+        n = K + 8
+        g_k = n * U32 / (1.0 - n * U32)
+        tol_pre = U16 * np.abs(ref) + FLOOR16 + (1.0 + U16) * ((U16 + U32 + g_k) * A + FLOOR16 * X1)
+        tol = np.maximum(tol, tol_pre)
+    return tol
+
+
+def check_against_oracle(p, Y, feature_rows=None, m_rows=None, block=1024, elementwise=True):
+    """Compare Y (fp16 [M, N], columns in original order when p.row_perm is given) with the oracle.
+
+    Asserts (1) relative Frobenius error <= 2e-3 over everything compared, (2) the same bound for every tile row
+    on its own (128 output features x the compared activation rows; only when whole tile rows are compared: one
+    wrong 16-row slab of one tile cannot hide in the norm of a large matrix), (3) the derived per-element bound of
+    `elementwise_tolerance`.  feature_rows: reordered output features to compare (default all, walked in blocks so
+    that the float64 dequantised weights of a 70B matrix never exist at once); m_rows: activation rows to compare
+    (default all); elementwise=False leaves (3) out (for a kernel with other arithmetic than the bound describes).
+    Returns the overall relative Frobenius error."""
+    from oracle import sfmp_oracle as O
+
+    Y = np.asarray(Y)
+    M, N, K = p.X.shape[0], p.N, p.K
+    assert Y.shape == (M, N)
+    assert np.isfinite(Y.astype(np.float32)).all()
+    mr = np.arange(M) if m_rows is None else np.unique(np.asarray(m_rows, dtype=np.int64))
+    X = np.ascontiguousarray(p.X[mr])
+    Xabs = np.abs(O.permute_activation(X, p.col_perm))
+    X1 = Xabs.sum(axis=1)[:, None]
+    whole_tile_rows = feature_rows is None
+    feats = np.arange(N, dtype=np.int64) if feature_rows is None else np.unique(np.asarray(feature_rows, dtype=np.int64))
+    sabs, zabs = np.abs(p.scales), np.abs(p.zeros)
+    num = den = 0.0
+    worst = (0.0, None)
+    for i0 in range(0, feats.size, block):
+        rows = feats[i0:i0 + block]
+        ref = O.gemm_rows(X, p.col_perm, p.codes, p.scales, p.zeros, rows)          # [m, rows], reordered features
+        A = Xabs @ np.abs(O.dequant_rows(p.codes, p.scales, p.zeros, rows)).T
+        B = Xabs @ O.dequant_rows(p.codes, sabs, zabs, rows).T
+        cols = rows if p.row_perm is None else np.asarray(p.row_perm, dtype=np.int64)[rows]
+        got = Y[np.ix_(mr, cols)].astype(np.float64)
+        err = np.abs(got - ref)
+        tol = elementwise_tolerance(M, K, ref, A, B, X1)
+        ratio = err / tol
+        k = int(np.argmax(ratio))
+        if ratio.flat[k] > worst[0]:
+            worst = (float(ratio.flat[k]), (int(mr[k // rows.size]), int(rows[k % rows.size]), float(got.flat[k]),
+                                            float(ref.flat[k]), float(tol.flat[k])))
+        assert not elementwise or worst[0] <= 1.0, f"element (m, reordered feature, got, ref, tol) = {worst[1]} exceeds its bound"
+        num += float((err ** 2).sum())
+        den += float((ref ** 2).sum())
+        if whole_tile_rows:
+            assert rows.size % 128 == 0 and rows[0] % 128 == 0
+            e2 = (err ** 2).reshape(mr.size, -1, 128).sum(axis=(0, 2))
+            r2 = (ref ** 2).reshape(mr.size, -1, 128).sum(axis=(0, 2))
+            bad = np.nonzero(e2 > (TOL ** 2) * r2)[0]
+            assert bad.size == 0, f"tile rows {(rows[0] // 128 + bad).tolist()} exceed {TOL} on their own"
+    rel = float(np.sqrt(num / den)) if den > 0 else float(np.sqrt(num))
+    assert rel <= TOL, rel
+    return rel

@@ -1,7 +1,9 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
 
 Integer work (packed bytes, unpacked codes) must match bit for bit; fp16 outputs must be within
-a relative Frobenius error of 2e-3 of the float64 oracle (the stated acceptance bound).
+a relative Frobenius error of 2e-3 of the float64 oracle (the stated acceptance bound) - over the whole output and
+over every tile row of it on its own - and every element within the bound derived from the kernels' arithmetic
+(tests/gpu_util.py).  Workspaces are handed over filled with 0xFF bytes.
 """
 import dataclasses
 
@@ -23,17 +25,16 @@ def torch_cuda():
     return torch
 
 
-def _check(p, Y, rows=None):
-    """Compare Y (fp16 [M,N]) with the oracle; `rows` = sampled reordered rows for big layers."""
-    assert np.isfinite(Y.astype(np.float32)).all()
-    if rows is None:
+def _check(p, Y, rows=None, m_rows=None, elementwise=True):
+    """Compare Y (fp16 [M,N]) with the oracle: relative Frobenius error <= 2e-3 overall and per tile row, and the
+    derived per-element bound (tests/gpu_util.py).  `rows` = sampled reordered output features, `m_rows` = sampled
+    activation rows (both default to everything)."""
+    from gpu_util import check_against_oracle
+    err = check_against_oracle(p, Y, feature_rows=rows, m_rows=m_rows, elementwise=elementwise)
+    if rows is None and m_rows is None and p.N * p.K <= 16 * 2 ** 20:
+        # the oracle's own whole-product routine (row un-permutation included) on everything that is small
         ref = O.gemm(p.X, p.col_perm, p.codes, p.scales, p.zeros, p.row_perm)
-        err = O.rel_frobenius(Y, ref)
-    else:
-        ref = O.gemm_rows(p.X, p.col_perm, p.codes, p.scales, p.zeros, rows)
-        cols = rows if p.row_perm is None else p.row_perm[rows]
-        err = O.rel_frobenius(Y[:, cols], ref)
-    assert err <= TOL, err
+        assert O.rel_frobenius(Y, ref) <= TOL
     return err
 
 
@@ -160,7 +161,7 @@ def test_batched_small_batch_mixed_staging(torch_cuda):
         Y = torch.full((M, p.N), float("nan"), dtype=torch.float16, device="cuda:0")
         batch.append((torch.from_numpy(p.X).to("cuda:0"), cp, dp, rp, Y))
         keep.append((dp, cp, rp))
-    ws = torch.empty(S.sfmp_gemm_batched_workspace(batch, M), dtype=torch.uint8, device="cuda:0")
+    ws = torch.empty(S.sfmp_gemm_batched_workspace(batch, M), dtype=torch.uint8, device="cuda:0").fill_(0xFF)
     S.sfmp_gemm_batched(batch, M, ws)
     torch.cuda.synchronize()
     for p, (_, _, _, _, Y), (dp, cp, rp) in zip(probs, batch, keep):
@@ -255,43 +256,78 @@ def _distinct_shapes(cid):
     return out
 
 
-def _run_config_shape(cid, si, sample_rows):
+def _prefill_row_subset(M, seed):
+    """Activation rows compared on the largest prefill shapes: the first and the last row of every 64-row block
+    (the kernels' blocks are 64, 128 or 256 rows) plus 16 random rows.  Every output row touches every weight tile,
+    so all N output features of these rows exercise the whole matrix."""
+    edges = np.concatenate([np.arange(0, M, 64), np.arange(63, M, 64), [M - 1]])
+    extra = np.random.default_rng(seed).choice(M, size=min(16, M), replace=False)
+    return np.unique(np.concatenate([edges, extra]))
+
+
+def _run_config_shape(cid, si):
+    """One shape of a benchmark configuration at full size, every M of the configuration.  Every output feature is
+    compared (the oracle walks the matrix in blocks of 1024 features); for M = 2048 on matrices above 64 Mi weights
+    a documented subset of the activation rows."""
     from gpu_util import device_problem, run_gemm
     spec = W.CONFIGS[cid]
     base = _config_problem(cid, si)
     dp, cp, rp = device_problem(base)
-    rows = None
-    if sample_rows and base.N * base.K > 64 * 2 ** 20:
-        rng = np.random.default_rng(cid * 100 + si)
-        # sampled output features: every tile row is hit, the oracle computes them one by one
-        rows = np.sort(np.concatenate([np.arange(base.N // 128) * 128 + rng.integers(0, 128, base.N // 128),
-                                       rng.choice(base.N, size=256, replace=False)]))
-        rows = np.unique(rows)
     errs = {}
     for M in spec.Ms:
         p = W.with_activations(base, M, outliers=spec.outliers)
-        errs[M] = _check(p, run_gemm(p, dp, cp, rp), rows)
+        m_rows = None
+        if M > 256 and base.N * base.K > 64 * 2 ** 20:
+            m_rows = _prefill_row_subset(M, cid * 100 + si)
+        errs[M] = _check(p, run_gemm(p, dp, cp, rp), m_rows=m_rows)
     print(f"config {cid} {base.label} K={base.K} N={base.N} avg_bits={base.avg_bits:.3f} rel_frob={errs}", flush=True)
 
 
 @pytest.mark.parametrize("si", _distinct_shapes(2))
 def test_config2_8b_decode(torch_cuda, si):
-    _run_config_shape(2, si, sample_rows=False)
+    _run_config_shape(2, si)
 
 
 @pytest.mark.parametrize("si", _distinct_shapes(3))
 def test_config3_8b_fractional(torch_cuda, si):
-    _run_config_shape(3, si, sample_rows=False)
+    _run_config_shape(3, si)
 
 
 @pytest.mark.parametrize("si", _distinct_shapes(4))
 def test_config4_70b_decode(torch_cuda, si):
-    _run_config_shape(4, si, sample_rows=True)
+    _run_config_shape(4, si)
 
 
 @pytest.mark.parametrize("si", _distinct_shapes(5))
 def test_config5_prefill(torch_cuda, si):
-    _run_config_shape(5, si, sample_rows=True)
+    _run_config_shape(5, si)
+
+
+def test_bench_step_replayed_as_graph_matches_oracle(torch_cuda):
+    """The step that bench.py times, exactly as it launches it: the seven projections of the 8B decode layer
+    (configs[1], fully quantised) in four launches (q|k|v, o, gate|up, down through sfmp_gemv_batched), captured in one
+    HIP graph per weight replica and replayed in rotation.  All seven outputs of every replay against the oracle."""
+    import bench
+    torch = torch_cuda
+    problems = bench.build_problems(W, 2)
+    layer = bench.Layer(problems, 3)
+    graphs = bench.capture_step_graphs(torch, layer, bench.FUSED_GROUPS)
+    first = None
+    for rnd in range(2):
+        for r, g in enumerate(graphs):
+            for d in layer.proj:
+                d["Y"].fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            ys = [d["Y"].cpu().numpy() for d in layer.proj]
+            if first is None:
+                first = ys
+                for p, y in zip(problems, ys):
+                    _check(p, y)
+            else:  # the replicas hold the same weights: every replay must repeat the first bit for bit
+                for y0, y in zip(first, ys):
+                    assert np.array_equal(y0.view(np.uint16), y.view(np.uint16)), (rnd, r)
 
 
 # ---------------------------------------------------------------------------------------------
@@ -350,7 +386,7 @@ def test_gemm_batched_shared_activations(torch_cuda, M):
     shared = S.sfmp_gemm_batched_workspace(batch[:3], M)
     single = S.sfmp_gemm_batched_workspace(batch[:1], M)
     assert shared == single  # one staged copy for the three problems that share X and col_perm
-    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0").fill_(0xFF)
     S.sfmp_gemm_batched(batch, M, ws)
     torch.cuda.synchronize()
     for p, (_, _, _, _, Y), (dp, cp, rp) in zip(probs, batch, keep):
@@ -375,6 +411,34 @@ def test_group_length_and_parameter_format(torch_cuda, group, scale_format, bloc
     _check(p, run_gemm(p))
 
 
+@pytest.mark.parametrize("M", [1, 8, 64])
+def test_small_magnitude_weights_bf16_parameters(torch_cuda, M):
+    # weights of standard deviation 1e-5 with bf16 scales and zeros: the scales (about 3e-6) lie below fp16's normal
+    # range.  The decode kernels (M <= 16) widen the parameters to fp32 and meet the usual bounds.  The matrix-core path
+    # (M = 64 here) converts them to fp16 and rounds the dequantised weight to fp16, which the header documents as
+    # costing up to 2^-25 absolute per parameter and per weight below 2^-14: a code of at most 15 times the scale's
+    # error, the zero's error and the weight's rounding give 17 * 2^-25 per weight on top of the usual bound.
+    from gpu_util import run_gemm, elementwise_tolerance, FLOOR16
+    p = W.make_problem("tinyw", 1024, 512, M, 4711, w_std=1e-5, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3},
+                       scale_format="bf16")
+    assert float(np.abs(p.scales).max()) < 2.0 ** -14
+    Y = run_gemm(p)
+    if M <= 16:
+        _check(p, Y)
+        return
+    ref = O.gemm(p.X, p.col_perm, p.codes, p.scales, p.zeros, p.row_perm)
+    w_hat = O.dequant(p.codes, p.scales, p.zeros)
+    Xabs = np.abs(O.permute_activation(p.X, p.col_perm))
+    A = Xabs @ np.abs(w_hat).T
+    B = Xabs @ O.dequant(p.codes, np.abs(p.scales), np.abs(p.zeros)).T
+    X1 = Xabs.sum(axis=1)[:, None]
+    inv = np.empty_like(p.row_perm)
+    inv[p.row_perm] = np.arange(p.N, dtype=np.int32)
+    tol = elementwise_tolerance(M, p.K, ref[:, p.row_perm], A, B, X1) + 17 * FLOOR16 * X1
+    assert np.all(np.abs(Y.astype(np.float64)[:, p.row_perm] - ref[:, p.row_perm]) <= tol)
+    assert O.rel_frobenius(Y, ref) <= 2e-2  # degraded, as documented, but not garbage
+
+
 def test_batched_launch_with_mixed_parameter_formats(torch_cuda):
     import paper_2602_01027_amd as S
     from gpu_util import device_problem
@@ -388,7 +452,7 @@ def test_batched_launch_with_mixed_parameter_formats(torch_cuda):
         Y = torch.full((3, p.N), float("nan"), dtype=torch.float16, device="cuda:0")
         probs.append(p)
         batch.append((X, cp, dp, rp, Y))
-    ws = torch.empty(S.sfmp_gemm_batched_workspace(batch, 3), dtype=torch.uint8, device="cuda:0")
+    ws = torch.empty(S.sfmp_gemm_batched_workspace(batch, 3), dtype=torch.uint8, device="cuda:0").fill_(0xFF)
     S.sfmp_gemm_batched(batch, 3, ws)
     torch.cuda.synchronize()
     for p, (_, _, _, _, Y) in zip(probs, batch):
@@ -459,7 +523,7 @@ def test_lut_gemv_against_oracles(torch_cuda, K, N, fractions, perms):
     from oracle import sfmp_lut_oracle as LO
     p = W.make_problem("lut", K, N, 1, 4100 + K + N, fractions=fractions, use_col_perm=perms, use_row_perm=perms)
     Y = _run_lut(torch_cuda, p)
-    _check(p, Y)  # against the plain definition
+    _check(p, Y, elementwise=False)  # against the plain definition (the table scheme has its own arithmetic)
     if K * N <= 512 * 384:  # and against the table algorithm itself, where that finishes in seconds
         planes, tile_off = LO.lut_pack(p.codes, p.bitmap)
         ref = LO.lut_gemv(p.X[0], p.col_perm, N, K, planes, tile_off, p.scales, p.zeros, p.row_perm)
@@ -475,7 +539,7 @@ def test_lut_gemv_full_size_sampled_and_repeatable(torch_cuda):
     Y2 = _run_lut(torch_cuda, p)
     assert np.array_equal(Y1.view(np.uint16), Y2.view(np.uint16))
     rows = np.random.default_rng(5).choice(p.N, size=96, replace=False)
-    _check(p, Y1, rows=np.sort(rows))
+    _check(p, Y1, rows=np.sort(rows), elementwise=False)
     assert O.rel_frobenius(Y1, run_gemm(p).astype(np.float64)) <= 2 * TOL
 
 
@@ -497,7 +561,7 @@ def test_lut_gemv_workspace_reuse(torch_cuda):
                             d(p.zeros), d(p.row_perm), Y, ws)
             torch.cuda.synchronize()
             outs.append(Y.cpu().numpy()[None, :])
-            _check(p, outs[-1])
+            _check(p, outs[-1], elementwise=False)
     for i in range(3):
         assert np.array_equal(outs[i].view(np.uint16), outs[i + 3].view(np.uint16))
 

@@ -92,7 +92,18 @@ def test_error_codes():
     # gemm refuses NULL buffers before touching any device
     assert lib.sfmp_gemm(None, 1, None, C.byref(L), None, None, None, None, None, None, None, None, None, None, 0,
                          None) == -1
-    for code in range(-8, 1):
+    # alignment is checked before any device work as well (the pointers are never dereferenced on the host)
+    ok = [C.c_void_p(0x7f0000001000 + 0x10000 * i) for i in range(8)]
+
+    def gemm_with(X=ok[0], cp=ok[1], scales=ok[2], Y=ok[3], M=1):
+        return lib.sfmp_gemm(X, M, cp, C.byref(L), None, ok[4], None, ok[5], scales, ok[6], None, None, Y, ok[7], 1 << 20,
+                             None)
+    assert gemm_with(X=C.c_void_p(0x7f0000001008)) == -9  # ALIGN: X needs 16 bytes
+    assert gemm_with(cp=C.c_void_p(0x7f0000011004)) == -9
+    assert gemm_with(scales=C.c_void_p(0x7f0000021002)) == -9
+    assert gemm_with(Y=C.c_void_p(0x7f0000031001)) == -9      # Y: 2 bytes at M <= 16 ...
+    assert gemm_with(Y=C.c_void_p(0x7f0000031002), M=17) == -9  # ... 16 bytes beyond
+    for code in range(-9, 1):
         assert S.sfmp_strerror(code)
     assert "unknown" in S.sfmp_strerror(-99)
 

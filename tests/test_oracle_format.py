@@ -102,7 +102,7 @@ def test_streams_hold_tiles_in_row_major_order_per_width():
 
 # ---- byte accounting pinned to the paper's closed forms ------------------------------------
 def test_metadata_overhead_matches_paper_value():
-    # Section 4.3 "Extra Metadata": 0.006 BPW on LLaMA-3.1-8B with (512,128) blocks.
+    # Section 4.2, paragraph "Extra Metadata": 0.006 BPW on LLaMA-3.1-8B with (512,128) blocks.
     shapes = [W.SHAPES_8B[n] for n in W.LAYER_8B]
     bpw = W.metadata_bits_per_weight(shapes)
     assert round(bpw, 3) == 0.006
