@@ -80,6 +80,9 @@ extern "C" {
 #define SFMP_ERR_PERM (-7)        /* sfmp_check_perm: not a permutation of 0..n-1 */
 #define SFMP_ERR_LAYOUT (-8)      /* layout struct inconsistent with itself */
 #define SFMP_ERR_ALIGN (-9)       /* a device pointer is not aligned as required (see sfmp_gemm) */
+#define SFMP_ERR_TOO_LARGE (-10)  /* sfmp_gemm_static: the problem needs more scratch than the static buffer holds */
+
+#define SFMP_STATIC_SCRATCH_BYTES (16 * 1024 * 1024)  /* scratch of sfmp_gemm_static, per GPU */
 
 /* Sizes of a packed matrix.  Filled by sfmp_pack_query / sfmp_pack; passed by the caller,
  * unchanged, to the device entry points. */
@@ -176,6 +179,22 @@ int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const s
               const void* scales_dev, const void* zeros_dev, const int8_t* bitmap_dev,
               const int32_t* row_perm_dev, void* Y_dev, void* workspace_dev, int64_t workspace_bytes,
               void* hip_stream);
+
+/* Device.  sfmp_gemm for callers that cannot allocate device memory and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same arguments and the same result, bit for
+ * bit, as sfmp_gemm, without the workspace: the scratch memory (staged or gathered activations, the product before the
+ * row un-permute, partial products of a split K) is a 256-byte aligned array of SFMP_STATIC_SCRATCH_BYTES (16 MiB) that
+ * is part of the library's device code, one copy per GPU, held from the moment the library is loaded on that GPU until
+ * the process ends.  The call allocates and frees nothing (no hipMalloc / hipFree, no allocating library routine); its
+ * first call on a device looks the array's address up once (hipGetSymbolAddress) - make that first call outside any
+ * graph capture.  SFMP_ERR_TOO_LARGE if sfmp_gemm_workspace(layout, M) exceeds SFMP_STATIC_SCRATCH_BYTES (for example
+ * M = 2048 on K = 4096; every M <= 16 fits for K up to 1 Mi); other errors as sfmp_gemm.  Nothing in the scratch
+ * has to start at zero: every call writes what it later reads, whatever the previous call left.  All calls on one
+ * GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two threads) race; order them. */
+int sfmp_gemm_static(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
+                     const void* s2_dev, const void* s3_dev, const void* s4_dev, const int32_t* index_dev,
+                     const void* scales_dev, const void* zeros_dev, const int8_t* bitmap_dev,
+                     const int32_t* row_perm_dev, void* Y_dev, void* hip_stream);
 
 /* One problem of a batched launch: the arguments of sfmp_gemm without M and workspace. */
 typedef struct sfmp_gemv_problem {

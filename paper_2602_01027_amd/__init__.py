@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     sfmp_gemm_workspace,
     sfmp_workspace_init,
     sfmp_gemm,
+    sfmp_gemm_static,
     sfmp_gemv_batched,
     sfmp_gemm_batched,
     sfmp_gemm_batched_workspace,

@@ -34,7 +34,7 @@ class SfmpGemvProblem(C.Structure):
 
 
 EXPORTS = ("sfmp_strerror", "sfmp_pack_query", "sfmp_layout_set_quant", "sfmp_pack", "sfmp_unpack", "sfmp_gemm_workspace",
-           "sfmp_workspace_init", "sfmp_gemm", "sfmp_gemv_batched", "sfmp_gemm_batched_workspace",
+           "sfmp_workspace_init", "sfmp_gemm", "sfmp_gemm_static", "sfmp_gemv_batched", "sfmp_gemm_batched_workspace",
            "sfmp_gemm_batched", "sfmp_check_perm", "sfmp_fold_perms", "sfmp_lut_pack_query",
            "sfmp_lut_pack", "sfmp_lut_gemv_workspace", "sfmp_lut_gemv")
 
@@ -63,6 +63,7 @@ def load_library():
     lib.sfmp_gemm_workspace.argtypes = [LP, i32, C.POINTER(i64)]
     lib.sfmp_workspace_init.argtypes = [vp, i64, vp]
     lib.sfmp_gemm.argtypes = [vp, i32, vp, LP, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.sfmp_gemm_static.argtypes = [vp, i32, vp, LP, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.sfmp_gemv_batched.argtypes = [vp, i32, vp]
     lib.sfmp_check_perm.argtypes = [vp, i32]
     lib.sfmp_lut_pack_query.argtypes = [vp, i32, i32, C.POINTER(i64), C.POINTER(i64)]
@@ -207,6 +208,16 @@ def sfmp_gemm(X, col_perm, layout: SfmpLayout, s2, s3, s4, index, scales, zeros,
                                     _dev_ptr(s4), _dev_ptr(index), _dev_ptr(scales), _dev_ptr(zeros),
                                     _dev_ptr(bitmap), _dev_ptr(row_perm), _dev_ptr(Y), _dev_ptr(workspace), nbytes,
                                     _stream_ptr(stream)))
+
+
+def sfmp_gemm_static(X, col_perm, layout: SfmpLayout, s2, s3, s4, index, scales, zeros, bitmap, row_perm, Y,
+                     stream=None) -> None:
+    """sfmp_gemm on the library's own static scratch memory (no workspace argument, no allocation)."""
+    M = int(X.shape[0])
+    _check(load_library().sfmp_gemm_static(_dev_ptr(X), M, _dev_ptr(col_perm), C.byref(layout), _dev_ptr(s2),
+                                           _dev_ptr(s3), _dev_ptr(s4), _dev_ptr(index), _dev_ptr(scales),
+                                           _dev_ptr(zeros), _dev_ptr(bitmap), _dev_ptr(row_perm), _dev_ptr(Y),
+                                           _stream_ptr(stream)))
 
 
 def make_gemv_batch(problems):

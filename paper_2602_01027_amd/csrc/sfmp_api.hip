@@ -33,6 +33,34 @@ int allow_full_lds(const void* fn, const char* what) {
 }
 }  // namespace sfmp
 
+// Scratch memory of sfmp_gemm_static: one array per GPU (every device that loads the library holds its own copy at
+// its own address until the process ends).  In host code the array's name is only a handle: its device address on
+// the current device comes from hipGetSymbolAddress, once per device, and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char g_static_scratch[SFMP_STATIC_SCRATCH_BYTES];
+
+static int static_scratch_of_current_device(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr_of[kMaxDevices] = {nullptr};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    note_hip_error("sfmp_gemm_static", "hipGetDevice failed or device ordinal above 63");
+    return SFMP_ERR_HIP;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of[dev]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch));
+    if (e != hipSuccess || !p) {
+      note_hip_error("hipGetSymbolAddress(static scratch)", hipGetErrorString(e));
+      return SFMP_ERR_HIP;
+    }
+    ptr_of[dev] = p;
+  }
+  *out = ptr_of[dev];
+  return SFMP_OK;
+}
+
 extern "C" {
 
 int sfmp_unpack(const sfmp_layout_t* layout, const void* s2_dev, const void* s3_dev, const void* s4_dev,
@@ -186,6 +214,24 @@ int sfmp_gemm(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const s
   if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < need) return SFMP_ERR_WORKSPACE;
   return gemm_with_workspace(X_dev, M, col_perm_dev, layout, s2_dev, s3_dev, s4_dev, index_dev, scales_dev, zeros_dev,
                              bitmap_dev, row_perm_dev, Y_dev, workspace_dev, workspace_bytes, hip_stream);
+}
+
+int sfmp_gemm_static(const void* X_dev, int32_t M, const int32_t* col_perm_dev, const sfmp_layout_t* layout,
+                     const void* s2_dev, const void* s3_dev, const void* s4_dev, const int32_t* index_dev,
+                     const void* scales_dev, const void* zeros_dev, const int8_t* bitmap_dev,
+                     const int32_t* row_perm_dev, void* Y_dev, void* hip_stream) {
+  if (int e = check_layout(layout)) return e;
+  if (M < 1) return SFMP_ERR_SHAPE;
+  if (int e = check_gemm_pointers(X_dev, col_perm_dev, layout, s2_dev, s3_dev, s4_dev, index_dev, scales_dev,
+                                  zeros_dev, bitmap_dev, row_perm_dev, Y_dev, M))
+    return e;
+  int64_t need = 0;
+  if (int e = sfmp_gemm_workspace(layout, M, &need)) return e;
+  if (need > (int64_t)SFMP_STATIC_SCRATCH_BYTES) return SFMP_ERR_TOO_LARGE;
+  void* ws = nullptr;
+  if (int e = static_scratch_of_current_device(&ws)) return e;
+  return gemm_with_workspace(X_dev, M, col_perm_dev, layout, s2_dev, s3_dev, s4_dev, index_dev, scales_dev, zeros_dev,
+                             bitmap_dev, row_perm_dev, Y_dev, ws, (int64_t)SFMP_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 }  // extern "C"

@@ -96,6 +96,7 @@ const char* sfmp_strerror(int code) {
     case SFMP_ERR_PERM: return "not a permutation of 0..n-1";
     case SFMP_ERR_LAYOUT: return "layout struct is inconsistent";
     case SFMP_ERR_ALIGN: return "a device pointer is not aligned as the header requires (16 bytes for most)";
+    case SFMP_ERR_TOO_LARGE: return "the problem needs more scratch memory than the static buffer of sfmp_gemm_static holds";
     default: return "unknown sfmp error code";
   }
 }

@@ -1,5 +1,8 @@
 """Helpers for the GPU parity tests: upload a problem, call the C ABI through the binding, and compare an
 output with the CPU oracle (whole-output and per-tile-row Frobenius error, and a derived per-element bound)."""
+import sys
+import time
+
 import numpy as np
 
 TOL = 2e-3          # stated acceptance bound: relative Frobenius error against the float64 oracle
@@ -111,7 +114,11 @@ def check_against_oracle(p, Y, feature_rows=None, m_rows=None, block=1024, eleme
     sabs, zabs = np.abs(p.scales), np.abs(p.zeros)
     num = den = 0.0
     worst = (0.0, None)
+    last_note = time.monotonic()
     for i0 in range(0, feats.size, block):
+        if time.monotonic() - last_note > 30.0:  # a long comparison says that it is alive
+            print(f"  oracle comparison: feature {i0} of {feats.size}", file=sys.stderr, flush=True)
+            last_note = time.monotonic()
         rows = feats[i0:i0 + block]
         ref = O.gemm_rows(X, p.col_perm, p.codes, p.scales, p.zeros, rows)          # [m, rows], reordered features
         A = Xabs @ np.abs(O.dequant_rows(p.codes, p.scales, p.zeros, rows)).T

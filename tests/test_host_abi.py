@@ -103,7 +103,7 @@ def test_error_codes():
     assert gemm_with(scales=C.c_void_p(0x7f0000021002)) == -9
     assert gemm_with(Y=C.c_void_p(0x7f0000031001)) == -9      # Y: 2 bytes at M <= 16 ...
     assert gemm_with(Y=C.c_void_p(0x7f0000031002), M=17) == -9  # ... 16 bytes beyond
-    for code in range(-9, 1):
+    for code in range(-10, 1):
         assert S.sfmp_strerror(code)
     assert "unknown" in S.sfmp_strerror(-99)
 
