@@ -529,6 +529,17 @@ def main():
             del lf, pf
             torch.cuda.empty_cache()
         if args.section in ("all", "decode"):
+            # group length 64 (the smallest n_b of the block-size ablation: 0.5 bit per weight of parameters), fp16
+            pg = build_problems(W, 2, fast=True, group=64)
+            bg = sum(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, index_words=p.bitmap.size, group=p.group) for p in pg)
+            lg = Layer(pg, int(np.ceil(2 ** 30 / bg)))
+            msg, _ = time_steps(torch, lg, 120, 12, use_graph=not args.eager, groups=FUSED_GROUPS)
+            extra["layer_8b_M1_group64"] = dict(
+                us_per_layer=round(msg * 1e3, 2), MB=round(bg / 1e6, 1), GBps=round(bg / msg / 1e6, 1),
+                pct_hbm_peak=round(100 * bg / msg / 1e6 / HBM_PEAK_GBPS, 2))
+            del lg, pg
+            torch.cuda.empty_cache()
+        if args.section in ("all", "decode"):
             # bitmaps as the method produces them: Algorithm 1 on synthetic salience, (512, 128) blocks, average 3.0
             # bits; rows and columns sorted by salience, so tile rows differ in bytes (4-bit rows first)
             pa = build_problems(W, 2, fast=True, allocated_bits=3.0)

@@ -10,7 +10,7 @@
  * where q is the integer code matrix of the reordered weight Wt [N, K] (N output features,
  * K input features), every 128 x 128 tile of Wt carries its own bit-width b in {2,3,4}
  * (the "bitmap"), and (s, z) is one fp16 scale / additive zero-point pair per row per
- * group of 128 reordered columns.
+ * group of 128 reordered columns (other group lengths and bf16 storage: sfmp_layout_set_quant).
  *
  * Conventions
  *   - Every function returns SFMP_OK (0) or a negative SFMP_ERR_* code and never throws.
@@ -105,10 +105,12 @@ const char* sfmp_strerror(int code);
 int sfmp_pack_query(const int8_t* bitmap_host, int32_t N, int32_t K, sfmp_layout_t* out);
 
 /* Host only.  Chooses the quantisation-parameter format of a layout filled by sfmp_pack_query / sfmp_pack
- * (which set group 128, fp16): group = 128, 256 or 512 columns per (scale, zero) pair, K a multiple of it
- * (Appendix "Effect of n_b": the block width n_b is also the group size); scale_format = SFMP_SCALE_FP16 or
+ * (which set group 128, fp16): group = 64, 128, 256 or 512 columns per (scale, zero) pair, K a multiple of it
+ * (Appendix G "Effect of n_b": the block width n_b is also the group size); scale_format = SFMP_SCALE_FP16 or
  * SFMP_SCALE_BF16.  The packed streams and the index table do not depend on either.  scales and zeros are then
- * [K/group, N] arrays of 16-bit values in that format.  SFMP_ERR_LAYOUT for any other value. */
+ * [K/group, N] arrays of 16-bit values in that format.  With group 64 a 128-column tile holds two groups, which share
+ * the tile's bit-width (a bit-allocation block narrower than 128 columns is not expressible: the bitmap has one entry
+ * per 128 x 128 tile).  SFMP_ERR_LAYOUT for any other value. */
 int sfmp_layout_set_quant(sfmp_layout_t* layout, int32_t group, int32_t scale_format);
 
 /* Host only.  Packs codes (uint8 [N, K] row-major, reordered coordinates, host) into the three
@@ -226,8 +228,9 @@ int sfmp_gemv_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, v
  * (q, k and v; gate and up) share one staged copy of the activations.  M = 1 is sfmp_gemv_batched.
  * sfmp_gemm_batched_workspace (host only) gives the workspace size for these problems and this M (never 0);
  * the workspace is device memory, 256-byte aligned, contents irrelevant on entry and unspecified on return.
- * SFMP_ERR_SHAPE if M is outside 1..16 or a problem would put more than 16 slabs on a workgroup (N above about
- * 65536 times its share of the grid) - call sfmp_gemm per problem then. */
+ * SFMP_ERR_SHAPE if M is outside 1..16, if a problem would put more than 16 slabs on a workgroup (N above about
+ * 65536 times its share of the grid), or if some but not all problems have group length 64 (one launch runs one of
+ * the two classes; sfmp_gemv_batched likewise) - call sfmp_gemm per problem then. */
 int sfmp_gemm_batched_workspace(const sfmp_gemv_problem_t* problems_host, int32_t count, int32_t M, int64_t* bytes);
 int sfmp_gemm_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, int32_t M, void* workspace_dev,
                       int64_t workspace_bytes, void* hip_stream);

@@ -80,7 +80,7 @@ int sfmp_gemm_workspace(const sfmp_layout_t* layout, int32_t M, int64_t* bytes) 
   if (int e = check_layout(layout)) return e;
   if (M < 1) return SFMP_ERR_SHAPE;
   if (M <= kDecodeMaxM) {
-    const DecodePlan d = make_decode_plan(layout->N, layout->K, M);
+    const DecodePlan d = make_decode_plan(layout->N, layout->K, M, layout->group);
     *bytes = d.workspace_bytes;
   } else if (use_chunked_decode(layout->N, layout->K, M)) {
     GemmArgs a{};

@@ -71,6 +71,31 @@ __device__ __forceinline__ float slab_dot_row0_units(const uint32_t* w, const ha
 
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"  // m0 is named as clobbered on purpose
+// The same for a group length of 64: the sums over columns 0-63 (k-steps 0, 1) and over columns 64-127 (k-steps 2, 3)
+// of the slab apart, both in units of 2^-24: one accumulator per k-step, each weighted by 2^-(its field position).
+template <int B>
+__device__ __forceinline__ void slab_dot_row0_halves(const uint32_t* w, const half8 (&a)[4], float& t_lo, float& t_hi) {
+  uint32_t op[4][4];
+  unpack_slab<B>(w, op);
+  floatx4 c[4];
+#pragma unroll
+  for (int kappa = 0; kappa < 4; ++kappa)
+    c[kappa] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[kappa], as_half8(op[kappa]), floatx4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+  t_lo = c[0][0] * pow2f(-step_pos<B>(0)) + c[1][0] * pow2f(-step_pos<B>(1));
+  t_hi = c[2][0] * pow2f(-step_pos<B>(2)) + c[3][0] * pow2f(-step_pos<B>(3));
+}
+template <int B>
+__device__ __forceinline__ void slab_dot_halves(const uint32_t* w, const half8 (&a)[4], floatx4& t_lo, floatx4& t_hi) {
+  uint32_t op[4][4];
+  unpack_slab<B>(w, op);
+  floatx4 c[4];
+#pragma unroll
+  for (int kappa = 0; kappa < 4; ++kappa)
+    c[kappa] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[kappa], as_half8(op[kappa]), floatx4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+  t_lo = c[0] * pow2f(-step_pos<B>(0)) + c[1] * pow2f(-step_pos<B>(1));
+  t_hi = c[2] * pow2f(-step_pos<B>(2)) + c[3] * pow2f(-step_pos<B>(3));
+}
+
 // Direct global->LDS copies written out by hand: scalar base address + 32-bit lane offset (no 64-bit vector
 // address arithmetic per copy), lanes chosen by a mask in scalar registers.  Lane l writes 16 bytes at LDS byte
 // lds_off + 16 l.  EXEC is restored inside the statement.  The compiler does not count these copies: the
@@ -93,20 +118,24 @@ __device__ __forceinline__ void lds_copy_b128(uint64_t sbase, uint32_t voff, uin
 // LDS byte lds_off, then 16 bytes per lane of the slab (scalar base + lane offset; lanes 0-31 always, of lanes 32-63
 // those whose bit is set in hi_lanes) to lds_off + slab_off.  Only the upper half of EXEC changes, and it is put back;
 // the writes to EXEC sit between each write of M0 and the copy that uses it (the wait state M0 needs).
+// (par_hi_lanes: 0, or all ones for a group length of 64, where lanes 32-63 bring the parameters of the tile column's
+// second group)
 __device__ __forceinline__ void lds_copy_item(uint64_t par_vaddr, uint64_t slab_sbase, uint32_t slab_voff,
-                                              uint32_t lds_off, uint32_t lds_off_slab, uint32_t hi_lanes) {
+                                              uint32_t lds_off, uint32_t lds_off_slab, uint32_t hi_lanes,
+                                              uint32_t par_hi_lanes = 0) {
   uint32_t saved;
   asm volatile(
       "s_mov_b32 m0, %3\n\t"
       "s_mov_b32 %0, exec_hi\n\t"
-      "s_mov_b32 exec_hi, 0\n\t"
+      "s_mov_b32 exec_hi, %7\n\t"
       "global_load_lds_dword %1, off\n\t"
       "s_mov_b32 m0, %4\n\t"
       "s_mov_b32 exec_hi, %5\n\t"
       "global_load_lds_dwordx4 %6, %2\n\t"
       "s_mov_b32 exec_hi, %0"
       : "=&s"(saved)
-      : "v"(par_vaddr), "s"(slab_sbase), "s"(lds_off), "s"(lds_off_slab), "s"(hi_lanes), "v"(slab_voff)
+      : "v"(par_vaddr), "s"(slab_sbase), "s"(lds_off), "s"(lds_off_slab), "s"(hi_lanes), "v"(slab_voff),
+        "s"(par_hi_lanes)
       : "memory", "m0");
 }
 #pragma clang diagnostic pop
@@ -131,6 +160,7 @@ struct GemvParams {
   int32_t max_slabs;  // slabs per workgroup (upper bound), sizes the reduction buffer
   int32_t gshift;     // log2(group / 128): tile column tc uses parameter row tc >> gshift
   int32_t bf16;       // scales and zeros are bfloat16 (else fp16)
+  int32_t g64;        // group length 64 (read by the host only: it selects the kernel instantiation)
 };
 
 constexpr int kGemvWaves = 16;       // wavefronts per workgroup; one workgroup per CU
@@ -145,6 +175,9 @@ constexpr int kGemvMaxSlabs = 16;    // slabs per workgroup kept in register acc
 constexpr int kGemvMaxItems = 64;    // items per wavefront: one lane of the item registers each
 constexpr int kSlotBytes = 1024 + 128;  // slab bytes (<= 1 KiB) + 16 scale dwords + 16 zero dwords
 constexpr int kGemvSlotParamBytes = 128;  // GEMV slots: [16 scale dwords | 16 zero dwords | slab]
+// group length 64: [16 scale + 16 zero dwords of columns 0-63 | the same of columns 64-127 | slab]
+constexpr int kGemvSlotParamBytes64 = 256;
+constexpr int kSlotBytes64 = 1024 + 256;
 
 typedef float floatx16v __attribute__((ext_vector_type(16)));
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -186,6 +219,17 @@ __device__ __forceinline__ float unit_group_sum(const half8& v) {
 }
 
 
+// the same over 8 lanes (= 64 columns = half a tile column): mirror inside each half row, then inside each quad
+__device__ __forceinline__ float unit_half_group_sum(const half8& v) {
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s += (float)v[e];
+  s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0x141, 0xF, 0xF, false));  // row_half_mirror
+  s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  return s;
+}
+
 // LDS stores the compiler does not see as LDS accesses.  After a direct global->LDS copy has been issued the
 // compiler puts a wait for ALL outstanding copies in front of every ordinary LDS store (it cannot tell the
 // destinations apart); these stores are used while ring copies are in flight, to regions no copy writes.
@@ -222,9 +266,12 @@ __host__ __device__ inline int64_t gemv_shared_region_bytes(int32_t K, int32_t m
 // a microsecond, so everything that depends on the arguments alone (tile descriptors, raw activations, column
 // permutation, the output positions of the end) is requested at once; the ring is filled as soon as the
 // descriptors are there, and the activations are permuted inside LDS while the first slabs are on their way.
-template <int NW, int S, bool PRELOADED, bool ANYFMT>
+// G64: group length 64 - two (scale, zero) pairs per row and tile column, the activation sums per half tile column.
+template <int NW, int S, bool PRELOADED, bool ANYFMT, bool G64 = false>
 __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid, const int G, unsigned char* lds_raw) {
   constexpr int NT = NW * 64;
+  constexpr int kPar = G64 ? kGemvSlotParamBytes64 : kGemvSlotParamBytes;  // parameter bytes in front of the slab
+  constexpr int kSlot = 1024 + kPar;
   // PRELOADED (the plain kernel): the integers and the four pointers of the first requests are in scalar registers
   // when the kernel starts; the other pointers are fetched behind those requests, see below.
   // Otherwise (a problem of a batch, whose arguments lie in the argument block): all arguments are fetched now, by
@@ -238,11 +285,11 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
                    "+s"(p.bf16)
                  : "s"(p.X), "s"(p.col_perm), "s"(p.s2), "s"(p.s3), "s"(p.s4), "s"(p.tile_desc), "s"(p.scales),
                    "s"(p.zeros), "s"(p.row_perm), "s"(p.Y));
-  // LDS: Xs [K] fp16 | Sx [ntc] f32 | shared region: raw activations, later red [max_slabs][NW][16] f32 |
-  //      rings [NW][S][kSlotBytes]
+  // LDS: Xs [K] fp16 | Sx [2 ntc] f32 (one sum per tile column, or two per tile column at group length 64) |
+  //      shared region: raw activations, later red [max_slabs][NW][16] f32 | rings [NW][S][slot bytes]
   _Float16* Xs = reinterpret_cast<_Float16*>(lds_raw);
   float* Sx = reinterpret_cast<float*>(lds_raw + (size_t)p.K * 2);
-  unsigned char* shared_region = lds_raw + (((size_t)p.K * 2 + (size_t)p.ntc * 4 + 15) & ~(size_t)15);
+  unsigned char* shared_region = lds_raw + (((size_t)p.K * 2 + (size_t)p.ntc * 8 + 15) & ~(size_t)15);
   _Float16* Xraw = reinterpret_cast<_Float16*>(shared_region);
   float* red = reinterpret_cast<float*>(shared_region);
   unsigned char* rings = shared_region + gemv_shared_region_bytes(p.K, p.max_slabs, NW);
@@ -328,7 +375,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
       // the aligned dword holding the fp16 scale of row 128*tr + sigma (rows 8*l + sigma are 16 bytes apart);
       // direct-to-LDS copies need dword-aligned addresses, the wanted fp16 is the low half for even sigma and
       // the high half for odd sigma
-      it_soff = 2u * (uint32_t)((it_tc >> p.gshift) * p.N + it_tr * kTile + (it_sigma & ~1));
+      it_soff = 2u * (uint32_t)((G64 ? 2u * it_tc : it_tc >> p.gshift) * p.N + it_tr * kTile + (it_sigma & ~1));
       it_misc = (uint32_t)it_tc | ((it_i == my_cnt - 1) ? 0x10000u : 0u) | ((uint32_t)it_j << 17) | (bm2 << 24) |
                 ((uint32_t)(it_sigma & 1) << 26);
     }
@@ -336,18 +383,20 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   // per-lane offsets of the copies of an item (bytes from the item's scalar base address)
   const uint32_t data_voff = lane * 16;
   // parameters: lanes 0-15 read the scale dwords, lanes 16-31 the zero dwords, in one copy (the two arrays may lie
-  // anywhere, hence a 64-bit lane part: array base + 16 bytes per row pair, to which the item's offset is added)
-  const uint64_t par_vbase = (lane < 16 ? (uint64_t)p.scales : (uint64_t)p.zeros) + (uint64_t)((lane & 15) * 16);
+  // anywhere, hence a 64-bit lane part: array base + 16 bytes per row pair, to which the item's offset is added);
+  // at group length 64 lanes 32-63 read the same of the next parameter row (columns 64-127 of the tile column)
+  const uint64_t par_vbase = ((lane & 16) == 0 ? (uint64_t)p.scales : (uint64_t)p.zeros) + (uint64_t)((lane & 15) * 16) +
+                             (G64 && lane >= 32 ? (uint64_t)p.N * 2 : (uint64_t)0);
 
   // Issue item e into ring slot s: two direct global->LDS copies, the 16 scale dwords + 16 zero dwords (lanes
   // 0-15 / 16-31) and the slab (16 B per lane, 32/48/64 lanes, scalar address).
-  const uint32_t ring_off = (uint32_t)(uintptr_t)(lptr_t)(rings + (size_t)wave * S * kSlotBytes);
+  const uint32_t ring_off = (uint32_t)(uintptr_t)(lptr_t)(rings + (size_t)wave * S * kSlot);
   auto issue_item = [&](int e, uint32_t slot) __attribute__((always_inline)) {
     const uint32_t wlo = (uint32_t)__builtin_amdgcn_readlane((int)it_wlo, e);
     const uint32_t whi = (uint32_t)__builtin_amdgcn_readlane((int)it_whi, e);
     const uint32_t xhi = (uint32_t)__builtin_amdgcn_readlane((int)it_xhi, e);
     const uint32_t soff = (uint32_t)__builtin_amdgcn_readlane((int)it_soff, e);
-    lds_copy_item(par_vbase + soff, ((uint64_t)whi << 32) | wlo, data_voff, slot, slot + kGemvSlotParamBytes, xhi);
+    lds_copy_item(par_vbase + soff, ((uint64_t)whi << 32) | wlo, data_voff, slot, slot + kPar, xhi, G64 ? ~0u : 0u);
   };
   constexpr int kCopiesPerItem = 2;
 
@@ -356,7 +405,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   // microsecond (the copies of 16 wavefronts queue up in one address unit), and the permutation would wait for it
   constexpr int kEarly = 2;
   const int npro = min(S, E);
-  for (int e = 0; e < min(kEarly, npro); ++e) issue_item(e, ring_off + (uint32_t)e * kSlotBytes);
+  for (int e = 0; e < min(kEarly, npro); ++e) issue_item(e, ring_off + (uint32_t)e * kSlot);
 
   // ---- while those copies are on their way: permute the activations inside LDS and add up each tile column
   barrier_lds_only();  // every wavefront's part of the raw copy has landed (each waited for its own above)
@@ -378,12 +427,17 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
       } else {
         v = *reinterpret_cast<const half8*>(Xs + 8 * i);
       }
-      const float s = unit_group_sum(v);
-      if ((lane & 15) == 0) lds_store_b32_untracked(Sx + i / 16, s);
+      if constexpr (G64) {
+        const float s = unit_half_group_sum(v);
+        if ((lane & 7) == 0) lds_store_b32_untracked(Sx + i / 8, s);
+      } else {
+        const float s = unit_group_sum(v);
+        if ((lane & 15) == 0) lds_store_b32_untracked(Sx + i / 16, s);
+      }
     }
   }
   barrier_lds_only();  // Xs and Sx are complete
-  for (int e = kEarly; e < npro; ++e) issue_item(e, ring_off + (uint32_t)e * kSlotBytes);
+  for (int e = kEarly; e < npro; ++e) issue_item(e, ring_off + (uint32_t)e * kSlot);
 
   half8 a[4];
 #pragma unroll
@@ -403,11 +457,17 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   // addresses are scalar plus a loop-invariant lane offset, the tile-column sums sit in one register (lane i:
   // this wavefront's i-th tile column) and reach a scalar register by v_readlane, the two parameters are
   // brought together by one byte permute and widened inside the fused multiply-adds.
-  float sx_lane = 0.f;
-  if (lane < my_cnt) sx_lane = Sx[wave + NW * lane];
-  uint32_t lane_w2 = kGemvSlotParamBytes + lane * 8, lane_w3 = kGemvSlotParamBytes + lane * 12,
-           lane_w4 = kGemvSlotParamBytes + lane * 16, lane_p = (lane & 15) * 4;
-  asm volatile("" : "+v"(lane_w2), "+v"(lane_w3), "+v"(lane_w4), "+v"(lane_p), "+v"(sx_lane));
+  float sx_lane = 0.f, sx_hi_lane = 0.f;  // (group length 64: the sums of columns 0-63 and 64-127)
+  if (lane < my_cnt) {
+    if constexpr (G64) {
+      sx_lane = Sx[2 * (wave + NW * lane)];
+      sx_hi_lane = Sx[2 * (wave + NW * lane) + 1];
+    } else {
+      sx_lane = Sx[wave + NW * lane];
+    }
+  }
+  uint32_t lane_w2 = kPar + lane * 8, lane_w3 = kPar + lane * 12, lane_w4 = kPar + lane * 16, lane_p = (lane & 15) * 4;
+  asm volatile("" : "+v"(lane_w2), "+v"(lane_w3), "+v"(lane_w4), "+v"(lane_p), "+v"(sx_lane), "+v"(sx_hi_lane));
   const unsigned char* lds0 = lds_raw - (uint32_t)(uintptr_t)(lptr_t)lds_raw;  // LDS byte 0
 
   auto consume = [&](int e, uint32_t slot) __attribute__((always_inline)) {
@@ -421,9 +481,43 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
     const float sx = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sx_lane), tc / NW));
     const uint32_t scw = *reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_p));
     const uint32_t zrw = *reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_p) + 64);
-    float t;
+    // low half: scale, high half: zero (bit 26 of misc: odd sigma -> the high halves of the two dwords)
+    const uint32_t sel = (misc & (1u << 26)) ? 0x07060302u : 0x05040100u;
     uint32_t w[4];
     const uint32_t* src;
+    if constexpr (G64) {
+      const float sx_hi =
+          __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sx_hi_lane), tc / NW));
+      const uint32_t scw_hi = *reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_p) + 128);
+      const uint32_t zrw_hi = *reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_p) + 192);
+      float t_lo, t_hi;
+      if (misc & (2u << 24)) {
+        src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w4));
+        w[0] = src[0], w[1] = src[1], w[2] = src[2], w[3] = src[3];
+        slab_dot_row0_halves<4>(w, a, t_lo, t_hi);
+      } else if (misc & (1u << 24)) {
+        src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w3));
+        w[0] = src[0], w[1] = src[1], w[2] = src[2];
+        slab_dot_row0_halves<3>(w, a, t_lo, t_hi);
+      } else {
+        src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w2));
+        w[0] = src[0], w[1] = src[1];
+        slab_dot_row0_halves<2>(w, a, t_lo, t_hi);
+      }
+      const uint32_t sz_lo = __builtin_amdgcn_perm(zrw, scw, sel), sz_hi = __builtin_amdgcn_perm(zrw_hi, scw_hi, sel);
+      float s_lo, z_lo, s_hi, z_hi;
+      params_to_float(sz_lo, sz_lo >> 16, 0, ANYFMT && p.bf16, s_lo, z_lo);
+      params_to_float(sz_hi, sz_hi >> 16, 0, ANYFMT && p.bf16, s_hi, z_hi);
+      acc_q += s_lo * t_lo + s_hi * t_hi;
+      acc_z += z_lo * sx + z_hi * sx_hi;
+      if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
+        asm volatile("" ::: "memory");
+        accs[(misc >> 17) & 15] = acc_q * 16777216.f + acc_z;
+        acc_q = 0.f, acc_z = 0.f;
+      }
+      return;
+    }
+    float t;
     if (misc & (2u << 24)) {
       src = reinterpret_cast<const uint32_t*>(lds0 + (slot + lane_w4));
       w[0] = src[0], w[1] = src[1], w[2] = src[2], w[3] = src[3];
@@ -437,8 +531,6 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
       w[0] = src[0], w[1] = src[1];
       t = slab_dot_row0_units<2>(w, a);
     }
-    // low half: scale, high half: zero (bit 26 of misc: odd sigma -> the high halves of the two dwords)
-    const uint32_t sel = (misc & (1u << 26)) ? 0x07060302u : 0x05040100u;
     const uint32_t sz = __builtin_amdgcn_perm(zrw, scw, sel);
     // (ANYFMT: the storage type of the parameters is looked up per item; the kernels for fp16 alone have no such
     // branch in the loop, which also spares the register copies where its two sides meet)
@@ -464,10 +556,10 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   uint32_t slot = ring_off;
   auto next_slot = [&]() __attribute__((always_inline)) {
     if constexpr (S == 2) {
-      slot = (2u * ring_off + kSlotBytes) - slot;
+      slot = (2u * ring_off + kSlot) - slot;
     } else {
-      slot += kSlotBytes;
-      if (slot == ring_off + S * kSlotBytes) slot = ring_off;
+      slot += kSlot;
+      if (slot == ring_off + S * kSlot) slot = ring_off;
     }
   };
   int e = 0;
@@ -519,7 +611,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
 // 14 dwords of scalar arguments (the four pointers of the first requests and the integers that address them) are
 // placed in scalar registers by the command processor before the first wavefront starts, so the kernel's first global
 // requests wait for no argument load; the rest of the arguments travel while those requests are in flight.
-template <int NW, int S, bool ANYFMT>
+template <int NW, int S, bool ANYFMT, bool G64 = false>
 __global__ __launch_bounds__(NW * 64) void gemv_kernel(
     const int32_t* tile_desc, const _Float16* X, const int32_t* col_perm, const int32_t* row_perm, int32_t nj_q,
     int32_t nj_r, int32_t ntr, int32_t ntc, int32_t K, int32_t grid, int32_t N, int32_t max_slabs, int32_t gshift,
@@ -530,7 +622,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(
   p.X = X, p.col_perm = col_perm, p.s2 = s2, p.s3 = s3, p.s4 = s4, p.tile_desc = tile_desc, p.scales = scales;
   p.zeros = zeros, p.row_perm = row_perm, p.Y = Y, p.N = N, p.K = K, p.ntr = ntr, p.ntc = ntc, p.nj_q = nj_q, p.nj_r = nj_r;
   p.max_slabs = max_slabs, p.gshift = gshift, p.bf16 = bf16;
-  gemv_body<NW, S, true, ANYFMT>(p, (int)blockIdx.x, grid, lds_raw);  // (gridDim.x would be one more load at entry)
+  gemv_body<NW, S, true, ANYFMT, G64>(p, (int)blockIdx.x, grid, lds_raw);  // (gridDim.x would be one more load at entry)
 }
 
 // Several independent M = 1 problems in one launch (for example q, k and v, or gate and up of a
@@ -558,7 +650,7 @@ __device__ __forceinline__ int batch_problem_of(const int32_t (&first)[kGemvMaxB
 // (first[1..8] arrive as scalar arguments, hence in preloaded scalar registers: a workgroup finds its problem, and
 // its range of workgroups, without a load and without a loop of dependent ones, then fetches that problem's arguments
 // in one go)
-template <int NW, int S, bool ANYFMT>
+template <int NW, int S, bool ANYFMT, bool G64 = false>
 __global__ __launch_bounds__(NW * 64) void gemv_batched_kernel(int32_t f1, int32_t f2, int32_t f3, int32_t f4,
                                                                int32_t f5, int32_t f6, int32_t f7, int32_t f8,
                                                                const GemvBatchProblems b) {
@@ -574,7 +666,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_batched_kernel(int32_t f1, int32
     hi = at_or_after ? hi : f[k];
   }
   const GemvParams p = b.p[i];
-  gemv_body<NW, S, false, ANYFMT>(p, bid - lo, hi - lo, lds_raw);
+  gemv_body<NW, S, false, ANYFMT, G64>(p, bid - lo, hi - lo, lds_raw);
 }
 
 // ============================================================================================
@@ -603,6 +695,7 @@ struct RSkinnyParams {
   int32_t M, N, K, ntr, ntc, max_slabs;
   int32_t nj_q, nj_r;  // as in GemvParams: slabs of workgroup b = nj_q + (b < nj_r)
   int32_t gshift, bf16;  // as in GemvParams
+  int32_t g64;           // group length 64 (read by the host only: it selects the kernel instantiation)
 };
 
 // one workgroup per tile column; thread (m, u) gathers the 8 columns of unit u' = u ^ m of row m
@@ -651,10 +744,13 @@ __host__ __device__ inline size_t rskinny_raw_bytes(int32_t M, int32_t K) { retu
 // ACC: slabs per workgroup whose finished sums are held in registers (4, 8 or 16; 4 x ACC registers).  With 16
 // the kernel needs about 130 vector registers and runs 8 wavefronts per CU; with 4 or 8 it stays below 128 and runs
 // 16, which is what covers the latencies of its loop.
-template <int NW, int S, int MB, bool RES, int ACC>
+// G64: group length 64 (two parameter pairs per row and tile column; never together with RES).
+template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false>
 __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int bid, const int G, unsigned char* lds_raw) {
+  static_assert(!(RES && G64), "the resident form keeps one activation sum per tile column");
   constexpr int NT = NW * 64;
-  constexpr int kSlot = RES ? kSlotBytes : rskinny_slot_bytes<MB>();
+  constexpr int kBase = G64 ? kSlotBytes64 : kSlotBytes;  // slab + parameters; the staged activations follow
+  constexpr int kSlot = RES ? kBase : kBase + MB * 256;
   constexpr int kCopies = RES ? 2 : 2 + MB / 4;  // direct copies per item: slab, scales+zeros, MB/4 x 1 KiB of activations
   constexpr int kRedGroups = NW / 4;  // the final sum over the wavefronts is taken in groups of four
   // LDS: red [NW/4][max_slabs][4][64] f32 | (Xs [ntc][MB][256 B] | SxL | raw activations [M][K] fp16) |
@@ -701,13 +797,15 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
                              ((d >> 2) * (8u * slab_bytes) + (uint32_t)sigma * slab_bytes);
       it_wlo = (uint32_t)waddr, it_whi = (uint32_t)(waddr >> 32);
       it_xhi = bm2 == 0 ? 0u : bm2 == 1 ? 0xFFFFu : 0xFFFFFFFFu;
-      it_soff = 2u * (uint32_t)((tc >> p.gshift) * p.N + tr * kTile + (sigma & ~1));
+      it_soff = 2u * (uint32_t)((G64 ? 2u * tc : tc >> p.gshift) * p.N + tr * kTile + (sigma & ~1));
       it_misc = (uint32_t)tc | ((i == (uint32_t)(my_cnt - 1)) ? 0x10000u : 0u) | ((uint32_t)j << 17) | (bm2 << 24) |
                 ((uint32_t)(sigma & 1) << 26);
     }
   };
   const uint32_t data_voff = lane * 16;
-  const uint64_t par_vbase = (lane < 16 ? (uint64_t)p.scales : (uint64_t)p.zeros) + (uint64_t)((lane & 15) * 16);
+  // (group length 64: lanes 32-63 read the next parameter row, as in the GEMV kernel)
+  const uint64_t par_vbase = ((lane & 16) == 0 ? (uint64_t)p.scales : (uint64_t)p.zeros) + (uint64_t)((lane & 15) * 16) +
+                             (G64 && lane >= 32 ? (uint64_t)p.N * 2 : (uint64_t)0);
 
   // Issue item e into ring slot s: the slab (scalar address, 32/48/64 lanes), the 16 scale + 16 zero dwords, and
   // without resident activations MB/4 KiB of staged activations of the item's tile column (scalar address)
@@ -720,12 +818,12 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
     const uint32_t xhi = (uint32_t)__builtin_amdgcn_readlane((int)it_xhi, e);
     const uint32_t soff = (uint32_t)__builtin_amdgcn_readlane((int)it_soff, e);
     const uint32_t slot = ring_off + (uint32_t)s * kSlot;
-    lds_copy_item(par_vbase + soff, ((uint64_t)whi << 32) | wlo, data_voff, slot + 1024, slot, xhi);
+    lds_copy_item(par_vbase + soff, ((uint64_t)whi << 32) | wlo, data_voff, slot + 1024, slot, xhi, G64 ? ~0u : 0u);
     if constexpr (!RES) {
       const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
       const uint64_t xsrc = xb + (uint64_t)(misc & 0xFFFF) * (MB * 256);
 #pragma unroll
-      for (int c = 0; c < MB / 4; ++c) lds_copy_b128(xsrc + c * 1024, data_voff, slot + kSlotBytes + c * 1024, ~0ull);
+      for (int c = 0; c < MB / 4; ++c) lds_copy_b128(xsrc + c * 1024, data_voff, slot + kBase + c * 1024, ~0ull);
     }
   };
 
@@ -814,7 +912,7 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   uint32_t a_off[4];
 #pragma unroll
   for (int kappa = 0; kappa < 4; ++kappa)
-    a_off[kappa] = (RES ? 0 : kSlotBytes) + i16 * 256 + (((4 * kappa + kb) ^ i16) * 16);
+    a_off[kappa] = (RES ? 0 : kBase) + i16 * 256 + (((4 * kappa + kb) ^ i16) * 16);
 
   // finished sums: accs[r][q] = output element r of this lane for slab q (register-indexed writes, no switch)
   static_assert(ACC == 4 || ACC == 8 || ACC == 16, "the finished sums live in 4-, 8- or 16-wide register vectors");
@@ -832,6 +930,48 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
       const unsigned char* abase = RES ? Xs + (size_t)(misc & 0xFFFF) * (MB * 256) : slot;
 #pragma unroll
       for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = *reinterpret_cast<const half8*>(abase + a_off[kappa]);
+    }
+    if constexpr (G64) {
+      // sums of the activations over columns 0-63 and 64-127, the code sums likewise, one parameter pair for each
+      floatx4 sx_lo = {0.f, 0.f, 0.f, 0.f}, sx_hi = {0.f, 0.f, 0.f, 0.f};
+      sx_lo = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[0], ones, sx_lo, 0, 0, 0);
+      sx_lo = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[1], ones, sx_lo, 0, 0, 0);
+      sx_hi = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[2], ones, sx_hi, 0, 0, 0);
+      sx_hi = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[3], ones, sx_hi, 0, 0, 0);
+      floatx4 t_lo, t_hi;
+      uint32_t w[4];
+      const uint32_t* src;
+      switch ((misc >> 24) & 3) {
+        case 0:
+          src = reinterpret_cast<const uint32_t*>(slot + lane * 8);
+          w[0] = src[0], w[1] = src[1];
+          slab_dot_halves<2>(w, a, t_lo, t_hi);
+          break;
+        case 1:
+          src = reinterpret_cast<const uint32_t*>(slot + lane * 12);
+          w[0] = src[0], w[1] = src[1], w[2] = src[2];
+          slab_dot_halves<3>(w, a, t_lo, t_hi);
+          break;
+        default:
+          src = reinterpret_cast<const uint32_t*>(slot + lane * 16);
+          w[0] = src[0], w[1] = src[1], w[2] = src[2], w[3] = src[3];
+          slab_dot_halves<4>(w, a, t_lo, t_hi);
+          break;
+      }
+      const uint32_t* par = reinterpret_cast<const uint32_t*>(slot + 1024 + (lane & 15) * 4);
+      float s_lo, z_lo, s_hi, z_hi;
+      params_to_float(par[0], par[16], (misc >> 22) & 16u, p.bf16 != 0, s_lo, z_lo);
+      params_to_float(par[32], par[48], (misc >> 22) & 16u, p.bf16 != 0, s_hi, z_hi);
+      acc_q += s_lo * t_lo + s_hi * t_hi;
+      acc_z += z_lo * sx_lo + z_hi * sx_hi;
+      if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
+        asm volatile("" ::: "memory");
+        const int q = (misc >> 17) & (ACC - 1);
+        const floatx4 acc = acc_q * 16777216.f + acc_z;
+        accs0[q] = acc[0], accs1[q] = acc[1], accs2[q] = acc[2], accs3[q] = acc[3];
+        acc_q = floatx4{0.f, 0.f, 0.f, 0.f}, acc_z = floatx4{0.f, 0.f, 0.f, 0.f};
+      }
+      return;
     }
     floatx4 sx;
     if constexpr (RES) {
@@ -950,10 +1090,10 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   }
 }
 
-template <int NW, int S, int MB, bool RES, int ACC>
+template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false>
 __global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  rskinny_body<NW, S, MB, RES, ACC>(p, (int)blockIdx.x, (int)gridDim.x, lds_raw);
+  rskinny_body<NW, S, MB, RES, ACC, G64>(p, (int)blockIdx.x, (int)gridDim.x, lds_raw);
 }
 
 // Several independent problems with the same M in one launch (q, k and v, or gate and up of a decoder
@@ -966,12 +1106,12 @@ struct RSkinnyBatch {  // laid out as GemvBatch
 };
 static_assert(offsetof(RSkinnyBatch, p) == 64, "the header of a batch is one 64-byte line");
 
-template <int NW, int S, int MB, bool RES, int ACC>
+template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false>
 __global__ __launch_bounds__(NW * 64) void rskinny_batched_kernel(const RSkinnyBatch b) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int i = batch_problem_of(b.first, (int)blockIdx.x);
   const RSkinnyParams p = b.p[i];
-  rskinny_body<NW, S, MB, RES, ACC>(p, (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
+  rskinny_body<NW, S, MB, RES, ACC, G64>(p, (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
 }
 
 // Staging for a batch: job j (one per distinct activation matrix) owns workgroups [first[j], first[j+1]).
@@ -1013,16 +1153,17 @@ struct GemvFit {
 };
 // LDS of the GEMV kernel in front of the rings: activations, their tile-column sums, the shared region
 static int64_t gemv_fixed_lds_bytes(int32_t K, int32_t max_slabs) {
-  return ((int64_t)K * 2 + (int64_t)(K / kTile) * 4 + 15) / 16 * 16 + gemv_shared_region_bytes(K, max_slabs, kGemvWaves);
+  return ((int64_t)K * 2 + (int64_t)(K / kTile) * 8 + 15) / 16 * 16 + gemv_shared_region_bytes(K, max_slabs, kGemvWaves);
 }
 static GemvFit gemv_fit(int32_t N, int32_t K, int32_t grid) {
   GemvFit f;
   const int32_t ntr = N / kTile, ntc = K / kTile, nslab = 8 * ntr;
   f.max_slabs = (nslab + grid - 1) / grid;
   const int64_t fixed = gemv_fixed_lds_bytes(K, f.max_slabs);
-  int64_t slots = (160 * 1024 - fixed) / ((int64_t)kGemvWaves * kSlotBytes);
+  // (the rings are sized for the slots of group length 64, 128 bytes larger, whatever the layout)
+  int64_t slots = (160 * 1024 - fixed) / ((int64_t)kGemvWaves * kSlotBytes64);
   if (slots > kGemvMaxSlots) slots = kGemvMaxSlots;
-  const int64_t ring_bytes = slots * kGemvWaves * kSlotBytes;
+  const int64_t ring_bytes = slots * kGemvWaves * kSlotBytes64;
   const int64_t items = (int64_t)f.max_slabs * ((ntc + kGemvWaves - 1) / kGemvWaves);
   f.ok = grid >= 8 && grid % 8 == 0 && grid <= nslab && slots >= kGemvMinSlots && f.max_slabs <= kGemvMaxSlabs &&
          items <= kGemvMaxItems && K / 8 <= kGemvUnitIters * kGemvWaves * 64;
@@ -1042,9 +1183,10 @@ static int32_t rskinny_mb(int32_t M) { return M <= 4 ? 4 : M <= 8 ? 8 : 16; }
 // their raw copy), rings
 static int64_t rskinny_lds_bytes(const RSkinnyConfig& c, int32_t max_slabs, int32_t M, int32_t K) {
   const int64_t red = (int64_t)max_slabs * 1024 * (c.nw / 4);
+  // (slots sized for group length 64, 128 bytes larger, whatever the layout)
   return c.resident ? red + (int64_t)c.mb * K * 2 + (int64_t)(K / kTile) * 64 + (int64_t)rskinny_raw_bytes(M, K) +
-                          (int64_t)c.nw * c.slots * kSlotBytes
-                    : red + (int64_t)c.nw * c.slots * (kSlotBytes + c.mb * 256);
+                          (int64_t)c.nw * c.slots * kSlotBytes64
+                    : red + (int64_t)c.nw * c.slots * (kSlotBytes64 + c.mb * 256);
 }
 // The resident variant (activations staged into LDS by every workgroup, no staging kernel) exists for blocks of
 // 4 rows and M x K activations of at most 32 KiB: measured, the saved launch outweighs 256 workgroups each permuting
@@ -1056,7 +1198,8 @@ constexpr int kSlotsResident = 3, kSlotsMb4 = 2, kSlotsMb8 = 2, kSlotsMb16 = 2;
 // wavefronts of the SIMD cover the wait)
 constexpr int kSlotsMb16Wide = 1;
 // max_slabs: the largest number of slabs of a workgroup over the problems of the launch; K: the largest K
-static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs) {
+// g64: group length 64, for which the resident form does not exist
+static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs, bool g64) {
   RSkinnyConfig c;
   c.mb = rskinny_mb(M);
   // 16 wavefronts where the finished sums fit beside the rest in 128 registers and the rings in LDS
@@ -1064,7 +1207,7 @@ static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs) {
   c.nw = wide ? 16 : 8;
   c.acc = !wide ? 16 : max_slabs <= 4 ? 4 : 8;
   c.resident = false;
-  if (c.mb == 4 && (int64_t)M * K * 2 <= kResidentMaxRawBytes && K / 8 <= kGemvUnitIters * c.nw * 64) {
+  if (!g64 && c.mb == 4 && (int64_t)M * K * 2 <= kResidentMaxRawBytes && K / 8 <= kGemvUnitIters * c.nw * 64) {
     c.resident = true;
     c.slots = kSlotsResident;
     if (rskinny_lds_bytes(c, max_slabs, M, K) > 160 * 1024) c.resident = false;
@@ -1073,7 +1216,7 @@ static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs) {
   return c;
 }
 
-DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
+DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M, int32_t group) {
   DecodePlan d;
   const int32_t ntr = N / kTile, ntc = K / kTile, nslab = 8 * ntr;
   // GEMV: persistent grid of at most 256 workgroups (multiple of 8), 16 wavefronts each.
@@ -1099,7 +1242,7 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M) {
   d.gemv = false;
   d.grid = grid;
   d.max_slabs = (nslab + grid - 1) / grid;
-  const RSkinnyConfig c = rskinny_config(M, K, d.max_slabs);
+  const RSkinnyConfig c = rskinny_config(M, K, d.max_slabs, group == 64);
   d.mb = c.mb;
   d.nw = c.nw;
   d.acc = c.acc;
@@ -1132,6 +1275,7 @@ static GemvParams gemv_params(const GemmArgs& a, int32_t max_slabs, int32_t grid
   p.max_slabs = max_slabs;
   p.gshift = L->group == 512 ? 2 : L->group == 256 ? 1 : 0;
   p.bf16 = L->scale_format == SFMP_SCALE_BF16;
+  p.g64 = L->group == 64;
   return p;
 }
 
@@ -1153,8 +1297,10 @@ static int launch_gemv_plain(GemvParams q, int32_t grid, size_t lds_bytes, void*
   void* kargs[] = {&q.tile_desc, &q.X, &q.col_perm, &q.row_perm, &q.nj_q, &q.nj_r, &q.ntr, &q.ntc, &q.K, &grid,
                    &q.N, &q.max_slabs, &q.gshift, &q.bf16, &q.s2, &q.s3, &q.s4, &q.scales, &q.zeros, &q.Y};
   const bool any = q.bf16 != 0;
-  const void* fn = any ? reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, 2, true>)
-                       : reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, 2, false>);
+  // (group length 64: one instantiation, which looks the storage type of the parameters up at run time)
+  const void* fn = q.g64 ? reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, 2, true, true>)
+                   : any ? reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, 2, true>)
+                         : reinterpret_cast<const void*>(&gemv_kernel<kGemvWaves, 2, false>);
   return launch_gemv_function(fn, kargs, (unsigned)grid, lds_bytes, stream);
 }
 
@@ -1162,9 +1308,12 @@ static int launch_gemv_batch(GemvBatch b, size_t lds_bytes, void* stream) {
   void* kargs[] = {&b.first[1], &b.first[2], &b.first[3], &b.first[4], &b.first[5],
                    &b.first[6], &b.first[7], &b.first[8], &b.probs};
   bool any = false;
-  for (int i = 0; i < b.count; ++i) any = any || b.probs.p[i].bf16 != 0;
-  const void* fn = any ? reinterpret_cast<const void*>(&gemv_batched_kernel<kGemvWaves, 2, true>)
-                       : reinterpret_cast<const void*>(&gemv_batched_kernel<kGemvWaves, 2, false>);
+  int n64 = 0;
+  for (int i = 0; i < b.count; ++i) any = any || b.probs.p[i].bf16 != 0, n64 += b.probs.p[i].g64 != 0;
+  if (n64 != 0 && n64 != b.count) return SFMP_ERR_SHAPE;  // one launch runs one group-length class: 64, or the others
+  const void* fn = n64    ? reinterpret_cast<const void*>(&gemv_batched_kernel<kGemvWaves, 2, true, true>)
+                   : any ? reinterpret_cast<const void*>(&gemv_batched_kernel<kGemvWaves, 2, true>)
+                         : reinterpret_cast<const void*>(&gemv_batched_kernel<kGemvWaves, 2, false>);
   return launch_gemv_function(fn, kargs, (unsigned)b.first[kGemvMaxBatch], lds_bytes, stream);
 }
 
@@ -1204,7 +1353,7 @@ int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
   for (int i = 0; i < count; ++i)
     if (!decode_offsets_fit(probs[i].L)) return SFMP_ERR_SHAPE;
   // a single problem takes the plain kernel: its arguments are the kernel's own, one line fetched once
-  if (count == 1 && probs[0].M == 1 && make_decode_plan(probs[0].L->N, probs[0].L->K, 1).gemv)
+  if (count == 1 && probs[0].M == 1 && make_decode_plan(probs[0].L->N, probs[0].L->K, 1, probs[0].L->group).gemv)
     return launch_decode(probs[0], stream);
   int32_t g[kGemvMaxBatch];
   if (int e = split_grid(probs, count, g)) return e;
@@ -1224,7 +1373,7 @@ int launch_gemv_batched(const GemmArgs* probs, int count, void* stream) {
   // with fewer slots than a problem could use alone its LDS footprint only shrinks: size for the largest
   for (int i = 0; i < count; ++i) {
     const sfmp_layout_t* L = probs[i].L;
-    const int64_t need = gemv_fixed_lds_bytes(L->K, b.probs.p[i].max_slabs) + (int64_t)slots * kGemvWaves * kSlotBytes;
+    const int64_t need = gemv_fixed_lds_bytes(L->K, b.probs.p[i].max_slabs) + (int64_t)slots * kGemvWaves * kSlotBytes64;
     lds = need > lds ? (int32_t)need : lds;
   }
   return launch_gemv_batch(b, (size_t)lds, stream);
@@ -1254,13 +1403,14 @@ static RSkinnyParams rskinny_params(const GemmArgs& a, int32_t M, const void* xb
   p.max_slabs = max_slabs;
   p.gshift = L->group == 512 ? 2 : L->group == 256 ? 1 : 0;
   p.bf16 = L->scale_format == SFMP_SCALE_BF16;
+  p.g64 = L->group == 64;
   return p;
 }
 
-template <int NW, int S, int MB, bool RES, int ACC>
+template <int NW, int S, int MB, bool RES, int ACC, bool G64>
 static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* stream) {
   const sfmp_layout_t* L = a.L;
-  const void* fn = reinterpret_cast<const void*>(&rskinny_kernel<NW, S, MB, RES, ACC>);
+  const void* fn = reinterpret_cast<const void*>(&rskinny_kernel<NW, S, MB, RES, ACC, G64>);
   if (int e = allow_full_lds(fn, "hipFuncSetAttribute(skinny)")) return e;
   if (!RES) {
     hipLaunchKernelGGL((stage_rows_kernel<MB>), dim3((unsigned)(L->K / kTile)), dim3(MB * 16), 0, (hipStream_t)stream,
@@ -1286,8 +1436,12 @@ static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* 
 
 static int launch_rskinny(const GemmArgs& a, const DecodePlan& d, void* stream) {
 #define SFMP_X(NW_, S_, MB_, RES_, ACC_)                                                      \
-  if (d.nw == NW_ && d.mb == MB_ && d.resident == RES_ && d.acc == ACC_ && d.slots == S_)     \
-    return launch_rskinny_variant<NW_, S_, MB_, RES_, ACC_>(a, d, stream);
+  if (d.nw == NW_ && d.mb == MB_ && d.resident == RES_ && d.acc == ACC_ && d.slots == S_) {   \
+    if constexpr (!RES_) {                                                                    \
+      if (a.L->group == 64) return launch_rskinny_variant<NW_, S_, MB_, RES_, ACC_, true>(a, d, stream); \
+    }                                                                                         \
+    return launch_rskinny_variant<NW_, S_, MB_, RES_, ACC_, false>(a, d, stream);             \
+  }
   SFMP_RSKINNY_CONFIGS(SFMP_X)
 #undef SFMP_X
   return SFMP_ERR_SHAPE;
@@ -1328,7 +1482,7 @@ int64_t batched_workspace_bytes(const GemmArgs* probs, int count, int32_t M) {
   return plan_batch_staging(probs, count, rskinny_mb(M)).bytes;
 }
 
-template <int NW, int S, int MB, bool RES, int ACC>
+template <int NW, int S, int MB, bool RES, int ACC, bool G64>
 static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int32_t M, const int32_t* g,
                                           void* workspace, void* stream) {
   const BatchStagePlan sp = plan_batch_staging(probs, count, MB);
@@ -1374,7 +1528,7 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
   for (int i = count; i <= kGemvMaxBatch; ++i) b.first[i] = first;
   for (int i = count; i < kGemvMaxBatch; ++i) b.p[i] = b.p[0];
   if (lds > 160 * 1024) return SFMP_ERR_SHAPE;
-  const void* fn = reinterpret_cast<const void*>(&rskinny_batched_kernel<NW, S, MB, RES, ACC>);
+  const void* fn = reinterpret_cast<const void*>(&rskinny_batched_kernel<NW, S, MB, RES, ACC, G64>);
   if (int e = allow_full_lds(fn, "hipFuncSetAttribute(skinny batched)")) return e;
   if (!RES) {
     hipLaunchKernelGGL((stage_rows_batched_kernel<MB>), dim3((unsigned)sfirst), dim3(MB * 16), 0, (hipStream_t)stream, sb);
@@ -1404,10 +1558,17 @@ int launch_decode_batched(const GemmArgs* probs, int count, int32_t M, void* wor
     max_slabs = std::max(max_slabs, (nslab + g[i] - 1) / g[i]);
     max_k = std::max(max_k, probs[i].L->K);
   }
-  const RSkinnyConfig c = rskinny_config(M, max_k, max_slabs);
+  int n64 = 0;
+  for (int i = 0; i < count; ++i) n64 += probs[i].L->group == 64;
+  if (n64 != 0 && n64 != count) return SFMP_ERR_SHAPE;  // one launch runs one group-length class: 64, or the others
+  const RSkinnyConfig c = rskinny_config(M, max_k, max_slabs, n64 != 0);
 #define SFMP_X(NW_, S_, MB_, RES_, ACC_)                                                    \
-  if (c.nw == NW_ && c.mb == MB_ && c.resident == RES_ && c.acc == ACC_ && c.slots == S_)   \
-    return launch_rskinny_batched_variant<NW_, S_, MB_, RES_, ACC_>(probs, count, M, g, workspace, stream);
+  if (c.nw == NW_ && c.mb == MB_ && c.resident == RES_ && c.acc == ACC_ && c.slots == S_) { \
+    if constexpr (!RES_) {                                                                  \
+      if (n64) return launch_rskinny_batched_variant<NW_, S_, MB_, RES_, ACC_, true>(probs, count, M, g, workspace, stream); \
+    }                                                                                       \
+    return launch_rskinny_batched_variant<NW_, S_, MB_, RES_, ACC_, false>(probs, count, M, g, workspace, stream); \
+  }
   SFMP_RSKINNY_CONFIGS(SFMP_X)
 #undef SFMP_X
   return SFMP_ERR_SHAPE;
@@ -1458,7 +1619,7 @@ static bool decode_offsets_fit(const sfmp_layout_t* L) { return (int64_t)L->N * 
 int launch_decode(const GemmArgs& a, void* stream) {
   const sfmp_layout_t* L = a.L;
   if (!decode_offsets_fit(L)) return SFMP_ERR_SHAPE;
-  const DecodePlan d = make_decode_plan(L->N, L->K, a.M);
+  const DecodePlan d = make_decode_plan(L->N, L->K, a.M, L->group);
   if (d.gemv) {
     const GemvParams p = gemv_params(a, d.max_slabs, d.grid);
     return launch_gemv_plain(p, d.grid, (size_t)d.lds_bytes, stream);

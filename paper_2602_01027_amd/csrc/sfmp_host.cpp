@@ -23,7 +23,8 @@ int check_layout(const sfmp_layout_t* L) {
   if (!L) return SFMP_ERR_NULL;
   if (check_shape(L->N, L->K) != SFMP_OK) return SFMP_ERR_SHAPE;
   if (L->tile != SFMP_TILE) return SFMP_ERR_LAYOUT;
-  if ((L->group != 128 && L->group != 256 && L->group != 512) || (L->K % L->group) != 0) return SFMP_ERR_LAYOUT;
+  if ((L->group != 64 && L->group != 128 && L->group != 256 && L->group != 512) || (L->K % L->group) != 0)
+    return SFMP_ERR_LAYOUT;
   if (L->scale_format != SFMP_SCALE_FP16 && L->scale_format != SFMP_SCALE_BF16) return SFMP_ERR_LAYOUT;
   const int64_t ntr = L->N / SFMP_TILE, ntc = L->K / SFMP_TILE, nt = ntr * ntc;
   if (L->count2 < 0 || L->count3 < 0 || L->count4 < 0) return SFMP_ERR_LAYOUT;

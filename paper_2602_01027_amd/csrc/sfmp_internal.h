@@ -23,7 +23,7 @@ struct DecodePlan {
   bool resident;     // ring-skinny: activations staged into LDS by the kernel itself, no staging launch
   int64_t workspace_bytes;  // staged activations of the ring-skinny kernel
 };
-DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M);
+DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M, int32_t group);
 
 // Prefill path (M > 16): workspace holds the column-gathered activation.
 struct PrefillPlan {

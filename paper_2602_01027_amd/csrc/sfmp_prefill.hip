@@ -222,7 +222,8 @@ struct PrefillShape {
   static constexpr int kPasses = BM / kRowsPerPass;
 };
 
-template <int BM, int WM, int WN, int IL = 2>
+// G64: group length 64 - a tile column has two (scale, zero) pairs per row, one for its k-steps 0-1 and one for 2-3.
+template <int BM, int WM, int WN, int IL = 2, bool G64 = false>
 __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) / 4)) void prefill_kernel(const PrefillParams p) {
   using S = PrefillShape<BM, WM, WN>;
   constexpr int MI = S::kMI, NS = S::kNS;
@@ -315,16 +316,19 @@ __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) 
   // Packed weights of one tile for this wavefront: one load of 4*b bytes per slab and lane, whatever the
   // width (equal load counts on the three paths keep the compiler's wait counts exact), plus NS
   // consecutive fp16 scales and zeros (rows 8*i16 + NS*wn + 0..NS-1 of the tile).
+  constexpr int NG = G64 ? 2 : 1;  // parameter pairs per row and tile column
   struct SZ {
-    uint32_t s[NS / 2], z[NS / 2];
+    uint32_t s[NG][NS / 2], z[NG][NS / 2];
   };
   auto issue_sz = [&](int tc, SZ& rsz) __attribute__((always_inline)) {
-    const int64_t off = (int64_t)(tc >> p.gshift) * p.N + (int64_t)tr * 128 + 8 * i16 + NS * wn;
+    const int64_t off = (int64_t)(G64 ? 2 * tc : tc >> p.gshift) * p.N + (int64_t)tr * 128 + 8 * i16 + NS * wn;
 #pragma unroll
-    for (int q = 0; q < NS / 2; ++q) {
-      rsz.s[q] = reinterpret_cast<const uint32_t*>(p.scales + off)[q];
-      rsz.z[q] = reinterpret_cast<const uint32_t*>(p.zeros + off)[q];
-    }
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+      for (int q = 0; q < NS / 2; ++q) {
+        rsz.s[g][q] = reinterpret_cast<const uint32_t*>(p.scales + off + (int64_t)g * p.N)[q];
+        rsz.z[g][q] = reinterpret_cast<const uint32_t*>(p.zeros + off + (int64_t)g * p.N)[q];
+      }
   };
   // width known at compile time (the next tile belongs to the same run): no branch around the loads, so
   // they land in place and nothing waits for them before the next step
@@ -382,7 +386,7 @@ __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) 
   // operand reads of block e have returned, block e+1 and tile e+1 have landed, a barrier, and the loads of
   // e+2 start; the fourth group then already prepares k-step 0 of tile e+1.
   u32x4 w[NS];
-  half2_ s2[NS], z2[NS];
+  half2_ s2[NG][NS], z2[NG][NS];
   half8 a0[MI], a1[MI], b0[NS], b1[NS];
 
   auto read_a = [&](int e, auto ktag, half8(&a)[MI]) __attribute__((always_inline)) {
@@ -394,7 +398,8 @@ __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) 
 #pragma unroll
     for (int j = 0; j < NS; ++j) {
       const uint32_t words[4] = {w[j][0], w[j][1], w[j][2], w[j][3]};
-      b[j] = dequant_operand<decltype(btag)::value, decltype(ktag)::value>(words, s2[j], z2[j], magic);
+      constexpr int g = G64 ? decltype(ktag)::value / 2 : 0;  // k-steps 0-1 / 2-3 = columns 0-63 / 64-127
+      b[j] = dequant_operand<decltype(btag)::value, decltype(ktag)::value>(words, s2[g][j], z2[g][j], magic);
     }
   };
   auto make_b_any = [&](int e, auto ktag, half8(&b)[NS]) __attribute__((always_inline)) {
@@ -433,27 +438,31 @@ __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) 
       asm volatile("" : "+v"(w[i]));
     }
 #pragma unroll
-    for (int i = 0; i < NS / 2; ++i) {
-      rsz.s[i] = fsz.s[i];
-      rsz.z[i] = fsz.z[i];
-      asm volatile("" : "+v"(rsz.s[i]), "+v"(rsz.z[i]));
-    }
+    for (int g = 0; g < NG; ++g)
 #pragma unroll
-    for (int j = 0; j < NS; ++j) {
-      union {
-        uint32_t u;
-        _Float16 h[2];
-      } sv, zv;
-      sv.u = rsz.s[j / 2];
-      zv.u = rsz.z[j / 2];
-      _Float16 sh = sv.h[j % 2], zh = zv.h[j % 2];
-      if (p.bf16) {  // bfloat16 = top half of a float; the dequantisation runs in fp16
-        sh = (_Float16)__uint_as_float((j % 2 ? sv.u >> 16 : sv.u & 0xFFFFu) << 16);
-        zh = (_Float16)__uint_as_float((j % 2 ? zv.u >> 16 : zv.u & 0xFFFFu) << 16);
+      for (int i = 0; i < NS / 2; ++i) {
+        rsz.s[g][i] = fsz.s[g][i];
+        rsz.z[g][i] = fsz.z[g][i];
+        asm volatile("" : "+v"(rsz.s[g][i]), "+v"(rsz.z[g][i]));
       }
-      s2[j] = half2_{sh, sh};
-      z2[j] = half2_{zh, zh};
-    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+      for (int j = 0; j < NS; ++j) {
+        union {
+          uint32_t u;
+          _Float16 h[2];
+        } sv, zv;
+        sv.u = rsz.s[g][j / 2];
+        zv.u = rsz.z[g][j / 2];
+        _Float16 sh = sv.h[j % 2], zh = zv.h[j % 2];
+        if (p.bf16) {  // bfloat16 = top half of a float; the dequantisation runs in fp16
+          sh = (_Float16)__uint_as_float((j % 2 ? sv.u >> 16 : sv.u & 0xFFFFu) << 16);
+          zh = (_Float16)__uint_as_float((j % 2 ? zv.u >> 16 : zv.u & 0xFFFFu) << 16);
+        }
+        s2[g][j] = half2_{sh, sh};
+        z2[g][j] = half2_{zh, zh};
+      }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -588,11 +597,11 @@ __global__ __launch_bounds__(64 * WM * WN, (BM <= 128 ? 2 : 1) * ((WM * WN + 3) 
   }
 }
 
-template <int BM, int WM, int WN, int IL = 2>
+template <int BM, int WM, int WN, bool G64>
 static void launch_prefill_shape(PrefillParams p, int M, hipStream_t stream) {
   p.n_mtiles = (M + BM - 1) / BM;
   const unsigned grid = (unsigned)p.n_mtiles * (unsigned)p.ntr * (unsigned)p.ksplit;
-  hipLaunchKernelGGL((prefill_kernel<BM, WM, WN, IL>), dim3(grid), dim3(64 * WM * WN), 0, stream, p);
+  hipLaunchKernelGGL((prefill_kernel<BM, WM, WN, 2, G64>), dim3(grid), dim3(64 * WM * WN), 0, stream, p);
 }
 
 PrefillPlan make_prefill_plan(int32_t N, int32_t K, int32_t M) {
@@ -665,10 +674,18 @@ int launch_prefill(const GemmArgs& a, void* stream) {
   p.n_mtiles = 0;
   p.ksplit = plan.ksplit;
   p.partial = plan.ksplit > 1 ? (float*)((char*)a.workspace + plan.xperm_bytes) : nullptr;
-  if (plan.bm == 64)
-    launch_prefill_shape<64, 1, 4>(p, a.M, (hipStream_t)stream);
-  else
-    launch_prefill_shape<128, 1, 4>(p, a.M, (hipStream_t)stream);
+  const bool g64 = L->group == 64;
+  if (plan.bm == 64) {
+    if (g64)
+      launch_prefill_shape<64, 1, 4, true>(p, a.M, (hipStream_t)stream);
+    else
+      launch_prefill_shape<64, 1, 4, false>(p, a.M, (hipStream_t)stream);
+  } else {
+    if (g64)
+      launch_prefill_shape<128, 1, 4, true>(p, a.M, (hipStream_t)stream);
+    else
+      launch_prefill_shape<128, 1, 4, false>(p, a.M, (hipStream_t)stream);
+  }
   if (int e = check_launch("sfmp_gemm prefill launch")) return e;
   if (plan.ksplit > 1) {
     hipLaunchKernelGGL(reduce_split_kernel, dim3((unsigned)a.M), dim3(1024), (size_t)L->N * 2, (hipStream_t)stream,

@@ -11,7 +11,7 @@ that a weight matrix is stored [N, K] = [output features, input features]):
   per block as in the "Extra Metadata" paragraph of Section 4.2).
 * ``codes``    uint8 ``[N, K]`` integer codes of ``Wt``; ``scales`` / ``zeros``
   ``[K/G, N]``: one (s, z) pair per row per group of G reordered columns (G = 128 by
-  default; 256 and 512 as in the paper's ablation of the block width n_b, which is also its
+  default; 64, 256 and 512 as in the paper's ablation of the block width n_b, which is also its
   group size), stored as fp16, or as bf16 (the paper's storage type) held in float32 arrays.
 """
 from __future__ import annotations
@@ -155,7 +155,11 @@ def _store(x: np.ndarray, scale_format: str) -> np.ndarray:
 
 
 def _group_widths(bitmap: np.ndarray, group: int) -> np.ndarray:
-    """Width of every (tile row, group): all tiles under a group must agree."""
+    """Width of every (tile row, group): all tiles under a group must agree; a group shorter than a tile (64)
+    has the width of the tile that holds it."""
+    if group < TILE:
+        assert TILE % group == 0
+        return np.repeat(bitmap, TILE // group, axis=1)
     tpg = group // TILE
     assert group % TILE == 0 and bitmap.shape[1] % tpg == 0
     bg = bitmap.reshape(bitmap.shape[0], bitmap.shape[1] // tpg, tpg)
@@ -285,7 +289,7 @@ class Problem:
     Wt: Optional[np.ndarray] = None  # fp16 [N, K] reordered, if kept
     seed: int = 0
     meta: dict = field(default_factory=dict)
-    group: int = GROUP  # quantisation group length along K (128, 256 or 512)
+    group: int = GROUP  # quantisation group length along K (64, 128, 256 or 512)
     scale_format: str = "fp16"  # storage type of scales and zeros: "fp16" or "bf16"
 
     @property

@@ -399,11 +399,12 @@ def test_gemm_batched_shared_activations(torch_cuda, M):
 # ---------------------------------------------------------------------------------------------
 # group lengths 256 / 512, bf16 parameters, (m_b, n_b) bit-allocation blocks
 # ---------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("M", [1, 5, 16, 48])
-@pytest.mark.parametrize("group,scale_format,block", [(128, "bf16", (4, 1)), (256, "fp16", (2, 2)),
-                                                      (256, "bf16", (4, 2)), (512, "bf16", (4, 4))])
+@pytest.mark.parametrize("M", [1, 5, 16, 48, 200])
+@pytest.mark.parametrize("group,scale_format,block", [(64, "fp16", (1, 1)), (64, "bf16", (4, 1)), (128, "bf16", (4, 1)),
+                                                      (256, "fp16", (2, 2)), (256, "bf16", (4, 2)), (512, "bf16", (4, 4))])
 def test_group_length_and_parameter_format(torch_cuda, group, scale_format, block, M):
-    # K = 1536: 12 tile columns = 6 / 3 groups of 256 / 512; N = 1024: two (512 x n_b) block rows
+    # K = 1536: 12 tile columns = 24 groups of 64 (two per tile) or 6 / 3 groups of 256 / 512; N = 1024: two
+    # (512 x n_b) block rows.  M = 200: the matrix-core kernel with 128-row blocks
     from gpu_util import run_gemm
     p = W.make_problem("fmt", 1536, 1024, M, 606 + group, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, outliers=True,
                        group=group, scale_format=scale_format, block=block)
@@ -437,6 +438,38 @@ def test_small_magnitude_weights_bf16_parameters(torch_cuda, M):
     tol = elementwise_tolerance(M, p.K, ref[:, p.row_perm], A, B, X1) + 17 * FLOOR16 * X1
     assert np.all(np.abs(Y.astype(np.float64)[:, p.row_perm] - ref[:, p.row_perm]) <= tol)
     assert O.rel_frobenius(Y, ref) <= 2e-2  # degraded, as documented, but not garbage
+
+
+@pytest.mark.parametrize("M", [1, 3, 12])
+def test_batched_launch_group_64(torch_cuda, M):
+    # group length 64 through the batched launches (GEMV, ring kernel); a batch that mixes it with another group
+    # length is refused (one launch runs one group-length class)
+    import paper_2602_01027_amd as S
+    from gpu_util import device_problem, run_gemm
+    torch = torch_cuda
+    probs, batch, keep = [], [], []
+    for i, (fmt, N) in enumerate([("fp16", 384), ("bf16", 256)]):
+        p = W.make_problem(f"g64.{i}", 1024, N, M, 950 + i, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, group=64,
+                           scale_format=fmt, outliers=True)
+        dp, cp, rp = device_problem(p)
+        Y = torch.full((M, p.N), float("nan"), dtype=torch.float16, device="cuda:0")
+        probs.append(p)
+        batch.append((torch.from_numpy(p.X).to("cuda:0"), cp, dp, rp, Y))
+        keep.append((dp, cp, rp))
+    ws = torch.empty(S.sfmp_gemm_batched_workspace(batch, M), dtype=torch.uint8, device="cuda:0").fill_(0xFF)
+    S.sfmp_gemm_batched(batch, M, ws)
+    torch.cuda.synchronize()
+    for p, (_, _, _, _, Y), (dp, cp, rp) in zip(probs, batch, keep):
+        y = Y.cpu().numpy()
+        _check(p, y)
+        assert np.array_equal(run_gemm(p, dp, cp, rp).view(np.uint16), y.view(np.uint16))
+    other = W.make_problem("g128", 1024, 256, M, 960, fractions={2: 0.5, 4: 0.5})
+    dpo, cpo, rpo = device_problem(other)
+    Yo = torch.zeros((M, other.N), dtype=torch.float16, device="cuda:0")
+    mixed = batch[:1] + [(torch.from_numpy(other.X).to("cuda:0"), cpo, dpo, rpo, Yo)]
+    with pytest.raises(S.SfmpError) as e:
+        S.sfmp_gemm_batched(mixed, M, ws)
+    assert e.value.code == -2
 
 
 def test_batched_launch_with_mixed_parameter_formats(torch_cuda):

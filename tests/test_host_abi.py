@@ -119,13 +119,13 @@ def test_layout_set_quant_accepts_the_documented_formats_only():
     bitmap = np.full((1, 4), 3, dtype=np.int8)  # N = 128, K = 512
     L = S.sfmp_pack_query(bitmap, 128, 512)
     assert (L.group, L.scale_format) == (128, 0)
-    for group in (128, 256, 512):
+    for group in (64, 128, 256, 512):
         for fmt, code in (("fp16", 0), ("bf16", 1)):
             S.sfmp_layout_set_quant(L, group, fmt)
             assert (L.group, L.scale_format) == (group, code)
     S.sfmp_layout_set_quant(L, 128, "fp16")
     lib = S.load_library()
-    for group, fmt in ((64, 0), (1024, 0), (384, 0), (128, 2), (256, -1)):
+    for group, fmt in ((32, 0), (1024, 0), (384, 0), (128, 2), (256, -1)):
         assert lib.sfmp_layout_set_quant(C.byref(L), group, fmt) == -8
         assert (L.group, L.scale_format) == (128, 0)  # a rejected call leaves the layout alone
     # K must be a multiple of the group

@@ -207,6 +207,40 @@ def test_longer_groups_match_bruteforce_and_reduce_to_group_128(group):
     assert (err <= 0.5 * step * (1 + 1e-2) + 1e-3 * np.abs(p.Wt.astype(np.float64)) + 1e-6).all()
 
 
+def test_group_64_matches_bruteforce_and_reduces_to_group_128():
+    # "Effect of n_b" (Appendix G): 64 columns per (scale, zero) pair, two groups inside every 128-column tile
+    p = _small_problem(seed=23, N=256, K=512, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, group=64)
+    assert p.scales.shape == (p.K // 64, p.N) and O.group_length(p.K, p.scales) == 64
+    w_hat = O.dequant(p.codes, p.scales, p.zeros)
+    rng = np.random.default_rng(4)
+    for n, k in zip(rng.integers(0, p.N, 300), rng.integers(0, p.K, 300)):
+        g = k // 64
+        assert w_hat[n, k] == float(p.scales[g, n]) * float(p.codes[n, k]) + float(p.zeros[g, n])
+    # columns 64..127 of a tile use the second pair: swapping the two pairs of a tile changes exactly those tiles
+    sw_s, sw_z = p.scales.copy(), p.zeros.copy()
+    sw_s[[0, 1]], sw_z[[0, 1]] = p.scales[[1, 0]], p.zeros[[1, 0]]
+    w_sw = O.dequant(p.codes, sw_s, sw_z)
+    assert np.array_equal(w_sw[:, 128:], w_hat[:, 128:]) and not np.array_equal(w_sw[:, :128], w_hat[:, :128])
+    # a group-128 parameter set repeated for both halves of its group is the group-128 result
+    q = _small_problem(seed=23, N=256, K=512, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3})
+    assert np.array_equal(O.dequant(q.codes, np.repeat(q.scales, 2, axis=0), np.repeat(q.zeros, 2, axis=0)),
+                          O.dequant(q.codes, q.scales, q.zeros))
+    rows = np.array([0, 77, 255])
+    assert np.array_equal(O.dequant_rows(p.codes, p.scales, p.zeros, rows), w_hat[rows])
+    # the quantiser used the tile's width for both of its groups: the error stays within half a step
+    err = np.abs(w_hat - p.Wt.astype(np.float64))
+    step = np.repeat(p.scales.astype(np.float64).T, 64, axis=1)
+    assert (err <= 0.5 * step * (1 + 1e-2) + 1e-3 * np.abs(p.Wt.astype(np.float64)) + 1e-6).all()
+    # and the product follows: gemm on these parameters equals the triple loop on a few outputs
+    Y = O.gemm(p.X, p.col_perm, p.codes, p.scales, p.zeros, p.row_perm)
+    for m, i in ((0, 3), (2, 200)):
+        acc = math.fsum(float(p.X[m, p.col_perm[k]]) * float(w_hat[i, k]) for k in range(p.K))
+        assert Y[m, p.row_perm[i]] == pytest.approx(acc, rel=1e-12)
+    # byte accounting: 0.5 bit per weight of parameters at group 64 (the ablation's overhead column)
+    extra = W.algorithmic_bytes(p.N, p.K, 1, p.bitmap, group=64) - W.algorithmic_bytes(p.N, p.K, 1, p.bitmap, group=128)
+    assert extra * 8 == p.N * p.K // 4  # 0.5 - 0.25 bit per weight
+
+
 def test_bf16_storage_values_and_bits():
     # bf16 keeps the top 16 bits of the float32 pattern, rounded to nearest even
     x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 3.14159, -2.5e-3, 0.0], dtype=np.float32)
