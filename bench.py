@@ -43,7 +43,8 @@ def parse_args():
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of HIP-graph replays")
     ap.add_argument("--separate", action="store_true",
                     help="one launch per projection (7) instead of q|k|v, o, gate|up, down sharing launches (4)")
-    ap.add_argument("--section", choices=("all", "decode", "layers", "batch", "prefill", "prefill_sweep", "sweep", "lut"),
+    ap.add_argument("--section", choices=("all", "decode", "layers", "layer70b", "batch", "prefill", "prefill_sweep", "sweep",
+                                          "lut"),
                     default="all",
                     help="which reports to run after the headline measurement (for profiling one kernel family at a "
                          "time): decode = per-projection and 70B M=1, layers = one layer of configs[2] and [3] at every "
@@ -370,7 +371,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     groups = None if args.separate else FUSED_GROUPS
-    if args.section in ("batch", "prefill", "sweep", "layers"):
+    if args.section in ("batch", "prefill", "prefill_sweep", "sweep", "layers", "layer70b"):
         args.steps, args.warmup = 2, 1
     ms_step, wall_ms = time_steps(torch, layer, args.steps, args.warmup, use_graph=not args.eager, groups=groups)
     us_layer = ms_step * 1e3
@@ -424,25 +425,59 @@ def main():
         },
     }
 
-    # second denominator: what a plain streaming read reaches on this machine (1 GiB, cold), beside the data sheet
+    # second denominator: what a plain streaming read reaches on this machine (1 GiB, cold), beside the data sheet;
+    # and the floor of the step: the same number of launches, each a bare streaming read of the bytes its launch of the
+    # step moves (nothing computed, no dependent start), replayed as a graph over rotating memory like the step itself
     try:
         from paper_2602_01027_amd import probe
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+        src = torch.empty((1 << 30) + (64 << 20), dtype=torch.uint8, device="cuda:0").random_(0, 255)
         outp = torch.empty(2048, dtype=torch.uint8, device="cuda:0")
+        whole = src[:1 << 30]
         for _ in range(2):
-            probe.stream_read(src, outp)
+            probe.stream_read(whole, outp)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(5):
-            probe.stream_read(src, outp)
+            probe.stream_read(whole, outp)
         e1.record()
         torch.cuda.synchronize()
         stream_gbps = 5 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
-        del src, outp
         result["roofline"]["measured_stream_read_GBps"] = round(stream_gbps, 1)
         result["roofline"]["frac_of_measured_stream_read"] = round(gbps / stream_gbps, 4)
+        launch_bytes = [sum(per_proj_bytes[i] for i in g) for g in (groups or [[i] for i in range(len(problems))])]
+        launch_bytes = [(int(b) + 255) // 256 * 256 for b in launch_bytes]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graphs, off = [], 0
+        for r in range(R):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for b in launch_bytes:
+                    if off + b > (1 << 30):
+                        off = 0
+                    probe.stream_read(src[off:off + b], outp, stream=torch.cuda.current_stream())
+                    off += b
+            graphs.append(g)
+        torch.cuda.synchronize()
+        nrep = max(args.steps, 2 * R)
+        for i in range(R):
+            graphs[i].replay()
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(nrep):
+            graphs[i % R].replay()
+        e1.record()
+        torch.cuda.synchronize()
+        floor_us = e0.elapsed_time(e1) * 1e3 / nrep
+        del src, outp, whole, graphs
+        result["roofline"]["bare_read_floor_us"] = round(floor_us, 3)
+        result["roofline"]["floor_over_value"] = round(floor_us / us_layer, 4)
+        result["roofline"]["note_floor"] = ("bare_read_floor_us = HIP-event time of a step made of the same number of launches, "
+                                            "each a plain streaming read (probe kernel, nothing computed) of the bytes its launch "
+                                            "moves, graph replay over rotating memory: what launch overhead plus HBM transfer cost "
+                                            "on this machine; floor_over_value = that floor / value")
     except Exception as ex:  # the probe is an aid: never let it take the bench line down
-        result["roofline"]["measured_stream_read_GBps"] = None
+        result["roofline"]["measured_stream_read_GBps"] = result["roofline"].get("measured_stream_read_GBps")
         result["roofline"]["measured_stream_read_error"] = str(ex)
 
     extra = {}
@@ -500,6 +535,8 @@ def main():
             extra["layer_8b_config3_2p5bit"] = [layer_line(torch, W, 3, M, 60 if M <= 16 else 30, args.eager, FUSED_GROUPS)
                                                 for M in (1, 4, 16, 64)]
             extra["layer_70b_config4_3p25bit"] = [layer_line(torch, W, 4, M, 40, args.eager, FUSED_GROUPS) for M in (1, 8)]
+        if args.section == "layer70b":  # the 70B decode layer alone, M = 1 (for a kernel trace of its own)
+            extra["layer_70b_config4_3p25bit"] = [layer_line(torch, W, 4, 1, 40, args.eager, FUSED_GROUPS)]
         if args.section in ("all", "decode"):
             # 70B-shaped decode layer (configs[3]) at M = 1, one launch per projection, and every projection alone
             p70 = build_problems(W, 4, Ms=(1,), fast=True)

@@ -35,41 +35,55 @@ namespace sfmp {
 // -------------------------------------------------------------------------------------------
 // column gather / column scatter, one row of fp16 through LDS per workgroup
 // -------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void gather_cols_kernel(const _Float16* __restrict__ X,
-                                                          const int32_t* __restrict__ col_perm,
-                                                          _Float16* __restrict__ Xp, int K) {
+// R rows per workgroup: the permutation entries of a unit of 8 columns are loaded once and serve all R rows (they
+// are twice the bytes of the data they steer), and R rows of loads are in flight per workgroup.
+template <int R>
+__global__ __launch_bounds__(1024) void gather_cols_kernel(const _Float16* __restrict__ X,
+                                                           const int32_t* __restrict__ col_perm,
+                                                           _Float16* __restrict__ Xp, int M, int K) {
   // Output layout: blocks of 128 rows x 128 columns, each block contiguous (32 KiB), block (mt, tc) at
   // (mt * K/128 + tc) * 16384 elements: the GEMM then reads one contiguous block per step instead of 128
   // row pieces K*2 bytes apart.
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  _Float16* row = reinterpret_cast<_Float16*>(lds_raw);
-  const int64_t m = blockIdx.x;
-  const uint4* src = reinterpret_cast<const uint4*>(X + m * K);
-  for (int i = threadIdx.x; i < K / 8; i += 256) reinterpret_cast<uint4*>(row)[i] = src[i];
+  _Float16* rows = reinterpret_cast<_Float16*>(lds_raw);  // [R][K]
+  const int64_t m0 = (int64_t)blockIdx.x * R;
+  const int units = K / 8;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    if (m0 + r < M) {
+      const uint4* src = reinterpret_cast<const uint4*>(X + (m0 + r) * K);
+      for (int i = threadIdx.x; i < units; i += 1024) reinterpret_cast<uint4*>(rows + (size_t)r * K)[i] = src[i];
+    }
+  }
   __syncthreads();
   const int64_t ntc = K / kTile;
-  _Float16* dst = Xp + (m / kTile) * ntc * (kTile * kTile) + (m % kTile) * kTile;
-  for (int i = threadIdx.x; i < K / 8; i += 256) {
-    if (!col_perm) {  // no permutation: the pass only changes the layout
-      *reinterpret_cast<uint4*>(dst + (int64_t)(i / 16) * (kTile * kTile) + (i % 16) * 8) =
-          reinterpret_cast<const uint4*>(row)[i];
-      continue;
+  for (int i = threadIdx.x; i < units; i += 1024) {
+    int4 c0 = int4{8 * i, 8 * i + 1, 8 * i + 2, 8 * i + 3}, c1 = int4{8 * i + 4, 8 * i + 5, 8 * i + 6, 8 * i + 7};
+    if (col_perm) {  // (no permutation: the pass only changes the layout)
+      c0 = reinterpret_cast<const int4*>(col_perm)[2 * i];
+      c1 = reinterpret_cast<const int4*>(col_perm)[2 * i + 1];
     }
-    const int4 c0 = reinterpret_cast<const int4*>(col_perm)[2 * i];
-    const int4 c1 = reinterpret_cast<const int4*>(col_perm)[2 * i + 1];
-    union {
-      _Float16 h[8];
-      uint4 u;
-    } v;
-    v.h[0] = row[c0.x];
-    v.h[1] = row[c0.y];
-    v.h[2] = row[c0.z];
-    v.h[3] = row[c0.w];
-    v.h[4] = row[c1.x];
-    v.h[5] = row[c1.y];
-    v.h[6] = row[c1.z];
-    v.h[7] = row[c1.w];
-    *reinterpret_cast<uint4*>(dst + (int64_t)(i / 16) * (kTile * kTile) + (i % 16) * 8) = v.u;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int64_t m = m0 + r;
+      if (m < M) {
+        const _Float16* row = rows + (size_t)r * K;
+        union {
+          _Float16 h[8];
+          uint4 u;
+        } v;
+        v.h[0] = row[c0.x];
+        v.h[1] = row[c0.y];
+        v.h[2] = row[c0.z];
+        v.h[3] = row[c0.w];
+        v.h[4] = row[c1.x];
+        v.h[5] = row[c1.y];
+        v.h[6] = row[c1.z];
+        v.h[7] = row[c1.w];
+        _Float16* dst = Xp + (m / kTile) * ntc * (kTile * kTile) + (m % kTile) * kTile;
+        *reinterpret_cast<uint4*>(dst + (int64_t)(i / 16) * (kTile * kTile) + (i % 16) * 8) = v.u;
+      }
+    }
   }
 }
 
@@ -643,17 +657,35 @@ int launch_prefill(const GemmArgs& a, void* stream) {
   if (((a.row_perm || plan.ksplit > 1) && (int64_t)L->N * 2 > 160 * 1024) ||
       L->K / kTile > kPrefillMaxTiles)
     return SFMP_ERR_SHAPE;
-  if (int e = allow_full_lds(reinterpret_cast<const void*>(&gather_cols_kernel), "hipFuncSetAttribute(gather)")) return e;
   if (plan.ksplit > 1) {
     if (int e = allow_full_lds(reinterpret_cast<const void*>(&reduce_split_kernel), "hipFuncSetAttribute(reduce)")) return e;
   } else if (a.row_perm) {
     if (int e = allow_full_lds(reinterpret_cast<const void*>(&scatter_cols_kernel), "hipFuncSetAttribute(scatter)")) return e;
   }
-  // activations -> workspace: column permutation applied (if any), 128x128 blocks each contiguous
+  // activations -> workspace: column permutation applied (if any), 128x128 blocks each contiguous.  Rows per
+  // workgroup: as many as fit in 128 KiB of LDS (8 at most), fewer while that would leave compute units without a
+  // workgroup.
   _Float16* Xp = (_Float16*)a.workspace;
-  hipLaunchKernelGGL(gather_cols_kernel, dim3((unsigned)a.M), dim3(256), (size_t)L->K * 2, (hipStream_t)stream,
-                     (const _Float16*)a.X, a.col_perm, Xp, (int)L->K);
-  if (int e = check_launch("sfmp_gemm activation staging launch")) return e;
+  {
+    int R = L->K <= 8192 ? 8 : L->K <= 16384 ? 4 : L->K <= 32768 ? 2 : 1;
+    while (R > 1 && (a.M + R - 1) / R < 256) R /= 2;
+    const void* fn = R == 8   ? reinterpret_cast<const void*>(&gather_cols_kernel<8>)
+                     : R == 4 ? reinterpret_cast<const void*>(&gather_cols_kernel<4>)
+                     : R == 2 ? reinterpret_cast<const void*>(&gather_cols_kernel<2>)
+                              : reinterpret_cast<const void*>(&gather_cols_kernel<1>);
+    if (int e = allow_full_lds(fn, "hipFuncSetAttribute(gather)")) return e;
+    const _Float16* Xa = (const _Float16*)a.X;
+    const int32_t* cp = a.col_perm;
+    int Ma = a.M, Ka = L->K;
+    void* kargs[] = {&Xa, &cp, &Xp, &Ma, &Ka};
+    hipError_t e = hipLaunchKernel(fn, dim3((unsigned)((a.M + R - 1) / R)), dim3(1024), kargs, (size_t)R * L->K * 2,
+                                   (hipStream_t)stream);
+    if (e != hipSuccess) {
+      note_hip_error("sfmp_gemm activation staging launch", hipGetErrorString(e));
+      return SFMP_ERR_HIP;
+    }
+    if (int e2 = check_launch("sfmp_gemm activation staging launch")) return e2;
+  }
   _Float16* Yt = a.row_perm ? (_Float16*)((char*)a.workspace + plan.xperm_bytes) : (_Float16*)a.Y;
   PrefillParams p;
   p.Xp = Xp;

@@ -3,8 +3,8 @@
  * needs it).  Built into its own shared object, libsfmp_probe.so.
  *
  * sfmp_probe_stream_read reads `bytes` (a multiple of 16, at least 16) from src_dev (device, 16-byte aligned) once
- * with plain streaming loads (a persistent grid of 512 workgroups, four independent 16-byte loads in flight per
- * thread) and writes 2048 bytes of check words to out_dev (device, 4-byte aligned), so that a bench can time it and
+ * with plain streaming loads (256 workgroups of 16 wavefronts, the launch shape of the decode kernels; every wavefront
+ * reads whole 1 KiB pieces, four independent 16-byte loads in flight per lane; no LDS, no barrier) and writes 2048 bytes of check words to out_dev (device, 4-byte aligned), so that a bench can time it and
  * print the streaming-read bandwidth this machine reaches beside the data-sheet figure.  Asynchronous on hip_stream
  * (a hipStream_t passed as void*).  Returns 0, -1 (NULL pointer), -2 (size / alignment) or -6 (launch failed).
  */
