@@ -733,6 +733,40 @@ __global__ __launch_bounds__(MB * 16) void stage_rows_kernel(const _Float16* __r
   stage_rows_tile<MB>(X, col_perm, xblk, M, K, (int)blockIdx.x);
 }
 
+// The same in operand order, for the kernels that keep their activations in registers: always 16 rows (rows >= M
+// zero), 4 KiB per tile column laid out as [k-step][lane][16 bytes], lane = 16 * (unit % 4) + row: a wavefront loads the
+// matrix-instruction operand of a k-step with one 16-byte load per lane, 1 KiB contiguous.
+__device__ __forceinline__ void stage_rows_tile_operand_order(const _Float16* __restrict__ X,
+                                                              const int32_t* __restrict__ col_perm, unsigned char* xblk,
+                                                              int M, int K, int tc) {
+  const int m = threadIdx.x / 16, unit = threadIdx.x % 16;
+  half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (m < M) {
+    const int k0 = tc * kTile + unit * 8;
+    if (col_perm) {
+      const int4 c0 = reinterpret_cast<const int4*>(col_perm + k0)[0];
+      const int4 c1 = reinterpret_cast<const int4*>(col_perm + k0)[1];
+      const _Float16* row = X + (int64_t)m * K;
+      v[0] = row[c0.x];
+      v[1] = row[c0.y];
+      v[2] = row[c0.z];
+      v[3] = row[c0.w];
+      v[4] = row[c1.x];
+      v[5] = row[c1.y];
+      v[6] = row[c1.z];
+      v[7] = row[c1.w];
+    } else {
+      v = *reinterpret_cast<const half8*>(X + (int64_t)m * K + k0);
+    }
+  }
+  *reinterpret_cast<half8*>(xblk + (((int64_t)tc * 4 + unit / 4) * 64 + 16 * (unit % 4) + m) * 16) = v;
+}
+__global__ __launch_bounds__(256) void stage_rows_operand_order_kernel(const _Float16* __restrict__ X,
+                                                                       const int32_t* __restrict__ col_perm,
+                                                                       unsigned char* xblk, int M, int K) {
+  stage_rows_tile_operand_order(X, col_perm, xblk, M, K, (int)blockIdx.x);
+}
+
 template <int MB>
 constexpr int rskinny_slot_bytes() { return kSlotBytes + MB * 256; }
 // resident variant: bytes of the raw copy of the activations in LDS
@@ -743,20 +777,31 @@ __host__ __device__ inline size_t rskinny_raw_bytes(int32_t M, int32_t K) { retu
 // swizzled layout; there is then no staging kernel and an item brings only its slab and parameters.
 // ACC: slabs per workgroup whose finished sums are held in registers (4, 8 or 16; 4 x ACC registers).  With 16
 // the kernel needs about 130 vector registers and runs 8 wavefronts per CU; with 4 or 8 it stays below 128 and runs
-// 16, which is what covers the latencies of its loop.
+// 16, which is what covers the latencies of its loop.  The forms with MB = 4 and with RA hold no sums in registers
+// (they write them to LDS as a slab finishes); there ACC only tells the variants for 16 and for 8 wavefronts apart.
 // G64: group length 64 (two parameter pairs per row and tile column; never together with RES).
-template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false>
+// RA (activations in registers): when a wavefront has at most two tile columns (K <= 256 NW) it loads their matrix-
+// instruction operands once, from a staged copy in operand order (stage_rows_operand_order_kernel), and keeps them in
+// registers for all its slabs: an item then brings only its slab and parameters (small slots, two of them per
+// wavefront at any M), and nothing is read from LDS for the activations.  16 rows always (MB = 16).
+template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false, bool RA = false>
 __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int bid, const int G, unsigned char* lds_raw) {
   static_assert(!(RES && G64), "the resident form keeps one activation sum per tile column");
+  static_assert(!(RES && RA) && (!RA || MB == 16), "activations in registers: 16 rows, no copy in LDS");
   constexpr int NT = NW * 64;
   constexpr int kBase = G64 ? kSlotBytes64 : kSlotBytes;  // slab + parameters; the staged activations follow
-  constexpr int kSlot = RES ? kBase : kBase + MB * 256;
-  constexpr int kCopies = RES ? 2 : 2 + MB / 4;  // direct copies per item: slab, scales+zeros, MB/4 x 1 KiB of activations
+  constexpr int kSlot = (RES || RA) ? kBase : kBase + MB * 256;
+  constexpr int kCopies = (RES || RA) ? 2 : 2 + MB / 4;  // direct copies per item: slab, scales+zeros, MB/4 x 1 KiB of activations
   constexpr int kRedGroups = NW / 4;  // the final sum over the wavefronts is taken in groups of four
+  // DS: the sums of a finished slab go straight into the wavefront's own block of LDS and none are held in
+  // registers: with the activations in registers (all 64 lanes hold sums) and with up to four activation rows
+  // (lanes 0-15 hold them all: output rows 4 (lane / 16) + r)
+  constexpr bool DS = RA || MB == 4;
+  constexpr int kFinLanes = RA ? 64 : 16;
   // LDS: red [NW/4][max_slabs][4][64] f32 | (Xs [ntc][MB][256 B] | SxL | raw activations [M][K] fp16) |
-  //      rings [NW][S][kSlot]
+  //      rings [NW][S][kSlot];  with RA: fin [NW][max_slabs][64][4] f32 | rings
   float* red = reinterpret_cast<float*>(lds_raw);
-  unsigned char* Xs = lds_raw + (size_t)p.max_slabs * 1024 * kRedGroups;
+  unsigned char* Xs = lds_raw + (DS ? (size_t)p.max_slabs * NW * kFinLanes * 16 : (size_t)p.max_slabs * 1024 * kRedGroups);
   // (resident) SxL [ntc][4 lane groups][4] f32: the sums of the activations of rows 4g..4g+3 over a tile column
   float* SxL = reinterpret_cast<float*>(Xs + (RES ? (size_t)p.ntc * (MB * 256) : (size_t)0));
   unsigned char* raw_region = reinterpret_cast<unsigned char*>(SxL) + (RES ? (size_t)p.ntc * 64 : (size_t)0);
@@ -819,7 +864,7 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
     const uint32_t soff = (uint32_t)__builtin_amdgcn_readlane((int)it_soff, e);
     const uint32_t slot = ring_off + (uint32_t)s * kSlot;
     lds_copy_item(par_vbase + soff, ((uint64_t)whi << 32) | wlo, data_voff, slot + 1024, slot, xhi, G64 ? ~0u : 0u);
-    if constexpr (!RES) {
+    if constexpr (!RES && !RA) {
       const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
       const uint64_t xsrc = xb + (uint64_t)(misc & 0xFFFF) * (MB * 256);
 #pragma unroll
@@ -908,6 +953,17 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   half8 a[4];
 #pragma unroll
   for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+  // (RA) the operands of this wavefront's first and second tile column, requested now (the address of the last tile
+  // column for a wavefront that has fewer: the loads are unconditional); first used when the first item is consumed
+  half8 aset0[4], aset1[4];
+  if constexpr (RA) {
+    const int tc0 = min(wave, p.ntc - 1), tc1 = min(wave + NW, p.ntc - 1);
+#pragma unroll
+    for (int kappa = 0; kappa < 4; ++kappa) {
+      aset0[kappa] = *reinterpret_cast<const half8*>(p.xblk + (((size_t)tc0 * 4 + kappa) * 64 + lane) * 16);
+      aset1[kappa] = *reinterpret_cast<const half8*>(p.xblk + (((size_t)tc1 * 4 + kappa) * 64 + lane) * 16);
+    }
+  }
   // operand addresses inside a slot: activation row i16, unit 4*kappa + kb at position unit ^ i16
   uint32_t a_off[4];
 #pragma unroll
@@ -920,17 +976,26 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   accv accs0, accs1, accs2, accs3;  // four named vectors: an array of them went to scratch memory
 #pragma unroll
   for (int q = 0; q < ACC; ++q) accs0[q] = 0.f, accs1[q] = 0.f, accs2[q] = 0.f, accs3[q] = 0.f;
+  // Keeping the sums of a finished slab (q is uniform).  A wavefront with one or two tile columns finishes a slab
+  // with every or every second item, and a register-indexed write into vectors of up to eight elements costs one
+  // conditional move per element (32 per finished slab).  DS: one 16-byte write into fin [NW][max_slabs][kFinLanes][4]
+  // f32 instead, and no sums in registers at all.
+  float* fin = reinterpret_cast<float*>(lds_raw);
+  auto keep_sums = [&](const int q, const floatx4 acc) __attribute__((always_inline)) {
+    if constexpr (DS) {
+      if (kFinLanes == 64 || lane < kFinLanes)
+        *reinterpret_cast<floatx4*>(fin + (((size_t)wave * p.max_slabs + q) * kFinLanes + lane) * 4) = acc;
+    } else {
+      accs0[q] = acc[0], accs1[q] = acc[1], accs2[q] = acc[2], accs3[q] = acc[3];
+    }
+  };
   // running sums of the current slab: scale * (code sums, in units of 2^-24) and zero * (activation sums)
   floatx4 acc_q = {0.f, 0.f, 0.f, 0.f}, acc_z = {0.f, 0.f, 0.f, 0.f};
 
-  auto consume = [&](int e, int s) __attribute__((always_inline)) {
-    const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
-    const unsigned char* slot = ring + s * kSlot;
-    if (MB == 16 || i16 < MB) {
-      const unsigned char* abase = RES ? Xs + (size_t)(misc & 0xFFFF) * (MB * 256) : slot;
-#pragma unroll
-      for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = *reinterpret_cast<const half8*>(abase + a_off[kappa]);
-    }
+  // one item with its activation operands given (a: four k-steps of 32 columns)
+  // (sx_known: the activation sums of the item's tile column when the caller has them already)
+  auto consume_with = [&](const uint32_t misc, const unsigned char* slot, const half8 (&a)[4],
+                          const floatx4 sx_known) __attribute__((always_inline)) {
     if constexpr (G64) {
       // sums of the activations over columns 0-63 and 64-127, the code sums likewise, one parameter pair for each
       floatx4 sx_lo = {0.f, 0.f, 0.f, 0.f}, sx_hi = {0.f, 0.f, 0.f, 0.f};
@@ -966,15 +1031,17 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
       acc_z += z_lo * sx_lo + z_hi * sx_hi;
       if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
         asm volatile("" ::: "memory");
-        const int q = (misc >> 17) & (ACC - 1);
+        const int q = (misc >> 17) & (DS ? 15 : ACC - 1);
         const floatx4 acc = acc_q * 16777216.f + acc_z;
-        accs0[q] = acc[0], accs1[q] = acc[1], accs2[q] = acc[2], accs3[q] = acc[3];
+        keep_sums(q, acc);
         acc_q = floatx4{0.f, 0.f, 0.f, 0.f}, acc_z = floatx4{0.f, 0.f, 0.f, 0.f};
       }
       return;
     }
     floatx4 sx;
-    if constexpr (RES) {
+    if constexpr (RA) {
+      sx = sx_known;
+    } else if constexpr (RES) {
       sx = *reinterpret_cast<const floatx4*>(SxL + (misc & 0xFFFF) * 16 + kb * 4);
     } else {
       sx = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -1011,10 +1078,36 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
     acc_z += zf * sx;
     if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
       asm volatile("" ::: "memory");  // keeps this a branch rather than a select over all the sums
-      const int q = (misc >> 17) & (ACC - 1);
+      const int q = (misc >> 17) & (DS ? 15 : ACC - 1);
       const floatx4 acc = acc_q * 16777216.f + acc_z;
-      accs0[q] = acc[0], accs1[q] = acc[1], accs2[q] = acc[2], accs3[q] = acc[3];
+      keep_sums(q, acc);
       acc_q = floatx4{0.f, 0.f, 0.f, 0.f}, acc_z = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+  };
+  // (RA, one parameter pair per tile column) the activation sums of the two tile columns, taken once for all slabs:
+  // the same four matrix instructions against ones, in the same order, that the other forms issue per item
+  floatx4 sx0 = {0.f, 0.f, 0.f, 0.f}, sx1 = {0.f, 0.f, 0.f, 0.f};
+  if constexpr (RA && !G64) {
+#pragma unroll
+    for (int kappa = 0; kappa < 4; ++kappa) sx0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aset0[kappa], ones, sx0, 0, 0, 0);
+#pragma unroll
+    for (int kappa = 0; kappa < 4; ++kappa) sx1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aset1[kappa], ones, sx1, 0, 0, 0);
+  }
+  auto consume = [&](int e, int s) __attribute__((always_inline)) {
+    const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
+    const unsigned char* slot = ring + s * kSlot;
+    if constexpr (RA) {
+      // this wavefront's first or second tile column (a uniform branch over two copies of the item's code: selecting
+      // the operands into a third set of registers cost 16 more of them)
+      if (((misc & 0xFFFF) >> (NW == 16 ? 4 : 3)) == 0) consume_with(misc, slot, aset0, sx0);
+      else consume_with(misc, slot, aset1, sx1);
+    } else {
+      if (MB == 16 || i16 < MB) {
+        const unsigned char* abase = RES ? Xs + (size_t)(misc & 0xFFFF) * (MB * 256) : slot;
+#pragma unroll
+        for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = *reinterpret_cast<const half8*>(abase + a_off[kappa]);
+      }
+      consume_with(misc, slot, a, floatx4{0.f, 0.f, 0.f, 0.f});
     }
   };
 
@@ -1053,8 +1146,36 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   }
   static_assert(S <= 8 && kCopies * 7 < 64, "the tail's waits cover up to 7 younger items");
 
-  // The wavefronts add their sums in a fixed order, so results repeat bit for bit: inside each group of four
-  // (wavefronts 4g..4g+3) one after the other into the group's buffer, then the groups in turn at the output.
+  // The wavefronts' sums are added in a fixed order, so results repeat bit for bit: inside each group of four
+  // (wavefronts 4g..4g+3) one after the other, then the groups in turn.
+  if constexpr (DS) {
+    // every wavefront's sums are in its block of fin already (a wavefront without a tile column wrote none: zeros)
+    if (my_cnt == 0 && lane < kFinLanes)
+      for (int q = 0; q < nj; ++q)
+        *reinterpret_cast<floatx4*>(fin + (((size_t)wave * p.max_slabs + q) * kFinLanes + lane) * 4) = floatx4{0.f, 0.f, 0.f, 0.f};
+    __syncthreads();
+    for (int o = tid; o < nj * kFinLanes * 4; o += NT) {
+      const int jj = o / (kFinLanes * 4), rem = o % (kFinLanes * 4);
+      const int l = rem / 4, r = rem % 4;
+      const int m = 4 * (l / 16) + r;
+      if (m < p.M) {
+        float sum = 0.f;
+#pragma unroll
+        for (int g = 0; g < kRedGroups; ++g) {
+          float part = 0.f;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) part += fin[(((size_t)(4 * g + w) * p.max_slabs + jj) * kFinLanes + l) * 4 + r];
+          sum = g == 0 ? part : sum + part;
+        }
+        const int v = bid + G * jj;
+        const int slab = (v % 8) * p.ntr + v / 8;
+        const int64_t row = (int64_t)(slab / 8) * kTile + 8 * (l % 16) + (slab % 8);
+        const int64_t col = p.row_perm ? p.row_perm[row] : row;
+        p.Y[(int64_t)m * p.N + col] = (_Float16)sum;
+      }
+    }
+    return;
+  }
   {
     float* mine = red + (size_t)(wave / 4) * p.max_slabs * 256;
     for (int w = 0; w < 4; ++w) {
@@ -1062,11 +1183,11 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
 #pragma unroll
         for (int q = 0; q < ACC; ++q)
           if (q < nj) {
-            const float fin[4] = {accs0[q], accs1[q], accs2[q], accs3[q]};
+            const float fin4[4] = {accs0[q], accs1[q], accs2[q], accs3[q]};
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               float* dst = mine + (q * 4 + r) * 64 + lane;
-              *dst = (w == 0 ? 0.f : *dst) + fin[r];
+              *dst = (w == 0 ? 0.f : *dst) + fin4[r];
             }
           }
       }
@@ -1090,10 +1211,10 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   }
 }
 
-template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false>
+template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false, bool RA = false>
 __global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  rskinny_body<NW, S, MB, RES, ACC, G64>(p, (int)blockIdx.x, (int)gridDim.x, lds_raw);
+  rskinny_body<NW, S, MB, RES, ACC, G64, RA>(p, (int)blockIdx.x, (int)gridDim.x, lds_raw);
 }
 
 // Several independent problems with the same M in one launch (q, k and v, or gate and up of a decoder
@@ -1106,12 +1227,12 @@ struct RSkinnyBatch {  // laid out as GemvBatch
 };
 static_assert(offsetof(RSkinnyBatch, p) == 64, "the header of a batch is one 64-byte line");
 
-template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false>
+template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false, bool RA = false>
 __global__ __launch_bounds__(NW * 64) void rskinny_batched_kernel(const RSkinnyBatch b) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int i = batch_problem_of(b.first, (int)blockIdx.x);
   const RSkinnyParams p = b.p[i];
-  rskinny_body<NW, S, MB, RES, ACC, G64>(p, (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
+  rskinny_body<NW, S, MB, RES, ACC, G64, RA>(p, (int)blockIdx.x - b.first[i], b.first[i + 1] - b.first[i], lds_raw);
 }
 
 // Staging for a batch: job j (one per distinct activation matrix) owns workgroups [first[j], first[j+1]).
@@ -1130,6 +1251,11 @@ __global__ __launch_bounds__(MB * 16) void stage_rows_batched_kernel(const Stage
   int j = 0;
   while (j + 1 < b.count && (int)blockIdx.x >= b.first[j + 1]) ++j;
   stage_rows_tile<MB>(b.X[j], b.col_perm[j], b.xblk[j], b.M[j], b.K[j], (int)blockIdx.x - b.first[j]);
+}
+__global__ __launch_bounds__(256) void stage_rows_operand_order_batched_kernel(const StageBatch b) {
+  int j = 0;
+  while (j + 1 < b.count && (int)blockIdx.x >= b.first[j + 1]) ++j;
+  stage_rows_tile_operand_order(b.X[j], b.col_perm[j], b.xblk[j], b.M[j], b.K[j], (int)blockIdx.x - b.first[j]);
 }
 
 // ============================================================================================
@@ -1177,6 +1303,7 @@ static GemvFit gemv_fit(int32_t N, int32_t K, int32_t grid) {
 struct RSkinnyConfig {
   int32_t mb, nw, slots, acc;
   bool resident;
+  bool ra;  // activations in registers (at most two tile columns per wavefront): 16-row operand-order staging, small slots
 };
 static int32_t rskinny_mb(int32_t M) { return M <= 4 ? 4 : M <= 8 ? 8 : 16; }
 // LDS of the ring-skinny kernel: reduction buffers, (resident: activations in operand layout, their tile-column sums,
@@ -1184,6 +1311,7 @@ static int32_t rskinny_mb(int32_t M) { return M <= 4 ? 4 : M <= 8 ? 8 : 16; }
 static int64_t rskinny_lds_bytes(const RSkinnyConfig& c, int32_t max_slabs, int32_t M, int32_t K) {
   const int64_t red = (int64_t)max_slabs * 1024 * (c.nw / 4);
   // (slots sized for group length 64, 128 bytes larger, whatever the layout)
+  if (c.ra) return (int64_t)max_slabs * 1024 * c.nw + (int64_t)c.nw * c.slots * kSlotBytes64;  // fin | rings
   return c.resident ? red + (int64_t)c.mb * K * 2 + (int64_t)(K / kTile) * 64 + (int64_t)rskinny_raw_bytes(M, K) +
                           (int64_t)c.nw * c.slots * kSlotBytes64
                     : red + (int64_t)c.nw * c.slots * (kSlotBytes64 + c.mb * 256);
@@ -1197,6 +1325,7 @@ constexpr int kSlotsResident = 3, kSlotsMb4 = 2, kSlotsMb8 = 2, kSlotsMb16 = 2;
 // 16 rows with 16 wavefronts: a slot carries 4 KiB of activations, and only one per wavefront fits in LDS (the other
 // wavefronts of the SIMD cover the wait)
 constexpr int kSlotsMb16Wide = 1;
+constexpr int kSlotsRegisterActs = 2;  // activations in registers: the slots hold a slab and its parameters only
 // max_slabs: the largest number of slabs of a workgroup over the problems of the launch; K: the largest K
 // g64: group length 64, for which the resident form does not exist
 static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs, bool g64) {
@@ -1207,10 +1336,23 @@ static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs, boo
   c.nw = wide ? 16 : 8;
   c.acc = !wide ? 16 : max_slabs <= 4 ? 4 : 8;
   c.resident = false;
+  c.ra = false;
+  if (c.mb == 4) c.acc = wide ? 4 : 16;  // up to four rows: the finished sums live in LDS, acc only names the variant
   if (!g64 && c.mb == 4 && (int64_t)M * K * 2 <= kResidentMaxRawBytes && K / 8 <= kGemvUnitIters * c.nw * 64) {
     c.resident = true;
     c.slots = kSlotsResident;
     if (rskinny_lds_bytes(c, max_slabs, M, K) > 160 * 1024) c.resident = false;
+  }
+  if (!c.resident && K / kTile <= 2 * c.nw) {
+    // at most two tile columns per wavefront: their operands stay in registers (any M up to 16 as 16 rows) and the
+    // finished sums in LDS, one KiB per wavefront and slab (no sums in registers: acc only names the variant);
+    // with 8 slabs per workgroup and 16 wavefronts that does not fit beside the rings: the ordinary form then
+    RSkinnyConfig r = c;
+    r.ra = true;
+    r.mb = 16;
+    r.acc = r.nw == 16 ? 4 : 16;
+    r.slots = kSlotsRegisterActs;
+    if (rskinny_lds_bytes(r, max_slabs, M, K) <= 160 * 1024) return r;
   }
   if (!c.resident) c.slots = c.mb == 4 ? kSlotsMb4 : c.mb == 8 ? kSlotsMb8 : wide ? kSlotsMb16Wide : kSlotsMb16;
   return c;
@@ -1247,6 +1389,7 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M, int32_t group) {
   d.nw = c.nw;
   d.acc = c.acc;
   d.resident = c.resident;
+  d.ra = c.ra;
   d.slots = c.slots;
   d.lds_bytes = (int32_t)rskinny_lds_bytes(c, d.max_slabs, M, K);
   d.workspace_bytes = round_up_256((int64_t)ntc * c.mb * 256);
@@ -1407,12 +1550,16 @@ static RSkinnyParams rskinny_params(const GemmArgs& a, int32_t M, const void* xb
   return p;
 }
 
-template <int NW, int S, int MB, bool RES, int ACC, bool G64>
+template <int NW, int S, int MB, bool RES, int ACC, bool G64, bool RA>
 static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* stream) {
   const sfmp_layout_t* L = a.L;
-  const void* fn = reinterpret_cast<const void*>(&rskinny_kernel<NW, S, MB, RES, ACC, G64>);
+  const void* fn = reinterpret_cast<const void*>(&rskinny_kernel<NW, S, MB, RES, ACC, G64, RA>);
   if (int e = allow_full_lds(fn, "hipFuncSetAttribute(skinny)")) return e;
-  if (!RES) {
+  if (RA) {
+    hipLaunchKernelGGL(stage_rows_operand_order_kernel, dim3((unsigned)(L->K / kTile)), dim3(256), 0, (hipStream_t)stream,
+                       (const _Float16*)a.X, a.col_perm, (unsigned char*)a.workspace, (int)a.M, (int)L->K);
+    if (int e = after_launch("sfmp_gemm activation staging launch")) return e;
+  } else if (!RES) {
     hipLaunchKernelGGL((stage_rows_kernel<MB>), dim3((unsigned)(L->K / kTile)), dim3(MB * 16), 0, (hipStream_t)stream,
                        (const _Float16*)a.X, a.col_perm, (unsigned char*)a.workspace, (int)a.M, (int)L->K);
     if (int e = after_launch("sfmp_gemm activation staging launch")) return e;
@@ -1427,20 +1574,21 @@ static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* 
   return after_launch("sfmp_gemm skinny launch");
 }
 
-// The compiled configurations (see rskinny_config): X(NW, S, MB, RES, ACC)
+// The compiled configurations (see rskinny_config): X(NW, S, MB, RES, ACC, RA)
 #define SFMP_RSKINNY_CONFIGS(X)                                                                                   \
-  X(16, kSlotsResident, 4, true, 4) X(16, kSlotsResident, 4, true, 8) X(8, kSlotsResident, 4, true, 16)                    \
-  X(16, kSlotsMb4, 4, false, 4) X(16, kSlotsMb4, 4, false, 8) X(8, kSlotsMb4, 4, false, 16)                 \
-  X(16, kSlotsMb8, 8, false, 4) X(16, kSlotsMb8, 8, false, 8) X(8, kSlotsMb8, 8, false, 16)                 \
-  X(16, kSlotsMb16Wide, 16, false, 4) X(16, kSlotsMb16Wide, 16, false, 8) X(8, kSlotsMb16, 16, false, 16)
+  X(16, kSlotsResident, 4, true, 4, false) X(8, kSlotsResident, 4, true, 16, false)                                        \
+  X(16, kSlotsMb4, 4, false, 4, false) X(8, kSlotsMb4, 4, false, 16, false)                                                \
+  X(16, kSlotsMb8, 8, false, 4, false) X(16, kSlotsMb8, 8, false, 8, false) X(8, kSlotsMb8, 8, false, 16, false)             \
+  X(16, kSlotsMb16Wide, 16, false, 4, false) X(16, kSlotsMb16Wide, 16, false, 8, false) X(8, kSlotsMb16, 16, false, 16, false) \
+  X(16, kSlotsRegisterActs, 16, false, 4, true) X(8, kSlotsRegisterActs, 16, false, 16, true)
 
 static int launch_rskinny(const GemmArgs& a, const DecodePlan& d, void* stream) {
-#define SFMP_X(NW_, S_, MB_, RES_, ACC_)                                                      \
-  if (d.nw == NW_ && d.mb == MB_ && d.resident == RES_ && d.acc == ACC_ && d.slots == S_) {   \
+#define SFMP_X(NW_, S_, MB_, RES_, ACC_, RA_)                                                 \
+  if (d.nw == NW_ && d.mb == MB_ && d.resident == RES_ && d.acc == ACC_ && d.slots == S_ && d.ra == RA_) { \
     if constexpr (!RES_) {                                                                    \
-      if (a.L->group == 64) return launch_rskinny_variant<NW_, S_, MB_, RES_, ACC_, true>(a, d, stream); \
+      if (a.L->group == 64) return launch_rskinny_variant<NW_, S_, MB_, RES_, ACC_, true, RA_>(a, d, stream); \
     }                                                                                         \
-    return launch_rskinny_variant<NW_, S_, MB_, RES_, ACC_, false>(a, d, stream);             \
+    return launch_rskinny_variant<NW_, S_, MB_, RES_, ACC_, false, RA_>(a, d, stream);        \
   }
   SFMP_RSKINNY_CONFIGS(SFMP_X)
 #undef SFMP_X
@@ -1477,12 +1625,8 @@ static BatchStagePlan plan_batch_staging(const GemmArgs* probs, int count, int32
   return sp;
 }
 
-int64_t batched_workspace_bytes(const GemmArgs* probs, int count, int32_t M) {
-  if (M < 2) return 0;
-  return plan_batch_staging(probs, count, rskinny_mb(M)).bytes;
-}
 
-template <int NW, int S, int MB, bool RES, int ACC, bool G64>
+template <int NW, int S, int MB, bool RES, int ACC, bool G64, bool RA>
 static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int32_t M, const int32_t* g,
                                           void* workspace, void* stream) {
   const BatchStagePlan sp = plan_batch_staging(probs, count, MB);
@@ -1518,8 +1662,8 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
     if (max_slabs > kGemvMaxSlabs) return SFMP_ERR_SHAPE;
     b.p[i] = rskinny_params(probs[i], probs[i].M, (const unsigned char*)workspace + sp.offset[sp.job_of[i]], max_slabs,
                             g[i]);
-    const RSkinnyConfig cfg = {MB, NW, S, ACC, RES};
-    if (max_slabs > ACC) return SFMP_ERR_SHAPE;
+    const RSkinnyConfig cfg = {MB, NW, S, ACC, RES, RA};
+    if (!RA && MB != 4 && max_slabs > ACC) return SFMP_ERR_SHAPE;  // (those two forms keep no sums in registers)
     const int64_t need = rskinny_lds_bytes(cfg, max_slabs, probs[i].M, L->K);
     lds = need > lds ? need : lds;
     b.first[i] = first;
@@ -1528,9 +1672,12 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
   for (int i = count; i <= kGemvMaxBatch; ++i) b.first[i] = first;
   for (int i = count; i < kGemvMaxBatch; ++i) b.p[i] = b.p[0];
   if (lds > 160 * 1024) return SFMP_ERR_SHAPE;
-  const void* fn = reinterpret_cast<const void*>(&rskinny_batched_kernel<NW, S, MB, RES, ACC, G64>);
+  const void* fn = reinterpret_cast<const void*>(&rskinny_batched_kernel<NW, S, MB, RES, ACC, G64, RA>);
   if (int e = allow_full_lds(fn, "hipFuncSetAttribute(skinny batched)")) return e;
-  if (!RES) {
+  if (RA) {
+    hipLaunchKernelGGL(stage_rows_operand_order_batched_kernel, dim3((unsigned)sfirst), dim3(256), 0, (hipStream_t)stream, sb);
+    if (int e = after_launch("sfmp_gemm_batched activation staging launch")) return e;
+  } else if (!RES) {
     hipLaunchKernelGGL((stage_rows_batched_kernel<MB>), dim3((unsigned)sfirst), dim3(MB * 16), 0, (hipStream_t)stream, sb);
     if (int e = after_launch("sfmp_gemm_batched activation staging launch")) return e;
   }
@@ -1543,31 +1690,49 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
   return after_launch("sfmp_gemm_batched launch");
 }
 
+// One configuration for a whole batched launch: the one that fits the problem with the most slabs per workgroup and
+// the largest K (resident or register activations only when every problem of the batch fits them).
+static int batch_config(const GemmArgs* probs, int count, int32_t M, int32_t* g, RSkinnyConfig* c, bool* g64) {
+  if (int e = split_grid(probs, count, g)) return e;
+  int32_t max_slabs = 0, max_k = 0;
+  int n64 = 0;
+  for (int i = 0; i < count; ++i) {
+    const int32_t nslab = 8 * (probs[i].L->N / kTile);
+    max_slabs = std::max(max_slabs, (nslab + g[i] - 1) / g[i]);
+    max_k = std::max(max_k, probs[i].L->K);
+    n64 += probs[i].L->group == 64;
+  }
+  if (n64 != 0 && n64 != count) return SFMP_ERR_SHAPE;  // one launch runs one group-length class: 64, or the others
+  *g64 = n64 != 0;
+  *c = rskinny_config(M, max_k, max_slabs, n64 != 0);
+  return SFMP_OK;
+}
+
+int64_t batched_workspace_bytes(const GemmArgs* probs, int count, int32_t M) {
+  if (M < 2) return 0;
+  int32_t g[kGemvMaxBatch];
+  RSkinnyConfig c;
+  bool g64 = false;
+  // a batch that the launch will refuse anyway gets the size of the largest staging layout
+  const int32_t mb = batch_config(probs, count, M, g, &c, &g64) == SFMP_OK ? c.mb : 16;
+  return plan_batch_staging(probs, count, mb).bytes;
+}
+
 int launch_decode_batched(const GemmArgs* probs, int count, int32_t M, void* workspace, void* stream) {
   if (count < 1 || count > kGemvMaxBatch || M < 1 || M > kDecodeMaxM) return SFMP_ERR_SHAPE;
   if (M == 1) return launch_gemv_batched(probs, count, stream);
   for (int i = 0; i < count; ++i)
     if (!decode_offsets_fit(probs[i].L)) return SFMP_ERR_SHAPE;
   int32_t g[kGemvMaxBatch];
-  if (int e = split_grid(probs, count, g)) return e;
-  // one configuration for the whole launch: the one that fits the problem with the most slabs per workgroup and
-  // the largest K (resident activations only when every problem of the batch fits them)
-  int32_t max_slabs = 0, max_k = 0;
-  for (int i = 0; i < count; ++i) {
-    const int32_t nslab = 8 * (probs[i].L->N / kTile);
-    max_slabs = std::max(max_slabs, (nslab + g[i] - 1) / g[i]);
-    max_k = std::max(max_k, probs[i].L->K);
-  }
-  int n64 = 0;
-  for (int i = 0; i < count; ++i) n64 += probs[i].L->group == 64;
-  if (n64 != 0 && n64 != count) return SFMP_ERR_SHAPE;  // one launch runs one group-length class: 64, or the others
-  const RSkinnyConfig c = rskinny_config(M, max_k, max_slabs, n64 != 0);
-#define SFMP_X(NW_, S_, MB_, RES_, ACC_)                                                    \
-  if (c.nw == NW_ && c.mb == MB_ && c.resident == RES_ && c.acc == ACC_ && c.slots == S_) { \
+  RSkinnyConfig c;
+  bool n64 = false;
+  if (int e = batch_config(probs, count, M, g, &c, &n64)) return e;
+#define SFMP_X(NW_, S_, MB_, RES_, ACC_, RA_)                                               \
+  if (c.nw == NW_ && c.mb == MB_ && c.resident == RES_ && c.acc == ACC_ && c.slots == S_ && c.ra == RA_) { \
     if constexpr (!RES_) {                                                                  \
-      if (n64) return launch_rskinny_batched_variant<NW_, S_, MB_, RES_, ACC_, true>(probs, count, M, g, workspace, stream); \
+      if (n64) return launch_rskinny_batched_variant<NW_, S_, MB_, RES_, ACC_, true, RA_>(probs, count, M, g, workspace, stream); \
     }                                                                                       \
-    return launch_rskinny_batched_variant<NW_, S_, MB_, RES_, ACC_, false>(probs, count, M, g, workspace, stream); \
+    return launch_rskinny_batched_variant<NW_, S_, MB_, RES_, ACC_, false, RA_>(probs, count, M, g, workspace, stream); \
   }
   SFMP_RSKINNY_CONFIGS(SFMP_X)
 #undef SFMP_X

@@ -396,6 +396,32 @@ def test_gemm_batched_shared_activations(torch_cuda, M):
         assert np.array_equal(run_gemm(p, dp, cp, rp).view(np.uint16), y.view(np.uint16))
 
 
+@pytest.mark.parametrize("M,group", [(2, 128), (5, 128), (16, 128), (3, 64), (16, 64)])
+def test_gemm_batched_five_slabs_per_workgroup_short_K(torch_cuda, M, group):
+    # two problems of 640 slabs on 128 workgroups each: five slabs per workgroup, with K = 2560 (20 tile columns:
+    # wavefronts 0-3 have two, the others one) and K = 1024 (8 tile columns: half of the wavefronts have none); the
+    # form of the small-batch kernel that keeps the activations in registers and every wavefront's sums in LDS
+    import paper_2602_01027_amd as S
+    from gpu_util import device_problem, run_gemm
+    torch = torch_cuda
+    probs = [W.make_problem("a", 2560, 10240, M, 8400, fractions={2: 0.5, 3: 0.5}, outliers=True, group=group),
+             W.make_problem("b", 1024, 10240, M, 8401, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, group=group)]
+    batch, keep = [], []
+    for p in probs:
+        dp, cp, rp = device_problem(p)
+        X = torch.from_numpy(p.X).to("cuda:0")
+        Y = torch.full((M, p.N), float("nan"), dtype=torch.float16, device="cuda:0")
+        batch.append((X, cp, dp, rp, Y))
+        keep.append((dp, cp, rp))
+    ws = torch.empty(S.sfmp_gemm_batched_workspace(batch, M), dtype=torch.uint8, device="cuda:0").fill_(0xFF)
+    S.sfmp_gemm_batched(batch, M, ws)
+    torch.cuda.synchronize()
+    for p, (_, _, _, _, Y), (dp, cp, rp) in zip(probs, batch, keep):
+        y = Y.cpu().numpy()
+        _check(p, y)
+        assert np.array_equal(run_gemm(p, dp, cp, rp).view(np.uint16), y.view(np.uint16))
+
+
 # ---------------------------------------------------------------------------------------------
 # group lengths 256 / 512, bf16 parameters, (m_b, n_b) bit-allocation blocks
 # ---------------------------------------------------------------------------------------------
