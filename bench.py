@@ -265,6 +265,37 @@ def time_each_projection(torch, layer, launches=60):
     return out
 
 
+def dense_fp16_us(torch, M, N, K, launches):
+    """Microseconds per call of a dense fp16 GEMM (torch.matmul: the vendor library) at this shape: N(0, 1) activations,
+    N(0, 0.02) weights rotated over enough copies to stay out of the caches, graph of back-to-back calls."""
+    dev = "cuda:0"
+    X = torch.randn(M, K, device=dev, dtype=torch.float16)
+    reps = max(2, min(8, int(2 ** 30 // (N * K * 2)) + 1))
+    Ws = [torch.randn(N, K, device=dev, dtype=torch.float16) * 0.02 for _ in range(reps)]
+    Y = torch.empty(M, N, device=dev, dtype=torch.float16)
+    for w in Ws:
+        torch.matmul(X, w.t(), out=Y)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        for j in range(launches):
+            torch.matmul(X, Ws[j % reps].t(), out=Y)
+    torch.cuda.synchronize()
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / launches
+    del Ws, X, Y, g
+    torch.cuda.empty_cache()
+    return round(us, 1)
+
+
 def time_lut(torch, S, p, replicas, launches):
     """Average microseconds per call of sfmp_lut_gemv on problem p (graph replay, weights rotated over replicas)."""
     dev = "cuda:0"
@@ -496,7 +527,7 @@ def main():
     if not args.no_prefill and args.section in ("all", "prefill"):
         # The matrix-core half of the metric: configs[4], M = 2048, all six shapes, one sfmp_gemm call each (staging +
         # GEMM + row un-permute where the configuration has a row permutation), codes drawn directly (timing only).
-        rows, tot_fl, tot_t = [], 0.0, 0.0
+        rows, tot_fl, tot_t, dense_t = [], 0.0, 0.0, 0.0
         kfig = figs.get("prefill_M2048", {})
         for pp in build_problems_iter(W, 5):
             lp = Layer([pp], 1)
@@ -506,9 +537,11 @@ def main():
             rows.append(dict(shape=f"{pp.K}->{pp.N}", us=round(t, 1), GFLOP=round(fl / 1e9, 1),
                              TFLOPs=round(fl / t / 1e6, 1), frac=round(fl / t / 1e6 / MFMA_F16_PEAK_TFLOPS, 4),
                              kernel_us=kus,
-                             kernel_frac=round(fl / kus / 1e6 / MFMA_F16_PEAK_TFLOPS, 4) if kus else None))
+                             kernel_frac=round(fl / kus / 1e6 / MFMA_F16_PEAK_TFLOPS, 4) if kus else None,
+                             dense_fp16_us=dense_fp16_us(torch, pp.M, pp.N, pp.K, args.prefill_launches)))
             tot_fl += fl
             tot_t += t
+            dense_t += rows[-1]["dense_fp16_us"]
             del lp, pp
             torch.cuda.empty_cache()
         result["roofline_prefill"] = {
@@ -523,6 +556,12 @@ def main():
             "workload": "configs[4]: M=2048 on 4096->4096, 4096->1024, 4096->14336, 14336->4096, 8192->28672, "
                         "28672->8192; 50 % 3-bit / 50 % 4-bit tiles, outlier columns",
             "per_shape": rows,
+            "dense_fp16_reference_TFLOPs": round(tot_fl / dense_t / 1e6, 1),
+            "achieved_over_dense_fp16_reference": round(dense_t / tot_t, 4),
+            "note_dense": "dense_fp16_us / dense_fp16_reference_TFLOPs = torch.matmul of fp16 [M, K] by fp16 [N, K]^T (the "
+                          "vendor GEMM library, unquantised weights, no permutations) on the same shapes, timed in this "
+                          "run the same way: what a dense fp16 GEMM sustains on this machine at random operands, as context "
+                          "for frac (not a target and not part of value)",
             "note": "achieved / frac = FLOP-weighted aggregate: total 2*M*N*K of the six shapes / total HIP-event time of "
                     "one whole sfmp_gemm call each (graph of back-to-back calls), measured in this run; per-shape "
                     f"kernel_us / kernel_frac = GEMM kernel alone from the tracked kernel trace ({kfig.get('source')}), "
