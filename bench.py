@@ -296,7 +296,7 @@ def dense_fp16_us(torch, M, N, K, launches):
     return round(us, 1)
 
 
-def time_lut(torch, S, p, replicas, launches):
+def time_lut(torch, S, p, replicas, launches, table_format="fp32"):
     """Average microseconds per call of sfmp_lut_gemv on problem p (graph replay, weights rotated over replicas)."""
     dev = "cuda:0"
     planes, tile_off = S.sfmp_lut_pack(p.codes, p.bitmap)
@@ -309,7 +309,7 @@ def time_lut(torch, S, p, replicas, launches):
 
     def call(j, stream):
         pl, to, sc, zr = reps[j % replicas]
-        S.sfmp_lut_gemv(X, cp, p.N, p.K, pl, to, sc, zr, rp, Y, ws, stream=stream)
+        S.sfmp_lut_gemv(X, cp, p.N, p.K, pl, to, sc, zr, rp, Y, ws, stream=stream, table_format=table_format)
 
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):
@@ -689,8 +689,10 @@ def main():
                     t_mfma = time_each_projection(torch, lm, launches=52)[0]
                     del lm
                     t_lut = time_lut(torch, S, q, 13, 52)
+                    t_lut16 = time_lut(torch, S, q, 13, 52, table_format="fp16")
                     wbytes = float(q.bitmap.astype(np.float64).sum()) * 2048.0
-                    rows.append(dict(shape=f"{K}->{N}", widths=label, lut_us=round(t_lut, 2), mfma_us=round(t_mfma, 2),
+                    rows.append(dict(shape=f"{K}->{N}", widths=label, lut_us=round(t_lut, 2),
+                                     lut_fp16_tables_us=round(t_lut16, 2), mfma_us=round(t_mfma, 2),
                                      lut_GBps=round(wbytes / t_lut / 1e3, 1)))
             extra["lut_gemv_vs_mfma_gemv_M1"] = rows
     if extra:

@@ -82,6 +82,9 @@ extern "C" {
 #define SFMP_ERR_ALIGN (-9)       /* a device pointer is not aligned as required (see sfmp_gemm) */
 #define SFMP_ERR_TOO_LARGE (-10)  /* sfmp_gemm_static: the problem needs more scratch than the static buffer holds */
 
+#define SFMP_LUT_TABLE_FP32 0  /* sfmp_lut_gemv: table entries held as fp32 */
+#define SFMP_LUT_TABLE_FP16 1  /* ... as fp16, the 2-byte entries of Appendix F (fp32 sum of the 8 activations, rounded once) */
+
 #define SFMP_STATIC_SCRATCH_BYTES (16 * 1024 * 1024)  /* scratch of sfmp_gemm_static, per GPU */
 
 /* Sizes of a packed matrix.  Filled by sfmp_pack_query / sfmp_pack; passed by the caller,
@@ -272,17 +275,19 @@ int sfmp_fold_perms(const int32_t* row_perm_prev_host, const int32_t* col_perm_n
  * sfmp_lut_gemv_workspace / sfmp_lut_gemv: device pointers throughout; X fp16 [K], col_perm int32 [K] or NULL,
  * planes and tile_off as packed (uploaded unchanged), scales / zeros fp16 [K/128, N], row_perm int32 [N] or NULL,
  * Y fp16 [N] fully overwritten; workspace of at least the queried bytes, 256-byte aligned, contents irrelevant
- * on entry and unspecified on return (fp32 partial sums of the K ranges).  fp32 tables and accumulation, one
- * round-to-nearest-even conversion at the end; results repeat bit for bit.  Asynchronous on hip_stream; two
- * launches; no global state.  Errors as for sfmp_gemm. */
+ * on entry and unspecified on return (fp32 partial sums of the K ranges).  table_format: SFMP_LUT_TABLE_FP32, or
+ * SFMP_LUT_TABLE_FP16 for the 2-byte table entries of Appendix F (each entry = the fp32 signed sum of its 8
+ * activations rounded once to fp16: a relative error of up to 2^-11 per looked-up value; SFMP_ERR_LAYOUT for any other
+ * value).  Accumulation in fp32 either way, one round-to-nearest-even conversion at the end; results repeat bit for
+ * bit.  Asynchronous on hip_stream; two launches; no global state.  Errors as for sfmp_gemm. */
 int sfmp_lut_pack_query(const int8_t* bitmap_host, int32_t N, int32_t K, int64_t* plane_bytes, int64_t* table_words);
 int sfmp_lut_pack(const uint8_t* codes_host, const int8_t* bitmap_host, int32_t N, int32_t K, uint8_t* planes_host,
                   uint32_t* tile_off_host);
 int sfmp_lut_gemv_workspace(int32_t N, int32_t K, int64_t* bytes);
 int sfmp_lut_gemv(const void* X_dev, const int32_t* col_perm_dev, int32_t N, int32_t K, const void* planes_dev,
                   const uint32_t* tile_off_dev, const void* scales_dev, const void* zeros_dev,
-                  const int32_t* row_perm_dev, void* Y_dev, void* workspace_dev, int64_t workspace_bytes,
-                  void* hip_stream);
+                  const int32_t* row_perm_dev, void* Y_dev, int32_t table_format, void* workspace_dev,
+                  int64_t workspace_bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -103,10 +103,13 @@ def table_lookup(table: np.ndarray, byte: np.ndarray) -> np.ndarray:
 
 def lut_gemv(x: np.ndarray, col_perm: Optional[np.ndarray], N: int, K: int, planes: np.ndarray,
              tile_off: np.ndarray, scales: np.ndarray, zeros: np.ndarray,
-             row_perm: Optional[np.ndarray] = None) -> np.ndarray:
+             row_perm: Optional[np.ndarray] = None, table_dtype=None) -> np.ndarray:
     """y [N] float64 from the bit-plane format, by table lookups (steps 1-4 of the module header).
 
-    x [K]; col_perm [K] or None; scales, zeros [K/128, N] (group length 128); row_perm [N] or None."""
+    x [K]; col_perm [K] or None; scales, zeros [K/128, N] (group length 128); row_perm [N] or None.
+    table_dtype=np.float16: the table entries are rounded to fp16 before they are looked up (the 2-byte entries of
+    Appendix F; every activation then enters the result through a rounded entry, the sum of a column's activations
+    included: it is minus the sum of the entries whose signs are all negative); everything else stays float64."""
     ntr, ntc = N // TILE, K // TILE
     xp = np.asarray(x, dtype=np.float64).reshape(-1)
     if col_perm is not None:
@@ -118,6 +121,9 @@ def lut_gemv(x: np.ndarray, col_perm: Optional[np.ndarray], N: int, K: int, plan
         xs = xp[tc * TILE:(tc + 1) * TILE]
         tables = [half_table(xs[8 * g:8 * g + 8]) for g in range(TILE // 8)]
         sum_x = xs.sum()
+        if table_dtype is not None:
+            tables = [tb.astype(table_dtype).astype(np.float64) for tb in tables]
+            sum_x = -sum(tb[0] for tb in tables)
         for tr in range(ntr):
             t = tr * ntc + tc
             b = int(tile_off[t + 1]) - int(tile_off[t])

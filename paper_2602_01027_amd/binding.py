@@ -69,7 +69,7 @@ def load_library():
     lib.sfmp_lut_pack_query.argtypes = [vp, i32, i32, C.POINTER(i64), C.POINTER(i64)]
     lib.sfmp_lut_pack.argtypes = [vp, vp, i32, i32, vp, vp]
     lib.sfmp_lut_gemv_workspace.argtypes = [i32, i32, C.POINTER(i64)]
-    lib.sfmp_lut_gemv.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.sfmp_lut_gemv.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, i32, vp, i64, vp]
     lib.sfmp_fold_perms.argtypes = [vp, vp, i32, vp]
     for name in EXPORTS:
         if name != "sfmp_strerror":
@@ -281,10 +281,15 @@ def sfmp_lut_gemv_workspace(N: int, K: int) -> int:
     return int(out.value)
 
 
+LUT_TABLE_FORMATS = {"fp32": 0, "fp16": 1}
+
+
 def sfmp_lut_gemv(X, col_perm, N: int, K: int, planes, tile_off, scales, zeros, row_perm, Y, workspace,
-                  stream=None) -> None:
-    """Device tensors throughout (see include/sfmp.h): X fp16 [K], Y fp16 [N]."""
+                  stream=None, table_format="fp32") -> None:
+    """Device tensors throughout (see include/sfmp.h): X fp16 [K], Y fp16 [N]; table_format "fp32", "fp16" or the
+    header's integer."""
     nbytes = workspace.numel() * workspace.element_size()
+    fmt = LUT_TABLE_FORMATS[table_format] if isinstance(table_format, str) else int(table_format)
     _check(load_library().sfmp_lut_gemv(_dev_ptr(X), _dev_ptr(col_perm), int(N), int(K), _dev_ptr(planes),
                                         _dev_ptr(tile_off), _dev_ptr(scales), _dev_ptr(zeros), _dev_ptr(row_perm),
-                                        _dev_ptr(Y), _dev_ptr(workspace), nbytes, _stream_ptr(stream)))
+                                        _dev_ptr(Y), fmt, _dev_ptr(workspace), nbytes, _stream_ptr(stream)))

@@ -4,13 +4,16 @@
 // The weights are b one-bit matrices per 128 x 128 tile (b = the tile's width), in the +-1 form of Appendix B:
 //   w = sum_i 2^i s^ W^_i + z^,   s^ = s/2,  W^_i = 2 W_i - 1,  z^ = z + (2^b - 1) s / 2.
 // A workgroup of 256 threads owns 256 output features (two tile rows) and a range of tile columns.  Per tile column
-// it builds, in LDS, the 16 tables of the column's 16 groups of 8 activations: 128 fp32 entries each, entry p =
+// it builds, in LDS, the 16 tables of the column's 16 groups of 8 activations: 128 entries each (fp32, or fp16 as
+// in Appendix F: 2 bytes per entry, the fp32 sum rounded once), entry p =
 // sum_t (+-) x_t with the sign of x_t given by bit t of p and x_7 always negative; an index with its top bit set is
 // served by the complemented index with the sign flipped (mirror storage: half the table).  Each thread then walks
 // its feature's 16 bytes per bit plane, one lookup per byte, adds the looked-up values over the groups, weights the
 // planes by 2^i, applies s^ and adds z^ times the sum of the column's activations.  The partial sums of the K
 // ranges (fp32 [ksplit, N]) are added in a fixed order by a second small kernel, which also undoes the row
 // permutation, so results repeat bit for bit.
+#include <type_traits>
+
 #include "sfmp_device.h"
 #include "sfmp_internal.h"
 
@@ -32,8 +35,11 @@ struct LutParams {
   int32_t N, K, ntc, ksplit;
 };
 
+// H16: table entries stored as fp16 (the accumulation stays in fp32)
+template <bool H16>
 __global__ __launch_bounds__(kLutThreads) void lut_gemv_kernel(const LutParams p) {
-  __shared__ __align__(16) float lut[2][16][128];  // double-buffered over tile columns
+  typedef typename std::conditional<H16, _Float16, float>::type entry_t;
+  __shared__ __align__(16) entry_t lut[2][16][128];  // double-buffered over tile columns
   const int tid = threadIdx.x;
   const int rb = (int)blockIdx.x / p.ksplit, ks = (int)blockIdx.x % p.ksplit;
   const int n = rb * kLutThreads + tid;                                   // output feature (reordered coordinates)
@@ -87,16 +93,23 @@ __global__ __launch_bounds__(kLutThreads) void lut_gemv_kernel(const LutParams p
 #pragma unroll
       for (int j = 0; j < 8; ++j)
         e[j] = base + 2.f * (((j & 1) ? x[0] : 0.f) + ((j & 2) ? x[1] : 0.f) + ((j & 4) ? x[2] : 0.f));
-      float* dst = &lut[buf][g_build][sub * 8];
-      *reinterpret_cast<floatx4*>(dst) = floatx4{e[0], e[1], e[2], e[3]};
-      *reinterpret_cast<floatx4*>(dst + 4) = floatx4{e[4], e[5], e[6], e[7]};
+      entry_t* dst = &lut[buf][g_build][sub * 8];
+      if constexpr (H16) {
+        half8 h;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) h[j] = (_Float16)e[j];  // round to nearest even, once per entry
+        *reinterpret_cast<half8*>(dst) = h;
+      } else {
+        *reinterpret_cast<floatx4*>(dst) = floatx4{e[0], e[1], e[2], e[3]};
+        *reinterpret_cast<floatx4*>(dst + 4) = floatx4{e[4], e[5], e[6], e[7]};
+      }
     }
     __syncthreads();  // (the other buffer is still being read by slower wavefronts: hence two buffers)
     if (active) {
       // sum of the column's activations = minus the sum of the entries with every sign negative
       float sum_x = 0.f;
 #pragma unroll
-      for (int g = 0; g < 16; ++g) sum_x -= lut[buf][g][0];
+      for (int g = 0; g < 16; ++g) sum_x -= (float)lut[buf][g][0];
       float total = 0.f;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -110,7 +123,7 @@ __global__ __launch_bounds__(kLutThreads) void lut_gemv_kernel(const LutParams p
               const int g = 4 * d + q;
               const int32_t top = (int32_t)(word << (24 - 8 * q)) >> 31;  // all ones if the byte's top bit is set
               const uint32_t idx = ((word >> (8 * q)) ^ (uint32_t)top) & 0x7Fu;
-              const float v = lut[buf][g][idx];
+              const float v = (float)lut[buf][g][idx];  // (fp16 -> fp32 is exact)
               plane_sum += __uint_as_float(__float_as_uint(v) ^ ((uint32_t)top & 0x80000000u));
             }
           }
@@ -163,11 +176,12 @@ int sfmp_lut_gemv_workspace(int32_t N, int32_t K, int64_t* bytes) {
 
 int sfmp_lut_gemv(const void* X_dev, const int32_t* col_perm_dev, int32_t N, int32_t K, const void* planes_dev,
                   const uint32_t* tile_off_dev, const void* scales_dev, const void* zeros_dev,
-                  const int32_t* row_perm_dev, void* Y_dev, void* workspace_dev, int64_t workspace_bytes,
-                  void* hip_stream) {
+                  const int32_t* row_perm_dev, void* Y_dev, int32_t table_format, void* workspace_dev,
+                  int64_t workspace_bytes, void* hip_stream) {
   using namespace sfmp;
   if (!X_dev || !planes_dev || !tile_off_dev || !scales_dev || !zeros_dev || !Y_dev) return SFMP_ERR_NULL;
   if (int e = check_shape(N, K)) return e;
+  if (table_format != SFMP_LUT_TABLE_FP32 && table_format != SFMP_LUT_TABLE_FP16) return SFMP_ERR_LAYOUT;
   const int ks = lut_ksplit(N, K);
   const int64_t need = round_up_256((int64_t)ks * N * 4);
   if (!workspace_dev || ((uintptr_t)workspace_dev & 255) != 0 || workspace_bytes < need) return SFMP_ERR_WORKSPACE;
@@ -184,7 +198,10 @@ int sfmp_lut_gemv(const void* X_dev, const int32_t* col_perm_dev, int32_t N, int
   p.ntc = K / kTile;
   p.ksplit = ks;
   const unsigned nrb = (unsigned)((N + kLutThreads - 1) / kLutThreads);
-  hipLaunchKernelGGL(lut_gemv_kernel, dim3(nrb * (unsigned)ks), dim3(kLutThreads), 0, (hipStream_t)hip_stream, p);
+  if (table_format == SFMP_LUT_TABLE_FP16)
+    hipLaunchKernelGGL(lut_gemv_kernel<true>, dim3(nrb * (unsigned)ks), dim3(kLutThreads), 0, (hipStream_t)hip_stream, p);
+  else
+    hipLaunchKernelGGL(lut_gemv_kernel<false>, dim3(nrb * (unsigned)ks), dim3(kLutThreads), 0, (hipStream_t)hip_stream, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
     note_hip_error("sfmp_lut_gemv launch", hipGetErrorString(e));

@@ -561,7 +561,7 @@ def test_folded_permutations_two_matrix_chain(torch_cuda, M):
 # ---------------------------------------------------------------------------------------------
 # one-bit lookup-table GEMV on the bit-plane format (the paper's own kernel scheme), M = 1
 # ---------------------------------------------------------------------------------------------
-def _run_lut(torch, p):
+def _run_lut(torch, p, table_format="fp32"):
     import paper_2602_01027_amd as S
     dev = "cuda:0"
     planes, tile_off = S.sfmp_lut_pack(p.codes, p.bitmap)
@@ -570,7 +570,8 @@ def _run_lut(torch, p):
     Y = torch.full((p.N,), float("nan"), dtype=torch.float16, device=dev)
     cp = d(p.col_perm) if p.col_perm is not None else None
     rp = d(p.row_perm) if p.row_perm is not None else None
-    S.sfmp_lut_gemv(d(p.X[0]), cp, p.N, p.K, d(planes), d(tile_off.view(np.int32)), d(p.scales), d(p.zeros), rp, Y, ws)
+    S.sfmp_lut_gemv(d(p.X[0]), cp, p.N, p.K, d(planes), d(tile_off.view(np.int32)), d(p.scales), d(p.zeros), rp, Y, ws,
+                    table_format=table_format)
     torch.cuda.synchronize()
     return Y.cpu().numpy()[None, :]
 
@@ -587,6 +588,36 @@ def test_lut_gemv_against_oracles(torch_cuda, K, N, fractions, perms):
         planes, tile_off = LO.lut_pack(p.codes, p.bitmap)
         ref = LO.lut_gemv(p.X[0], p.col_perm, N, K, planes, tile_off, p.scales, p.zeros, p.row_perm)
         assert O.rel_frobenius(Y, ref[None, :]) <= TOL
+
+
+@pytest.mark.parametrize("K,N,fractions,perms", [
+    (128, 128, {4: 1.0}, True), (512, 384, None, True), (1152, 640, None, False), (4096, 1024, {2: 0.5, 4: 0.5}, True)])
+def test_lut_gemv_fp16_tables_against_oracles(torch_cuda, K, N, fractions, perms):
+    # 2-byte table entries (Appendix F): against the plain definition at the stated bound, and, where the table
+    # algorithm of the oracle finishes in seconds, against that algorithm with its entries rounded to fp16 the same
+    # way: what is left then is the order of the fp32 sums and the final rounding
+    from oracle import sfmp_lut_oracle as LO
+    p = W.make_problem("lut16", K, N, 1, 4300 + K + N, fractions=fractions, use_col_perm=perms, use_row_perm=perms)
+    Y = _run_lut(torch_cuda, p, "fp16")
+    _check(p, Y, elementwise=False)
+    if K * N <= 1152 * 640:
+        planes, tile_off = LO.lut_pack(p.codes, p.bitmap)
+        ref16 = LO.lut_gemv(p.X[0], p.col_perm, N, K, planes, tile_off, p.scales, p.zeros, p.row_perm, table_dtype=np.float16)
+        ref = LO.lut_gemv(p.X[0], p.col_perm, N, K, planes, tile_off, p.scales, p.zeros, p.row_perm)
+        e16 = O.rel_frobenius(Y, ref16[None, :])
+        assert e16 <= 4e-4, e16  # fp16 rounding of the result alone is 2^-11 / sqrt(3) = 2.8e-4 in this norm
+        # and the kernel is closer to the oracle that rounds its entries than the two oracles are to each other
+        # once the entries' rounding shows (K > 128: more than one tile column of looked-up values per output)
+        if K > 128:
+            assert np.linalg.norm(Y[0] - ref16) <= np.linalg.norm(Y[0] - ref) * 1.05
+
+
+def test_lut_gemv_rejects_unknown_table_format(torch_cuda):
+    import paper_2602_01027_amd as S
+    p = W.make_problem("lutfmt", 128, 128, 1, 4399)
+    with pytest.raises(S.SfmpError) as e:
+        _run_lut(torch_cuda, p, 7)
+    assert e.value.code == -8
 
 
 def test_lut_gemv_full_size_sampled_and_repeatable(torch_cuda):

@@ -107,3 +107,49 @@ def test_a_dropped_plane_weight_or_mirror_sign_is_caught():
     flipped[3 * 2048:] ^= 0x80  # top sign of every byte of the highest plane
     bad = L.lut_gemv(p.X[0], p.col_perm, 128, 128, flipped, tile_off, p.scales, p.zeros, p.row_perm)
     assert not np.allclose(good, bad, rtol=1e-6, atol=0)
+
+
+# ---- table entries rounded to fp16 (the 2-byte entries of Appendix F) -------------------------------------
+def test_fp16_tables_change_nothing_when_every_entry_is_representable():
+    # small integer activations: every signed sum of 8 of them is an integer below 2048, exact in fp16
+    rng = np.random.default_rng(14)
+    N, K = 128, 256
+    bitmap = np.array([[2, 4]], dtype=np.int8)
+    codes = np.zeros((N, K), dtype=np.uint8)
+    codes[:, :128] = rng.integers(0, 4, (N, 128))
+    codes[:, 128:] = rng.integers(0, 16, (N, 128))
+    x = rng.integers(-100, 101, size=K).astype(np.float64)
+    planes, tile_off = L.lut_pack(codes, bitmap)
+    s, z = rng.uniform(0.5, 2.0, (2, N)), rng.normal(size=(2, N))
+    y = L.lut_gemv(x, None, N, K, planes, tile_off, s, z)
+    y16 = L.lut_gemv(x, None, N, K, planes, tile_off, s, z, table_dtype=np.float16)
+    assert np.array_equal(y, y16)
+
+
+def test_fp16_tables_stay_within_the_rounding_bound_and_do_round():
+    # |y16 - y| <= 2^-11 * sum over the looked-up entries of |entry| * (their weight s^ 2^i), plus the same for the
+    # entries that make up the column sums (weight |z^|); written out here with loops over the plain definition
+    p = _problem(9, 128, 256, {3: 0.5, 4: 0.5})
+    planes, tile_off = L.lut_pack(p.codes, p.bitmap)
+    y = L.lut_gemv(p.X[0], p.col_perm, p.N, p.K, planes, tile_off, p.scales, p.zeros, p.row_perm)
+    y16 = L.lut_gemv(p.X[0], p.col_perm, p.N, p.K, planes, tile_off, p.scales, p.zeros, p.row_perm, table_dtype=np.float16)
+    assert not np.array_equal(y, y16)  # Gaussian activations: the entries do get rounded
+    xp = p.X[0].astype(np.float64)[p.col_perm]
+    s, z = p.scales.astype(np.float64), p.zeros.astype(np.float64)
+    bound_t = np.zeros(p.N)
+    for n in range(p.N):
+        for tc in range(p.K // 128):
+            b = int(p.bitmap[n // 128, tc])
+            s_hat = abs(s[tc, n]) / 2
+            z_hat = abs(z[tc, n] + 0.5 * (2 ** b - 1) * s[tc, n])
+            for g in range(16):
+                xs = xp[tc * 128 + 8 * g:tc * 128 + 8 * g + 8]
+                q = p.codes[n, tc * 128 + 8 * g:tc * 128 + 8 * g + 8].astype(np.int64)
+                for i in range(b):
+                    signs = 2.0 * ((q >> i) & 1) - 1.0
+                    bound_t[n] += s_hat * (2 ** i) * abs(float(signs @ xs))
+                bound_t[n] += z_hat * abs(float(xs.sum()))
+    bound = np.zeros(p.N)
+    bound[p.row_perm] = bound_t
+    assert np.all(np.abs(y16 - y) <= 2.0 ** -11 * bound * (1 + 1e-9))
+    assert np.linalg.norm(y16 - y) / np.linalg.norm(y) < 1e-3
