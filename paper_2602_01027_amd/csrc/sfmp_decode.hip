@@ -780,14 +780,15 @@ __host__ __device__ inline size_t rskinny_raw_bytes(int32_t M, int32_t K) { retu
 // 16, which is what covers the latencies of its loop.  The forms with MB = 4 and with RA hold no sums in registers
 // (they write them to LDS as a slab finishes); there ACC only tells the variants for 16 and for 8 wavefronts apart.
 // G64: group length 64 (two parameter pairs per row and tile column; never together with RES).
-// RA (activations in registers): when a wavefront has at most two tile columns (K <= 256 NW) it loads their matrix-
-// instruction operands once, from a staged copy in operand order (stage_rows_operand_order_kernel), and keeps them in
-// registers for all its slabs: an item then brings only its slab and parameters (small slots, two of them per
-// wavefront at any M), and nothing is read from LDS for the activations.  16 rows always (MB = 16).
-template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false, bool RA = false>
+// RA (activations in registers; 0, 2 or 4): when a wavefront has at most RA tile columns (K <= 128 RA NW) it loads
+// their matrix-instruction operands once, from a staged copy in operand order (stage_rows_operand_order_kernel), and
+// keeps them in registers (16 per tile column) for all its slabs: an item then brings only its slab and parameters
+// (small slots, two of them per wavefront at any M), and nothing is read from LDS for the activations.  16 rows
+// always (MB = 16).
+template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false, int RA = 0>
 __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int bid, const int G, unsigned char* lds_raw) {
   static_assert(!(RES && G64), "the resident form keeps one activation sum per tile column");
-  static_assert(!(RES && RA) && (!RA || MB == 16), "activations in registers: 16 rows, no copy in LDS");
+  static_assert(!(RES && RA) && (!RA || MB == 16) && (RA == 0 || RA == 2 || RA == 4), "activations in registers: 16 rows, no copy in LDS");
   constexpr int NT = NW * 64;
   constexpr int kBase = G64 ? kSlotBytes64 : kSlotBytes;  // slab + parameters; the staged activations follow
   constexpr int kSlot = (RES || RA) ? kBase : kBase + MB * 256;
@@ -953,15 +954,16 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   half8 a[4];
 #pragma unroll
   for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = half8{0, 0, 0, 0, 0, 0, 0, 0};
-  // (RA) the operands of this wavefront's first and second tile column, requested now (the address of the last tile
-  // column for a wavefront that has fewer: the loads are unconditional); first used when the first item is consumed
-  half8 aset0[4], aset1[4];
-  if constexpr (RA) {
-    const int tc0 = min(wave, p.ntc - 1), tc1 = min(wave + NW, p.ntc - 1);
+  // (RA) the operands of this wavefront's tile columns, requested now (the address of the last tile column for a
+  // wavefront that has fewer: the loads are unconditional); first used when the first item is consumed
+  half8 aset[RA > 0 ? RA : 1][4];
+  if constexpr (RA > 0) {
 #pragma unroll
-    for (int kappa = 0; kappa < 4; ++kappa) {
-      aset0[kappa] = *reinterpret_cast<const half8*>(p.xblk + (((size_t)tc0 * 4 + kappa) * 64 + lane) * 16);
-      aset1[kappa] = *reinterpret_cast<const half8*>(p.xblk + (((size_t)tc1 * 4 + kappa) * 64 + lane) * 16);
+    for (int t = 0; t < RA; ++t) {
+      const int tc = min(wave + NW * t, p.ntc - 1);
+#pragma unroll
+      for (int kappa = 0; kappa < 4; ++kappa)
+        aset[t][kappa] = *reinterpret_cast<const half8*>(p.xblk + (((size_t)tc * 4 + kappa) * 64 + lane) * 16);
     }
   }
   // operand addresses inside a slot: activation row i16, unit 4*kappa + kb at position unit ^ i16
@@ -1039,7 +1041,7 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
       return;
     }
     floatx4 sx;
-    if constexpr (RA) {
+    if constexpr (RA == 2) {
       sx = sx_known;
     } else if constexpr (RES) {
       sx = *reinterpret_cast<const floatx4*>(SxL + (misc & 0xFFFF) * 16 + kb * 4);
@@ -1084,23 +1086,32 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
       acc_q = floatx4{0.f, 0.f, 0.f, 0.f}, acc_z = floatx4{0.f, 0.f, 0.f, 0.f};
     }
   };
-  // (RA, one parameter pair per tile column) the activation sums of the two tile columns, taken once for all slabs:
-  // the same four matrix instructions against ones, in the same order, that the other forms issue per item
+  // (two tile columns in registers, one parameter pair per tile column) the activation sums of the two tile columns,
+  // taken once for all slabs: the same four matrix instructions against ones, in the same order, that the other forms
+  // issue per item (with four tile columns the registers go to the operands, and the sums are taken per item)
   floatx4 sx0 = {0.f, 0.f, 0.f, 0.f}, sx1 = {0.f, 0.f, 0.f, 0.f};
-  if constexpr (RA && !G64) {
+  if constexpr (RA == 2 && !G64) {
 #pragma unroll
-    for (int kappa = 0; kappa < 4; ++kappa) sx0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aset0[kappa], ones, sx0, 0, 0, 0);
+    for (int kappa = 0; kappa < 4; ++kappa) sx0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aset[0][kappa], ones, sx0, 0, 0, 0);
 #pragma unroll
-    for (int kappa = 0; kappa < 4; ++kappa) sx1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aset1[kappa], ones, sx1, 0, 0, 0);
+    for (int kappa = 0; kappa < 4; ++kappa) sx1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aset[1][kappa], ones, sx1, 0, 0, 0);
   }
   auto consume = [&](int e, int s) __attribute__((always_inline)) {
     const uint32_t misc = (uint32_t)__builtin_amdgcn_readlane((int)it_misc, e);
     const unsigned char* slot = ring + s * kSlot;
     if constexpr (RA) {
-      // this wavefront's first or second tile column (a uniform branch over two copies of the item's code: selecting
-      // the operands into a third set of registers cost 16 more of them)
-      if (((misc & 0xFFFF) >> (NW == 16 ? 4 : 3)) == 0) consume_with(misc, slot, aset0, sx0);
-      else consume_with(misc, slot, aset1, sx1);
+      // which of this wavefront's tile columns (a uniform branch over RA copies of the item's code: selecting the
+      // operands into one more set of registers cost 16 more of them)
+      const uint32_t t = (misc & 0xFFFF) >> (NW == 16 ? 4 : 3);
+      if constexpr (RA == 2) {
+        if (t == 0) consume_with(misc, slot, aset[0], sx0);
+        else consume_with(misc, slot, aset[1], sx1);
+      } else {
+        if (t == 0) consume_with(misc, slot, aset[0], sx0);
+        else if (t == 1) consume_with(misc, slot, aset[1], sx0);
+        else if (t == 2) consume_with(misc, slot, aset[2], sx0);
+        else consume_with(misc, slot, aset[3], sx0);
+      }
     } else {
       if (MB == 16 || i16 < MB) {
         const unsigned char* abase = RES ? Xs + (size_t)(misc & 0xFFFF) * (MB * 256) : slot;
@@ -1211,7 +1222,7 @@ __device__ __forceinline__ void rskinny_body(const RSkinnyParams& p, const int b
   }
 }
 
-template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false, bool RA = false>
+template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false, int RA = 0>
 __global__ __launch_bounds__(NW * 64) void rskinny_kernel(const RSkinnyParams p) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   rskinny_body<NW, S, MB, RES, ACC, G64, RA>(p, (int)blockIdx.x, (int)gridDim.x, lds_raw);
@@ -1227,7 +1238,7 @@ struct RSkinnyBatch {  // laid out as GemvBatch
 };
 static_assert(offsetof(RSkinnyBatch, p) == 64, "the header of a batch is one 64-byte line");
 
-template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false, bool RA = false>
+template <int NW, int S, int MB, bool RES, int ACC, bool G64 = false, int RA = 0>
 __global__ __launch_bounds__(NW * 64) void rskinny_batched_kernel(const RSkinnyBatch b) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int i = batch_problem_of(b.first, (int)blockIdx.x);
@@ -1303,7 +1314,7 @@ static GemvFit gemv_fit(int32_t N, int32_t K, int32_t grid) {
 struct RSkinnyConfig {
   int32_t mb, nw, slots, acc;
   bool resident;
-  bool ra;  // activations in registers (at most two tile columns per wavefront): 16-row operand-order staging, small slots
+  int32_t ra;  // activations in registers (at most 2 or 4 tile columns per wavefront; 0: not): 16-row operand-order staging, small slots
 };
 static int32_t rskinny_mb(int32_t M) { return M <= 4 ? 4 : M <= 8 ? 8 : 16; }
 // LDS of the ring-skinny kernel: reduction buffers, (resident: activations in operand layout, their tile-column sums,
@@ -1325,6 +1336,8 @@ constexpr int kSlotsResident = 3, kSlotsMb4 = 2, kSlotsMb8 = 2, kSlotsMb16 = 2;
 // 16 rows with 16 wavefronts: a slot carries 4 KiB of activations, and only one per wavefront fits in LDS (the other
 // wavefronts of the SIMD cover the wait)
 constexpr int kSlotsMb16Wide = 1;
+constexpr int kSkinnyWideSlabs = 8;  // slabs per workgroup up to which the ring-skinny kernels run 16 wavefronts
+constexpr int kSkinnyMaxRounds = 4;  // workgroups per CU, one after the other, accepted to get there
 constexpr int kSlotsRegisterActs = 2;  // activations in registers: the slots hold a slab and its parameters only
 // max_slabs: the largest number of slabs of a workgroup over the problems of the launch; K: the largest K
 // g64: group length 64, for which the resident form does not exist
@@ -1332,23 +1345,23 @@ static RSkinnyConfig rskinny_config(int32_t M, int32_t K, int32_t max_slabs, boo
   RSkinnyConfig c;
   c.mb = rskinny_mb(M);
   // 16 wavefronts where the finished sums fit beside the rest in 128 registers and the rings in LDS
-  const bool wide = max_slabs <= 8;
+  const bool wide = max_slabs <= kSkinnyWideSlabs;
   c.nw = wide ? 16 : 8;
   c.acc = !wide ? 16 : max_slabs <= 4 ? 4 : 8;
   c.resident = false;
-  c.ra = false;
+  c.ra = 0;
   if (c.mb == 4) c.acc = wide ? 4 : 16;  // up to four rows: the finished sums live in LDS, acc only names the variant
   if (!g64 && c.mb == 4 && (int64_t)M * K * 2 <= kResidentMaxRawBytes && K / 8 <= kGemvUnitIters * c.nw * 64) {
     c.resident = true;
     c.slots = kSlotsResident;
     if (rskinny_lds_bytes(c, max_slabs, M, K) > 160 * 1024) c.resident = false;
   }
-  if (!c.resident && K / kTile <= 2 * c.nw) {
-    // at most two tile columns per wavefront: their operands stay in registers (any M up to 16 as 16 rows) and the
-    // finished sums in LDS, one KiB per wavefront and slab (no sums in registers: acc only names the variant);
+  if (!c.resident && K / kTile <= 4 * c.nw) {
+    // at most two or four tile columns per wavefront: their operands stay in registers (any M up to 16 as 16 rows)
+    // and the finished sums in LDS, one KiB per wavefront and slab (no sums in registers: acc only names the variant);
     // with 8 slabs per workgroup and 16 wavefronts that does not fit beside the rings: the ordinary form then
     RSkinnyConfig r = c;
-    r.ra = true;
+    r.ra = K / kTile <= 2 * c.nw ? 2 : 4;
     r.mb = 16;
     r.acc = r.nw == 16 ? 4 : 16;
     r.slots = kSlotsRegisterActs;
@@ -1380,6 +1393,10 @@ DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M, int32_t group) {
   // Everything else goes through the ring-skinny kernel: one workgroup per CU while a workgroup's share
   // stays within 16 slabs (N <= 65536), more workgroups beyond that.
   int32_t grid = nslab < kGemvMaxGrid ? nslab : kGemvMaxGrid;
+  // (two to four workgroups per CU, one after the other, while that brings a workgroup's share down to 8 slabs and
+  // the kernel to 16 wavefronts: N up to 131072)
+  for (int rounds = 2; rounds <= kSkinnyMaxRounds && (nslab + grid - 1) / grid > kSkinnyWideSlabs; ++rounds)
+    if ((nslab + rounds * kGemvMaxGrid - 1) / (rounds * kGemvMaxGrid) <= kSkinnyWideSlabs) grid = rounds * kGemvMaxGrid;
   if ((nslab + grid - 1) / grid > kGemvMaxSlabs) grid = ((nslab + kGemvMaxSlabs - 1) / kGemvMaxSlabs + 7) / 8 * 8;
   d.gemv = false;
   d.grid = grid;
@@ -1462,7 +1479,7 @@ static int launch_gemv_batch(GemvBatch b, size_t lds_bytes, void* stream) {
 
 // Splits the 256 workgroups of a persistent launch between `count` problems in units of 8 (one per XCD), greedily to
 // the problem with the most packed bytes per workgroup, never giving a problem more workgroups than it has slabs.
-static int split_grid(const GemmArgs* probs, int count, int32_t* g) {
+static int split_grid(const GemmArgs* probs, int count, int32_t* g, int32_t max_grid = kGemvMaxGrid) {
   int64_t bytes[kGemvMaxBatch];
   int32_t total = 0;
   for (int i = 0; i < count; ++i) {
@@ -1471,8 +1488,8 @@ static int split_grid(const GemmArgs* probs, int count, int32_t* g) {
     g[i] = 8;
     total += 8;
   }
-  if (total > kGemvMaxGrid) return SFMP_ERR_SHAPE;
-  while (total + 8 <= kGemvMaxGrid) {
+  if (total > max_grid) return SFMP_ERR_SHAPE;
+  while (total + 8 <= max_grid) {
     int best = -1;
     double best_load = 0.0;
     for (int i = 0; i < count; ++i) {
@@ -1550,7 +1567,7 @@ static RSkinnyParams rskinny_params(const GemmArgs& a, int32_t M, const void* xb
   return p;
 }
 
-template <int NW, int S, int MB, bool RES, int ACC, bool G64, bool RA>
+template <int NW, int S, int MB, bool RES, int ACC, bool G64, int RA>
 static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* stream) {
   const sfmp_layout_t* L = a.L;
   const void* fn = reinterpret_cast<const void*>(&rskinny_kernel<NW, S, MB, RES, ACC, G64, RA>);
@@ -1576,11 +1593,12 @@ static int launch_rskinny_variant(const GemmArgs& a, const DecodePlan& d, void* 
 
 // The compiled configurations (see rskinny_config): X(NW, S, MB, RES, ACC, RA)
 #define SFMP_RSKINNY_CONFIGS(X)                                                                                   \
-  X(16, kSlotsResident, 4, true, 4, false) X(8, kSlotsResident, 4, true, 16, false)                                        \
-  X(16, kSlotsMb4, 4, false, 4, false) X(8, kSlotsMb4, 4, false, 16, false)                                                \
-  X(16, kSlotsMb8, 8, false, 4, false) X(16, kSlotsMb8, 8, false, 8, false) X(8, kSlotsMb8, 8, false, 16, false)             \
-  X(16, kSlotsMb16Wide, 16, false, 4, false) X(16, kSlotsMb16Wide, 16, false, 8, false) X(8, kSlotsMb16, 16, false, 16, false) \
-  X(16, kSlotsRegisterActs, 16, false, 4, true) X(8, kSlotsRegisterActs, 16, false, 16, true)
+  X(16, kSlotsResident, 4, true, 4, 0) X(8, kSlotsResident, 4, true, 16, 0)                                        \
+  X(16, kSlotsMb4, 4, false, 4, 0) X(8, kSlotsMb4, 4, false, 16, 0)                                                \
+  X(16, kSlotsMb8, 8, false, 4, 0) X(16, kSlotsMb8, 8, false, 8, 0) X(8, kSlotsMb8, 8, false, 16, 0)             \
+  X(16, kSlotsMb16Wide, 16, false, 4, 0) X(16, kSlotsMb16Wide, 16, false, 8, 0) X(8, kSlotsMb16, 16, false, 16, 0) \
+  X(16, kSlotsRegisterActs, 16, false, 4, 2) X(8, kSlotsRegisterActs, 16, false, 16, 2)                                    \
+  X(16, kSlotsRegisterActs, 16, false, 4, 4) X(8, kSlotsRegisterActs, 16, false, 16, 4)
 
 static int launch_rskinny(const GemmArgs& a, const DecodePlan& d, void* stream) {
 #define SFMP_X(NW_, S_, MB_, RES_, ACC_, RA_)                                                 \
@@ -1626,7 +1644,7 @@ static BatchStagePlan plan_batch_staging(const GemmArgs* probs, int count, int32
 }
 
 
-template <int NW, int S, int MB, bool RES, int ACC, bool G64, bool RA>
+template <int NW, int S, int MB, bool RES, int ACC, bool G64, int RA>
 static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int32_t M, const int32_t* g,
                                           void* workspace, void* stream) {
   const BatchStagePlan sp = plan_batch_staging(probs, count, MB);
@@ -1693,12 +1711,28 @@ static int launch_rskinny_batched_variant(const GemmArgs* probs, int count, int3
 // One configuration for a whole batched launch: the one that fits the problem with the most slabs per workgroup and
 // the largest K (resident or register activations only when every problem of the batch fits them).
 static int batch_config(const GemmArgs* probs, int count, int32_t M, int32_t* g, RSkinnyConfig* c, bool* g64) {
-  if (int e = split_grid(probs, count, g)) return e;
   int32_t max_slabs = 0, max_k = 0;
   int n64 = 0;
+  // one workgroup per CU, or (rounds) two to four per CU one after the other while that brings a workgroup's share
+  // down to 8 slabs: with up to 8 slabs the kernels run 16 wavefronts, with more only 8 (see rskinny_config)
+  for (int rounds = 1; rounds <= kSkinnyMaxRounds; ++rounds) {
+    if (int e = split_grid(probs, count, g, rounds * kGemvMaxGrid)) return e;
+    max_slabs = 0;
+    for (int i = 0; i < count; ++i) {
+      const int32_t nslab = 8 * (probs[i].L->N / kTile);
+      max_slabs = std::max(max_slabs, (nslab + g[i] - 1) / g[i]);
+    }
+    if (max_slabs <= kSkinnyWideSlabs) break;
+  }
+  if (max_slabs > kSkinnyWideSlabs) {  // not reachable within four rounds: one round, 8 wavefronts
+    if (int e = split_grid(probs, count, g)) return e;
+    max_slabs = 0;
+    for (int i = 0; i < count; ++i) {
+      const int32_t nslab = 8 * (probs[i].L->N / kTile);
+      max_slabs = std::max(max_slabs, (nslab + g[i] - 1) / g[i]);
+    }
+  }
   for (int i = 0; i < count; ++i) {
-    const int32_t nslab = 8 * (probs[i].L->N / kTile);
-    max_slabs = std::max(max_slabs, (nslab + g[i] - 1) / g[i]);
     max_k = std::max(max_k, probs[i].L->K);
     n64 += probs[i].L->group == 64;
   }

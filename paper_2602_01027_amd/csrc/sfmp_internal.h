@@ -21,7 +21,7 @@ struct DecodePlan {
   int32_t nw;        // ring-skinny: wavefronts per workgroup (8 or 16)
   int32_t acc;       // ring-skinny: slabs per workgroup held in registers (4, 8 or 16)
   bool resident;     // ring-skinny: activations staged into LDS by the kernel itself, no staging launch
-  bool ra;           // ring-skinny: activations in registers (operand-order staging of 16 rows)
+  int32_t ra;        // ring-skinny: tile columns per wavefront whose activations are held in registers (0, 2, 4)
   int64_t workspace_bytes;  // staged activations of the ring-skinny kernel
 };
 DecodePlan make_decode_plan(int32_t N, int32_t K, int32_t M, int32_t group);

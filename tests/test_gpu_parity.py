@@ -422,6 +422,26 @@ def test_gemm_batched_five_slabs_per_workgroup_short_K(torch_cuda, M, group):
         assert np.array_equal(run_gemm(p, dp, cp, rp).view(np.uint16), y.view(np.uint16))
 
 
+@pytest.mark.parametrize("K,N,M,group", [(5120, 1024, 6, 128), (8192, 2048, 16, 128), (8192, 1024, 9, 128), (6144, 1024, 3, 64),
+                                         (8192, 1024, 16, 64), (8192, 1280, 16, 256)])
+def test_small_batch_three_and_four_tile_columns_per_wavefront(torch_cuda, K, N, M, group):
+    # 4096 < K <= 8192: the activations of a wavefront's three or four tile columns are held in registers (K = 5120:
+    # wavefronts 0-7 have three tile columns, the others two; K = 6144 at group length 64: no resident form at M = 3)
+    from gpu_util import run_gemm
+    p = W.make_problem("ra4", K, N, M, 8600 + M + K // 128, fractions={2: 0.4, 3: 0.3, 4: 0.3}, outliers=True, group=group)
+    _check(p, run_gemm(p))
+
+
+@pytest.mark.parametrize("K,N,M", [(1024, 40960, 3), (1024, 40960, 8), (4224, 36864, 8), (4224, 36864, 16)])
+def test_small_batch_more_than_2048_slabs(torch_cuda, K, N, M):
+    # more than 8 slabs per workgroup on 256 workgroups: the launch takes 512 workgroups (two per CU in turn, 5 slabs
+    # each) and keeps 16 wavefronts; K = 1024 with the activations resident in LDS (M = 3) or in registers, K = 4224
+    # (33 tile columns) with the activations travelling through the ring slots
+    from gpu_util import run_gemm
+    p = W.make_problem("wide", K, N, M, 8500 + M + K, fractions={2: 0.5, 3: 0.25, 4: 0.25})
+    _check(p, run_gemm(p))
+
+
 # ---------------------------------------------------------------------------------------------
 # group lengths 256 / 512, bf16 parameters, (m_b, n_b) bit-allocation blocks
 # ---------------------------------------------------------------------------------------------

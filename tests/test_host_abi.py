@@ -167,16 +167,19 @@ def _plan_mirror(N, K, M):
         if M == 1 and K <= 32768 - 1:  # the GEMV kernel holds the activation vector in LDS: no workspace
             return "gemv", None
         mb = 4 if M <= 4 else 8 if M <= 8 else 16
-        # a wavefront with at most two tile columns keeps the activations in registers (staged as 16 rows), unless
+        # a wavefront with at most four tile columns keeps the activations in registers (staged as 16 rows), unless
         # the kernel stages M <= 4 rows into LDS by itself (at most 32 KiB of them)
         grid = min(8 * ntr, 256)
+        for rounds in (2, 3, 4):  # up to four workgroups per CU in turn, to get down to 8 slabs per workgroup
+            if -(-8 * ntr // grid) > 8 and -(-8 * ntr // (256 * rounds)) <= 8:
+                grid = 256 * rounds
         if -(-8 * ntr // grid) > 16:
             grid = (-(-8 * ntr // 16) + 7) // 8 * 8
         max_slabs = -(-8 * ntr // grid)
         nw = 16 if max_slabs <= 8 else 8
         resident = mb == 4 and M * K * 2 <= 32 * 1024 and K // 8 <= 4 * nw * 64
         # (that form keeps each wavefront's finished sums in LDS, 1 KiB per slab, beside two ring slots of 1280 bytes)
-        if not resident and ntc <= 2 * nw and nw * (max_slabs * 1024 + 2 * 1280) <= 160 * 1024:
+        if not resident and ntc <= 4 * nw and nw * (max_slabs * 1024 + 2 * 1280) <= 160 * 1024:
             mb = 16
         return "ring", up256(ntc * mb * 256)
     chunks = (M + 15) // 16
@@ -194,7 +197,7 @@ def _plan_mirror(N, K, M):
     return f"mfma bm={bm} ksplit={ks}", xperm + ytmp
 
 
-@pytest.mark.parametrize("N,K,M", [(4096, 4096, 4), (4096, 4096, 3), (14336, 4096, 5), (32768, 4096, 2), (4096, 8192, 3), (4096, 14336, 16), (1024, 4096, 128), (1152, 4096, 128),
+@pytest.mark.parametrize("N,K,M", [(4096, 4096, 4), (4096, 4096, 3), (14336, 4096, 5), (32768, 4096, 2), (57344, 4096, 8), (57344, 8192, 8), (4096, 8192, 3), (4096, 14336, 16), (1024, 4096, 128), (1152, 4096, 128),
                                     (4096, 4096, 32), (4096, 4096, 33), (4096, 14336, 256), (14336, 4096, 48),
                                     (14336, 4096, 256), (4096, 4096, 2048), (28672, 8192, 2048), (4096, 2048, 100),
                                     (8192, 28672, 512)])
