@@ -432,6 +432,24 @@ def test_small_batch_three_and_four_tile_columns_per_wavefront(torch_cuda, K, N,
     _check(p, run_gemm(p))
 
 
+@pytest.mark.parametrize("K,N,M,group", [(9216, 512, 5, 128), (14336, 1024, 16, 128), (14336, 4096, 16, 128), (28672, 1024, 8, 64),
+                                         (16512, 384, 7, 128), (14336, 1024, 40, 128), (28672, 8192, 8, 256)])
+def test_small_batch_long_K(torch_cuda, K, N, M, group):
+    # K > 8192 at 5 <= M <= 16 (and chunks of 16 rows: M = 40): more tile columns per wavefront than fit in registers,
+    # the activations travel through the ring slots; repeated calls give the same bits
+    from gpu_util import device_problem, run_gemm
+    p = W.make_problem("longk", K, N, M, 8700 + M + K // 128, fractions={2: 0.3, 3: 0.4, 4: 0.3}, outliers=True, group=group,
+                       fast_codes=N * K > (1 << 27))
+    dp, cp, rp = device_problem(p)
+    Y = run_gemm(p, dp, cp, rp)
+    if N * K > (1 << 27):
+        _check(p, Y, m_rows=[0, M - 1])
+    else:
+        _check(p, Y)
+    for _ in range(3):
+        assert np.array_equal(run_gemm(p, dp, cp, rp).view(np.uint16), Y.view(np.uint16))
+
+
 @pytest.mark.parametrize("K,N,M", [(1024, 40960, 3), (1024, 40960, 8), (4224, 36864, 8), (4224, 36864, 16)])
 def test_small_batch_more_than_2048_slabs(torch_cuda, K, N, M):
     # more than 8 slabs per workgroup on 256 workgroups: the launch takes 512 workgroups (two per CU in turn, 5 slabs
