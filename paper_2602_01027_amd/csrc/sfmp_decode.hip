@@ -164,7 +164,8 @@ struct GemvParams {
 };
 
 constexpr int kGemvWaves = 16;       // wavefronts per workgroup; one workgroup per CU
-constexpr int kGemvMaxGrid = 256;    // persistent grid: at most one workgroup per CU
+constexpr int kGemvMaxGrid = 256;    // persistent grid: at most one workgroup per CU (two per CU, which the GEMV
+                                     // kernels' 60 registers and LDS footprint allow on most shapes, measured 2-5 % slower)
 // Ring slots per wavefront.  Two: one item being consumed, one on its way.  The 4096 wavefronts of a launch are
 // what keeps the memory system busy; deeper rings (up to 8 were tried, all that LDS allows) were measured slower by
 // up to 14 %: every wavefront then requests its whole share at once, the data comes back wavefront by wavefront,
@@ -442,13 +443,11 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   half8 a[4];
 #pragma unroll
   for (int kappa = 0; kappa < 4; ++kappa) a[kappa] = half8{0, 0, 0, 0, 0, 0, 0, 0};
-  // One fp32 sum per slab of this workgroup, kept in registers.
-  // (a vector type: the write of element j at the end of a slab becomes one indexed register move; a switch over
-  // 16 scalars became a ladder of some 40 branches and moves that ran after every second item when K = 4096)
-  static_assert(kGemvMaxSlabs == 16, "per-slab sums are held in a 16-element vector");
-  floatx16v accs;
-#pragma unroll
-  for (int q = 0; q < kGemvMaxSlabs; ++q) accs[q] = 0.f;
+  // One fp32 sum per slab of this workgroup and wavefront (16 output features: lanes 0-15), written into the
+  // reduction buffer as the slab finishes: red [slab][wavefront][16].  (The buffer shares its LDS with the raw copy of
+  // the activations, which nobody reads after the barrier above.  Held in a 16-element register vector instead, the
+  // sums cost 16 registers and an indexed register move per slab: 1.5 % of a layer, 4 % of the small launches.)
+  float* red_mine = red + wave * 16 + lane;
   // running sums of the current slab: scale * (code sum, in units of 2^-24) and zero * (activation sum)
   float acc_q = 0.f, acc_z = 0.f;
 
@@ -512,7 +511,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
       acc_z += z_lo * sx + z_hi * sx_hi;
       if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
         asm volatile("" ::: "memory");
-        accs[(misc >> 17) & 15] = acc_q * 16777216.f + acc_z;
+        if (lane < 16) red_mine[((misc >> 17) & 15) * (NW * 16)] = acc_q * 16777216.f + acc_z;
         acc_q = 0.f, acc_z = 0.f;
       }
       return;
@@ -545,7 +544,7 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
     }
     if (misc & 0x10000u) {  // this wavefront's share of slab j is complete
       asm volatile("" ::: "memory");  // keeps this a branch: as a select it copied all 16 sums after every item
-      accs[(misc >> 17) & 15] = acc_q * 16777216.f + acc_z;
+      if (lane < 16) red_mine[((misc >> 17) & 15) * (NW * 16)] = acc_q * 16777216.f + acc_z;
       acc_q = 0.f, acc_z = 0.f;
     }
   };
@@ -593,11 +592,8 @@ __device__ __forceinline__ void gemv_body(const GemvParams& p_in, const int bid,
   }
   static_assert(S <= 8 && kCopiesPerItem * 7 < 64, "the tail's waits cover up to 7 younger items");
 
-  if (lane < 16) {
-#pragma unroll
-    for (int q = 0; q < kGemvMaxSlabs; ++q)
-      if (q < nj) red[(q * NW + wave) * 16 + lane] = accs[q];
-  }
+  if (my_cnt == 0 && lane < 16)  // a wavefront without a tile column has written no sums: zeros
+    for (int q = 0; q < nj; ++q) red_mine[q * (NW * 16)] = 0.f;
   __syncthreads();
   if (tid < nj * 16) {  // nj <= 16: one sum per thread at most
     float sum = 0.f;
