@@ -180,7 +180,6 @@ constexpr int kGemvSlotParamBytes = 128;  // GEMV slots: [16 scale dwords | 16 z
 constexpr int kGemvSlotParamBytes64 = 256;
 constexpr int kSlotBytes64 = 1024 + 256;
 
-typedef float floatx16v __attribute__((ext_vector_type(16)));
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
