@@ -164,6 +164,12 @@ int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream);
  * Alignment (SFMP_ERR_ALIGN otherwise): X, col_perm, row_perm, s2, s3, s4, scales and zeros 16 bytes (the kernels
  * read them with 16-byte vector loads and direct global-to-LDS copies); index 4 bytes; Y 2 bytes for M <= 16 and
  * 16 bytes for M > 16 (whole 16-byte row segments are stored there).
+ * Precision for M <= 16 (and the chunks of 16 rows): the codes go through the matrix cores as fp16 denormals, and
+ * v_mfma_f32_16x16x32_f16 aligns its 32 products by nominal exponents (2^-14 for a denormal) and keeps 24 bits below the
+ * largest: a product whose activation lies 2^4 or more below the largest activation of its 32 columns loses low-order
+ * bits, less than |s| 2^(E-14) each (E = exponent of that largest activation) - of the order of 2^-14 of the largest
+ * product of those 32 columns, above fp32 rounding and far below the fp16 rounding of the result unless the result is
+ * a small difference of large terms.
  * Number range: for M <= 16 scales and zeros are widened to fp32 and never rounded.  For M > 16 on the matrix-core
  * path the dequantised weight s*q + z is formed and rounded ONCE in fp16 (bf16 parameters are converted to fp16 first,
  * which is exact inside fp16's normal range): scales, zeros and weights must lie within fp16's normal range,

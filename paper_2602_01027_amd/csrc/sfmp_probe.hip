@@ -32,7 +32,35 @@ __global__ __launch_bounds__(1024) void stream_read_kernel(const u32x4* __restri
   if (lane == 0 && wave < 512) out[wave] = r;  // 2048 bytes of check words
 }
 
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+// One v_mfma_f32_16x16x32_f16 per workgroup (one wavefront): A row 0 = a[32], B column 0 = b[32], everything else
+// zero, C = 0; the result element (0, 0).  Lane kb * 16 holds the products k = 8 kb .. 8 kb + 7.
+__global__ __launch_bounds__(64) void mfma_dot_kernel(const _Float16* __restrict__ a, const _Float16* __restrict__ b,
+                                                      float* __restrict__ out) {
+  const int t = blockIdx.x, lane = threadIdx.x, i16 = lane % 16, kb = lane / 16;
+  half8 av, bv;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    av[j] = i16 == 0 ? a[(size_t)t * 32 + 8 * kb + j] : (_Float16)0;
+    bv[j] = i16 == 0 ? b[(size_t)t * 32 + 8 * kb + j] : (_Float16)0;
+  }
+  floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+  acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc, 0, 0, 0);
+  if (lane == 0) out[t] = acc[0];
+}
+
 }  // namespace
+
+extern "C" int sfmp_probe_mfma_dot(const void* a_dev, const void* b_dev, int32_t count, void* out_dev, void* hip_stream) {
+  if (!a_dev || !b_dev || !out_dev) return -1;
+  if (count < 1 || (reinterpret_cast<uintptr_t>(a_dev) % 2) != 0 || (reinterpret_cast<uintptr_t>(b_dev) % 2) != 0 ||
+      (reinterpret_cast<uintptr_t>(out_dev) % 4) != 0)
+    return -2;
+  hipLaunchKernelGGL(mfma_dot_kernel, dim3((unsigned)count), dim3(64), 0, (hipStream_t)hip_stream, (const _Float16*)a_dev,
+                     (const _Float16*)b_dev, (float*)out_dev);
+  return hipGetLastError() == hipSuccess ? 0 : -6;
+}
 
 extern "C" int sfmp_probe_stream_read(const void* src_dev, int64_t bytes, void* out_dev, void* hip_stream) {
   if (!src_dev || !out_dev) return -1;

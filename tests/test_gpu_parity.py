@@ -597,6 +597,67 @@ def test_folded_permutations_two_matrix_chain(torch_cuda, M):
 
 
 # ---------------------------------------------------------------------------------------------
+# what the error bound of the decode kernels assumes about the matrix instruction, pinned on the hardware
+# ---------------------------------------------------------------------------------------------
+def test_mfma_alignment_model(torch_cuda):
+    """v_mfma_f32_16x16x32_f16 with an fp16-denormal operand (the decode kernels' codes, q * 2^(p-24)).  The products are
+    aligned by NOMINAL exponents (2^-14 for the denormal, whatever its leading bit) and 24 bits are kept below the
+    largest: within the 8 products of a lane the cut is exactly at 2^(E - 38), E = the lane's largest activation
+    exponent, and the bits below are cut off, not rounded; a lone product of another lane comes through at fp32
+    precision.  In general a product loses less than 2^(E - 38), E over the 32 activations of the instruction, and only
+    if its own exponent is at most E - 4: tests/gpu_util.py::mfma_alignment_loss turns that into a term of the
+    per-element bound of the decode kernels, and this test pins it on the hardware."""
+    from paper_2602_01027_amd import probe
+    torch = torch_cuda
+    rows_a, rows_b, expect = [], [], []
+    for pos in (0, 2, 6):
+        for slot in (1, 7, 8, 31):           # 1, 7: same lane as element 0; 8, 31: other lanes
+            for E in range(0, 16):
+                a = np.zeros(32); b = np.zeros(32)
+                a[0], b[0] = 2.0 ** E, 2.0 ** (pos - 24)
+                a[slot], b[slot] = 1025.0 / 1024.0, 3.0 * 2.0 ** (pos - 24)   # 3075 units of 2^(pos-34)
+                rows_a.append(a); rows_b.append(b)
+                big = 2.0 ** (E + pos - 24)
+                if slot < 8:
+                    cut = max(E - 4 - pos, 0)  # bits of the small product below 2^(E-38), in its units of 2^(pos-34)
+                    kept = (3075 >> cut) << cut
+                    expect.append(big + kept * 2.0 ** (pos - 34))  # fits in fp32 exactly
+                else:
+                    expect.append(float(np.float32(big + 3075 * 2.0 ** (pos - 34))))  # fp32 of the exact sum
+    A = torch.from_numpy(np.array(rows_a, dtype=np.float16)).to("cuda:0")
+    B = torch.from_numpy(np.array(rows_b, dtype=np.float16)).to("cuda:0")
+    assert np.array_equal(B.cpu().numpy().astype(np.float64), np.array(rows_b))  # the denormals survive the upload
+    got = probe.mfma_dot(A, B).cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, np.array(expect)), np.nonzero(got != np.array(expect))[0][:8]
+
+    # random operands shaped like the kernels' (2-bit codes at position 0; with and without an outlier column; all
+    # four lanes, and one lane alone): the error stays within the bound, and it is far above fp32 rounding
+    rng = np.random.default_rng(11)
+    n = 4096
+    for outlier, one_lane in ((True, False), (False, False), (True, True)):
+        a = rng.normal(size=(n, 32))
+        if outlier:
+            a[:, 5] *= 20.0
+        if one_lane:
+            a[:, 8:] = 0.0
+        a = a.astype(np.float16).astype(np.float64)
+        b = rng.integers(0, 4, size=(n, 32)).astype(np.float64) * 2.0 ** -24
+        got = probe.mfma_dot(torch.from_numpy(a.astype(np.float16)).to("cuda:0"),
+                             torch.from_numpy(b.astype(np.float16)).to("cuda:0")).cpu().numpy().astype(np.float64)
+        prod = a * b
+        exact = prod.sum(axis=1)
+        _, e = np.frexp(np.abs(a))
+        e = np.maximum(e - 1, -14)
+        E = np.where(a != 0, e, -100).max(axis=1)
+        lossy = ((prod != 0) & (e <= E[:, None] - 4)).sum(axis=1)
+        bound = lossy * np.ldexp(1.0, E - 38) + 2.0 ** -23 * np.abs(exact)
+        err = np.abs(got - exact)
+        assert np.all(err <= bound), float((err / np.maximum(bound, 1e-300)).max())
+        i = int(np.argmax(err))
+        assert err[i] > 50 * 2.0 ** -24 * np.abs(prod[i]).sum()  # not an fp32-accurate sum of exact products
+
+
+# ---------------------------------------------------------------------------------------------
 # one-bit lookup-table GEMV on the bit-plane format (the paper's own kernel scheme), M = 1
 # ---------------------------------------------------------------------------------------------
 def _run_lut(torch, p, table_format="fp32"):
