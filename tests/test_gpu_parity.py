@@ -597,6 +597,39 @@ def test_folded_permutations_two_matrix_chain(torch_cuda, M):
 
 
 # ---------------------------------------------------------------------------------------------
+# seeded random small shapes across the corners of the path selection
+# ---------------------------------------------------------------------------------------------
+def test_random_small_shapes(torch_cuda):
+    # tile-row and tile-column counts around the limits of the decode forms (1, 16/17, 32/33, 64/65 tile columns per
+    # 16 wavefronts; 8/9, 17, 33, 40 tile rows), every M class, all group lengths and both parameter formats, with and
+    # without permutations and activation outliers; whole outputs against the oracle, and repeatable
+    from gpu_util import device_problem, run_gemm
+    rng = np.random.default_rng(2)
+    done = 0
+    for c in range(110):
+        ntr = int(rng.choice([1, 2, 3, 5, 8, 9, 17, 33, 40]))
+        ntc = int(rng.choice([1, 2, 7, 8, 15, 16, 17, 31, 32, 33, 48, 63, 64, 65, 72]))
+        M = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 40]))
+        group = int(rng.choice([64, 128, 128, 256])) if ntc % 2 == 0 else int(rng.choice([64, 128]))
+        fmt = str(rng.choice(["fp16", "bf16"]))
+        outliers, use_cp, use_rp = bool(rng.integers(2)), bool(rng.integers(4)), bool(rng.integers(4))
+        N, K = 128 * ntr, 128 * ntc
+        if N * K > 24 * 2 ** 20:
+            continue
+        p = W.make_problem(f"rnd{c}", K, N, M, 90000 + c, fractions={2: 0.3, 3: 0.4, 4: 0.3}, outliers=outliers,
+                           use_col_perm=use_cp, use_row_perm=use_rp, group=group, scale_format=fmt)
+        dp, cp, rp = device_problem(p)
+        Y = run_gemm(p, dp, cp, rp)
+        try:
+            _check(p, Y)
+        except AssertionError as ex:
+            raise AssertionError(f"case {c}: N={N} K={K} M={M} group={group} {fmt}: {ex}") from None
+        assert np.array_equal(run_gemm(p, dp, cp, rp).view(np.uint16), Y.view(np.uint16)), (c, N, K, M)
+        done += 1
+    assert done >= 80
+
+
+# ---------------------------------------------------------------------------------------------
 # what the error bound of the decode kernels assumes about the matrix instruction, pinned on the hardware
 # ---------------------------------------------------------------------------------------------
 def test_mfma_alignment_model(torch_cuda):
