@@ -330,6 +330,81 @@ def test_bench_step_replayed_as_graph_matches_oracle(torch_cuda):
                     assert np.array_equal(y0.view(np.uint16), y.view(np.uint16)), (rnd, r)
 
 
+@pytest.mark.parametrize("M", [4, 16, 40])
+def test_small_batch_calls_replayed_as_graph(torch_cuda, M):
+    """Small-batch calls under HIP-graph capture: a batched launch of three projections over shared activations (staging
+    kernel + ring kernel; at M = 4 the resident form, at M = 16 the activations in registers), one long-K call whose
+    activations travel through the ring slots, and at M = 40 the chunked form, all in one graph.  Replayed three times
+    with new activations written by eager work between the replays; every replay bit for bit what eager calls give."""
+    import dataclasses
+    import paper_2602_01027_amd as S
+    from gpu_util import device_problem, make_workspace
+    torch = torch_cuda
+    base = W.make_problem("g0", 1024, 512, M, 8900 + M, fractions={2: 0.5, 3: 0.5}, outliers=True)
+    shared = [base] + [dataclasses.replace(W.make_problem(f"g{i}", 1024, n, M, 8910 + i), X=base.X, col_perm=base.col_perm)
+                       for i, n in enumerate((256, 384), 1)]
+    longk = W.make_problem("gl", 9216, 256, M, 8920)
+    Xs = torch.from_numpy(base.X).to("cuda:0")
+    Xl = torch.from_numpy(longk.X).to("cuda:0")
+    cps = torch.from_numpy(base.col_perm).to("cuda:0")
+    batch, keep = [], []
+    for p in shared:
+        dp, cp, rp = device_problem(p)
+        batch.append((Xs, cps, dp, rp, torch.empty((M, p.N), dtype=torch.float16, device="cuda:0")))
+        keep.append(dp)
+    dl, cpl, rpl = device_problem(longk)
+    Yl = torch.empty((M, longk.N), dtype=torch.float16, device="cuda:0")
+    wsl = make_workspace(dl.layout, M)
+    use_batched = M <= 16
+    if use_batched:
+        wsb = torch.empty(S.sfmp_gemm_batched_workspace(batch, M), dtype=torch.uint8, device="cuda:0").fill_(0xFF)
+    else:
+        wss = [make_workspace(b[2].layout, M) for b in batch]
+
+    def launch(stream):
+        if use_batched:
+            S.sfmp_gemm_batched(batch, M, wsb, stream=stream)
+        else:
+            for (X, cp, dp, rp, Y), ws in zip(batch, wss):
+                S.sfmp_gemm(X, cp, dp.layout, dp.s2, dp.s3, dp.s4, dp.index, dp.scales, dp.zeros, dp.bitmap, rp, Y, ws, stream=stream)
+        S.sfmp_gemm(Xl, cpl, dl.layout, dl.s2, dl.s3, dl.s4, dl.index, dl.scales, dl.zeros, dl.bitmap, rpl, Yl, wsl, stream=stream)
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        launch(side)
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        launch(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(77)
+    for rep in range(3):
+        # new activations (eager copies), outputs poisoned, workspaces poisoned
+        xs = (rng.normal(size=base.X.shape)).astype(np.float16)
+        xl = (rng.normal(size=longk.X.shape)).astype(np.float16)
+        Xs.copy_(torch.from_numpy(xs)); Xl.copy_(torch.from_numpy(xl))
+        for b in batch:
+            b[4].fill_(float("nan"))
+        Yl.fill_(float("nan"))
+        wsl.fill_(0xFF)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = [b[4].cpu().numpy().copy() for b in batch] + [Yl.cpu().numpy().copy()]
+        for b in batch:
+            b[4].fill_(float("nan"))
+        Yl.fill_(float("nan"))
+        launch(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        eager = [b[4].cpu().numpy() for b in batch] + [Yl.cpu().numpy()]
+        for a, e in zip(got, eager):
+            assert np.isfinite(a.astype(np.float32)).all()
+            assert np.array_equal(a.view(np.uint16), e.view(np.uint16)), rep
+        if rep == 0:  # and the values are right
+            for p, y, x in zip(shared + [longk], got, [xs, xs, xs, xl]):
+                _check(dataclasses.replace(p, X=x), y)
+
+
 # ---------------------------------------------------------------------------------------------
 # several M = 1 problems in one launch
 # ---------------------------------------------------------------------------------------------
