@@ -176,9 +176,10 @@ int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream);
  * 2^-14 <= |v| <= 65504 (or be 0), to keep full precision; below it a weight carries an absolute error of up to 2^-25,
  * above it it overflows.
  * M = 1 runs the bandwidth-bound GEMV kernel, 2 <= M <= 16 (and M = 1 with K above about 32k) the
- * same scheme with the activations staged per tile column, 16 < M <= 128 on narrow matrices with
- * K >= 4096 (N <= 1024: M <= 128; N <= 4096: M <= 32) that kernel once more, on chunks of 16 rows side
- * by side in one launch, and everything else the MFMA prefill kernels (with K
+ * same scheme with the activations staged per tile column, 16 < M <= 128 with K >= 4096 on matrices and
+ * batch sizes where that measured faster (N <= 1024: M <= 128; K <= 8192: M <= 32 on any N, M <= 64 up to
+ * 1536 tiles of 128 x 128, M <= 96 up to 1024 tiles; longer K: M <= 32 on N <= 4096) that kernel once more, on
+ * chunks of 16 rows side by side in one launch, and everything else the MFMA prefill kernels (with K
  * cut into ranges and fp32 partial products in the workspace when there would be few workgroups;
  * SFMP_ERR_SHAPE there if K > 57344, or, with a row permutation or a split K, N > 81920; the kernels for
  * M <= 16 and for the chunked form return SFMP_ERR_SHAPE if N * K >= 2^33).

@@ -1769,18 +1769,28 @@ int launch_decode_batched(const GemmArgs* probs, int count, int32_t M, void* wor
   return SFMP_ERR_SHAPE;
 }
 
-// 16 < M <= 128 on a narrow matrix: the product is cut into chunks of 16 activation rows, one problem of the
-// batched ring kernel each (the same weights, its own rows of X and Y).  The chunks run side by side on their
-// shares of the CUs and read the same weights at about the same time, so the matrix comes from HBM once and
-// from the caches for the other chunks.  Against the MFMA kernel with a split K the cost grows quickly with the
-// number of chunks and with N; measured on the 8B / 70B shapes the chunked form wins for
-//   N <= 1024: up to 8 chunks (4096 -> 1024: 13-17 us against 18-19);  N <= 4096: 2 chunks (4096 -> 4096: 16 us
-//   against 19);  wider, or K below 4096 (not measured): never.
+// 16 < M <= 128: the product may be cut into chunks of 16 activation rows, one problem of the batched ring kernel
+// each (the same weights, its own rows of X and Y).  The chunks run side by side on their shares of the CUs and read
+// the same weights at about the same time, so the matrix comes from HBM once and from the caches for the other
+// chunks.  Against the MFMA kernel (with a split K on these sizes) the cost grows with the number of chunks and with
+// the matrix; measured on the 8B / 70B shapes (same-box A/B, whole calls) the chunked form wins
+//   with K <= 8192 (the chunks keep their activations in registers): two chunks on every shape tried (4096 -> 4096
+//   12 us against 19 for the MFMA kernel at M = 32, 4096 -> 14336 22 against 27, 8192 -> 28672 66 against 73); three
+//   and four chunks up to 1536 tiles (4096 -> 6144: 17 against 21, 20 against 21.5; not 4096 -> 14336: 31 against 29,
+//   nor 8192 -> 8192: 33 against 31); five and six up to 1024 tiles (4096 -> 4096: 18.4 against 21.1, 20.1 against 21.8;
+//   eight: 33.5 against 22.9); eight on N <= 1024;
+//   with a longer K (activations through the ring slots): N <= 1024 up to 8 chunks (14336 -> 1024), N <= 4096 two;
+//   with K below 4096 (not measured): never.
 bool use_chunked_decode(int32_t N, int32_t K, int32_t M) {
   if (M <= kDecodeMaxM || M > kDecodeMaxM * kGemvMaxBatch) return false;
   const int32_t ntr = N / kTile, ntc = K / kTile, chunks = (M + kDecodeMaxM - 1) / kDecodeMaxM;
   if (ntc < 32) return false;
-  return chunks <= (ntr <= 8 ? 8 : ntr <= 32 ? 2 : 0);
+  if (ntr <= 8) return true;  // (chunks <= 8 here)
+  if (ntc <= 64) {
+    const int64_t tiles = (int64_t)ntr * ntc;
+    return chunks <= 2 || (chunks <= 4 && tiles <= 1536) || (chunks <= 6 && tiles <= 1024);
+  }
+  return chunks <= 2 && ntr <= 32;
 }
 
 static int chunk_problems(const GemmArgs& a, GemmArgs* probs) {

@@ -171,11 +171,13 @@ def test_batched_small_batch_mixed_staging(torch_cuda):
 
 
 @pytest.mark.parametrize("K,N,M", [(4096, 512, 17), (4096, 512, 100), (4096, 1024, 128), (4096, 1152, 128),
-                                   (4096, 4096, 32), (4096, 4096, 33), (4096, 8192, 64)])
+                                   (4096, 4096, 32), (4096, 4096, 33), (4096, 8192, 64), (4096, 4096, 96), (4096, 4096, 97),
+                                   (4096, 6144, 64), (4096, 6144, 65), (4096, 14336, 32), (4096, 14336, 33),
+                                   (8192, 8192, 32), (8192, 8192, 40), (14336, 4096, 32), (14336, 4096, 33)])
 def test_medium_batch_chunked_and_prefill_sides(torch_cuda, K, N, M):
-    # 16 < M <= 128 with K >= 4096: chunks of 16 rows through the batched ring kernel while the matrix is narrow
-    # enough (last chunk of 1 and of 4 rows, the full 8 chunks), the MFMA kernel with a split K beyond; both sides
-    # of each limit
+    # 16 < M <= 128 with K >= 4096: chunks of 16 rows through the batched ring kernel where that measured faster
+    # (last chunk of 1 and of 4 rows, the full 8 chunks; with K <= 8192 two chunks on any matrix, four up to 1536 tiles,
+    # six up to 1024; two on N <= 4096 with a longer K), the MFMA kernel with a split K beyond; both sides of each limit
     from gpu_util import run_gemm
     p = W.make_problem("medium", K, N, M, 6200 + N + M, fractions={2: 1 / 3, 3: 1 / 3, 4: 1 / 3}, outliers=True,
                        fast_codes=True)

@@ -183,7 +183,14 @@ def _plan_mirror(N, K, M):
             mb = 16
         return "ring", up256(ntc * mb * 256)
     chunks = (M + 15) // 16
-    if M <= 128 and ntc >= 32 and chunks <= (8 if ntr <= 8 else 2 if ntr <= 32 else 0):
+    if ntr <= 8:
+        chunked = chunks <= 8
+    elif ntc <= 64:  # K <= 8192: the chunks keep their activations in registers
+        tiles = ntr * ntc
+        chunked = chunks <= 2 or (chunks <= 4 and tiles <= 1536) or (chunks <= 6 and tiles <= 1024)
+    else:
+        chunked = chunks <= 2 and ntr <= 32
+    if M <= 128 and ntc >= 32 and chunked:
         return "chunked", chunks * up256(ntc * 16 * 256)
     bm = 64 if ((M + 127) // 128) * ntr <= 128 else 128
     blocks = ((M + bm - 1) // bm) * ntr
@@ -198,7 +205,8 @@ def _plan_mirror(N, K, M):
 
 
 @pytest.mark.parametrize("N,K,M", [(4096, 4096, 4), (4096, 4096, 3), (14336, 4096, 5), (32768, 4096, 2), (57344, 4096, 8), (57344, 8192, 8), (4096, 8192, 3), (4096, 14336, 16), (1024, 4096, 128), (1152, 4096, 128),
-                                    (4096, 4096, 32), (4096, 4096, 33), (4096, 14336, 256), (14336, 4096, 48),
+                                    (4096, 4096, 32), (4096, 4096, 33), (4096, 4096, 96), (4096, 4096, 97), (6144, 4096, 64), (14336, 4096, 32),
+                                    (14336, 4096, 33), (8192, 8192, 32), (8192, 8192, 48), (28672, 8192, 32), (4096, 14336, 32), (4096, 14336, 256), (14336, 4096, 48),
                                     (14336, 4096, 256), (4096, 4096, 2048), (28672, 8192, 2048), (4096, 2048, 100),
                                     (8192, 28672, 512)])
 def test_workspace_query_follows_the_documented_path_selection(N, K, M):
