@@ -358,8 +358,43 @@ def profile_figures():
         return {}
 
 
+def bare_read_floor_us(torch, launch_bytes, replicas, nrep, src=None):
+    """The floor of a step: HIP-event microseconds per step of a step made of len(launch_bytes) launches, each a bare
+    streaming read (the probe library's kernel: nothing computed, no dependent start) of the bytes its launch of the
+    step moves, replayed as a graph over rotating memory (1 GiB) like the step itself."""
+    from paper_2602_01027_amd import probe
+    if src is None:
+        src = torch.empty((1 << 30) + (64 << 20), dtype=torch.uint8, device="cuda:0").random_(0, 255)
+    outp = torch.empty(2048, dtype=torch.uint8, device="cuda:0")
+    launch_bytes = [(int(b) + 255) // 256 * 256 for b in launch_bytes]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graphs, off = [], 0
+    for r in range(replicas):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for b in launch_bytes:
+                if off + b > (1 << 30):
+                    off = 0
+                probe.stream_read(src[off:off + b], outp, stream=torch.cuda.current_stream())
+                off += b
+        graphs.append(g)
+    torch.cuda.synchronize()
+    for i in range(replicas):
+        graphs[i].replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(nrep):
+        graphs[i % replicas].replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / nrep
+
+
 def layer_line(torch, W, cid, M, steps, eager, groups):
-    """One transformer layer of configuration cid at batch M: microseconds per layer and its share of the bounds."""
+    """One transformer layer of configuration cid at batch M: microseconds per layer and its share of the bounds; at
+    M = 1 also the floor of its launches (bare streaming reads of the same bytes, bare_read_floor_us)."""
     fused = groups is not None and M <= 16
     pb = build_problems(W, cid, Ms=(M,), fast=True)
     bb = sum(W.algorithmic_bytes(p.N, p.K, p.M, p.bitmap, index_words=p.bitmap.size) for p in pb)
@@ -370,8 +405,18 @@ def layer_line(torch, W, cid, M, steps, eager, groups):
                MB=round(bb / 1e6, 1), GBps=round(bb / ms / 1e6, 1),
                frac_hbm_peak=round(bb / ms / 1e6 / HBM_PEAK_GBPS, 4),
                TFLOPs=round(fl / ms / 1e9, 2), frac_mfma_peak=round(fl / ms / 1e9 / MFMA_F16_PEAK_TFLOPS, 4))
+    per = lb.bytes_per_proj(W)
+    replicas = lb.replicas
     del lb, pb
     torch.cuda.empty_cache()
+    if M == 1 and fused:
+        try:
+            floor = bare_read_floor_us(torch, [sum(per[i] for i in g) for g in groups], replicas, max(steps, 2 * replicas))
+            row["bare_read_floor_us"] = round(floor, 2)
+            row["floor_over_value"] = round(floor / (ms * 1e3), 4)
+        except Exception as ex:  # the probe is an aid: never let it take the bench line down
+            row["bare_read_floor_error"] = str(ex)
+        torch.cuda.empty_cache()
     return row
 
 
@@ -476,31 +521,8 @@ def main():
         result["roofline"]["measured_stream_read_GBps"] = round(stream_gbps, 1)
         result["roofline"]["frac_of_measured_stream_read"] = round(gbps / stream_gbps, 4)
         launch_bytes = [sum(per_proj_bytes[i] for i in g) for g in (groups or [[i] for i in range(len(problems))])]
-        launch_bytes = [(int(b) + 255) // 256 * 256 for b in launch_bytes]
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        graphs, off = [], 0
-        for r in range(R):
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=side):
-                for b in launch_bytes:
-                    if off + b > (1 << 30):
-                        off = 0
-                    probe.stream_read(src[off:off + b], outp, stream=torch.cuda.current_stream())
-                    off += b
-            graphs.append(g)
-        torch.cuda.synchronize()
-        nrep = max(args.steps, 2 * R)
-        for i in range(R):
-            graphs[i].replay()
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(nrep):
-            graphs[i % R].replay()
-        e1.record()
-        torch.cuda.synchronize()
-        floor_us = e0.elapsed_time(e1) * 1e3 / nrep
-        del src, outp, whole, graphs
+        floor_us = bare_read_floor_us(torch, launch_bytes, R, max(args.steps, 2 * R), src=src)
+        del src, outp, whole
         result["roofline"]["bare_read_floor_us"] = round(floor_us, 3)
         result["roofline"]["floor_over_value"] = round(floor_us / us_layer, 4)
         result["roofline"]["note_floor"] = ("bare_read_floor_us = HIP-event time of a step made of the same number of launches, "
