@@ -158,7 +158,9 @@ int sfmp_workspace_init(void* workspace_dev, int64_t bytes, void* hip_stream);
  *   row_perm  int32 [N]; output feature i of the reordered product is stored at column
  *             row_perm[i] of Y (undoing P_row of Eq. 9); NULL = leave the rows reordered.
  *   Y         fp16 [M, N] row-major; fully overwritten.  fp32 accumulation, one
- *             round-to-nearest-even conversion at the end.
+ *             round-to-nearest-even conversion at the end.  The order of the fp32 sums is fixed for a given
+ *             (N, K, M, group length): the same call on the same inputs gives the same bits, on any stream
+ *             (no floating-point atomics anywhere).
  *   workspace device memory of at least sfmp_gemm_workspace() bytes, 256-byte aligned; contents
  *             on entry are irrelevant, contents on return are unspecified.
  * Alignment (SFMP_ERR_ALIGN otherwise): X, col_perm, row_perm, s2, s3, s4, scales and zeros 16 bytes (the kernels
@@ -236,6 +238,10 @@ int sfmp_gemv_batched(const sfmp_gemv_problem_t* problems_host, int32_t count, v
  * sfmp_gemm computes; X_dev of a problem is fp16 [M, K], Y_dev fp16 [M, N]), in one launch of the GEMM kernel plus,
  * for M >= 2, one launch of the activation staging kernel.  Problems that pass the same X_dev, col_perm_dev and K
  * (q, k and v; gate and up) share one staged copy of the activations.  M = 1 is sfmp_gemv_batched.
+ * One launch runs one form of the kernel, chosen for the whole batch (by its largest K and its largest share of
+ * slabs per workgroup), which may not be the form a single sfmp_gemm call takes for one of its problems: the operation
+ * is the same, the order of the fp32 sums and hence the last bit of an output may differ from the single call.  The
+ * same batch on the same inputs gives the same bits every time.
  * sfmp_gemm_batched_workspace (host only) gives the workspace size for these problems and this M (never 0);
  * the workspace is device memory, 256-byte aligned, contents irrelevant on entry and unspecified on return.
  * SFMP_ERR_SHAPE if M is outside 1..16, if a problem would put more than 16 slabs on a workgroup (N above about

@@ -706,6 +706,65 @@ def test_random_small_shapes(torch_cuda):
     assert done >= 80
 
 
+def test_random_batches(torch_cuda):
+    # seeded random batches through sfmp_gemv_batched / sfmp_gemm_batched: one to eight problems of unrelated shapes
+    # (or sharing K and the activations, as q, k and v do), every M class of the decode path, mixed parameter formats
+    # and group lengths (64 for all problems or for none: one launch runs one class); a launch picks ONE form of the
+    # kernel for the whole batch, by its largest K and its largest share of slabs per workgroup.  Every output against
+    # the oracle, and a second call (workspace refilled with other bytes) gives the same bits.
+    import paper_2602_01027_amd as S
+    from gpu_util import device_problem
+    torch = torch_cuda
+    rng = np.random.default_rng(5)
+    done = 0
+    for c in range(36):
+        count = int(rng.integers(1, 9))
+        M = int(rng.choice([1, 1, 2, 3, 4, 5, 8, 9, 16]))
+        g64 = bool(rng.integers(4) == 0)
+        K0 = 128 * int(rng.choice([1, 4, 8, 16, 20, 32, 33, 64, 72, 112]))
+        share = bool(rng.integers(2))
+        probs = []
+        for i in range(count):
+            K = K0 if (share or rng.integers(2)) else 128 * int(rng.choice([2, 8, 32, 40]))
+            N = 128 * int(rng.choice([1, 2, 3, 8, 9, 17, 32, 80]))
+            if N * K > 16 * 2 ** 20:
+                N = 128 * 8
+            group = 64 if g64 else int(rng.choice([128, 128, 256])) if (K // 128) % 2 == 0 else 128
+            probs.append(W.make_problem(f"rb{c}.{i}", K, N, M, 95000 + 16 * c + i, fractions={2: 0.3, 3: 0.4, 4: 0.3},
+                                        outliers=bool(rng.integers(2)), use_col_perm=bool(rng.integers(4)),
+                                        use_row_perm=bool(rng.integers(4)), group=group,
+                                        scale_format=str(rng.choice(["fp16", "bf16"]))))
+        batch, shared = [], {}
+        for p in probs:
+            dp, cp, rp = device_problem(p)
+            if share and p.K in shared:  # the same activations through this problem's own column permutation
+                X = shared[p.K]
+                p.X[...] = X.cpu().numpy()
+            else:
+                X = shared[p.K] = torch.from_numpy(p.X).to("cuda:0")
+            batch.append((X, cp, dp, rp, torch.full((M, p.N), float("nan"), dtype=torch.float16, device="cuda:0")))
+        ws = None if M == 1 else torch.empty(S.sfmp_gemm_batched_workspace(batch, M), dtype=torch.uint8, device="cuda:0")
+        outs = []
+        for fill in (0xFF, 0x7F):
+            for b in batch:
+                b[4].fill_(float("nan"))
+            if M == 1:
+                S.sfmp_gemv_batched(batch)
+            else:
+                ws.fill_(fill)
+                S.sfmp_gemm_batched(batch, M, ws)
+            torch.cuda.synchronize()
+            outs.append([b[4].cpu().numpy().copy() for b in batch])
+        for p, y0, y1 in zip(probs, outs[0], outs[1]):
+            try:
+                _check(p, y0)
+            except AssertionError as ex:
+                raise AssertionError(f"case {c}: M={M} {[(q.N, q.K, q.group) for q in probs]}: {p.label}: {ex}") from None
+            assert np.array_equal(y0.view(np.uint16), y1.view(np.uint16)), (c, p.label)
+        done += 1
+    assert done == 36
+
+
 # ---------------------------------------------------------------------------------------------
 # what the error bound of the decode kernels assumes about the matrix instruction, pinned on the hardware
 # ---------------------------------------------------------------------------------------------
