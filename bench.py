@@ -549,18 +549,24 @@ def main():
     if not args.no_prefill and args.section in ("all", "prefill"):
         # The matrix-core half of the metric: configs[4], M = 2048, all six shapes, one sfmp_gemm call each (staging +
         # GEMM + row un-permute where the configuration has a row permutation), codes drawn directly (timing only).
-        rows, tot_fl, tot_t, dense_t = [], 0.0, 0.0, 0.0
+        rows, tot_fl, tot_t, dense_t, tot_traffic = [], 0.0, 0.0, 0.0, 0
         kfig = figs.get("prefill_M2048", {})
         for pp in build_problems_iter(W, 5):
             lp = Layer([pp], 1)
             t = time_each_projection(torch, lp, launches=args.prefill_launches)[0]
             fl = 2.0 * pp.M * pp.N * pp.K
             kus = kfig.get("kernel_us", {}).get(f"{pp.K}->{pp.N}")
+            ktr = kfig.get("kernel_traffic_bytes", {}).get(f"{pp.K}->{pp.N}")
+            # what the GEMM kernel has to move at least: packed weights and parameters, the staged activations, the product
+            alg = int(W.algorithmic_bytes(pp.N, pp.K, pp.M, pp.bitmap, col_perm=False, row_perm=False,
+                                          index_words=pp.bitmap.size, group=pp.group))
             rows.append(dict(shape=f"{pp.K}->{pp.N}", us=round(t, 1), GFLOP=round(fl / 1e9, 1),
                              TFLOPs=round(fl / t / 1e6, 1), frac=round(fl / t / 1e6 / MFMA_F16_PEAK_TFLOPS, 4),
                              kernel_us=kus,
                              kernel_frac=round(fl / kus / 1e6 / MFMA_F16_PEAK_TFLOPS, 4) if kus else None,
+                             kernel_traffic_bytes=ktr, kernel_algorithmic_bytes=alg,
                              dense_fp16_us=dense_fp16_us(torch, pp.M, pp.N, pp.K, args.prefill_launches)))
+            tot_traffic = (tot_traffic + ktr) if (ktr is not None and tot_traffic is not None) else None
             tot_fl += fl
             tot_t += t
             dense_t += rows[-1]["dense_fp16_us"]
@@ -574,7 +580,7 @@ def main():
             "peak": MFMA_F16_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(tot_fl / tot_t / 1e6 / MFMA_F16_PEAK_TFLOPS, 4),
-            "traffic": None,
+            "traffic": tot_traffic,
             "workload": "configs[4]: M=2048 on 4096->4096, 4096->1024, 4096->14336, 14336->4096, 8192->28672, "
                         "28672->8192; 50 % 3-bit / 50 % 4-bit tiles, outlier columns",
             "per_shape": rows,
@@ -587,7 +593,11 @@ def main():
             "note": "achieved / frac = FLOP-weighted aggregate: total 2*M*N*K of the six shapes / total HIP-event time of "
                     "one whole sfmp_gemm call each (graph of back-to-back calls), measured in this run; per-shape "
                     f"kernel_us / kernel_frac = GEMM kernel alone from the tracked kernel trace ({kfig.get('source')}), "
-                    "constants of that profile",
+                    "constants of that profile; traffic = FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 of the GEMM kernel (counter runs "
+                    "of the same profile, factors from a 256 MiB copy), summed over the six launches, per shape as "
+                    "kernel_traffic_bytes beside kernel_algorithmic_bytes (packed weights and parameters once, staged "
+                    "activations in, product out): the excess is the weights read once per XCD (8 L2s) and activation "
+                    "blocks that left an L2 before every workgroup sharing them had read them",
         }
 
     if not args.no_extra:
